@@ -1,0 +1,208 @@
+/*
+ * cfpp — single-token decode of GPT-NeoX / Pythia decoder blocks on MI355X (gfx950).
+ *
+ * C ABI of the hot path of "ClusterFusion++" (arXiv 2604.23553): one call runs,
+ * for one new token per sequence, the paper's fused region (Sec. 2.2)
+ *
+ *   pre-attention LayerNorm -> QKV projection + KV-cache update -> partial
+ *   rotary embedding -> decode attention over the cache -> output projection
+ *   -> post-attention LayerNorm -> MLP up / GELU / down -> residual
+ *
+ * in the residual form GPT-NeoX defines:
+ *   out = x + Dense(Attn(LN1(x))) + Down(GELU(Up(LN2(x)))).
+ * A second pair of calls runs an L-layer stack of such blocks as one launch
+ * sequence or as one replayable HIP graph with static buffers (Sec. 2.3).
+ *
+ * Conventions
+ *   - Every pointer named *device* is device memory owned by the caller
+ *     (e.g. a torch tensor) that must stay alive while the library uses it;
+ *     the library allocates no device memory.  Pointers must be 16-byte
+ *     aligned.  Pointers named *host* are ordinary host memory.
+ *   - fp16 means IEEE binary16.  All arithmetic accumulates in fp32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Compute calls only enqueue work; they never synchronise.
+ *   - Every call returns a cfpp_status; nothing throws or exits.  The text of
+ *     the last failure on the calling thread is in cfpp_last_error().
+ *   - Results are bit-identical from run to run: every reduction has a fixed
+ *     order and no floating-point atomics are used (the paper's fp16-atomic
+ *     output accumulation, Sec. 3 "Output fidelity", is deliberately replaced).
+ */
+#ifndef CFPP_H
+#define CFPP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t cfpp_status;
+#define CFPP_OK            0
+#define CFPP_EINVAL       (-1)  /* bad argument (null, misaligned, out of range)   */
+#define CFPP_EUNSUPPORTED (-2)  /* valid request this build has no kernel for      */
+#define CFPP_ENOMEM       (-3)  /* caller-provided buffer too small                */
+#define CFPP_EHIP         (-4)  /* a HIP runtime call failed (see last_error)      */
+#define CFPP_ESTATE       (-5)  /* call out of order (e.g. replay before capture)  */
+#define CFPP_EDEVICE      (-6)  /* a kernel flagged an error (bad pos, barrier timeout) */
+
+typedef void *cfpp_stream;      /* hipStream_t */
+
+/* Model shape and limits.  Supported: head_dim in {64, 80, 128};
+ * hidden == n_heads * head_dim; hidden and ffn multiples of 8; hidden <= 8192;
+ * rotary_dims even, <= head_dim (Pythia: head_dim / 4, paper Sec. 2.2
+ * "Architecture-Specific Adaptations"); 1 <= n_layers <= 64. */
+typedef struct cfpp_config {
+    int32_t hidden;       /* h                                               */
+    int32_t n_heads;      /* H                                               */
+    int32_t head_dim;     /* d                                               */
+    int32_t rotary_dims;  /* r: leading dims of each head that are rotated   */
+    int32_t ffn;          /* f: MLP width                                    */
+    int32_t n_layers;     /* L: blocks in the stack                          */
+    int32_t max_seq;      /* KV-cache capacity in positions (pos < max_seq)  */
+    int32_t max_batch;    /* sequences the KV cache and workspace are sized for */
+    float   rope_base;    /* 10000 for Pythia                                */
+    float   ln_eps;       /* 1e-5 for Pythia                                 */
+    int32_t flags;        /* reserved, must be 0                             */
+} cfpp_config;
+
+/* The 12 canonical fp16 tensors of one GPT-NeoX block, DEVICE pointers,
+ * row-major.  w_qkv rows are interleaved per head (paper Sec. 2.2): row
+ * (3*n + c)*d + i is dim i of q (c=0), k (c=1) or v (c=2) of head n. */
+typedef struct cfpp_layer_src {
+    const void *ln1_g, *ln1_b;      /* [h]  pre-attention LayerNorm  */
+    const void *ln2_g, *ln2_b;      /* [h]  post-attention LayerNorm */
+    const void *w_qkv, *b_qkv;      /* [3h, h], [3h]                 */
+    const void *w_dense, *b_dense;  /* [h, h],  [h]                  */
+    const void *w_up, *b_up;        /* [f, h],  [f]                  */
+    const void *w_down, *b_down;    /* [h, f],  [h]                  */
+} cfpp_layer_src;
+
+typedef struct cfpp_ctx cfpp_ctx;
+
+/* ---- errors -------------------------------------------------------------- */
+const char *cfpp_status_string(cfpp_status s);
+const char *cfpp_last_error(void);          /* thread-local, never NULL */
+
+/* ---- host-only helpers (no GPU needed) ----------------------------------- */
+
+/* CFPP_OK if `cfg` is a shape this build supports, else EINVAL / EUNSUPPORTED. */
+cfpp_status cfpp_validate_config(const cfpp_config *cfg);
+
+/* Bytes of one packed layer, of one layer's KV cache, and of the workspace.
+ * 0 if cfg is invalid. */
+size_t cfpp_packed_layer_bytes(const cfpp_config *cfg);
+size_t cfpp_kv_layer_bytes(const cfpp_config *cfg);
+size_t cfpp_workspace_bytes(const cfpp_config *cfg);
+
+/* HBM bytes the method must move for one decode step of `n_layers` blocks:
+ * per layer, the fp16 parameters (12h^2 + 13h values), the K and V rows of
+ * positions 0..pos[b]-1 read, the new K and V rows written; plus x read and out
+ * written once.  This is the numerator of the roofline fraction.  pos_host:
+ * [batch] host array. */
+cfpp_status cfpp_algorithmic_bytes(const cfpp_config *cfg, const int32_t *pos_host,
+                                   int32_t batch, int32_t n_layers, uint64_t *bytes);
+
+/* ---- one-time data preparation (device work, off the hot path) ----------- */
+
+/* Packs one block's canonical tensors into the streaming layout the kernels
+ * read: one blob with the LayerNorm parameters, the biases, and the four
+ * matrices stored row-major so that a wavefront reads 1 KiB contiguous per
+ * load; the QKV rows of each head are reordered so that the two rows of a
+ * rotary pair (i, i + r/2) are adjacent.  packed_dst: DEVICE,
+ * cfpp_packed_layer_bytes(cfg) bytes. */
+cfpp_status cfpp_pack_layer(const cfpp_config *cfg, const cfpp_layer_src *src,
+                            void *packed_dst, cfpp_stream stream);
+
+/* KV cache of one layer, as the kernels keep it (DEVICE,
+ * cfpp_kv_layer_bytes(cfg) bytes):
+ *     fp16 [2 (K, V)][max_batch][n_heads][head_dim/16][max_seq][16]
+ * i.e. for each head, 16-dim slabs with the position index next-to-innermost,
+ * so that consecutive positions of a slab are contiguous 32-byte records.
+ * Cached K rows are stored already rotated.
+ *
+ * cfpp_kv_import copies positions [0, n_pos) of sequence `b` from canonical
+ * fp16 tensors k_src, v_src (DEVICE, [n_heads, src_capacity, head_dim]) into
+ * kv_layer; cfpp_kv_export copies positions [pos_begin, pos_begin + n_pos) back
+ * out into canonical tensors of the same shape convention (row t of the
+ * destination receives position t). */
+cfpp_status cfpp_kv_import(const cfpp_config *cfg, const void *k_src, const void *v_src,
+                           int32_t src_capacity, int32_t n_pos, int32_t b,
+                           void *kv_layer, cfpp_stream stream);
+cfpp_status cfpp_kv_export(const cfpp_config *cfg, const void *kv_layer, int32_t b,
+                           int32_t pos_begin, int32_t n_pos, int32_t dst_capacity,
+                           void *k_dst, void *v_dst, cfpp_stream stream);
+
+/* ---- context ------------------------------------------------------------- */
+
+/* Creates a context over a caller-owned DEVICE workspace of at least
+ * cfpp_workspace_bytes(cfg) bytes (static intermediate buffers, the rotary
+ * cos/sin table, barrier words).  Initialises the workspace synchronously on
+ * the current device.  The context holds only host bookkeeping and, after
+ * cfpp_stack_capture, the instantiated graph. */
+cfpp_status cfpp_create(const cfpp_config *cfg, void *workspace, size_t workspace_bytes,
+                        cfpp_ctx **out_ctx);
+void cfpp_destroy(cfpp_ctx *ctx);
+
+/* Launch tuning.  Options may be changed between calls (not between capture
+ * and replay). */
+#define CFPP_OPT_MODE     1  /* 0: one kernel per phase (3 per block);
+                                1: one persistent kernel per block;
+                                2: one persistent kernel for the whole stack  */
+#define CFPP_OPT_GRID     2  /* workgroups; 0 = one per compute unit          */
+#define CFPP_OPT_THREADS  3  /* threads per workgroup: 256 or 512             */
+cfpp_status cfpp_set_option(cfpp_ctx *ctx, int32_t option, int64_t value);
+cfpp_status cfpp_get_option(const cfpp_ctx *ctx, int32_t option, int64_t *value);
+
+/* ---- the hot path --------------------------------------------------------- */
+
+/* One decode step of ONE block (paper Sec. 2.2) for `batch` sequences.
+ *   packed_layer : DEVICE, from cfpp_pack_layer
+ *   kv_layer     : DEVICE, layout above; for sequence b the K and V rows of the
+ *                  new token are written at position pos[b]; positions
+ *                  0..pos[b]-1 are read; later positions are never touched
+ *   x            : DEVICE fp16 [batch, hidden] block input
+ *   pos_dev      : DEVICE int32 [batch]; 0 <= pos[b] < max_seq.  Read by the
+ *                  kernels at run time (so a captured graph follows updates).
+ *                  An out-of-range value makes the kernels skip the step and
+ *                  raise the context's device error flag (cfpp_device_error).
+ *   out          : DEVICE fp16 [batch, hidden] block output; must not alias x
+ * Asynchronous on `stream`. */
+cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer, void *kv_layer,
+                              const void *x, const int32_t *pos_dev, int32_t batch,
+                              void *out, cfpp_stream stream);
+
+/* One decode step through cfg.n_layers blocks.  packed_layers, kv_layers: HOST
+ * arrays of n_layers DEVICE pointers.  The residual stream between blocks is
+ * kept in fp32 in the workspace; fp16 only at x and out. */
+cfpp_status cfpp_stack_decode(cfpp_ctx *ctx, const void *const *packed_layers,
+                              void *const *kv_layers, const void *x,
+                              const int32_t *pos_dev, int32_t batch, void *out,
+                              cfpp_stream stream);
+
+/* Graph mode with static buffers (paper Sec. 2.3): capture records the whole
+ * stack step for these exact pointers into one HIP graph (nothing executes);
+ * each replay is one graph launch.  Between replays the caller updates the
+ * CONTENTS of x and pos_dev.  `stream` must not be the default stream. */
+cfpp_status cfpp_stack_capture(cfpp_ctx *ctx, const void *const *packed_layers,
+                               void *const *kv_layers, const void *x,
+                               const int32_t *pos_dev, int32_t batch, void *out,
+                               cfpp_stream stream);
+cfpp_status cfpp_stack_replay(cfpp_ctx *ctx, cfpp_stream stream);
+
+/* Synchronises `stream` and reports (and clears) the device error flag:
+ * CFPP_OK, or CFPP_EDEVICE with the reason in cfpp_last_error(). */
+cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream);
+
+/* Test tap: synchronises `stream`, then copies a workspace intermediate of the
+ * most recent block to HOST memory as fp32.  which: 0 = rotated q [batch, h],
+ * 1 = GELU(up) [batch, f], 2 = down projection incl. bias [batch, h],
+ * 3 = attention output before the output projection [batch, h].
+ * count = number of floats to copy (from the start). */
+cfpp_status cfpp_debug_read(cfpp_ctx *ctx, int32_t which, float *dst_host, size_t count,
+                            cfpp_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CFPP_H */

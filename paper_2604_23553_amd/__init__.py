@@ -1,0 +1,15 @@
+"""cfpp: MI355X-native single-token decode of GPT-NeoX / Pythia decoder blocks.
+
+The product is the C-ABI HIP library `libcfpp.so` (see include/cfpp.h); this
+package is its thin ctypes binding.  Every step of the decode path runs in the
+library's kernels; PyTorch is used by callers only for device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    CfppError, Config, lib, library_path,
+    cfpp_validate_config, cfpp_packed_layer_bytes, cfpp_kv_layer_bytes, cfpp_workspace_bytes,
+    cfpp_algorithmic_bytes, cfpp_pack_layer, cfpp_kv_import, cfpp_kv_export,
+    cfpp_create, cfpp_destroy, cfpp_set_option, cfpp_get_option,
+    cfpp_block_decode, cfpp_stack_decode, cfpp_stack_capture, cfpp_stack_replay,
+    cfpp_device_error, cfpp_debug_read,
+    OPT_MODE, OPT_GRID, OPT_THREADS,
+)

@@ -1,0 +1,561 @@
+// Host side of the C ABI declared in include/cfpp.h: argument checks, layout
+// arithmetic, context bookkeeping, launch-shape selection, graph capture.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "cfpp.h"
+#include "decode_params.h"
+
+using namespace cfpp;
+
+// ---- errors -----------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static cfpp_status fail(cfpp_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+#define HIP_OK(call)                                                                  \
+    do {                                                                              \
+        hipError_t e_ = (call);                                                       \
+        if (e_ != hipSuccess)                                                         \
+            return fail(CFPP_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));    \
+    } while (0)
+
+extern "C" const char *cfpp_status_string(cfpp_status s)
+{
+    switch (s) {
+    case CFPP_OK: return "ok";
+    case CFPP_EINVAL: return "invalid argument";
+    case CFPP_EUNSUPPORTED: return "unsupported configuration";
+    case CFPP_ENOMEM: return "buffer too small";
+    case CFPP_EHIP: return "HIP runtime error";
+    case CFPP_ESTATE: return "call out of order";
+    case CFPP_EDEVICE: return "device-side error";
+    }
+    return "unknown status";
+}
+
+extern "C" const char *cfpp_last_error(void) { return g_err; }
+
+// ---- config -------------------------------------------------------------------
+static bool aligned16(const void *p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+extern "C" cfpp_status cfpp_validate_config(const cfpp_config *c)
+{
+    if (!c) return fail(CFPP_EINVAL, "config is NULL");
+    if (c->hidden <= 0 || c->n_heads <= 0 || c->head_dim <= 0 || c->ffn <= 0 || c->n_layers <= 0 ||
+        c->max_seq <= 0 || c->max_batch <= 0 || c->rotary_dims < 0)
+        return fail(CFPP_EINVAL, "config has a non-positive dimension");
+    if ((long long)c->n_heads * c->head_dim != c->hidden)
+        return fail(CFPP_EINVAL, "hidden (%d) != n_heads (%d) * head_dim (%d)", c->hidden, c->n_heads,
+                    c->head_dim);
+    if ((c->rotary_dims & 1) || c->rotary_dims > c->head_dim)
+        return fail(CFPP_EINVAL, "rotary_dims (%d) must be even and <= head_dim", c->rotary_dims);
+    if (c->flags != 0) return fail(CFPP_EINVAL, "flags must be 0");
+    if (!(c->ln_eps >= 0.f) || !(c->rope_base > 0.f))
+        return fail(CFPP_EINVAL, "ln_eps must be >= 0 and rope_base > 0");
+    if (c->head_dim != 64 && c->head_dim != 80 && c->head_dim != 128)
+        return fail(CFPP_EUNSUPPORTED, "head_dim %d: only 64, 80 and 128 have kernels", c->head_dim);
+    if ((c->hidden % 8) || (c->ffn % 8))
+        return fail(CFPP_EUNSUPPORTED, "hidden and ffn must be multiples of 8");
+    if (c->hidden > 8192) return fail(CFPP_EUNSUPPORTED, "hidden %d > 8192", c->hidden);
+    if (c->ffn > 32768) return fail(CFPP_EUNSUPPORTED, "ffn %d > 32768", c->ffn);
+    if (c->n_layers > kMaxLayers) return fail(CFPP_EUNSUPPORTED, "n_layers %d > %d", c->n_layers, kMaxLayers);
+    if (c->max_seq > (1 << 20)) return fail(CFPP_EUNSUPPORTED, "max_seq %d > 2^20", c->max_seq);
+    if (c->max_batch > 64) return fail(CFPP_EUNSUPPORTED, "max_batch %d > 64", c->max_batch);
+    return CFPP_OK;
+}
+
+static Dims dims_of(const cfpp_config &c)
+{
+    Dims m;
+    m.h = c.hidden; m.H = c.n_heads; m.d = c.head_dim; m.r = c.rotary_dims; m.f = c.ffn;
+    m.max_seq = c.max_seq; m.max_batch = c.max_batch; m.ln_eps = c.ln_eps;
+    return m;
+}
+
+extern "C" size_t cfpp_packed_layer_bytes(const cfpp_config *c)
+{
+    if (cfpp_validate_config(c) != CFPP_OK) return 0;
+    return packed_layout(c->hidden, c->ffn).total * sizeof(__half);
+}
+
+extern "C" size_t cfpp_kv_layer_bytes(const cfpp_config *c)
+{
+    if (cfpp_validate_config(c) != CFPP_OK) return 0;
+    return kv_layer_elems(dims_of(*c)) * sizeof(__half);
+}
+
+extern "C" size_t cfpp_workspace_bytes(const cfpp_config *c)
+{
+    if (cfpp_validate_config(c) != CFPP_OK) return 0;
+    return workspace_layout(dims_of(*c)).total;
+}
+
+extern "C" cfpp_status cfpp_algorithmic_bytes(const cfpp_config *c, const int32_t *pos_host,
+                                              int32_t batch, int32_t n_layers, uint64_t *bytes)
+{
+    cfpp_status st = cfpp_validate_config(c);
+    if (st != CFPP_OK) return st;
+    if (!pos_host || !bytes || batch <= 0 || batch > c->max_batch || n_layers <= 0)
+        return fail(CFPP_EINVAL, "bad pos/batch/n_layers/bytes argument");
+    const uint64_t h = c->hidden, f = c->ffn;
+    const uint64_t params = 3 * h * h + h * h + 2 * h * f + (3 * h + h + f + h) + 4 * h;  // 12h^2+13h when f = 4h
+    uint64_t per_layer = params * 2;
+    for (int b = 0; b < batch; ++b) {
+        if (pos_host[b] < 0 || pos_host[b] >= c->max_seq) return fail(CFPP_EINVAL, "pos[%d] out of range", b);
+        per_layer += (uint64_t)pos_host[b] * 2 * h * 2;   // cached K and V rows read
+        per_layer += 2 * h * 2;                           // new K and V rows written
+    }
+    *bytes = per_layer * (uint64_t)n_layers + (uint64_t)batch * h * 2 * 2;  // x read, out written
+    return CFPP_OK;
+}
+
+// ---- data preparation ------------------------------------------------------------
+extern "C" cfpp_status cfpp_pack_layer(const cfpp_config *c, const cfpp_layer_src *src, void *packed_dst,
+                                       cfpp_stream stream)
+{
+    cfpp_status st = cfpp_validate_config(c);
+    if (st != CFPP_OK) return st;
+    if (!src) return fail(CFPP_EINVAL, "src is NULL");
+    const void *p[12] = {src->ln1_g, src->ln1_b, src->ln2_g, src->ln2_b, src->w_qkv, src->b_qkv,
+                         src->w_dense, src->b_dense, src->w_up, src->b_up, src->w_down, src->b_down};
+    for (int i = 0; i < 12; ++i)
+        if (!aligned16(p[i])) return fail(CFPP_EINVAL, "source tensor %d is NULL or not 16-byte aligned", i);
+    if (!aligned16(packed_dst)) return fail(CFPP_EINVAL, "packed_dst is NULL or not 16-byte aligned");
+    const Dims dm = dims_of(*c);
+    HIP_OK(launch_pack_layer(dm, packed_layout(dm.h, dm.f), p, static_cast<__half *>(packed_dst),
+                             static_cast<hipStream_t>(stream)));
+    return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_kv_import(const cfpp_config *c, const void *k_src, const void *v_src,
+                                      int32_t src_capacity, int32_t n_pos, int32_t b, void *kv_layer,
+                                      cfpp_stream stream)
+{
+    cfpp_status st = cfpp_validate_config(c);
+    if (st != CFPP_OK) return st;
+    if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(kv_layer))
+        return fail(CFPP_EINVAL, "NULL or misaligned pointer");
+    if (n_pos < 0 || n_pos > src_capacity || n_pos > c->max_seq || b < 0 || b >= c->max_batch)
+        return fail(CFPP_EINVAL, "n_pos/b out of range");
+    HIP_OK(launch_kv_import(dims_of(*c), static_cast<const __half *>(k_src), static_cast<const __half *>(v_src),
+                            src_capacity, n_pos, b, static_cast<__half *>(kv_layer),
+                            static_cast<hipStream_t>(stream)));
+    return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_kv_export(const cfpp_config *c, const void *kv_layer, int32_t b,
+                                      int32_t pos_begin, int32_t n_pos, int32_t dst_capacity, void *k_dst,
+                                      void *v_dst, cfpp_stream stream)
+{
+    cfpp_status st = cfpp_validate_config(c);
+    if (st != CFPP_OK) return st;
+    if (!aligned16(k_dst) || !aligned16(v_dst) || !aligned16(kv_layer))
+        return fail(CFPP_EINVAL, "NULL or misaligned pointer");
+    if (n_pos < 0 || pos_begin < 0 || (long long)pos_begin + n_pos > c->max_seq || n_pos > dst_capacity ||
+        b < 0 || b >= c->max_batch)
+        return fail(CFPP_EINVAL, "position range or b out of range");
+    HIP_OK(launch_kv_export(dims_of(*c), static_cast<const __half *>(kv_layer), b, pos_begin, n_pos,
+                            dst_capacity, static_cast<__half *>(k_dst), static_cast<__half *>(v_dst),
+                            static_cast<hipStream_t>(stream)));
+    return CFPP_OK;
+}
+
+// ---- context -----------------------------------------------------------------------
+struct cfpp_ctx {
+    cfpp_config cfg;
+    Dims dm;
+    PackedLayout lay;
+    WorkspaceLayout wl;
+    char *ws;
+    int n_cu;
+    int mode, grid, threads;
+    size_t lds_limit;
+    bool prepared;
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+    int last_batch;
+};
+
+extern "C" cfpp_status cfpp_create(const cfpp_config *c, void *workspace, size_t workspace_bytes,
+                                   cfpp_ctx **out_ctx)
+{
+    cfpp_status st = cfpp_validate_config(c);
+    if (st != CFPP_OK) return st;
+    if (!out_ctx) return fail(CFPP_EINVAL, "out_ctx is NULL");
+    *out_ctx = nullptr;
+    if (!aligned16(workspace)) return fail(CFPP_EINVAL, "workspace is NULL or not 16-byte aligned");
+    const Dims dm = dims_of(*c);
+    const WorkspaceLayout wl = workspace_layout(dm);
+    if (workspace_bytes < wl.total)
+        return fail(CFPP_ENOMEM, "workspace has %zu bytes, needs %zu", workspace_bytes, wl.total);
+
+    int dev = 0;
+    HIP_OK(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIP_OK(hipGetDeviceProperties(&prop, dev));
+
+    cfpp_ctx *ctx = new (std::nothrow) cfpp_ctx();
+    if (!ctx) return fail(CFPP_ENOMEM, "out of host memory");
+    ctx->cfg = *c;
+    ctx->dm = dm;
+    ctx->lay = packed_layout(dm.h, dm.f);
+    ctx->wl = wl;
+    ctx->ws = static_cast<char *>(workspace);
+    ctx->n_cu = prop.multiProcessorCount;
+    ctx->mode = 0;
+    ctx->grid = 0;
+    ctx->threads = 512;
+    ctx->lds_limit = prop.sharedMemPerBlock > 0 ? (size_t)prop.sharedMemPerBlock : 65536;
+    ctx->prepared = false;
+    ctx->graph = nullptr;
+    ctx->exec = nullptr;
+    ctx->last_batch = 1;
+
+    // barrier words, error flag and per-head arrival counters start at zero
+    hipError_t e = hipMemset(ctx->ws + wl.sync, 0, wl.layer_ptrs - wl.sync);
+    // rotary table in double on the host: angle = pos * base^(-2j/r)
+    std::vector<float> tab;
+    const int half = dm.r / 2;
+    if (e == hipSuccess && half > 0) {
+        tab.resize((size_t)dm.max_seq * half * 2);
+        for (int j = 0; j < half; ++j) {
+            const double theta = std::pow((double)c->rope_base, -2.0 * j / (double)dm.r);
+            for (int t = 0; t < dm.max_seq; ++t) {
+                const double a = (double)t * theta;
+                tab[((size_t)t * half + j) * 2 + 0] = (float)std::cos(a);
+                tab[((size_t)t * half + j) * 2 + 1] = (float)std::sin(a);
+            }
+        }
+        e = hipMemcpy(ctx->ws + wl.rope, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        delete ctx;
+        return fail(CFPP_EHIP, "workspace initialisation failed: %s", hipGetErrorString(e));
+    }
+    *out_ctx = ctx;
+    return CFPP_OK;
+}
+
+extern "C" void cfpp_destroy(cfpp_ctx *ctx)
+{
+    if (!ctx) return;
+    if (ctx->exec) (void)hipGraphExecDestroy(ctx->exec);
+    if (ctx->graph) (void)hipGraphDestroy(ctx->graph);
+    delete ctx;
+}
+
+extern "C" cfpp_status cfpp_set_option(cfpp_ctx *ctx, int32_t option, int64_t value)
+{
+    if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
+    switch (option) {
+    case CFPP_OPT_MODE:
+        if (value < 0 || value > 2) return fail(CFPP_EINVAL, "mode must be 0, 1 or 2");
+        ctx->mode = (int)value;
+        return CFPP_OK;
+    case CFPP_OPT_GRID:
+        if (value < 0 || value > kMaxGrid) return fail(CFPP_EINVAL, "grid must be in [0, %d]", kMaxGrid);
+        ctx->grid = (int)value;
+        return CFPP_OK;
+    case CFPP_OPT_THREADS:
+        if (value != 256 && value != 512) return fail(CFPP_EINVAL, "threads must be 256 or 512");
+        ctx->threads = (int)value;
+        return CFPP_OK;
+    }
+    return fail(CFPP_EINVAL, "unknown option %d", option);
+}
+
+extern "C" cfpp_status cfpp_get_option(const cfpp_ctx *ctx, int32_t option, int64_t *value)
+{
+    if (!ctx || !value) return fail(CFPP_EINVAL, "NULL argument");
+    switch (option) {
+    case CFPP_OPT_MODE: *value = ctx->mode; return CFPP_OK;
+    case CFPP_OPT_GRID: *value = ctx->grid ? ctx->grid : ctx->n_cu; return CFPP_OK;
+    case CFPP_OPT_THREADS: *value = ctx->threads; return CFPP_OK;
+    }
+    return fail(CFPP_EINVAL, "unknown option %d", option);
+}
+
+// ---- launch shape ---------------------------------------------------------------------
+static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// K-slices per row for a GEMV where a workgroup owns `nrows` rows of `nchunk`
+// chunks and has `nw` wavefronts: minimise rounds * (chunks per slice + fixed
+// cost of finishing a unit).
+static int pick_slices(int nrows, int nchunk, int nw)
+{
+    int best = 1;
+    double best_cost = 1e30;
+    for (int nsl = 1; nsl <= nchunk; ++nsl) {
+        const int cps = ceil_div(nchunk, nsl);
+        if (ceil_div(nchunk, cps) != nsl) continue;       // same slicing as a smaller nsl
+        const int rounds = ceil_div(nrows * nsl, nw);
+        const double cost = rounds * (cps + 0.5);
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = nsl; }
+    }
+    return best;
+}
+
+struct Shape {
+    int grid, threads;
+    int rows_qkv, rows_up, rows_h, nsl_down, nsl_dense;
+    unsigned lds_floats;
+};
+
+static cfpp_status launch_shape(const cfpp_ctx *ctx, Shape *sh)
+{
+    const Dims &dm = ctx->dm;
+    sh->grid = ctx->grid ? ctx->grid : ctx->n_cu;
+    sh->threads = ctx->threads;
+    const int nw = sh->threads / 64, G = sh->grid;
+    sh->rows_qkv = (ceil_div(3 * dm.h, G) + 1) & ~1;
+    sh->rows_up = ceil_div(dm.f, G);
+    sh->rows_h = ceil_div(dm.h, G);
+    const int nch_h = ceil_div(dm.h, kChunk), nch_f = ceil_div(dm.f, kChunk);
+    sh->nsl_down = pick_slices(sh->rows_h, nch_f, nw);
+    sh->nsl_dense = pick_slices(sh->rows_h, nch_h, nw);
+    const size_t a = 3 * (size_t)nch_h * kChunk + sh->rows_qkv + sh->rows_up + 16;
+    const size_t b = (size_t)nch_f * kChunk + (size_t)sh->rows_h * sh->nsl_down + (size_t)nw * (dm.d + 2) + 4;
+    const size_t c = (size_t)nch_h * kChunk + (size_t)sh->rows_h * sh->nsl_dense;
+    size_t m = a > b ? a : b;
+    m = m > c ? m : c;
+    m = (m + 63) / 64 * 64;
+    if (m * 4 > 160 * 1024) return fail(CFPP_EUNSUPPORTED, "needs %zu bytes of LDS (> 160 KiB)", m * 4);
+    sh->lds_floats = (unsigned)m;
+    return CFPP_OK;
+}
+
+// Launches that need more than the default 64 KiB of dynamic LDS must raise the
+// kernels' limit first (once, outside any stream capture).
+static cfpp_status prepare(cfpp_ctx *ctx)
+{
+    if (ctx->prepared) return CFPP_OK;
+    HIP_OK(prepare_kernels(160 * 1024));
+    ctx->prepared = true;
+    return CFPP_OK;
+}
+
+static StepParams make_params(const cfpp_ctx *ctx, const Shape &sh, int b, const void *x,
+                              const int32_t *pos_dev, void *out, int n_layers)
+{
+    const Dims &dm = ctx->dm;
+    const WorkspaceLayout &wl = ctx->wl;
+    StepParams P;
+    P.dm = dm;
+    P.lay = ctx->lay;
+    P.sync = reinterpret_cast<unsigned *>(ctx->ws + wl.sync);
+    P.seg_cnt = reinterpret_cast<unsigned *>(ctx->ws + wl.seg_cnt) + (size_t)b * dm.H;
+    P.rope = reinterpret_cast<const float2 *>(ctx->ws + wl.rope);
+    P.xres = reinterpret_cast<float *>(ctx->ws + wl.xres) + (size_t)b * 2 * dm.h;
+    P.q = reinterpret_cast<float *>(ctx->ws + wl.q) + (size_t)b * dm.h;
+    P.m = reinterpret_cast<float *>(ctx->ws + wl.m) + (size_t)b * dm.f;
+    P.g = reinterpret_cast<float *>(ctx->ws + wl.g) + (size_t)b * dm.h;
+    P.o = reinterpret_cast<float *>(ctx->ws + wl.o) + (size_t)b * dm.h;
+    P.part = reinterpret_cast<float *>(ctx->ws + wl.part) + (size_t)b * dm.H * wl.part_slots * (dm.d + 2);
+    P.part_slots = wl.part_slots;
+    P.pos = pos_dev + b;
+    P.b = b;
+    P.x_in = static_cast<const __half *>(x) + (size_t)b * dm.h;
+    P.out = static_cast<__half *>(out) + (size_t)b * dm.h;
+    P.n_layers = n_layers;
+    P.rows_qkv = sh.rows_qkv; P.rows_up = sh.rows_up; P.rows_h = sh.rows_h;
+    P.nsl_down = sh.nsl_down; P.nsl_dense = sh.nsl_dense;
+    P.lds_floats = sh.lds_floats;
+    return P;
+}
+
+static cfpp_status check_persistent(const cfpp_ctx *ctx, const Shape &sh)
+{
+    int per_cu = 0;
+    HIP_OK(persistent_occupancy(ctx->dm.d, sh.threads, (size_t)sh.lds_floats * 4, &per_cu));
+    if ((long long)per_cu * ctx->n_cu < sh.grid)
+        return fail(CFPP_EUNSUPPORTED,
+                    "persistent mode needs all %d workgroups resident, device fits %d x %d", sh.grid,
+                    per_cu, ctx->n_cu);
+    return CFPP_OK;
+}
+
+static cfpp_status check_io(const cfpp_ctx *ctx, const void *x, const int32_t *pos_dev, int32_t batch,
+                            const void *out)
+{
+    if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
+    if (!aligned16(x) || !aligned16(out)) return fail(CFPP_EINVAL, "x or out is NULL or not 16-byte aligned");
+    if (!pos_dev || (reinterpret_cast<uintptr_t>(pos_dev) & 3u)) return fail(CFPP_EINVAL, "pos_dev is NULL or misaligned");
+    if (batch <= 0 || batch > ctx->cfg.max_batch)
+        return fail(CFPP_EINVAL, "batch %d outside [1, max_batch = %d]", batch, ctx->cfg.max_batch);
+    const char *xb = static_cast<const char *>(x), *ob = static_cast<const char *>(out);
+    const size_t n = (size_t)batch * ctx->dm.h * 2;
+    if (xb < ob + n && ob < xb + n) return fail(CFPP_EINVAL, "out overlaps x");
+    return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer, void *kv_layer,
+                                         const void *x, const int32_t *pos_dev, int32_t batch, void *out,
+                                         cfpp_stream stream)
+{
+    cfpp_status st = check_io(ctx, x, pos_dev, batch, out);
+    if (st != CFPP_OK) return st;
+    if (!aligned16(packed_layer) || !aligned16(kv_layer))
+        return fail(CFPP_EINVAL, "packed_layer or kv_layer is NULL or not 16-byte aligned");
+    Shape sh;
+    if ((st = launch_shape(ctx, &sh)) != CFPP_OK) return st;
+    if ((st = prepare(ctx)) != CFPP_OK) return st;
+    if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int b = 0; b < batch; ++b) {
+        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, 1);
+        if (ctx->mode == 0)
+            HIP_OK(launch_phases(P, static_cast<const __half *>(packed_layer), static_cast<__half *>(kv_layer),
+                                 0, sh.grid, sh.threads, s));
+        else
+            HIP_OK(launch_block_persistent(P, static_cast<const __half *>(packed_layer),
+                                           static_cast<__half *>(kv_layer), 0, sh.grid, sh.threads, s));
+    }
+    ctx->last_batch = batch;
+    return CFPP_OK;
+}
+
+// store_table: also enqueue the copy of the pointer table into the workspace
+// (the whole-stack kernel reads it from device memory).  Capture stores it
+// ahead of the captured region, so a replay is the decode kernels alone.
+static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers, void *const *kv_layers,
+                                 const void *x, const int32_t *pos_dev, int32_t batch, void *out,
+                                 hipStream_t s, bool store_table, bool launch)
+{
+    cfpp_status st = check_io(ctx, x, pos_dev, batch, out);
+    if (st != CFPP_OK) return st;
+    if (!packed_layers || !kv_layers) return fail(CFPP_EINVAL, "layer pointer arrays are NULL");
+    const int L = ctx->cfg.n_layers;
+    for (int l = 0; l < L; ++l)
+        if (!aligned16(packed_layers[l]) || !aligned16(kv_layers[l]))
+            return fail(CFPP_EINVAL, "layer %d: NULL or misaligned pointer", l);
+    Shape sh;
+    if ((st = launch_shape(ctx, &sh)) != CFPP_OK) return st;
+    if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
+    LayerPtrs ptrs;
+    std::memset(&ptrs, 0, sizeof ptrs);
+    for (int l = 0; l < L; ++l) {
+        ptrs.w[l] = static_cast<const __half *>(packed_layers[l]);
+        ptrs.kv[l] = static_cast<__half *>(kv_layers[l]);
+    }
+    LayerPtrs *dev_ptrs = reinterpret_cast<LayerPtrs *>(ctx->ws + ctx->wl.layer_ptrs);
+    if (store_table && ctx->mode == 2) HIP_OK(launch_store_layer_ptrs(ptrs, dev_ptrs, L, s));
+    if (!launch) return CFPP_OK;
+    for (int b = 0; b < batch; ++b) {
+        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, L);
+        if (ctx->mode == 2) {
+            HIP_OK(launch_stack_persistent(P, dev_ptrs, sh.grid, sh.threads, s));
+        } else {
+            for (int l = 0; l < L; ++l) {
+                if (ctx->mode == 0)
+                    HIP_OK(launch_phases(P, ptrs.w[l], ptrs.kv[l], l, sh.grid, sh.threads, s));
+                else
+                    HIP_OK(launch_block_persistent(P, ptrs.w[l], ptrs.kv[l], l, sh.grid, sh.threads, s));
+            }
+        }
+    }
+    ctx->last_batch = batch;
+    return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_stack_decode(cfpp_ctx *ctx, const void *const *packed_layers,
+                                         void *const *kv_layers, const void *x, const int32_t *pos_dev,
+                                         int32_t batch, void *out, cfpp_stream stream)
+{
+    if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
+    cfpp_status st = prepare(ctx);
+    if (st != CFPP_OK) return st;
+    return enqueue_stack(ctx, packed_layers, kv_layers, x, pos_dev, batch, out, static_cast<hipStream_t>(stream),
+                         true, true);
+}
+
+extern "C" cfpp_status cfpp_stack_capture(cfpp_ctx *ctx, const void *const *packed_layers,
+                                          void *const *kv_layers, const void *x, const int32_t *pos_dev,
+                                          int32_t batch, void *out, cfpp_stream stream)
+{
+    if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!s) return fail(CFPP_EINVAL, "capture needs a non-default stream");
+    cfpp_status st = prepare(ctx);
+    if (st != CFPP_OK) return st;
+    if (ctx->exec) { (void)hipGraphExecDestroy(ctx->exec); ctx->exec = nullptr; }
+    if (ctx->graph) { (void)hipGraphDestroy(ctx->graph); ctx->graph = nullptr; }
+    // validate and store the pointer table first (executes now, not captured)
+    st = enqueue_stack(ctx, packed_layers, kv_layers, x, pos_dev, batch, out, s, true, false);
+    if (st != CFPP_OK) return st;
+    HIP_OK(hipStreamSynchronize(s));
+    HIP_OK(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+    st = enqueue_stack(ctx, packed_layers, kv_layers, x, pos_dev, batch, out, s, false, true);
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamEndCapture(s, &graph);
+    if (st != CFPP_OK) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return st;
+    }
+    if (e != hipSuccess) return fail(CFPP_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+    ctx->graph = graph;
+    e = hipGraphInstantiate(&ctx->exec, graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        ctx->exec = nullptr;
+        return fail(CFPP_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+    }
+    return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_stack_replay(cfpp_ctx *ctx, cfpp_stream stream)
+{
+    if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
+    if (!ctx->exec) return fail(CFPP_ESTATE, "cfpp_stack_replay before cfpp_stack_capture");
+    HIP_OK(hipGraphLaunch(ctx->exec, static_cast<hipStream_t>(stream)));
+    return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream)
+{
+    if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
+    HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    unsigned words[64];
+    HIP_OK(hipMemcpy(words, ctx->ws + ctx->wl.sync, sizeof words, hipMemcpyDeviceToHost));
+    const unsigned err = words[kSyncErr];
+    if (err == kErrNone) return CFPP_OK;
+    // clear the flag and re-arm the barrier words and arrival counters
+    HIP_OK(hipMemset(ctx->ws + ctx->wl.sync, 0, ctx->wl.layer_ptrs - ctx->wl.sync));
+    HIP_OK(hipDeviceSynchronize());
+    if (err == kErrBadPos) return fail(CFPP_EDEVICE, "a position in pos_dev was outside [0, max_seq)");
+    if (err == kErrBarrierTimeout) return fail(CFPP_EDEVICE, "grid barrier timed out (workgroups not co-resident?)");
+    return fail(CFPP_EDEVICE, "device error code %u", err);
+}
+
+extern "C" cfpp_status cfpp_debug_read(cfpp_ctx *ctx, int32_t which, float *dst_host, size_t count,
+                                       cfpp_stream stream)
+{
+    if (!ctx || !dst_host) return fail(CFPP_EINVAL, "NULL argument");
+    const Dims &dm = ctx->dm;
+    size_t off, n;
+    switch (which) {
+    case 0: off = ctx->wl.q; n = (size_t)dm.max_batch * dm.h; break;
+    case 1: off = ctx->wl.m; n = (size_t)dm.max_batch * dm.f; break;
+    case 2: off = ctx->wl.g; n = (size_t)dm.max_batch * dm.h; break;
+    case 3: off = ctx->wl.o; n = (size_t)dm.max_batch * dm.h; break;
+    default: return fail(CFPP_EINVAL, "unknown tap %d", which);
+    }
+    if (count > n) return fail(CFPP_EINVAL, "count %zu exceeds the buffer (%zu floats)", count, n);
+    HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    HIP_OK(hipMemcpy(dst_host, ctx->ws + off, count * sizeof(float), hipMemcpyDeviceToHost));
+    return CFPP_OK;
+}

@@ -1,0 +1,57 @@
+// Arguments the host passes (by value) to the decode kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include "layout.h"
+
+namespace cfpp {
+
+struct StepParams {
+    Dims dm;
+    PackedLayout lay;
+    // workspace views (already offset to this sequence where per-sequence)
+    unsigned *sync;
+    unsigned *seg_cnt;   // [H] for this sequence
+    const float2 *rope;
+    float *xres;         // [2][h] for this sequence
+    float *q, *m, *g, *o;
+    float *part;         // [H][part_slots][d+2] for this sequence
+    int part_slots;
+    const int *pos;      // device, this sequence's position
+    int b;               // sequence index inside the KV cache
+    const __half *x_in;  // fp16 [h] input of layer 0
+    __half *out;         // fp16 [h] output of the last layer
+    int n_layers;
+    // work split (chosen on the host from the grid and the workgroup size)
+    int rows_qkv, rows_up, rows_h;   // matrix rows per workgroup (rows_qkv even)
+    int nsl_down, nsl_dense;         // K-slices per row for the two GEMVs with few rows
+    unsigned lds_floats;             // dynamic LDS the launch provides, in floats
+};
+
+struct LayerPtrs {
+    const __half *w[kMaxLayers];
+    __half *kv[kMaxLayers];
+};
+
+// implemented in decode_kernels.hip
+hipError_t launch_phases(const StepParams &P, const __half *w, __half *kv, int layer,
+                         int grid, int threads, hipStream_t s);
+hipError_t launch_block_persistent(const StepParams &P, const __half *w, __half *kv, int layer,
+                                   int grid, int threads, hipStream_t s);
+// ptrs: DEVICE copy of the table (launch_store_layer_ptrs writes it)
+hipError_t launch_stack_persistent(const StepParams &P, const LayerPtrs *ptrs,
+                                   int grid, int threads, hipStream_t s);
+hipError_t launch_store_layer_ptrs(const LayerPtrs &ptrs, LayerPtrs *dst, int n, hipStream_t s);
+// most co-resident workgroups per compute unit for the persistent kernels
+hipError_t persistent_occupancy(int head_dim, int threads, size_t lds_bytes, int *blocks_per_cu);
+hipError_t prepare_kernels(size_t lds_bytes);
+
+// implemented in prep_kernels.hip
+hipError_t launch_pack_layer(const Dims &dm, const PackedLayout &lay, const void *const src[12],
+                             __half *dst, hipStream_t s);
+hipError_t launch_kv_import(const Dims &dm, const __half *k_src, const __half *v_src, int src_cap,
+                            int n_pos, int b, __half *kv, hipStream_t s);
+hipError_t launch_kv_export(const Dims &dm, const __half *kv, int b, int pos_begin, int n_pos,
+                            int dst_cap, __half *k_dst, __half *v_dst, hipStream_t s);
+
+}  // namespace cfpp

@@ -1,0 +1,165 @@
+// Wavefront-level building blocks for gfx950 (wave64): DPP reductions, fp16
+// unpacking, 128-bit streaming loads, and the grid barrier used by the
+// persistent kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include "layout.h"
+
+namespace cfpp {
+
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// ---- data-parallel-primitive lane exchanges (row = 16 lanes) ---------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <- lane 7-i within each 8
+constexpr int kDppMirror = 0x140;     // lane i <- lane 15-i within each 16
+constexpr int kDppRor4 = 0x124;       // rotate right by 4 within each 16
+constexpr int kDppRor8 = 0x128;       // rotate right by 8 within each 16
+
+__device__ __forceinline__ float readlane_f(float v, int lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// Sum over the 64 lanes, same value returned in every lane.  Fixed tree.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_mov<kDppXor1>(v);
+    v += dpp_mov<kDppXor2>(v);
+    v += dpp_mov<kDppHalfMirror>(v);
+    v += dpp_mov<kDppMirror>(v);      // every lane: sum of its row of 16
+    return (readlane_f(v, 0) + readlane_f(v, 16)) + (readlane_f(v, 32) + readlane_f(v, 48));
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = fmaxf(v, dpp_mov<kDppXor1>(v));
+    v = fmaxf(v, dpp_mov<kDppXor2>(v));
+    v = fmaxf(v, dpp_mov<kDppHalfMirror>(v));
+    v = fmaxf(v, dpp_mov<kDppMirror>(v));
+    return fmaxf(fmaxf(readlane_f(v, 0), readlane_f(v, 16)), fmaxf(readlane_f(v, 32), readlane_f(v, 48)));
+}
+
+// Sum over the 32 lanes that share this lane's parity (lane & 1); every lane
+// gets its parity's total.  Fixed tree.
+__device__ __forceinline__ float parity_sum(float v)
+{
+    v += dpp_mov<kDppXor2>(v);
+    v += dpp_mov<kDppRor4>(v);
+    v += dpp_mov<kDppRor8>(v);        // every lane: sum over its parity within its row
+    const int odd = threadIdx.x & 1;
+    float r0 = readlane_f(v, 0), r1 = readlane_f(v, 16), r2 = readlane_f(v, 32), r3 = readlane_f(v, 48);
+    float s0 = readlane_f(v, 1), s1 = readlane_f(v, 17), s2 = readlane_f(v, 33), s3 = readlane_f(v, 49);
+    float even_t = (r0 + r1) + (r2 + r3);
+    float odd_t = (s0 + s1) + (s2 + s3);
+    return odd ? odd_t : even_t;
+}
+
+// ---- fp16 ------------------------------------------------------------------
+__device__ __forceinline__ float2 unpack_h2(unsigned w)
+{
+    __half2 h = *reinterpret_cast<const __half2 *>(&w);
+    return __half22float2(h);
+}
+
+// 8 fp16 weights (one 16-byte load) times 8 fp32 activations, fp32 accumulate
+__device__ __forceinline__ float dot8(u32x4 w, float4 ya, float4 yb, float acc)
+{
+    float2 a = unpack_h2(w.x), b = unpack_h2(w.y), c = unpack_h2(w.z), d = unpack_h2(w.w);
+    acc = fmaf(a.x, ya.x, acc); acc = fmaf(a.y, ya.y, acc);
+    acc = fmaf(b.x, ya.z, acc); acc = fmaf(b.y, ya.w, acc);
+    acc = fmaf(c.x, yb.x, acc); acc = fmaf(c.y, yb.y, acc);
+    acc = fmaf(d.x, yb.z, acc); acc = fmaf(d.y, yb.w, acc);
+    return acc;
+}
+
+__device__ __forceinline__ u32x4 load16(const __half *p)
+{
+    return *reinterpret_cast<const u32x4 *>(p);
+}
+// streamed once, never reused: keep it from displacing the activations in cache
+__device__ __forceinline__ u32x4 load16_stream(const __half *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
+
+// Position of activation element k inside an LDS vector laid out for the GEMV
+// inner loop: per 512-element chunk, lane l reads elements 8l..8l+7 as two
+// float4 at [l*4] and [256 + l*4], so that consecutive lanes touch consecutive
+// 16-byte words (no bank conflicts).
+__device__ __forceinline__ int lds_perm(int k)
+{
+    int c = k >> 9, w = k & 511, l = w >> 3, e = w & 7;
+    return (c << 9) + ((e >> 2) << 8) + (l << 2) + (e & 3);
+}
+
+// exact (erf) GELU
+__device__ __forceinline__ float gelu_erf(float z)
+{
+    return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
+}
+
+// ---- grid barrier ------------------------------------------------------------
+// All workgroups of a launch must be resident (the host checks the grid against
+// the occupancy limit).  sync[kSyncCount] returns to 0 after every barrier and
+// sync[kSyncGen] only grows, so nothing needs resetting between launches or
+// graph replays.  The wait is bounded: after ~2 s of wall clock the waiter sets
+// the error flag and every later barrier falls through, so the grid always
+// drains.
+struct GridBarrier {
+    unsigned *sync;
+    unsigned gen;      // generation this workgroup waits to leave (thread 0 only)
+    unsigned nwg;
+
+    __device__ __forceinline__ void init(unsigned *s, unsigned n)
+    {
+        sync = s;
+        nwg = n;
+        gen = 0;
+        if (threadIdx.x == 0)
+            gen = __hip_atomic_load(&sync[kSyncGen], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    __device__ __forceinline__ void wait()
+    {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            unsigned old = __hip_atomic_fetch_add(&sync[kSyncCount], 1u, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+            if (old == nwg - 1) {
+                __hip_atomic_store(&sync[kSyncCount], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(&sync[kSyncGen], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                const unsigned long long t0 = wall_clock64();
+                unsigned spins = 0;
+                while (__hip_atomic_load(&sync[kSyncGen], __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT) == gen) {
+                    __builtin_amdgcn_s_sleep(1);
+                    if ((++spins & 1023u) == 0) {
+                        if (__hip_atomic_load(&sync[kSyncErr], __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT) == kErrBarrierTimeout)
+                            break;
+                        if (wall_clock64() - t0 > 200000000ull) {   // 100 MHz counter: 2 s
+                            __hip_atomic_store(&sync[kSyncErr], (unsigned)kErrBarrierTimeout,
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            gen += 1;
+        }
+        __syncthreads();
+    }
+};
+
+}  // namespace cfpp

@@ -1,0 +1,99 @@
+// One-time data preparation kernels: packing a block's canonical tensors into
+// the streaming layout, and moving KV rows between the canonical layout
+// [n_heads, capacity, head_dim] and the slabbed cache layout.  Pure data
+// movement, off the hot path.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include "decode_params.h"
+
+namespace cfpp {
+
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// dst[p][:] = src[map(p)][:], 16 bytes per thread; cols % 8 == 0
+__global__ void k_copy_rows(const __half *__restrict__ src, __half *__restrict__ dst, long long rows,
+                            int cols, int qkv_d, int qkv_r)
+{
+    const long long per_row = cols / 8;
+    const long long n = rows * per_row;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long p = i / per_row, c8 = i - p * per_row;
+        const long long sr = qkv_d ? qkv_packed_to_canonical_row((int)p, qkv_d, qkv_r) : p;
+        *reinterpret_cast<u32x4 *>(dst + p * cols + c8 * 8) =
+            *reinterpret_cast<const u32x4 *>(src + sr * cols + c8 * 8);
+    }
+}
+
+__global__ void k_copy_vec(const __half *__restrict__ src, __half *__restrict__ dst, int n, int qkv_d,
+                           int qkv_r)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x)
+        dst[i] = src[qkv_d ? qkv_packed_to_canonical_row(i, qkv_d, qkv_r) : i];
+}
+
+hipError_t launch_pack_layer(const Dims &dm, const PackedLayout &lay, const void *const src[12],
+                             __half *dst, hipStream_t s)
+{
+    const int h = dm.h, f = dm.f;
+    auto vec = [&](int idx, size_t off, int n, bool qkv) {
+        hipLaunchKernelGGL(k_copy_vec, dim3((n + 255) / 256), dim3(256), 0, s,
+                           (const __half *)src[idx], dst + off, n, qkv ? dm.d : 0, dm.r);
+    };
+    auto mat = [&](int idx, size_t off, long long rows, int cols, bool qkv) {
+        hipLaunchKernelGGL(k_copy_rows, dim3(2048), dim3(256), 0, s, (const __half *)src[idx],
+                           dst + off, rows, cols, qkv ? dm.d : 0, dm.r);
+    };
+    // order of src: ln1_g ln1_b ln2_g ln2_b w_qkv b_qkv w_dense b_dense w_up b_up w_down b_down
+    vec(0, lay.ln1_g, h, false); vec(1, lay.ln1_b, h, false);
+    vec(2, lay.ln2_g, h, false); vec(3, lay.ln2_b, h, false);
+    mat(4, lay.w_qkv, 3LL * h, h, true); vec(5, lay.b_qkv, 3 * h, true);
+    mat(6, lay.w_dense, h, h, false); vec(7, lay.b_dense, h, false);
+    mat(8, lay.w_up, f, h, false); vec(9, lay.b_up, f, false);
+    mat(10, lay.w_down, h, f, false); vec(11, lay.b_down, h, false);
+    return hipGetLastError();
+}
+
+// one thread per (which, head, position, 8-dim group)
+__global__ void k_kv_move(Dims dm, const __half *k_can, const __half *v_can, int cap, int pos_begin,
+                          int n_pos, int b, __half *kv, int to_cache)
+{
+    const int d8 = dm.d / 8;
+    const long long n = 2LL * dm.H * n_pos * d8;
+    for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n;
+         i += (long long)gridDim.x * blockDim.x) {
+        long long r = i;
+        const int j = (int)(r % d8); r /= d8;
+        const int t = (int)(r % n_pos); r /= n_pos;
+        const int hd = (int)(r % dm.H);
+        const int which = (int)(r / dm.H);
+        const __half *can = which ? v_can : k_can;
+        // canonical row index: import reads row pos, export writes row (pos - pos_begin)
+        const int pos = pos_begin + t;
+        const int crow = to_cache ? pos : t;
+        __half *cp = const_cast<__half *>(can) + ((size_t)hd * cap + crow) * dm.d + j * 8;
+        __half *kp = kv + kv_offset(dm, which, b, hd, j * 8, pos);
+        if (to_cache) *reinterpret_cast<u32x4 *>(kp) = *reinterpret_cast<const u32x4 *>(cp);
+        else *reinterpret_cast<u32x4 *>(cp) = *reinterpret_cast<const u32x4 *>(kp);
+    }
+}
+
+hipError_t launch_kv_import(const Dims &dm, const __half *k_src, const __half *v_src, int src_cap,
+                            int n_pos, int b, __half *kv, hipStream_t s)
+{
+    if (n_pos == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_kv_move, dim3(1024), dim3(256), 0, s, dm, k_src, v_src, src_cap, 0, n_pos, b,
+                       kv, 1);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_export(const Dims &dm, const __half *kv, int b, int pos_begin, int n_pos,
+                            int dst_cap, __half *k_dst, __half *v_dst, hipStream_t s)
+{
+    if (n_pos == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_kv_move, dim3(1024), dim3(256), 0, s, dm, (const __half *)k_dst,
+                       (const __half *)v_dst, dst_cap, pos_begin, n_pos, b, const_cast<__half *>(kv), 0);
+    return hipGetLastError();
+}
+
+}  // namespace cfpp

@@ -1,0 +1,97 @@
+"""GPU parity of one decoder block against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import synth
+from tests.parity import assert_block_close, assert_fp16_rows_match, errors
+
+pytestmark = pytest.mark.gpu
+
+
+def run_block(orc, shape, seed, S, cap, mode=0, grid=None, threads=None, taps=False, repeats=1):
+    from paper_2604_23553_amd.harness import DeviceStack
+    w = synth.layer_weights(shape, seed, 0)
+    K, V = synth.kv_cache(shape, seed, 0, S, cap)
+    x = synth.x_input(shape, seed)
+    print(f"[case] shape={shape.name or shape.hidden} seed={seed} S={S} cap={cap} mode={mode} grid={grid} threads={threads}", flush=True)
+    ds = DeviceStack(shape, cap, 1, 1)
+    try:
+        ds.set_options(mode=mode, grid=grid, threads=threads)
+        ds.load_layer(0, w)
+        ds.load_kv(0, K, V, S)
+        ds.set_inputs(x, S)
+        outs = []
+        for _ in range(repeats):
+            ds.block_decode(0)
+            ds.check()
+            outs.append(ds.result().copy())
+        k_all, v_all = ds.export_kv(0, 0, 0, cap)
+        tap = None
+        if taps:
+            tap = {n: ds.tap(i, shape.ffn if n == "m" else shape.hidden)
+                   for i, n in enumerate(("q", "m", "g", "attn"))}
+    finally:
+        ds.close()
+    Ko, Vo = K[0].copy(), V[0].copy()
+    ref, otaps = orc.block_decode(shape, w, Ko, Vo, S, orc.half_to_real(x[0]), taps=True)
+    return outs, (k_all, v_all), (Ko, Vo), orc.real_to_half(ref), tap, otaps
+
+
+def check_block(orc, shape, seed, S, cap, **kw):
+    outs, (kg, vg), (Ko, Vo), ref16, tap, otaps = run_block(orc, shape, seed, S, cap, **kw)
+    ma, rl = assert_block_close(outs[0][0], ref16, "block output")
+    # appended rows, and every other slot untouched (bit-exact, NaN poison included)
+    assert_fp16_rows_match(kg[:, S], Ko[:, S], "appended K")
+    assert_fp16_rows_match(vg[:, S], Vo[:, S], "appended V")
+    assert np.array_equal(np.ascontiguousarray(kg[:, :S]).view(np.uint16), np.ascontiguousarray(Ko[:, :S]).view(np.uint16))
+    assert np.array_equal(np.ascontiguousarray(vg[:, :S]).view(np.uint16), np.ascontiguousarray(Vo[:, :S]).view(np.uint16))
+    assert np.isnan(kg[:, S + 1:].astype(np.float32)).all() and np.isnan(vg[:, S + 1:].astype(np.float32)).all()
+    for o in outs[1:]:
+        assert np.array_equal(o.view(np.uint16), outs[0].view(np.uint16)), "not bit-identical run to run"
+    if tap is not None:
+        for n in ("q", "m", "g", "attn"):
+            e = errors(tap[n], otaps[n])
+            assert e[0] < 2e-3 and e[1] < 2e-4, f"intermediate {n}: {e}"
+    return ma, rl
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_small_block_config(orc, mode):
+    """hidden 512, 8 heads x 64, rotary 16, FFN 2048, 128 cached positions."""
+    check_block(orc, synth.SMALL_BLOCK, synth.MASTER_SEED, 128, 129, mode=mode, taps=True, repeats=3)
+
+
+@pytest.mark.parametrize("S", [0, 1, 31, 32, 33, 63, 64, 65, 257, 1000])
+def test_context_lengths_and_ragged_rows(orc, S):
+    check_block(orc, synth.SMALL_BLOCK, 7 + S, S, S + 3, mode=0, taps=True)
+
+
+@pytest.mark.parametrize("grid,threads", [(1, 256), (7, 512), (64, 256), (256, 256), (300, 512), (1024, 512)])
+def test_launch_shapes(orc, grid, threads):
+    check_block(orc, synth.SMALL_BLOCK, 11, 200, 201, mode=0, grid=grid, threads=threads, taps=True)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_pythia_2_8b_block(orc, mode):
+    """hidden 2560, 32 heads x 80, rotary 20, FFN 10240, 1024 cached positions."""
+    check_block(orc, synth.PYTHIA_2_8B, synth.MASTER_SEED, 1024, 1025, mode=mode, taps=True, repeats=3)
+
+
+def test_pythia_6_9b_block(orc):
+    check_block(orc, synth.PYTHIA_6_9B, synth.MASTER_SEED, 333, 334, mode=0, taps=True, repeats=2)
+
+
+@pytest.mark.parametrize("shape", [
+    synth.ModelShape(576, 9, 64, 16, 1160, name="ragged-h576"),     # K not a multiple of 512
+    synth.ModelShape(640, 8, 80, 20, 2048, name="d80-h640"),
+    synth.ModelShape(1024, 8, 128, 32, 520, name="d128-f520"),
+    synth.ModelShape(512, 8, 64, 0, 2048, name="no-rotary"),
+    synth.ModelShape(512, 8, 64, 64, 2048, name="full-rotary"),
+])
+def test_odd_shapes(orc, shape):
+    check_block(orc, shape, 5, 70, 80, mode=0, taps=True)
+    check_block(orc, shape, 5, 70, 71, mode=1, grid=40, threads=256)
+
+
+def test_last_slot_of_the_cache(orc):
+    check_block(orc, synth.SMALL_BLOCK, 3, 95, 96, mode=0)
