@@ -151,6 +151,9 @@ void cfpp_destroy(cfpp_ctx *ctx);
                                 2: one persistent kernel for the whole stack  */
 #define CFPP_OPT_GRID     2  /* workgroups; 0 = one per compute unit          */
 #define CFPP_OPT_THREADS  3  /* threads per workgroup: 256 or 512             */
+#define CFPP_OPT_PROFILE_SKIP 100 /* profiling aid only: bit mask of sub-steps to
+                                skip so the others can be timed alone; any
+                                non-zero value makes the results wrong         */
 cfpp_status cfpp_set_option(cfpp_ctx *ctx, int32_t option, int64_t value);
 cfpp_status cfpp_get_option(const cfpp_ctx *ctx, int32_t option, int64_t *value);
 
@@ -201,6 +204,19 @@ cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream);
  * count = number of floats to copy (from the start). */
 cfpp_status cfpp_debug_read(cfpp_ctx *ctx, int32_t which, float *dst_host, size_t count,
                             cfpp_stream stream);
+
+/* ---- bandwidth calibration (measurement aids, not part of the method) -------- */
+
+/* Plain streaming kernels whose HBM traffic is known exactly, used to find the
+ * streaming bandwidth this GPU sustains and to scale hardware traffic counters.
+ * cfpp_stream_read loads every 16-byte word of src (DEVICE, `bytes` a multiple of
+ * 16) once and XORs a checksum into sink (DEVICE, uint32[grid], caller-zeroed);
+ * cfpp_stream_copy copies src to dst.  grid <= 65536, threads 256 or 512,
+ * unroll = 16-byte loads in flight per thread (2, 4 or 8). */
+cfpp_status cfpp_stream_read(const void *src, size_t bytes, void *sink, int32_t grid,
+                             int32_t threads, int32_t unroll, cfpp_stream stream);
+cfpp_status cfpp_stream_copy(const void *src, void *dst, size_t bytes, int32_t grid,
+                             int32_t threads, cfpp_stream stream);
 
 #ifdef __cplusplus
 }

@@ -189,3 +189,13 @@ def cfpp_debug_read(ctx: int, which: int, count: int, stream=None):
                                  out.ctypes.data_as(C.POINTER(C.c_float)), C.c_size_t(count),
                                  _ptr(stream)), "cfpp_debug_read")
     return out
+
+
+def cfpp_stream_read(src, nbytes: int, sink, grid: int, threads: int, unroll: int, stream=None):
+    _check(lib().cfpp_stream_read(_ptr(src), C.c_size_t(nbytes), _ptr(sink), C.c_int32(grid),
+                                  C.c_int32(threads), C.c_int32(unroll), _ptr(stream)), "cfpp_stream_read")
+
+
+def cfpp_stream_copy(src, dst, nbytes: int, grid: int, threads: int, stream=None):
+    _check(lib().cfpp_stream_copy(_ptr(src), _ptr(dst), C.c_size_t(nbytes), C.c_int32(grid),
+                                  C.c_int32(threads), _ptr(stream)), "cfpp_stream_copy")

@@ -183,7 +183,7 @@ struct cfpp_ctx {
     WorkspaceLayout wl;
     char *ws;
     int n_cu;
-    int mode, grid, threads;
+    int mode, grid, threads, debug;
     size_t lds_limit;
     bool prepared;
     hipGraph_t graph;
@@ -220,6 +220,7 @@ extern "C" cfpp_status cfpp_create(const cfpp_config *c, void *workspace, size_t
     ctx->mode = 0;
     ctx->grid = 0;
     ctx->threads = 512;
+    ctx->debug = 0;
     ctx->lds_limit = prop.sharedMemPerBlock > 0 ? (size_t)prop.sharedMemPerBlock : 65536;
     ctx->prepared = false;
     ctx->graph = nullptr;
@@ -276,6 +277,9 @@ extern "C" cfpp_status cfpp_set_option(cfpp_ctx *ctx, int32_t option, int64_t va
         if (value != 256 && value != 512) return fail(CFPP_EINVAL, "threads must be 256 or 512");
         ctx->threads = (int)value;
         return CFPP_OK;
+    case CFPP_OPT_PROFILE_SKIP:
+        ctx->debug = (int)value;
+        return CFPP_OK;
     }
     return fail(CFPP_EINVAL, "unknown option %d", option);
 }
@@ -329,13 +333,16 @@ static cfpp_status launch_shape(const cfpp_ctx *ctx, Shape *sh)
     const int nch_h = ceil_div(dm.h, kChunk), nch_f = ceil_div(dm.f, kChunk);
     sh->nsl_down = pick_slices(sh->rows_h, nch_f, nw);
     sh->nsl_dense = pick_slices(sh->rows_h, nch_h, nw);
-    const size_t a = 3 * (size_t)nch_h * kChunk + sh->rows_qkv + sh->rows_up + 16;
+    const size_t a = 2 * (size_t)nch_h * kChunk + sh->rows_qkv + sh->rows_up + 16;
     const size_t b = (size_t)nch_f * kChunk + (size_t)sh->rows_h * sh->nsl_down + (size_t)nw * (dm.d + 2) + 4;
     const size_t c = (size_t)nch_h * kChunk + (size_t)sh->rows_h * sh->nsl_dense;
     size_t m = a > b ? a : b;
     m = m > c ? m : c;
     m = (m + 63) / 64 * 64;
     if (m * 4 > 160 * 1024) return fail(CFPP_EUNSUPPORTED, "needs %zu bytes of LDS (> 160 KiB)", m * 4);
+    if ((size_t)dm.h > (size_t)32 * sh->threads)    // the LayerNorm keeps 32 values per thread
+        return fail(CFPP_EUNSUPPORTED, "hidden %d needs more than 32 values per thread at %d threads", dm.h,
+                    sh->threads);
     sh->lds_floats = (unsigned)m;
     return CFPP_OK;
 }
@@ -376,6 +383,7 @@ static StepParams make_params(const cfpp_ctx *ctx, const Shape &sh, int b, const
     P.rows_qkv = sh.rows_qkv; P.rows_up = sh.rows_up; P.rows_h = sh.rows_h;
     P.nsl_down = sh.nsl_down; P.nsl_dense = sh.nsl_dense;
     P.lds_floats = sh.lds_floats;
+    P.debug = ctx->debug;
     return P;
 }
 
@@ -557,5 +565,25 @@ extern "C" cfpp_status cfpp_debug_read(cfpp_ctx *ctx, int32_t which, float *dst_
     if (count > n) return fail(CFPP_EINVAL, "count %zu exceeds the buffer (%zu floats)", count, n);
     HIP_OK(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
     HIP_OK(hipMemcpy(dst_host, ctx->ws + off, count * sizeof(float), hipMemcpyDeviceToHost));
+    return CFPP_OK;
+}
+
+// ---- bandwidth calibration -------------------------------------------------------------
+extern "C" cfpp_status cfpp_stream_read(const void *src, size_t bytes, void *sink, int32_t grid,
+                                        int32_t threads, int32_t unroll, cfpp_stream stream)
+{
+    if (!aligned16(src) || !aligned16(sink) || (bytes & 15)) return fail(CFPP_EINVAL, "bad src/sink/bytes");
+    if (grid <= 0 || grid > 65536 || (threads != 256 && threads != 512)) return fail(CFPP_EINVAL, "bad launch shape");
+    HIP_OK(launch_stream_read(src, bytes, static_cast<unsigned *>(sink), grid, threads, unroll,
+                              static_cast<hipStream_t>(stream)));
+    return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_stream_copy(const void *src, void *dst, size_t bytes, int32_t grid,
+                                        int32_t threads, cfpp_stream stream)
+{
+    if (!aligned16(src) || !aligned16(dst) || (bytes & 15)) return fail(CFPP_EINVAL, "bad src/dst/bytes");
+    if (grid <= 0 || grid > 65536 || (threads != 256 && threads != 512)) return fail(CFPP_EINVAL, "bad launch shape");
+    HIP_OK(launch_stream_copy(src, dst, bytes, grid, threads, static_cast<hipStream_t>(stream)));
     return CFPP_OK;
 }

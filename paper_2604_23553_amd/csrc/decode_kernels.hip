@@ -23,6 +23,7 @@
 #include <hip/hip_fp16.h>
 #include "decode_params.h"
 #include "device_utils.h"
+#include <type_traits>
 
 namespace cfpp {
 
@@ -35,13 +36,77 @@ constexpr int kMaxThreads = 512;
 // activation vector held in LDS (fp32, lds_perm order, zero padded to a chunk
 // multiple) and leaves the slice's partial sum in part[unit].
 template <int U>
-__device__ __forceinline__ void wg_gemv_u(const __half *__restrict__ Wm, int K, int row_begin,
-                                          int nrows, int nsl, const float *y, float *part)
+__device__ __forceinline__ void gemv_issue(u32x4 (&wv)[U], const __half *p)
+{
+#pragma unroll
+    for (int i = 0; i < U; ++i) wv[i] = load16_stream(p + (size_t)i * kChunk);
+}
+
+template <int U>
+__device__ __forceinline__ float gemv_consume(const u32x4 (&wv)[U], const float *yl, float acc)
+{
+    float a0 = acc, a1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+        const float4 ya = *reinterpret_cast<const float4 *>(yl + i * kChunk);
+        const float4 yb = *reinterpret_cast<const float4 *>(yl + i * kChunk + 256);
+        if (i & 1) a1 = dot8(wv[i], ya, yb, a1);
+        else a0 = dot8(wv[i], ya, yb, a0);
+    }
+    return a0 + a1;
+}
+
+// Fast path: K a multiple of 512 and every slice a whole number of U-chunk
+// steps.  The wavefront walks its (unit, step) sequence with the loads of the
+// next step already in flight while it multiplies the current one, so the
+// reduction at the end of a unit never drains the memory pipeline.
+template <int U>
+__device__ __forceinline__ void wg_gemv_pipelined(const __half *__restrict__ Wm, int K, int row_begin,
+                                                  int nrows, int nsl, int cps, const float *y, float *part)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int spu = cps / U;                         // steps per unit
+    const int nunits = nrows * nsl;
+    const __half *wl = Wm + (size_t)row_begin * K + lane * 8;
+    const float *yl = y + lane * 4;
+    int u = wave, step = 0;
+    if (u >= nunits) return;
+    u32x4 cur[U], nxt[U];
+    {
+        const int rl = u / nsl, sl = u - rl * nsl;
+        gemv_issue<U>(cur, wl + (size_t)rl * K + (size_t)(sl * cps) * kChunk);
+    }
+    float acc = 0.f;
+    while (u < nunits) {
+        int un = u, stn = step + 1;
+        if (stn == spu) { stn = 0; un = u + nw; }
+        if (un < nunits) {
+            const int rl = un / nsl, sl = un - rl * nsl;
+            gemv_issue<U>(nxt, wl + (size_t)rl * K + (size_t)(sl * cps + stn * U) * kChunk);
+        }
+        {
+            const int sl = u % nsl;
+            acc = gemv_consume<U>(cur, yl + (sl * cps + step * U) * kChunk, acc);
+        }
+        if (stn == 0) {
+            const float tot = wave_sum(acc);
+            if (lane == 0) part[u] = tot;
+            acc = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < U; ++i) cur[i] = nxt[i];
+        u = un;
+        step = stn;
+    }
+}
+
+// General path: any K that is a multiple of 8 (ragged last chunk), any slicing.
+__device__ __forceinline__ void wg_gemv_general(const __half *__restrict__ Wm, int K, int row_begin,
+                                                int nrows, int nsl, const float *y, float *part)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
     const int nchunk = (K + kChunk - 1) / kChunk;
     const int cps = (nchunk + nsl - 1) / nsl;
-    const int nfull = K / kChunk;                  // chunks with all 512 columns present
     const int nunits = nrows * nsl;
     for (int u = wave; u < nunits; u += nw) {
         const int rl = u / nsl, sl = u - rl * nsl;
@@ -49,28 +114,15 @@ __device__ __forceinline__ void wg_gemv_u(const __half *__restrict__ Wm, int K, 
         const int c1 = min(nchunk, c0 + cps);
         const __half *wrow = Wm + (size_t)(row_begin + rl) * K + lane * 8;
         const float *yl = y + lane * 4;
-        float acc0 = 0.f, acc1 = 0.f;
-        int c = c0;
-        for (; c + U <= c1 && c + U <= nfull; c += U) {
-            u32x4 wv[U];
-#pragma unroll
-            for (int i = 0; i < U; ++i) wv[i] = load16_stream(wrow + (size_t)(c + i) * kChunk);
-#pragma unroll
-            for (int i = 0; i < U; ++i) {
-                const float4 ya = *reinterpret_cast<const float4 *>(yl + (c + i) * kChunk);
-                const float4 yb = *reinterpret_cast<const float4 *>(yl + (c + i) * kChunk + 256);
-                if (i & 1) acc1 = dot8(wv[i], ya, yb, acc1);
-                else acc0 = dot8(wv[i], ya, yb, acc0);
-            }
-        }
-        for (; c < c1; ++c) {                      // leftover chunks, the last may be ragged
+        float acc = 0.f;
+        for (int c = c0; c < c1; ++c) {
             u32x4 wv = {0u, 0u, 0u, 0u};
             if (c * kChunk + lane * 8 < K) wv = load16_stream(wrow + (size_t)c * kChunk);
             const float4 ya = *reinterpret_cast<const float4 *>(yl + c * kChunk);
             const float4 yb = *reinterpret_cast<const float4 *>(yl + c * kChunk + 256);
-            acc0 = dot8(wv, ya, yb, acc0);
+            acc = dot8(wv, ya, yb, acc);
         }
-        const float tot = wave_sum(acc0 + acc1);
+        const float tot = wave_sum(acc);
         if (lane == 0) part[u] = tot;
     }
 }
@@ -81,9 +133,11 @@ __device__ __forceinline__ void wg_gemv(const __half *__restrict__ Wm, int K, in
     if (nrows <= 0) return;
     const int nchunk = (K + kChunk - 1) / kChunk;
     const int cps = (nchunk + nsl - 1) / nsl;
-    if (cps % 8 == 0) wg_gemv_u<8>(Wm, K, row_begin, nrows, nsl, y, part);
-    else if (cps % 5 == 0) wg_gemv_u<5>(Wm, K, row_begin, nrows, nsl, y, part);
-    else wg_gemv_u<4>(Wm, K, row_begin, nrows, nsl, y, part);
+    const bool regular = (K % kChunk) == 0 && cps * nsl == nchunk;
+    if (regular && cps % 8 == 0) wg_gemv_pipelined<8>(Wm, K, row_begin, nrows, nsl, cps, y, part);
+    else if (regular && cps % 5 == 0) wg_gemv_pipelined<5>(Wm, K, row_begin, nrows, nsl, cps, y, part);
+    else if (regular && cps % 4 == 0) wg_gemv_pipelined<4>(Wm, K, row_begin, nrows, nsl, cps, y, part);
+    else wg_gemv_general(Wm, K, row_begin, nrows, nsl, y, part);
 }
 
 // sum of a value over the workgroup, fixed order; red: >= 16 floats of LDS
@@ -119,13 +173,13 @@ __device__ __forceinline__ LayerIO layer_io(const StepParams &P, int layer)
 
 __device__ __forceinline__ float load_x(const LayerIO &io, int i)
 {
-    return io.x16 ? __half2float(io.x16[i]) : io.x32[i];
+    return io.x16 ? __half2float(io.x16[i]) : xwg_load(io.x32 + i);
 }
 
 __device__ __forceinline__ int round_up_chunk(int k) { return (k + kChunk - 1) / kChunk * kChunk; }
 
 // ---------------------------------------------------------------------------
-// Phase A.  LDS: y1[Kp] y2[Kp] xs[Kp] part[rows_qkv + rows_up] red[16]
+// Phase A.  LDS: y1[Kp] y2[Kp] part[rows_qkv + rows_up] red[16]
 __device__ void phase_a(const StepParams &P, const __half *__restrict__ w, __half *__restrict__ kv,
                         int layer, int pos, float *lds)
 {
@@ -133,48 +187,88 @@ __device__ void phase_a(const StepParams &P, const __half *__restrict__ w, __hal
     const int h = dm.h, f = dm.f, d = dm.d, r = dm.r;
     const int tid = threadIdx.x, nt = blockDim.x, g = blockIdx.x;
     const int Kp = round_up_chunk(h);
-    float *y1 = lds, *y2 = lds + Kp, *xs = lds + 2 * Kp, *part = lds + 3 * Kp;
+    float *y1 = lds, *y2 = lds + Kp, *part = lds + 2 * Kp;
     float *red = part + P.rows_qkv + P.rows_up;
     const LayerIO io = layer_io(P, layer);
 
-    // both LayerNorms read the block input: stage x in LDS (fp32), then two-pass
-    // statistics and the two affine outputs from LDS
-    constexpr int XU = 8;                       // loads in flight per thread
-    float s = 0.f;
-    for (int base = 0; base < h; base += XU * nt) {
-        float xv[XU];
+    // Both LayerNorms read the block input.  A thread owns up to GU groups of 8
+    // consecutive elements; x and the four parameter vectors are fetched with
+    // 16-byte loads that are all in flight together, statistics are two-pass on
+    // registers.
+    constexpr int GU = 4;
+    const int ngrp = h >> 3, ngrp_p = Kp >> 3;
+    float xv[GU][8];
+    u32x4 pg1[GU], pb1[GU], pg2[GU], pb2[GU];
+    const __half *g1 = w + P.lay.ln1_g, *b1 = w + P.lay.ln1_b;
+    const __half *g2 = w + P.lay.ln2_g, *b2 = w + P.lay.ln2_b;
 #pragma unroll
-        for (int j = 0; j < XU; ++j) {
-            const int i = base + tid + j * nt;
-            xv[j] = i < h ? load_x(io, i) : 0.f;
-        }
+    for (int j = 0; j < GU; ++j) {
+        const int gi = tid + j * nt;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        pg1[j] = z; pb1[j] = z; pg2[j] = z; pb2[j] = z;
 #pragma unroll
-        for (int j = 0; j < XU; ++j) {
-            const int i = base + tid + j * nt;
-            if (i < h) xs[i] = xv[j];
-            s += xv[j];
+        for (int e = 0; e < 8; ++e) xv[j][e] = 0.f;
+        if (gi < ngrp) {
+            if (io.x16) {
+                const u32x4 xr = load16(io.x16 + gi * 8);
+                const float2 a = unpack_h2(xr.x), b = unpack_h2(xr.y), c = unpack_h2(xr.z), e2 = unpack_h2(xr.w);
+                xv[j][0] = a.x; xv[j][1] = a.y; xv[j][2] = b.x; xv[j][3] = b.y;
+                xv[j][4] = c.x; xv[j][5] = c.y; xv[j][6] = e2.x; xv[j][7] = e2.y;
+            } else {
+                const float *xp = io.x32 + gi * 8;
+                const float2 a = xwg_load2(xp), b = xwg_load2(xp + 2), c = xwg_load2(xp + 4), e2 = xwg_load2(xp + 6);
+                xv[j][0] = a.x; xv[j][1] = a.y; xv[j][2] = b.x; xv[j][3] = b.y;
+                xv[j][4] = c.x; xv[j][5] = c.y; xv[j][6] = e2.x; xv[j][7] = e2.y;
+            }
+            pg1[j] = load16(g1 + gi * 8); pb1[j] = load16(b1 + gi * 8);
+            pg2[j] = load16(g2 + gi * 8); pb2[j] = load16(b2 + gi * 8);
         }
     }
-    const float mean = block_sum(s, red) / (float)h;    // (its barriers also publish xs)
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < GU; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += xv[j][e];
+    const float mean = block_sum(s, red) / (float)h;
     float v = 0.f;
-    for (int i = tid; i < h; i += nt) {
-        const float dlt = xs[i] - mean;
-        v += dlt * dlt;
+#pragma unroll
+    for (int j = 0; j < GU; ++j) {
+        if (tid + j * nt < ngrp) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float dlt = xv[j][e] - mean;
+                v += dlt * dlt;
+            }
+        }
     }
     const float var = block_sum(v, red) / (float)h;
     const float inv = 1.0f / sqrtf(var + dm.ln_eps);
-    const __half *g1 = w + P.lay.ln1_g, *b1 = w + P.lay.ln1_b;
-    const __half *g2 = w + P.lay.ln2_g, *b2 = w + P.lay.ln2_b;
-    for (int i = tid; i < Kp; i += nt) {
-        float a = 0.f, b = 0.f;
-        if (i < h) {
-            const float t = (xs[i] - mean) * inv;
-            a = t * __half2float(g1[i]) + __half2float(b1[i]);
-            b = t * __half2float(g2[i]) + __half2float(b2[i]);
+#pragma unroll
+    for (int j = 0; j < GU; ++j) {
+        const int gi = tid + j * nt;
+        if (gi < ngrp_p) {
+            float ya[8], yb[8];
+            const bool real = gi < ngrp;
+            const unsigned wg1[4] = {pg1[j].x, pg1[j].y, pg1[j].z, pg1[j].w};
+            const unsigned wb1[4] = {pb1[j].x, pb1[j].y, pb1[j].z, pb1[j].w};
+            const unsigned wg2[4] = {pg2[j].x, pg2[j].y, pg2[j].z, pg2[j].w};
+            const unsigned wb2[4] = {pb2[j].x, pb2[j].y, pb2[j].z, pb2[j].w};
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const float2 ga = unpack_h2(wg1[e2]), ba = unpack_h2(wb1[e2]);
+                const float2 gb = unpack_h2(wg2[e2]), bb = unpack_h2(wb2[e2]);
+                const float t0 = (xv[j][2 * e2] - mean) * inv, t1 = (xv[j][2 * e2 + 1] - mean) * inv;
+                ya[2 * e2] = real ? t0 * ga.x + ba.x : 0.f;
+                ya[2 * e2 + 1] = real ? t1 * ga.y + ba.y : 0.f;
+                yb[2 * e2] = real ? t0 * gb.x + bb.x : 0.f;
+                yb[2 * e2 + 1] = real ? t1 * gb.y + bb.y : 0.f;
+            }
+            const int at = ((gi >> 6) << 9) + ((gi & 63) << 2);     // = lds_perm(8 * gi)
+            *reinterpret_cast<float4 *>(y1 + at) = float4{ya[0], ya[1], ya[2], ya[3]};
+            *reinterpret_cast<float4 *>(y1 + at + 256) = float4{ya[4], ya[5], ya[6], ya[7]};
+            *reinterpret_cast<float4 *>(y2 + at) = float4{yb[0], yb[1], yb[2], yb[3]};
+            *reinterpret_cast<float4 *>(y2 + at + 256) = float4{yb[4], yb[5], yb[6], yb[7]};
         }
-        const int at = lds_perm(i);
-        y1[at] = a;
-        y2[at] = b;
     }
     __syncthreads();
 
@@ -202,41 +296,102 @@ __device__ void phase_a(const StepParams &P, const __half *__restrict__ w, __hal
             d0 = j; d1 = j + (r >> 1);
         }
         if (c == 0) {
-            P.q[n * d + d0] = v0;
-            P.q[n * d + d1] = v1;
+            xwg_store(P.q + n * d + d0, v0);
+            xwg_store(P.q + n * d + d1, v1);
         } else {
-            kv[kv_offset(dm, c - 1, P.b, n, d0, pos)] = __float2half_rn(v0);
-            kv[kv_offset(dm, c - 1, P.b, n, d1, pos)] = __float2half_rn(v1);
+            xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d0, pos), v0);
+            xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d1, pos), v1);
         }
     }
     const __half *bu = w + P.lay.b_up;
     for (int t = tid; t < u_n; t += nt)
-        P.m[u_begin + t] = gelu_erf(part[P.rows_qkv + t] + __half2float(bu[u_begin + t]));
+        xwg_store(P.m + u_begin + t, gelu_erf(part[P.rows_qkv + t] + __half2float(bu[u_begin + t])));
 }
 
 // ---------------------------------------------------------------------------
 // Split-KV decode attention over this workgroup's share of the cache.
 //
-// All (head, 32-position row) pairs of the sequence form one line of
-// T = H * ceil(n_tok/32) rows; workgroup g owns rows [T*g/G, T*(g+1)/G), which
-// may cover the tail of one head and the start of the next.  Inside a head, a
-// wavefront step covers 32 positions: lane l handles position l/2 and the 8-dim
-// half (l & 1) of every 16-dim slab, so one load instruction reads 1 KiB
-// contiguous.  Each lane pair keeps its own online-softmax state (running max,
-// sum, d/2 accumulators); states are merged lane -> wavefront -> workgroup ->
-// head in fixed orders.  The workgroup that delivers the last partial of a
-// head combines all of that head's partials in slot order.
+// LPP lanes share one cache position (2 for head_dim 64 and 80, 4 for 128), so a
+// wavefront step ("row") covers PPW = 64/LPP positions.  Lane (position p,
+// sub-lane u) handles the 8-dim pieces u, u+LPP, ... of the head; piece c lives
+// in slab c/2, half c%2 of the cache layout, so one load instruction reads
+// whole 32-byte records of consecutive positions (>= 512 B contiguous runs).
+//
+// All (head, row) pairs of the sequence form one line of T = H * ceil(n_tok/PPW)
+// rows; workgroup g owns rows [T*g/G, T*(g+1)/G), which may cover the tail of
+// one head and the start of the next.  Each lane group keeps its own
+// online-softmax state (running max, sum, accumulators for its pieces); states
+// are merged lane -> wavefront -> workgroup -> head, each in a fixed order.  The
+// workgroup that delivers the last partial of a head combines all of that
+// head's partials in slot order.  K/V loads of the next row are issued before
+// the current row is processed.
 // scr: nw*(D+2) + 4 floats of LDS.
+template <int D> struct AttnShape {
+    static constexpr int LPP = D >= 128 ? 4 : 2;
+    static constexpr int PPW = 64 / LPP;
+    static constexpr int NP = D / 8 / LPP;     // pieces per lane
+    static constexpr int NV = NP * 8;          // accumulators per lane
+};
+
+template <int M>
+__device__ __forceinline__ float lane_xor(float v)
+{
+    if constexpr (M == 1) return dpp_mov<kDppXor1>(v);
+    else if constexpr (M == 2) return dpp_mov<kDppXor2>(v);
+    else return __shfl_xor(v, M, 64);
+}
+
+// Butterfly reduce-scatter of vals[0..NV) over the lanes that differ in the bits
+// M0, 2*M0, ..., 32: at each step a lane keeps one half of its list and adds
+// the partner's copy of it.  On return the lane holds `cnt` finished sums, for
+// original indices off .. off+cnt-1, in vals[0..cnt).
+template <int NV, int M0>
+__device__ __forceinline__ void reduce_scatter(float (&vals)[NV], int lane, int &off, int &cnt)
+{
+    off = 0;
+    cnt = NV;
+    auto step = [&](auto mtag, auto ntag) {
+        constexpr int M = decltype(mtag)::value, N = decltype(ntag)::value;
+        constexpr int HALF = (N + 1) / 2;
+        const bool high = (lane & M) != 0;
+#pragma unroll
+        for (int i = 0; i < HALF; ++i) {
+            const float lo = vals[i];
+            const float hi = (i + HALF < N) ? vals[i + HALF] : 0.f;
+            const float recv = lane_xor<M>(high ? lo : hi);
+            vals[i] = (high ? hi : lo) + recv;
+        }
+        off += high ? HALF : 0;
+        cnt = high ? max(0, cnt - HALF) : min(cnt, HALF);
+    };
+    using std::integral_constant;
+    constexpr int N0 = NV, N1 = (N0 + 1) / 2, N2 = (N1 + 1) / 2, N3 = (N2 + 1) / 2, N4 = (N3 + 1) / 2;
+    if constexpr (M0 == 2) {
+        step(integral_constant<int, 2>{}, integral_constant<int, N0>{});
+        step(integral_constant<int, 4>{}, integral_constant<int, N1>{});
+        step(integral_constant<int, 8>{}, integral_constant<int, N2>{});
+        step(integral_constant<int, 16>{}, integral_constant<int, N3>{});
+        step(integral_constant<int, 32>{}, integral_constant<int, N4>{});
+    } else {
+        static_assert(M0 == 4, "lanes per position must be 2 or 4");
+        step(integral_constant<int, 4>{}, integral_constant<int, N0>{});
+        step(integral_constant<int, 8>{}, integral_constant<int, N1>{});
+        step(integral_constant<int, 16>{}, integral_constant<int, N2>{});
+        step(integral_constant<int, 32>{}, integral_constant<int, N3>{});
+    }
+}
+
 template <int D>
 __device__ void attn_share(const StepParams &P, const __half *__restrict__ kv, int n_tok, float *scr)
 {
-    constexpr int NG = D / 16;
+    using A = AttnShape<D>;
+    constexpr int LPP = A::LPP, PPW = A::PPW, NP = A::NP, NV = A::NV;
     const Dims &dm = P.dm;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
-    const int hp = lane & 1, tl = lane >> 1;
+    const int sub = lane & (LPP - 1), tl = lane / LPP;
     const int H = dm.H;
     const long long g = blockIdx.x;
-    const int R = (n_tok + kRowPos - 1) / kRowPos;
+    const int R = (n_tok + PPW - 1) / PPW;
     const long long T = (long long)R * H;
     // with fewer rows than workgroups only the first T workgroups take part, so
     // that every participant owns at least one row (no empty ranges in between)
@@ -249,84 +404,106 @@ __device__ void attn_share(const StepParams &P, const __half *__restrict__ kv, i
     float *wp = scr, *wm = scr + nw * D, *wl = wm + nw;
     int *flag = reinterpret_cast<int *>(wl + nw);
 
+    // element offset of this lane's piece k inside a head, for position 0
+    size_t koff[NP];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const int pc = sub + LPP * k;
+        koff[k] = (size_t)(pc >> 1) * dm.max_seq * 16 + (pc & 1) * 8;
+    }
+
     for (long long sb = r0; sb < r1;) {
         const int s = (int)(sb / R);                       // head
         const long long se = min(r1, (long long)(s + 1) * R);
         const int row_lo = (int)(sb - (long long)s * R), row_hi = (int)(se - (long long)s * R);
-        const __half *Kh = Kb + (size_t)s * hs + hp * 8;
-        const __half *Vh = Vb + (size_t)s * hs + hp * 8;
+        const __half *Kh = Kb + (size_t)s * hs;
+        const __half *Vh = Vb + (size_t)s * hs;
 
-        float q[NG][8];
-        {
-            const float *qp = P.q + s * D + hp * 8;
+        float q[NP][8];
 #pragma unroll
-            for (int jj = 0; jj < NG; ++jj) {
-                const float4 a = *reinterpret_cast<const float4 *>(qp + 16 * jj);
-                const float4 b = *reinterpret_cast<const float4 *>(qp + 16 * jj + 4);
-                q[jj][0] = a.x; q[jj][1] = a.y; q[jj][2] = a.z; q[jj][3] = a.w;
-                q[jj][4] = b.x; q[jj][5] = b.y; q[jj][6] = b.z; q[jj][7] = b.w;
-            }
+        for (int k = 0; k < NP; ++k) {
+            const float *qp = P.q + s * D + 8 * (sub + LPP * k);
+            const float2 a = xwg_load2(qp), b = xwg_load2(qp + 2), c = xwg_load2(qp + 4), e = xwg_load2(qp + 6);
+            q[k][0] = a.x; q[k][1] = a.y; q[k][2] = b.x; q[k][3] = b.y;
+            q[k][4] = c.x; q[k][5] = c.y; q[k][6] = e.x; q[k][7] = e.y;
         }
-        float acc[NG][8];
+        float acc[NV];
 #pragma unroll
-        for (int jj = 0; jj < NG; ++jj)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[jj][e] = 0.f;
+        for (int i = 0; i < NV; ++i) acc[i] = 0.f;
         float mrun = -INFINITY, lrun = 0.f;
 
-        for (int row = row_lo + wave; row < row_hi; row += nw) {
-            const int t = row * kRowPos + tl;
-            const bool valid = t < n_tok;
-            u32x4 kk[NG], vv[NG];
+        auto issue = [&](u32x4 (&kk)[NP], u32x4 (&vv)[NP], int row) {
+            const int t = row * PPW + tl;
 #pragma unroll
-            for (int jj = 0; jj < NG; ++jj) {
-                kk[jj] = u32x4{0u, 0u, 0u, 0u};
-                vv[jj] = u32x4{0u, 0u, 0u, 0u};
+            for (int k = 0; k < NP; ++k) {
+                kk[k] = u32x4{0u, 0u, 0u, 0u};
+                vv[k] = u32x4{0u, 0u, 0u, 0u};
             }
-            if (valid) {
+            if (t < n_tok - 1) {
 #pragma unroll
-                for (int jj = 0; jj < NG; ++jj)
-                    kk[jj] = load16_stream(Kh + ((size_t)jj * dm.max_seq + t) * 16);
+                for (int k = 0; k < NP; ++k) kk[k] = load16_stream(Kh + koff[k] + (size_t)t * 16);
 #pragma unroll
-                for (int jj = 0; jj < NG; ++jj)
-                    vv[jj] = load16_stream(Vh + ((size_t)jj * dm.max_seq + t) * 16);
+                for (int k = 0; k < NP; ++k) vv[k] = load16_stream(Vh + koff[k] + (size_t)t * 16);
+            } else if (t == n_tok - 1) {               // appended during this launch by other workgroups
+#pragma unroll
+                for (int k = 0; k < NP; ++k) kk[k] = xwg_load16(Kh + koff[k] + (size_t)t * 16);
+#pragma unroll
+                for (int k = 0; k < NP; ++k) vv[k] = xwg_load16(Vh + koff[k] + (size_t)t * 16);
             }
+        };
+
+        u32x4 kA[NP], vA[NP], kB[NP], vB[NP];
+        int row = row_lo + wave;
+        if (row < row_hi) issue(kA, vA, row);
+        for (; row < row_hi; row += nw) {
+            if (row + nw < row_hi) issue(kB, vB, row + nw);
+            const bool valid = row * PPW + tl < n_tok;
             float sp = 0.f;
 #pragma unroll
-            for (int jj = 0; jj < NG; ++jj) {
-                const float4 qa = {q[jj][0], q[jj][1], q[jj][2], q[jj][3]};
-                const float4 qb = {q[jj][4], q[jj][5], q[jj][6], q[jj][7]};
-                sp = dot8(kk[jj], qa, qb, sp);
+            for (int k = 0; k < NP; ++k) {
+                const float4 qa = {q[k][0], q[k][1], q[k][2], q[k][3]};
+                const float4 qb = {q[k][4], q[k][5], q[k][6], q[k][7]};
+                sp = dot8(kA[k], qa, qb, sp);
             }
-            sp += dpp_mov<kDppXor1>(sp);                   // both halves of the head dim
+            sp += lane_xor<1>(sp);                         // the lanes sharing this position
+            if constexpr (LPP == 4) sp += lane_xor<2>(sp);
             const float sc = valid ? sp * scale : -INFINITY;
             const float mn = fmaxf(mrun, sc);
             const float corr = mrun == -INFINITY ? 0.f : expf(mrun - mn);
             const float p = valid ? expf(sc - mn) : 0.f;
             lrun = lrun * corr + p;
 #pragma unroll
-            for (int jj = 0; jj < NG; ++jj) {
-                const float2 a = unpack_h2(vv[jj].x), b = unpack_h2(vv[jj].y);
-                const float2 c = unpack_h2(vv[jj].z), e = unpack_h2(vv[jj].w);
-                acc[jj][0] = fmaf(p, a.x, acc[jj][0] * corr); acc[jj][1] = fmaf(p, a.y, acc[jj][1] * corr);
-                acc[jj][2] = fmaf(p, b.x, acc[jj][2] * corr); acc[jj][3] = fmaf(p, b.y, acc[jj][3] * corr);
-                acc[jj][4] = fmaf(p, c.x, acc[jj][4] * corr); acc[jj][5] = fmaf(p, c.y, acc[jj][5] * corr);
-                acc[jj][6] = fmaf(p, e.x, acc[jj][6] * corr); acc[jj][7] = fmaf(p, e.y, acc[jj][7] * corr);
+            for (int k = 0; k < NP; ++k) {
+                const float2 a = unpack_h2(vA[k].x), b = unpack_h2(vA[k].y);
+                const float2 c = unpack_h2(vA[k].z), e = unpack_h2(vA[k].w);
+                float *ac = acc + 8 * k;
+                ac[0] = fmaf(p, a.x, ac[0] * corr); ac[1] = fmaf(p, a.y, ac[1] * corr);
+                ac[2] = fmaf(p, b.x, ac[2] * corr); ac[3] = fmaf(p, b.y, ac[3] * corr);
+                ac[4] = fmaf(p, c.x, ac[4] * corr); ac[5] = fmaf(p, c.y, ac[5] * corr);
+                ac[6] = fmaf(p, e.x, ac[6] * corr); ac[7] = fmaf(p, e.y, ac[7] * corr);
             }
             mrun = mn;
+#pragma unroll
+            for (int k = 0; k < NP; ++k) { kA[k] = kB[k]; vA[k] = vB[k]; }
         }
 
         // lanes -> wavefront
         const float mw = wave_max(mrun);
         const float fl = mrun == -INFINITY ? 0.f : expf(mrun - mw);
-        const float lw = wave_sum(hp == 0 ? lrun * fl : 0.f);
+        const float lw = wave_sum(sub == 0 ? lrun * fl : 0.f);
 #pragma unroll
-        for (int jj = 0; jj < NG; ++jj)
+        for (int i = 0; i < NV; ++i) acc[i] *= fl;
+        int off, cnt;
+        reduce_scatter<NV, LPP>(acc, lane, off, cnt);
+        constexpr int NLEFT = LPP == 2 ? (((((NV + 1) / 2 + 1) / 2 + 1) / 2 + 1) / 2 + 1) / 2
+                                       : ((((NV + 1) / 2 + 1) / 2 + 1) / 2 + 1) / 2;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float tot = parity_sum(acc[jj][e] * fl);
-                if (lane < 2) wp[wave * D + 16 * jj + 8 * hp + e] = tot;
+        for (int i = 0; i < NLEFT; ++i) {
+            if (i < cnt) {
+                const int idx = off + i;                   // accumulator index: piece idx/8, element idx%8
+                wp[wave * D + 8 * (sub + LPP * (idx >> 3)) + (idx & 7)] = acc[i];
             }
+        }
         if (lane == 0) { wm[wave] = mw; wl[wave] = lw; }
         __syncthreads();
 
@@ -345,31 +522,31 @@ __device__ void attn_share(const StepParams &P, const __half *__restrict__ kv, i
                 L += wl[wv] * e;
                 O += wp[wv * D + tid] * e;
             }
-            slot[tid] = O;
-            if (tid == 0) { slot[D] = M; slot[D + 1] = L; }
+            xwg_store(slot + tid, O);
+            if (tid == 0) { xwg_store(slot + D, M); xwg_store(slot + D + 1, L); }
         }
-        __threadfence();
+        if (P.debug & 8) { __syncthreads(); sb = se; continue; }
+        xwg_wait_stores();
         __syncthreads();
         if (tid == 0) {
-            const unsigned old = __hip_atomic_fetch_add(&P.seg_cnt[s], 1u, __ATOMIC_ACQ_REL,
+            const unsigned old = __hip_atomic_fetch_add(&P.seg_cnt[s], 1u, __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_AGENT);
             *flag = old == (unsigned)(ncover - 1);
         }
         __syncthreads();
         if (*flag) {                                       // this workgroup delivered the last partial
-            __threadfence();
             if (tid < D) {
                 const float *base = P.part + (size_t)s * P.part_slots * (D + 2);
                 float M = -INFINITY;
-                for (int j = 0; j < ncover; ++j) M = fmaxf(M, base[(size_t)j * (D + 2) + D]);
+                for (int j = 0; j < ncover; ++j) M = fmaxf(M, xwg_load(base + (size_t)j * (D + 2) + D));
                 float L = 0.f, O = 0.f;
                 for (int j = 0; j < ncover; ++j) {
                     const float *sj = base + (size_t)j * (D + 2);
-                    const float e = expf(sj[D] - M);
-                    L += sj[D + 1] * e;
-                    O += sj[tid] * e;
+                    const float e = expf(xwg_load(sj + D) - M);
+                    L += xwg_load(sj + D + 1) * e;
+                    O += xwg_load(sj + tid) * e;
                 }
-                P.o[s * D + tid] = O / L;
+                xwg_store(P.o + s * D + tid, O / L);
             }
             if (tid == 0)
                 __hip_atomic_store(&P.seg_cnt[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -379,11 +556,27 @@ __device__ void attn_share(const StepParams &P, const __half *__restrict__ kv, i
     }
 }
 
-// copy a workspace vector into LDS in GEMV order, zero padded
+// copy an exchanged workspace vector (n a multiple of 8) into LDS in GEMV order,
+// zero padded to a chunk multiple; coherent 8-byte loads, a batch in flight
+// together
 __device__ __forceinline__ void stage_vector(const float *__restrict__ src, int n, float *dst)
 {
-    const int np = round_up_chunk(n);
-    for (int i = threadIdx.x; i < np; i += blockDim.x) dst[lds_perm(i)] = i < n ? src[i] : 0.f;
+    constexpr int UN = 10;
+    const int n2 = n >> 1, np2 = round_up_chunk(n) >> 1;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    for (int base = 0; base < np2; base += UN * nt) {
+        float2 v[UN];
+#pragma unroll
+        for (int j = 0; j < UN; ++j) {
+            const int i2 = base + tid + j * nt;
+            v[j] = i2 < n2 ? xwg_load2(src + 2 * i2) : float2{0.f, 0.f};
+        }
+#pragma unroll
+        for (int j = 0; j < UN; ++j) {
+            const int i2 = base + tid + j * nt;
+            if (i2 < np2) *reinterpret_cast<float2 *>(dst + lds_perm(i2 * 2)) = v[j];
+        }
+    }
 }
 
 // Phase B.  LDS: m[Kp_f] part[rows_h*nsl_down] scr[nw*(D+2)+4]
@@ -395,17 +588,17 @@ __device__ void phase_b(const StepParams &P, const __half *__restrict__ w, const
     const int h = dm.h, f = dm.f, tid = threadIdx.x, nt = blockDim.x, g = blockIdx.x;
     const int Kp = round_up_chunk(f);
     float *ml = lds, *part = lds + Kp, *scr = part + P.rows_h * P.nsl_down;
-    stage_vector(P.m, f, ml);
-    attn_share<D>(P, kv, pos + 1, scr);
+    if (!(P.debug & 1)) stage_vector(P.m, f, ml);
+    if (!(P.debug & 2)) attn_share<D>(P, kv, pos + 1, scr);
     __syncthreads();
     const int r_begin = g * P.rows_h, r_n = max(0, min(P.rows_h, h - r_begin));
-    wg_gemv(w + P.lay.w_down, f, r_begin, r_n, P.nsl_down, ml, part);
+    if (!(P.debug & 4)) wg_gemv(w + P.lay.w_down, f, r_begin, r_n, P.nsl_down, ml, part);
     __syncthreads();
     const __half *bd = w + P.lay.b_down;
     for (int t = tid; t < r_n; t += nt) {
         float a = 0.f;
         for (int sl = 0; sl < P.nsl_down; ++sl) a += part[t * P.nsl_down + sl];
-        P.g[r_begin + t] = a + __half2float(bd[r_begin + t]);
+        xwg_store(P.g + r_begin + t, a + __half2float(bd[r_begin + t]));
     }
 }
 
@@ -427,9 +620,9 @@ __device__ void phase_c(const StepParams &P, const __half *__restrict__ w, int l
         float a = 0.f;
         for (int sl = 0; sl < P.nsl_dense; ++sl) a += part[t * P.nsl_dense + sl];
         a += __half2float(bd[r_begin + t]);
-        const float res = (load_x(io, r_begin + t) + a) + P.g[r_begin + t];
+        const float res = (load_x(io, r_begin + t) + a) + xwg_load(P.g + r_begin + t);
         if (io.o16) io.o16[r_begin + t] = __float2half_rn(res);
-        else io.o32[r_begin + t] = res;
+        else xwg_store(io.o32 + r_begin + t, res);
     }
 }
 

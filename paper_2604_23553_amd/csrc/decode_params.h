@@ -26,6 +26,7 @@ struct StepParams {
     int rows_qkv, rows_up, rows_h;   // matrix rows per workgroup (rows_qkv even)
     int nsl_down, nsl_dense;         // K-slices per row for the two GEMVs with few rows
     unsigned lds_floats;             // dynamic LDS the launch provides, in floats
+    int debug;                       // profiling aid: bit mask of parts to skip (results are then wrong)
 };
 
 struct LayerPtrs {
@@ -53,5 +54,9 @@ hipError_t launch_kv_import(const Dims &dm, const __half *k_src, const __half *v
                             int n_pos, int b, __half *kv, hipStream_t s);
 hipError_t launch_kv_export(const Dims &dm, const __half *kv, int b, int pos_begin, int n_pos,
                             int dst_cap, __half *k_dst, __half *v_dst, hipStream_t s);
+
+hipError_t launch_stream_read(const void *src, size_t bytes, unsigned *sink, int grid, int threads,
+                              int unroll, hipStream_t s);
+hipError_t launch_stream_copy(const void *src, void *dst, size_t bytes, int grid, int threads, hipStream_t s);
 
 }  // namespace cfpp

@@ -106,9 +106,54 @@ __device__ __forceinline__ float gelu_erf(float z)
     return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
 }
 
+// ---- data exchanged between workgroups --------------------------------------
+// Values one workgroup writes and another reads within the same launch go
+// through device-scope (sc1) stores and loads: those are coherent across the
+// per-XCD L2 caches by themselves, so neither side needs an L2 write-back or
+// invalidate (which cost tens of microseconds when every wavefront issues
+// them).  Ordering is by program order plus xwg_wait_stores(): once it returns,
+// this wavefront's earlier exchange stores have been acknowledged by memory.
+__device__ __forceinline__ void xwg_store(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float xwg_load(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 xwg_load2(const float *p)      // p 8-byte aligned
+{
+    const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    float2 f;
+    f.x = __uint_as_float((unsigned)(v & 0xffffffffull));
+    f.y = __uint_as_float((unsigned)(v >> 32));
+    return f;
+}
+__device__ __forceinline__ void xwg_store_half(__half *p, float v)
+{
+    const __half hv = __float2half_rn(v);
+    __hip_atomic_store(reinterpret_cast<unsigned short *>(p), __half_as_ushort(hv), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+// 16 bytes of fp16 as two coherent 8-byte loads
+__device__ __forceinline__ u32x4 xwg_load16(const __half *p)
+{
+    const unsigned long long *q = reinterpret_cast<const unsigned long long *>(p);
+    const unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return u32x4{(unsigned)(a & 0xffffffffull), (unsigned)(a >> 32), (unsigned)(b & 0xffffffffull),
+                 (unsigned)(b >> 32)};
+}
+__device__ __forceinline__ void xwg_wait_stores()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 // ---- grid barrier ------------------------------------------------------------
 // All workgroups of a launch must be resident (the host checks the grid against
-// the occupancy limit).  sync[kSyncCount] returns to 0 after every barrier and
+// the occupancy limit).  The barrier orders only exchange data (xwg_store /
+// xwg_load): it issues no cache write-back or invalidate.  sync[kSyncCount] returns to 0 after every barrier and
 // sync[kSyncGen] only grows, so nothing needs resetting between launches or
 // graph replays.  The wait is bounded: after ~2 s of wall clock the waiter sets
 // the error flag and every later barrier falls through, so the grid always
@@ -129,14 +174,15 @@ struct GridBarrier {
 
     __device__ __forceinline__ void wait()
     {
+        xwg_wait_stores();          // every wavefront: its exchange stores are in memory
         __syncthreads();
         if (threadIdx.x == 0) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             unsigned old = __hip_atomic_fetch_add(&sync[kSyncCount], 1u, __ATOMIC_RELAXED,
                                                   __HIP_MEMORY_SCOPE_AGENT);
             if (old == nwg - 1) {
                 __hip_atomic_store(&sync[kSyncCount], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_fetch_add(&sync[kSyncGen], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                xwg_wait_stores();  // the reset lands before anyone can leave
+                __hip_atomic_fetch_add(&sync[kSyncGen], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
                 const unsigned long long t0 = wall_clock64();
                 unsigned spins = 0;
@@ -155,7 +201,6 @@ struct GridBarrier {
                     }
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             gen += 1;
         }
         __syncthreads();

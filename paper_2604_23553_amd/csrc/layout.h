@@ -15,7 +15,6 @@ namespace cfpp {
 constexpr int kChunk = 512;        // fp16 values one wavefront covers with one 16-byte load per lane
 constexpr int kMaxLayers = 64;
 constexpr int kMaxGrid = 1024;     // most workgroups any launch uses
-constexpr int kRowPos = 32;        // cache positions one wavefront covers per attention step
 
 CFPP_HD size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -96,4 +96,64 @@ hipError_t launch_kv_export(const Dims &dm, const __half *kv, int b, int pos_beg
     return hipGetLastError();
 }
 
+
+// ---- plain streaming kernels of known traffic (bandwidth calibration) ---------
+// read: every 16-byte word of src is loaded once and folded into a checksum, one
+// word per workgroup written to sink; copy: dst = src.
+template <int U>
+__global__ void __launch_bounds__(512) k_stream_read(const u32x4 *__restrict__ src, long long n16,
+                                                      unsigned *__restrict__ sink)
+{
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    unsigned acc = 0;
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
+        u32x4 v[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) v[j] = __builtin_nontemporal_load(src + i + j * stride);
+#pragma unroll
+        for (int j = 0; j < U; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+    }
+    for (; i < n16; i += stride) {
+        const u32x4 v = __builtin_nontemporal_load(src + i);
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    for (int m = 32; m > 0; m >>= 1) acc ^= __shfl_xor(acc, m, 64);
+    if ((threadIdx.x & 63) == 0) atomicXor(sink + blockIdx.x, acc);
+}
+
+__global__ void __launch_bounds__(512) k_stream_copy(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
+                                                      long long n16)
+{
+    constexpr int U = 4;
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
+        u32x4 v[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) v[j] = __builtin_nontemporal_load(src + i + j * stride);
+#pragma unroll
+        for (int j = 0; j < U; ++j) __builtin_nontemporal_store(v[j], dst + i + j * stride);
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_stream_read(const void *src, size_t bytes, unsigned *sink, int grid, int threads,
+                              int unroll, hipStream_t s)
+{
+    const long long n16 = (long long)(bytes / 16);
+    const u32x4 *p = static_cast<const u32x4 *>(src);
+    if (unroll >= 8) hipLaunchKernelGGL(k_stream_read<8>, dim3(grid), dim3(threads), 0, s, p, n16, sink);
+    else if (unroll >= 4) hipLaunchKernelGGL(k_stream_read<4>, dim3(grid), dim3(threads), 0, s, p, n16, sink);
+    else hipLaunchKernelGGL(k_stream_read<2>, dim3(grid), dim3(threads), 0, s, p, n16, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_copy(const void *src, void *dst, size_t bytes, int grid, int threads, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_stream_copy, dim3(grid), dim3(threads), 0, s, static_cast<const u32x4 *>(src),
+                       static_cast<u32x4 *>(dst), (long long)(bytes / 16));
+    return hipGetLastError();
+}
+
 }  // namespace cfpp

@@ -1,0 +1,283 @@
+"""GPU parity of the layer stack (direct launches and graph replay), batches,
+determinism and error paths, against the CPU oracle through the C ABI."""
+import numpy as np
+import pytest
+
+import synth
+from tests.parity import assert_block_close, assert_fp16_rows_match, errors
+
+pytestmark = pytest.mark.gpu
+
+TINY_STACK = synth.ModelShape(512, 8, 64, 16, 2048, n_layers=4, name="neox-h512-x4")
+
+
+def build_stack(shape, seed, S, cap, batch=1, layers=None):
+    from paper_2604_23553_amd.harness import DeviceStack
+    L = shape.n_layers if layers is None else layers
+    ds = DeviceStack(shape, cap, batch, L)
+    ws = [synth.layer_weights(shape, seed, l) for l in range(L)]
+    kvs = [synth.kv_cache(shape, seed, l, S, cap, batch) for l in range(L)]
+    for l in range(L):
+        ds.load_layer(l, ws[l])
+        ds.load_kv(l, kvs[l][0], kvs[l][1], S)
+    return ds, ws, kvs
+
+
+def oracle_stack(orc, shape, ws, kvs, S, x, b=0):
+    """Oracle over the same tensors; returns fp16 output, per-layer unrounded outputs
+    and the oracle's updated caches."""
+    Ks = [kv[0][b].copy() for kv in kvs]
+    Vs = [kv[1][b].copy() for kv in kvs]
+    per = []
+    out16, _ = orc.stack_decode(shape, ws, Ks, Vs, int(S), x, per_layer=per)
+    return out16, per, Ks, Vs
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("graph", [False, True])
+def test_tiny_stack_direct_and_graph(orc, mode, graph):
+    S, cap = 70, 75
+    print(f"[case] tiny stack mode={mode} graph={graph}", flush=True)
+    ds, ws, kvs = build_stack(TINY_STACK, 21, S, cap)
+    try:
+        ds.set_options(mode=mode)
+        xs = [synth.x_input(TINY_STACK, 100 + i) for i in range(3)]
+        ds.set_inputs(xs[0], S)
+        if graph:
+            ds.capture()
+        outs = []
+        # different inputs between runs: a stale exchanged value from an earlier
+        # run (or replay) would show up as a mismatch
+        for i in (0, 1, 2, 0, 1, 2):
+            ds.set_inputs(xs[i], S)
+            ds.replay() if graph else ds.stack_decode()
+            ds.check()
+            outs.append(ds.result()[0].copy())
+        for i in range(3):
+            ref16, _, Ks, Vs = oracle_stack(orc, TINY_STACK, ws, kvs, S, xs[i][0])
+            assert_block_close(outs[i], ref16, f"stack out (input {i})")
+            assert np.array_equal(outs[i].view(np.uint16), outs[i + 3].view(np.uint16)), "not bit-identical"
+        # the caches hold the rows appended by the last run (input 2)
+        ref16, _, Ks, Vs = oracle_stack(orc, TINY_STACK, ws, kvs, S, xs[2][0])
+        for l in range(TINY_STACK.n_layers):
+            kg, vg = ds.export_kv(l, 0, S, 1)
+            assert_fp16_rows_match(kg[:, 0], Ks[l][:, S], f"layer {l} appended K")
+            assert_fp16_rows_match(vg[:, 0], Vs[l][:, S], f"layer {l} appended V")
+    finally:
+        ds.close()
+
+
+def test_graph_follows_position_updates(orc):
+    """pos is read from device memory at run time: one captured graph serves
+    successive decode positions."""
+    S, cap = 40, 48
+    ds, ws, kvs = build_stack(TINY_STACK, 22, S, cap)
+    try:
+        ds.set_options(mode=2)
+        x0 = synth.x_input(TINY_STACK, 200)
+        ds.set_inputs(x0, S)
+        ds.capture()
+        Ks = [kv[0][0].copy() for kv in kvs]
+        Vs = [kv[1][0].copy() for kv in kvs]
+        for step in range(4):
+            x = synth.x_input(TINY_STACK, 200 + step)
+            ds.set_inputs(x, S + step)
+            ds.replay()
+            ds.check()
+            got = ds.result()[0]
+            ref16, _ = orc.stack_decode(TINY_STACK, ws, Ks, Vs, S + step, x[0])   # appends to Ks, Vs
+            assert_block_close(got, ref16, f"decode step {step}")
+    finally:
+        ds.close()
+
+
+def test_teacher_forced_layers(orc):
+    """Each layer of the stack checked on its own: the oracle block is fed the
+    GPU's own (fp16-rounded) input of that layer, so per-block tolerance is not
+    blurred by drift."""
+    shape = synth.ModelShape(2560, 32, 80, 20, 10240, n_layers=3, name="pythia-2.8b-x3")
+    S, cap = 300, 301
+    from paper_2604_23553_amd.harness import DeviceStack
+    ds, ws, kvs = build_stack(shape, 23, S, cap)
+    try:
+        x = synth.x_input(shape, 23)
+        cur = x
+        for l in range(shape.n_layers):
+            ds.set_inputs(cur, S)
+            ds.block_decode(l)
+            ds.check()
+            got = ds.result().copy()
+            ref = orc.block_decode_f16(shape, ws[l], kvs[l][0][0].copy(), kvs[l][1][0].copy(), S, cur[0])
+            assert_block_close(got[0], ref, f"layer {l}")
+            cur = got
+    finally:
+        ds.close()
+
+
+@pytest.mark.parametrize("mode", [0, 2])
+def test_batch_of_sequences_with_different_lengths(orc, mode):
+    shape = synth.ModelShape(1024, 8, 128, 32, 4096, n_layers=2, name="d128-x2")
+    B, cap = 3, 200
+    lens = np.array([5, 199, 64], dtype=np.int32)
+    from paper_2604_23553_amd.harness import DeviceStack
+    ds = DeviceStack(shape, cap, B, 2)
+    try:
+        ds.set_options(mode=mode)
+        ws = [synth.layer_weights(shape, 31, l) for l in range(2)]
+        kvs = [synth.kv_cache(shape, 31, l, lens, cap, B) for l in range(2)]
+        for l in range(2):
+            ds.load_layer(l, ws[l])
+            ds.load_kv(l, kvs[l][0], kvs[l][1], lens)
+        x = synth.x_input(shape, 31, B)
+        ds.set_inputs(x, lens)
+        ds.stack_decode()
+        ds.check()
+        got = ds.result()
+        for b in range(B):
+            ref16, _, _, _ = oracle_stack(orc, shape, ws, kvs, lens[b], x[b], b)
+            assert_block_close(got[b], ref16, f"sequence {b}")
+    finally:
+        ds.close()
+
+
+def test_full_pythia_2_8b_stack_graph_and_argmax(orc):
+    """The target workload: 32 layers, 4096 cached positions, batch 1, one graph
+    replay; every output element against the oracle, bit-identical replays, and
+    greedy argmax through a random LM head (computed by the oracle's LM head on
+    both outputs)."""
+    shape = synth.PYTHIA_2_8B
+    S, cap = 4096, 4097
+    print("[case] full 2.8B stack: generating inputs", flush=True)
+    from paper_2604_23553_amd.harness import DeviceStack
+    ds = DeviceStack(shape, cap, 1)
+    try:
+        ws = synth.stack_weights(shape, synth.MASTER_SEED, workers=16)
+        kvs = []
+        for l in range(shape.n_layers):
+            ds.load_layer(l, ws[l])
+            kv = synth.kv_cache(shape, synth.MASTER_SEED, l, S, cap)
+            ds.load_kv(l, kv[0], kv[1], S)
+            kvs.append(kv)
+        print("[case] full 2.8B stack: running", flush=True)
+        x = synth.x_input(shape, synth.MASTER_SEED)
+        ds.set_inputs(x, S)
+        ds.set_options(mode=0)
+        ds.capture()
+        outs = []
+        for _ in range(5):
+            ds.replay()
+            ds.check()
+            outs.append(ds.result()[0].copy())
+        for o in outs[1:]:
+            assert np.array_equal(o.view(np.uint16), outs[0].view(np.uint16)), "not bit-identical"
+        print("[case] full 2.8B stack: oracle", flush=True)
+        ref16, per, _, _ = oracle_stack(orc, shape, ws, kvs, S, x[0])
+        ma, rl = assert_block_close(outs[0], ref16, "32-layer output")
+        print(f"[result] max-abs {ma:.4e} rel-L2 {rl:.4e}", flush=True)
+        head = synth.lm_head(shape, synth.MASTER_SEED)
+        lg_ref = orc.lm_head_logits(shape, head, orc.half_to_real(ref16))
+        lg_gpu = orc.lm_head_logits(shape, head, orc.half_to_real(outs[0]))
+        top2 = np.sort(lg_ref)[-2:]
+        margin, err = float(top2[1] - top2[0]), float(np.abs(lg_ref - lg_gpu).max())
+        print(f"[result] logit margin {margin:.4f}, max logit error {err:.4f}", flush=True)
+        if margin > 2 * err:
+            assert int(np.argmax(lg_gpu)) == int(np.argmax(lg_ref))
+        else:   # a near-tie: either of the two leaders is a correct greedy choice
+            assert int(np.argmax(lg_gpu)) in np.argsort(lg_ref)[-2:]
+    finally:
+        ds.close()
+
+
+def test_pythia_6_9b_stack_shape(orc):
+    """6.9B-shaped layers (head_dim 128, hidden 4096, FFN 16384), 4 of them, 2048
+    cached positions, whole-stack kernel."""
+    shape = synth.ModelShape(4096, 32, 128, 32, 16384, n_layers=4, name="pythia-6.9b-x4")
+    S, cap = 2048, 2049
+    ds, ws, kvs = build_stack(shape, synth.MASTER_SEED, S, cap)
+    try:
+        x = synth.x_input(shape, synth.MASTER_SEED)
+        for mode in (0, 2):
+            ds.set_options(mode=mode)
+            ds.set_inputs(x, S)
+            ds.stack_decode()
+            ds.check()
+            got = ds.result()[0].copy()
+            ref16, _, _, _ = oracle_stack(orc, shape, ws, kvs, S, x[0])
+            assert_block_close(got, ref16, f"6.9B-shape stack mode {mode}")
+    finally:
+        ds.close()
+
+
+def test_batch8_block_with_long_ragged_contexts(orc):
+    """One 6.9B-shaped block, 8 sequences with cached lengths drawn from
+    [1024, 8192]."""
+    shape = synth.ModelShape(4096, 32, 128, 32, 16384, n_layers=1, name="pythia-6.9b-block")
+    B = 8
+    lens = synth.seq_lens(synth.MASTER_SEED, B, 1024, 8192)
+    cap = int(lens.max()) + 1
+    from paper_2604_23553_amd.harness import DeviceStack
+    ds = DeviceStack(shape, cap, B, 1)
+    try:
+        w = synth.layer_weights(shape, synth.MASTER_SEED, 0)
+        K, V = synth.kv_cache(shape, synth.MASTER_SEED, 0, lens, cap, B)
+        ds.load_layer(0, w)
+        ds.load_kv(0, K, V, lens)
+        x = synth.x_input(shape, synth.MASTER_SEED, B)
+        ds.set_inputs(x, lens)
+        ds.block_decode(0)
+        ds.check()
+        got = ds.result()
+        for b in range(B):
+            ref = orc.block_decode_f16(shape, w, K[b].copy(), V[b].copy(), int(lens[b]), x[b])
+            assert_block_close(got[b], ref, f"sequence {b} (S={lens[b]})")
+    finally:
+        ds.close()
+
+
+def test_out_of_range_position_is_reported_not_written(orc):
+    import paper_2604_23553_amd as cf
+    S, cap = 10, 12
+    ds, ws, kvs = build_stack(TINY_STACK, 41, S, cap, layers=1)
+    try:
+        x = synth.x_input(TINY_STACK, 41)
+        before = ds.kv[0].clone()
+        for bad in (cap, -1, 1 << 30):
+            ds.set_inputs(x, bad)
+            ds.block_decode(0)
+            with pytest.raises(cf.CfppError) as e:
+                ds.check()
+            assert e.value.status == -6
+            assert bool((ds.kv[0] == before).all()), "the cache was written for an invalid position"
+        # the context recovers
+        ds.set_inputs(x, S)
+        ds.block_decode(0)
+        ds.check()
+        ref = orc.block_decode_f16(TINY_STACK, ws[0], kvs[0][0][0].copy(), kvs[0][1][0].copy(), S, x[0])
+        assert_block_close(ds.result()[0], ref, "after recovery")
+    finally:
+        ds.close()
+
+
+def test_api_misuse_on_the_gpu():
+    import paper_2604_23553_amd as cf
+    from paper_2604_23553_amd.harness import DeviceStack
+    ds = DeviceStack(TINY_STACK, 16, 1, 1)
+    try:
+        with pytest.raises(cf.CfppError) as e:
+            ds.replay()
+        assert e.value.status == -5                       # replay before capture
+        ds.batch = 1
+        with pytest.raises(cf.CfppError):
+            cf.cfpp_block_decode(ds.ctx, ds.packed[0], ds.kv[0], ds.x, ds.pos, 2, ds.out, ds.s)   # batch > max_batch
+        with pytest.raises(cf.CfppError):
+            cf.cfpp_block_decode(ds.ctx, ds.packed[0], ds.kv[0], ds.x, ds.pos, 1, ds.x, ds.s)     # out aliases x
+        with pytest.raises(cf.CfppError):
+            cf.cfpp_block_decode(ds.ctx, ds.packed[0].data_ptr() + 2, ds.kv[0], ds.x, ds.pos, 1, ds.out, ds.s)
+        with pytest.raises(cf.CfppError):
+            cf.cfpp_set_option(ds.ctx, cf.OPT_THREADS, 100)
+        ds.set_options(mode=2, grid=1024, threads=512)    # cannot all be resident
+        with pytest.raises(cf.CfppError) as e:
+            ds.block_decode(0)
+        assert e.value.status == -2
+    finally:
+        ds.close()
