@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark: one decode step of the 32-layer Pythia-2.8B-shaped stack
+(4096 cached positions, batch 1, fp16 weights/KV, fp32 accumulate) replayed
+from one HIP graph on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode M] [--no-cpu]
+
+Prints ONE JSON line.  A "step" is one replay of the whole stack.  Inputs are
+the seeded synthetic tensors of synth/ (resident in HBM before timing starts).
+The roofline entry divides the algorithmic bytes of one replay by its average
+duration measured with HIP events on the launch stream; cpu_baseline times the
+CPU oracle on a few layers of the same workload on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+PAPER_CONTEXT = {"paper_speedup_vs_hf": 1.34,
+                 "paper_hw": "RTX 5090-class, Pythia-2.8B, 2048 decode tokens (context only)"}
+
+
+def read_traffic_note():
+    """HBM traffic per replay from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", "stack_decode_pythia2.8b_s4096_hbm_traffic.txt")
+    try:
+        vals = {}
+        for line in open(path):
+            if "=" in line and not line.lstrip().startswith("#"):
+                k, v = line.split("=", 1)
+                vals[k.strip()] = float(v.split()[0])
+        return vals["fetch_bytes_per_replay"] + vals["write_bytes_per_replay"]
+    except Exception:
+        return None
+
+
+def cpu_baseline(shape, layers, kvs, x, S, n_layers_sample):
+    """The oracle as it stands, timed on `n_layers_sample` layers of the workload."""
+    import oracle
+    orc = oracle.load("f64")
+    Ks = [kvs[l][0][0].copy() for l in range(n_layers_sample)]
+    Vs = [kvs[l][1][0].copy() for l in range(n_layers_sample)]
+    x0 = orc.half_to_real(x[0])
+    # repeat the sample until about 10 s of CPU work have been timed
+    t0 = time.perf_counter()
+    n_eval = 0
+    while True:
+        cur = x0
+        for l in range(n_layers_sample):
+            cur = orc.block_decode(shape, layers[l], Ks[l], Vs[l], S, cur)
+        n_eval += n_layers_sample
+        dt = time.perf_counter() - t0
+        if dt >= 10.0:
+            break
+    cores = len(os.sched_getaffinity(0))
+    omp = os.environ.get("OMP_NUM_THREADS")
+    if omp:
+        cores = min(cores, int(omp))
+    per_token_us = dt / n_eval * shape.n_layers * 1e6
+    return {"value": per_token_us, "unit": "us/token", "cores": cores, "kind": "oracle",
+            "sample": f"layers 0..{n_layers_sample - 1} of the same {shape.n_layers}-layer workload, "
+                      f"{n_eval} block evaluations in {dt:.1f} s (fp64 C oracle, OpenMP over rows/heads), "
+                      f"scaled to {shape.n_layers} layers per token",
+            "seconds_measured": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--mode", type=int, default=int(os.environ.get("CFPP_MODE", "0")),
+                    help="0: kernel per phase, 1: persistent per block, 2: persistent stack")
+    ap.add_argument("--grid", type=int, default=int(os.environ.get("CFPP_GRID", "0")))
+    ap.add_argument("--threads", type=int, default=int(os.environ.get("CFPP_THREADS", "512")))
+    ap.add_argument("--ctx", type=int, default=4096, help="cached positions per layer")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
+              "(no collectives or sharding are part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    import paper_2604_23553_amd as cf
+    from paper_2604_23553_amd.harness import DeviceStack
+
+    shape = synth.PYTHIA_2_8B
+    S, cap = args.ctx, args.ctx + 1
+    seed = synth.MASTER_SEED
+    t_gen = time.perf_counter()
+    layers = synth.stack_weights(shape, seed, workers=16)
+    ds = DeviceStack(shape, cap, 1)
+    kvs = []
+    for l in range(shape.n_layers):
+        ds.load_layer(l, layers[l])
+        kv = synth.kv_cache(shape, seed, l, S, cap, poison=False)
+        ds.load_kv(l, kv[0], kv[1], S)
+        kvs.append(kv if l < 4 else None)      # the CPU leg only needs a few layers
+    x = synth.x_input(shape, seed)
+    ds.set_inputs(x, S)
+    ds.set_options(mode=args.mode, grid=args.grid, threads=args.threads)
+    t_gen = time.perf_counter() - t_gen
+
+    ds.capture()
+    for _ in range(args.warmup):
+        ds.replay()
+    ds.check()
+
+    # timed region: exactly K replays between two synchronisations; HIP events on
+    # the launch stream bracket every replay for the per-launch duration
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in evs:
+        a.record(ds.stream)
+        ds.replay()
+        b.record(ds.stream)
+    ds.stream.synchronize()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ds.check()
+    per = np.array([a.elapsed_time(b) for a, b in evs]) * 1e3        # us per replay
+    us_wall = wall / args.steps * 1e6
+    us_launch = float(per.mean())
+
+    alg_bytes = cf.cfpp_algorithmic_bytes(ds.cfg, [S], shape.n_layers)
+    achieved = alg_bytes / (us_launch * 1e-6) / 1e9
+    grid = cf.cfpp_get_option(ds.ctx, cf.OPT_GRID)
+    out = {
+        "metric": "us_per_token_decode_32L_pythia2.8b_bs1",
+        "value": us_wall,
+        "unit": "us/token",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": us_wall / 1e3,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 weights/KV, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"32-layer Pythia-2.8B-shaped decode step, ctx {S}, batch 1, one HIP graph replay",
+                   "hidden": shape.hidden, "n_heads": shape.n_heads, "head_dim": shape.head_dim,
+                   "ffn": shape.ffn, "n_layers": shape.n_layers, "ctx": S, "batch": 1,
+                   "launch_mode": args.mode, "grid": grid, "threads": args.threads},
+        "tokens_per_s": 1e6 / us_wall,
+        "us_per_block": us_wall / shape.n_layers,
+        "us_per_replay_events": {"mean": us_launch, "median": float(np.median(per)),
+                                 "min": float(per.min()), "p95": float(np.percentile(per, 95))},
+        "achieved_hbm_GBps": achieved,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic_note(),
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "launch": "one graph replay = all kernels of the 32-layer step"},
+        "context": PAPER_CONTEXT,
+        "input_generation_s": t_gen,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(shape, layers, kvs, x, S, 4)
+    ds.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
