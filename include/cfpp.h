@@ -148,7 +148,11 @@ void cfpp_destroy(cfpp_ctx *ctx);
  * and replay). */
 #define CFPP_OPT_MODE     1  /* 0: one kernel per phase (3 per block);
                                 1: one persistent kernel per block;
-                                2: one persistent kernel for the whole stack  */
+                                2: one persistent kernel for the whole stack;
+                                3: one wave-specialised streaming kernel for the
+                                   whole stack (split-phase events, prefetched
+                                   tiles; selected shape classes, else
+                                   CFPP_EUNSUPPORTED)                          */
 #define CFPP_OPT_GRID     2  /* workgroups; 0 = one per compute unit          */
 #define CFPP_OPT_THREADS  3  /* threads per workgroup: 256 or 512             */
 #define CFPP_OPT_PROFILE_SKIP 100 /* profiling aid only: bit mask of sub-steps to
@@ -201,6 +205,7 @@ cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream);
  * most recent block to HOST memory as fp32.  which: 0 = rotated q [batch, h],
  * 1 = GELU(up) [batch, f], 2 = down projection incl. bias [batch, h],
  * 3 = attention output before the output projection [batch, h].
+ * (Mode 3 keeps the down projection on chip: tap 2 is then not updated.)
  * count = number of floats to copy (from the start). */
 cfpp_status cfpp_debug_read(cfpp_ctx *ctx, int32_t which, float *dst_host, size_t count,
                             cfpp_stream stream);

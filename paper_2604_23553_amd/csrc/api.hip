@@ -184,6 +184,7 @@ struct cfpp_ctx {
     char *ws;
     int n_cu;
     int mode, grid, threads, debug;
+    int events_grid;   // grid size the stream kernel's event counters are consistent with (0: zeroed)
     size_t lds_limit;
     bool prepared;
     hipGraph_t graph;
@@ -221,6 +222,7 @@ extern "C" cfpp_status cfpp_create(const cfpp_config *c, void *workspace, size_t
     ctx->grid = 0;
     ctx->threads = 512;
     ctx->debug = 0;
+    ctx->events_grid = 0;
     ctx->lds_limit = prop.sharedMemPerBlock > 0 ? (size_t)prop.sharedMemPerBlock : 65536;
     ctx->prepared = false;
     ctx->graph = nullptr;
@@ -229,6 +231,7 @@ extern "C" cfpp_status cfpp_create(const cfpp_config *c, void *workspace, size_t
 
     // barrier words, error flag and per-head arrival counters start at zero
     hipError_t e = hipMemset(ctx->ws + wl.sync, 0, wl.layer_ptrs - wl.sync);
+    if (e == hipSuccess) e = hipMemset(ctx->ws + wl.events, 0, wl.rope - wl.events);
     // rotary table in double on the host: angle = pos * base^(-2j/r)
     std::vector<float> tab;
     const int half = dm.r / 2;
@@ -266,7 +269,7 @@ extern "C" cfpp_status cfpp_set_option(cfpp_ctx *ctx, int32_t option, int64_t va
     if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
     switch (option) {
     case CFPP_OPT_MODE:
-        if (value < 0 || value > 2) return fail(CFPP_EINVAL, "mode must be 0, 1 or 2");
+        if (value < 0 || value > 3) return fail(CFPP_EINVAL, "mode must be 0, 1, 2 or 3");
         ctx->mode = (int)value;
         return CFPP_OK;
     case CFPP_OPT_GRID:
@@ -353,6 +356,7 @@ static cfpp_status prepare(cfpp_ctx *ctx)
 {
     if (ctx->prepared) return CFPP_OK;
     HIP_OK(prepare_kernels(160 * 1024));
+    HIP_OK(prepare_stream_kernels(160 * 1024));
     ctx->prepared = true;
     return CFPP_OK;
 }
@@ -384,6 +388,7 @@ static StepParams make_params(const cfpp_ctx *ctx, const Shape &sh, int b, const
     P.nsl_down = sh.nsl_down; P.nsl_dense = sh.nsl_dense;
     P.lds_floats = sh.lds_floats;
     P.debug = ctx->debug;
+    P.trace = reinterpret_cast<unsigned long long *>(ctx->ws + wl.trace);
     return P;
 }
 
@@ -412,6 +417,39 @@ static cfpp_status check_io(const cfpp_ctx *ctx, const void *x, const int32_t *p
     return CFPP_OK;
 }
 
+// Stream mode (3): shape and residency checks, event counters consistent with the grid.
+static cfpp_status stream_check(cfpp_ctx *ctx, Shape *sh)
+{
+    sh->threads = 512;
+    if (!stream_supported(ctx->dm, sh->grid))
+        return fail(CFPP_EUNSUPPORTED,
+                    "stream mode supports the 2.8B-like (d 80, h 2560), 6.9B-like (d 128, h 4096) and "
+                    "h-512 (d 64) shape classes with grid >= n_heads; use mode 0 for this shape");
+    return CFPP_OK;
+}
+
+static cfpp_status stream_residency(const cfpp_ctx *ctx, const Shape &sh, const StepParams &P)
+{
+    const size_t lds = stream_lds_bytes(ctx->dm, P, sh.threads, nullptr);
+    if (lds > 160 * 1024) return fail(CFPP_EUNSUPPORTED, "stream mode needs %zu bytes of LDS", lds);
+    int per_cu = 0;
+    HIP_OK(stream_occupancy(ctx->dm, sh.threads, lds, &per_cu));
+    if ((long long)per_cu * ctx->n_cu < sh.grid)
+        return fail(CFPP_EUNSUPPORTED, "stream mode needs all %d workgroups resident, device fits %d x %d",
+                    sh.grid, per_cu, ctx->n_cu);
+    return CFPP_OK;
+}
+
+// (not capturable: records a memset) zero the event counters when the grid they
+// were counted with changes
+static cfpp_status stream_rearm(cfpp_ctx *ctx, int grid, hipStream_t s)
+{
+    if (ctx->events_grid == grid) return CFPP_OK;
+    HIP_OK(hipMemsetAsync(ctx->ws + ctx->wl.events, 0, ctx->wl.rope - ctx->wl.events, s));
+    ctx->events_grid = grid;
+    return CFPP_OK;
+}
+
 extern "C" cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer, void *kv_layer,
                                          const void *x, const int32_t *pos_dev, int32_t batch, void *out,
                                          cfpp_stream stream)
@@ -423,8 +461,26 @@ extern "C" cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer
     Shape sh;
     if ((st = launch_shape(ctx, &sh)) != CFPP_OK) return st;
     if ((st = prepare(ctx)) != CFPP_OK) return st;
-    if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (ctx->mode == 3) {
+        if ((st = stream_check(ctx, &sh)) != CFPP_OK) return st;
+        if ((st = stream_residency(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, 1))) != CFPP_OK) return st;
+        if ((st = stream_rearm(ctx, sh.grid, s)) != CFPP_OK) return st;
+        LayerPtrs ptrs;
+        std::memset(&ptrs, 0, sizeof ptrs);
+        ptrs.w[0] = static_cast<const __half *>(packed_layer);
+        ptrs.kv[0] = static_cast<__half *>(kv_layer);
+        LayerPtrs *dev_ptrs = reinterpret_cast<LayerPtrs *>(ctx->ws + ctx->wl.layer_ptrs);
+        HIP_OK(launch_store_layer_ptrs(ptrs, dev_ptrs, 1, s));
+        for (int b = 0; b < batch; ++b) {
+            const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, 1);
+            HIP_OK(launch_stack_stream(P, dev_ptrs, reinterpret_cast<unsigned long long *>(ctx->ws + ctx->wl.events),
+                                       sh.grid, sh.threads, s));
+        }
+        ctx->last_batch = batch;
+        return CFPP_OK;
+    }
+    if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
     for (int b = 0; b < batch; ++b) {
         const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, 1);
         if (ctx->mode == 0)
@@ -454,7 +510,12 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
             return fail(CFPP_EINVAL, "layer %d: NULL or misaligned pointer", l);
     Shape sh;
     if ((st = launch_shape(ctx, &sh)) != CFPP_OK) return st;
-    if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
+    if (ctx->mode == 3) {
+        if ((st = stream_check(ctx, &sh)) != CFPP_OK) return st;
+        if ((st = stream_residency(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, L))) != CFPP_OK) return st;
+        if (store_table && (st = stream_rearm(ctx, sh.grid, s)) != CFPP_OK) return st;
+        if (!store_table && ctx->events_grid != sh.grid) return fail(CFPP_ESTATE, "event counters not armed for this grid");
+    } else if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
     LayerPtrs ptrs;
     std::memset(&ptrs, 0, sizeof ptrs);
     for (int l = 0; l < L; ++l) {
@@ -462,11 +523,14 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
         ptrs.kv[l] = static_cast<__half *>(kv_layers[l]);
     }
     LayerPtrs *dev_ptrs = reinterpret_cast<LayerPtrs *>(ctx->ws + ctx->wl.layer_ptrs);
-    if (store_table && ctx->mode == 2) HIP_OK(launch_store_layer_ptrs(ptrs, dev_ptrs, L, s));
+    if (store_table && ctx->mode >= 2) HIP_OK(launch_store_layer_ptrs(ptrs, dev_ptrs, L, s));
     if (!launch) return CFPP_OK;
     for (int b = 0; b < batch; ++b) {
         const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, L);
-        if (ctx->mode == 2) {
+        if (ctx->mode == 3) {
+            HIP_OK(launch_stack_stream(P, dev_ptrs, reinterpret_cast<unsigned long long *>(ctx->ws + ctx->wl.events),
+                                       sh.grid, sh.threads, s));
+        } else if (ctx->mode == 2) {
             HIP_OK(launch_stack_persistent(P, dev_ptrs, sh.grid, sh.threads, s));
         } else {
             for (int l = 0; l < L; ++l) {
@@ -543,6 +607,8 @@ extern "C" cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream)
     if (err == kErrNone) return CFPP_OK;
     // clear the flag and re-arm the barrier words and arrival counters
     HIP_OK(hipMemset(ctx->ws + ctx->wl.sync, 0, ctx->wl.layer_ptrs - ctx->wl.sync));
+    HIP_OK(hipMemset(ctx->ws + ctx->wl.events, 0, ctx->wl.rope - ctx->wl.events));
+    ctx->events_grid = 0;
     HIP_OK(hipDeviceSynchronize());
     if (err == kErrBadPos) return fail(CFPP_EDEVICE, "a position in pos_dev was outside [0, max_seq)");
     if (err == kErrBarrierTimeout) return fail(CFPP_EDEVICE, "grid barrier timed out (workgroups not co-resident?)");
@@ -560,6 +626,7 @@ extern "C" cfpp_status cfpp_debug_read(cfpp_ctx *ctx, int32_t which, float *dst_
     case 1: off = ctx->wl.m; n = (size_t)dm.max_batch * dm.f; break;
     case 2: off = ctx->wl.g; n = (size_t)dm.max_batch * dm.h; break;
     case 3: off = ctx->wl.o; n = (size_t)dm.max_batch * dm.h; break;
+    case 4: off = ctx->wl.trace; n = (size_t)kTraceWaves * kTraceLen * 4; break;   // raw timeline words
     default: return fail(CFPP_EINVAL, "unknown tap %d", which);
     }
     if (count > n) return fail(CFPP_EINVAL, "count %zu exceeds the buffer (%zu floats)", count, n);

@@ -26,7 +26,9 @@ struct StepParams {
     int rows_qkv, rows_up, rows_h;   // matrix rows per workgroup (rows_qkv even)
     int nsl_down, nsl_dense;         // K-slices per row for the two GEMVs with few rows
     unsigned lds_floats;             // dynamic LDS the launch provides, in floats
-    int debug;                       // profiling aid: bit mask of parts to skip (results are then wrong)
+    int debug;                       // profiling aid: bit mask of parts to skip (results are then wrong);
+                                     // bit 16: workgroup (debug >> 8) records a timeline into `trace`
+    unsigned long long *trace;
 };
 
 struct LayerPtrs {
@@ -46,6 +48,15 @@ hipError_t launch_store_layer_ptrs(const LayerPtrs &ptrs, LayerPtrs *dst, int n,
 // most co-resident workgroups per compute unit for the persistent kernels
 hipError_t persistent_occupancy(int head_dim, int threads, size_t lds_bytes, int *blocks_per_cu);
 hipError_t prepare_kernels(size_t lds_bytes);
+
+// implemented in stream_kernel.hip: the wave-specialised whole-stack kernel
+bool stream_supported(const Dims &dm, int grid);
+struct StreamLds;
+size_t stream_lds_bytes(const Dims &dm, const StepParams &P, int threads, StreamLds *out);
+hipError_t launch_stack_stream(const StepParams &P, const LayerPtrs *ptrs, unsigned long long *events,
+                               int grid, int threads, hipStream_t s);
+hipError_t stream_occupancy(const Dims &dm, int threads, size_t lds_bytes, int *blocks_per_cu);
+hipError_t prepare_stream_kernels(size_t lds_bytes);
 
 // implemented in prep_kernels.hip
 hipError_t launch_pack_layer(const Dims &dm, const PackedLayout &lay, const void *const src[12],

@@ -10,6 +10,16 @@ namespace cfpp {
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
+// Pointers that come out of a table in memory (per-layer weights, KV caches) lose
+// their address space; the explicit global address space keeps the compiler from
+// emitting FLAT instructions (which also tie up the LDS counter) for them.
+#define CFPP_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ CFPP_GLOBAL T *as_global(T *p)
+{
+    return (CFPP_GLOBAL T *)p;
+}
+
 // ---- data-parallel-primitive lane exchanges (row = 16 lanes) ---------------
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float v)
@@ -82,12 +92,12 @@ __device__ __forceinline__ float dot8(u32x4 w, float4 ya, float4 yb, float acc)
 
 __device__ __forceinline__ u32x4 load16(const __half *p)
 {
-    return *reinterpret_cast<const u32x4 *>(p);
+    return *as_global(reinterpret_cast<const u32x4 *>(p));
 }
 // streamed once, never reused: keep it from displacing the activations in cache
 __device__ __forceinline__ u32x4 load16_stream(const __half *p)
 {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
 }
 
 // Position of activation element k inside an LDS vector laid out for the GEMV
@@ -115,15 +125,15 @@ __device__ __forceinline__ float gelu_erf(float z)
 // this wavefront's earlier exchange stores have been acknowledged by memory.
 __device__ __forceinline__ void xwg_store(float *p, float v)
 {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float xwg_load(const float *p)
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float2 xwg_load2(const float *p)      // p 8-byte aligned
 {
-    const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
+    const unsigned long long v = __hip_atomic_load(as_global(reinterpret_cast<const unsigned long long *>(p)),
                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     float2 f;
     f.x = __uint_as_float((unsigned)(v & 0xffffffffull));
@@ -133,13 +143,13 @@ __device__ __forceinline__ float2 xwg_load2(const float *p)      // p 8-byte ali
 __device__ __forceinline__ void xwg_store_half(__half *p, float v)
 {
     const __half hv = __float2half_rn(v);
-    __hip_atomic_store(reinterpret_cast<unsigned short *>(p), __half_as_ushort(hv), __ATOMIC_RELAXED,
+    __hip_atomic_store(as_global(reinterpret_cast<unsigned short *>(p)), __half_as_ushort(hv), __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
 }
 // 16 bytes of fp16 as two coherent 8-byte loads
 __device__ __forceinline__ u32x4 xwg_load16(const __half *p)
 {
-    const unsigned long long *q = reinterpret_cast<const unsigned long long *>(p);
+    CFPP_GLOBAL const unsigned long long *q = as_global(reinterpret_cast<const unsigned long long *>(p));
     const unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return u32x4{(unsigned)(a & 0xffffffffull), (unsigned)(a >> 32), (unsigned)(b & 0xffffffffull),

@@ -15,6 +15,7 @@ namespace cfpp {
 constexpr int kChunk = 512;        // fp16 values one wavefront covers with one 16-byte load per lane
 constexpr int kMaxLayers = 64;
 constexpr int kMaxGrid = 1024;     // most workgroups any launch uses
+constexpr int kTraceWaves = 8, kTraceLen = 512;   // timeline trace of one workgroup (profiling aid)
 
 CFPP_HD size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -80,6 +81,7 @@ struct WorkspaceLayout {
     size_t sync;      // uint32[64]: grid-barrier words, device error flag
     size_t seg_cnt;   // uint32[max_batch*H]: arrivals per (sequence, head) in the split-KV combine
     size_t layer_ptrs; // device copy of the per-layer pointer table of the stack kernel
+    size_t events;    // uint64 counters of the stream kernel's events: [4 types][1 top + 64 groups], 64 B apart
     size_t rope;      // float2[max_seq][r/2]: (cos, sin) of pos * theta_j
     size_t xres;      // float[2][max_batch][h]: fp32 residual stream between blocks (ping-pong)
     size_t q;         // float[max_batch][h]: rotated queries
@@ -87,6 +89,7 @@ struct WorkspaceLayout {
     size_t g;         // float[max_batch][h]: down projection + bias
     size_t o;         // float[max_batch][h]: attention output
     size_t part;      // float[max_batch*H][part_slots][d+2]: split-KV partials (acc[d], max, sum)
+    size_t trace;     // uint64[kTraceWaves][kTraceLen][2]: (tag, 100 MHz clock) pairs, profiling aid
     size_t total;
     int part_slots;
 };
@@ -102,6 +105,7 @@ CFPP_HD WorkspaceLayout workspace_layout(const Dims &m)
     W.sync = take(64 * 4);
     W.seg_cnt = take((size_t)m.max_batch * m.H * 4);
     W.layer_ptrs = take(2 * kMaxLayers * sizeof(void *));
+    W.events = take(4 * 65 * 64);
     W.rope = take((size_t)m.max_seq * (m.r / 2 > 0 ? m.r / 2 : 1) * 8);
     W.xres = take(2 * (size_t)m.max_batch * m.h * 4);
     W.q = take((size_t)m.max_batch * m.h * 4);
@@ -109,6 +113,7 @@ CFPP_HD WorkspaceLayout workspace_layout(const Dims &m)
     W.g = take((size_t)m.max_batch * m.h * 4);
     W.o = take((size_t)m.max_batch * m.h * 4);
     W.part = take((size_t)m.max_batch * m.H * W.part_slots * (m.d + 2) * 4);
+    W.trace = take((size_t)kTraceWaves * kTraceLen * 16);
     W.total = o;
     return W;
 }

@@ -50,12 +50,14 @@ def check_block(orc, shape, seed, S, cap, **kw):
         assert np.array_equal(o.view(np.uint16), outs[0].view(np.uint16)), "not bit-identical run to run"
     if tap is not None:
         for n in ("q", "m", "g", "attn"):
+            if n == "g" and kw.get("mode") == 3:
+                continue        # the stream kernel keeps the down projection in LDS
             e = errors(tap[n], otaps[n])
             assert e[0] < 2e-3 and e[1] < 2e-4, f"intermediate {n}: {e}"
     return ma, rl
 
 
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 3])
 def test_small_block_config(orc, mode):
     """hidden 512, 8 heads x 64, rotary 16, FFN 2048, 128 cached positions."""
     check_block(orc, synth.SMALL_BLOCK, synth.MASTER_SEED, 128, 129, mode=mode, taps=True, repeats=3)
@@ -71,7 +73,7 @@ def test_launch_shapes(orc, grid, threads):
     check_block(orc, synth.SMALL_BLOCK, 11, 200, 201, mode=0, grid=grid, threads=threads, taps=True)
 
 
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 3])
 def test_pythia_2_8b_block(orc, mode):
     """hidden 2560, 32 heads x 80, rotary 20, FFN 10240, 1024 cached positions."""
     check_block(orc, synth.PYTHIA_2_8B, synth.MASTER_SEED, 1024, 1025, mode=mode, taps=True, repeats=3)

@@ -33,7 +33,7 @@ def oracle_stack(orc, shape, ws, kvs, S, x, b=0):
     return out16, per, Ks, Vs
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
 @pytest.mark.parametrize("graph", [False, True])
 def test_tiny_stack_direct_and_graph(orc, mode, graph):
     S, cap = 70, 75
