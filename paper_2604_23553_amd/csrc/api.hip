@@ -475,7 +475,7 @@ extern "C" cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer
         for (int b = 0; b < batch; ++b) {
             const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, 1);
             HIP_OK(launch_stack_stream(P, dev_ptrs, reinterpret_cast<unsigned long long *>(ctx->ws + ctx->wl.events),
-                                       sh.grid, sh.threads, s));
+                                       reinterpret_cast<float *>(ctx->ws + ctx->wl.tagged), sh.grid, sh.threads, s));
         }
         ctx->last_batch = batch;
         return CFPP_OK;
@@ -529,7 +529,7 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
         const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, L);
         if (ctx->mode == 3) {
             HIP_OK(launch_stack_stream(P, dev_ptrs, reinterpret_cast<unsigned long long *>(ctx->ws + ctx->wl.events),
-                                       sh.grid, sh.threads, s));
+                                       reinterpret_cast<float *>(ctx->ws + ctx->wl.tagged), sh.grid, sh.threads, s));
         } else if (ctx->mode == 2) {
             HIP_OK(launch_stack_persistent(P, dev_ptrs, sh.grid, sh.threads, s));
         } else {

@@ -53,8 +53,9 @@ hipError_t prepare_kernels(size_t lds_bytes);
 bool stream_supported(const Dims &dm, int grid);
 struct StreamLds;
 size_t stream_lds_bytes(const Dims &dm, const StepParams &P, int threads, StreamLds *out);
+// tagged: the workspace's tagged-word region (see stream_tagged_bytes)
 hipError_t launch_stack_stream(const StepParams &P, const LayerPtrs *ptrs, unsigned long long *events,
-                               int grid, int threads, hipStream_t s);
+                               float *tagged, int grid, int threads, hipStream_t s);
 hipError_t stream_occupancy(const Dims &dm, int threads, size_t lds_bytes, int *blocks_per_cu);
 hipError_t prepare_stream_kernels(size_t lds_bytes);
 

@@ -81,7 +81,8 @@ struct WorkspaceLayout {
     size_t sync;      // uint32[64]: grid-barrier words, device error flag
     size_t seg_cnt;   // uint32[max_batch*H]: arrivals per (sequence, head) in the split-KV combine
     size_t layer_ptrs; // device copy of the per-layer pointer table of the stack kernel
-    size_t events;    // uint64 counters of the stream kernel's events: [4 types][1 top + 64 groups], 64 B apart
+    size_t events;    // uint64 counters of the stream kernel's M event: [1 top + 64 groups], 64 B apart
+    size_t tagged;    // stream kernel's tagged words (value, epoch): xt[2][h] qkv[3][h] ot[h] part[H][slots][d+2]
     size_t rope;      // float2[max_seq][r/2]: (cos, sin) of pos * theta_j
     size_t xres;      // float[2][max_batch][h]: fp32 residual stream between blocks (ping-pong)
     size_t q;         // float[max_batch][h]: rotated queries
@@ -105,7 +106,8 @@ CFPP_HD WorkspaceLayout workspace_layout(const Dims &m)
     W.sync = take(64 * 4);
     W.seg_cnt = take((size_t)m.max_batch * m.H * 4);
     W.layer_ptrs = take(2 * kMaxLayers * sizeof(void *));
-    W.events = take(4 * 65 * 64);
+    W.events = take(65 * 64);
+    W.tagged = take(8 * ((size_t)6 * m.h + (size_t)m.H * W.part_slots * (m.d + 2)));
     W.rope = take((size_t)m.max_seq * (m.r / 2 > 0 ? m.r / 2 : 1) * 8);
     W.xres = take(2 * (size_t)m.max_batch * m.h * 4);
     W.q = take((size_t)m.max_batch * m.h * 4);

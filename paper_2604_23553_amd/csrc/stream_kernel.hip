@@ -15,15 +15,22 @@
 //     epilogues (bias, partial rotary, KV append, GELU, residual), the split-KV
 //     merge and last-arriver combine, staging of exchanged vectors into LDS,
 //     and all cross-workgroup signalling.
-//   * Cross-workgroup dependencies are split-phase events (arrive early, wait
+//   * Cross-workgroup dependencies are split-phase (produce early, consume
 //     late).  The block (paper Sec. 2.2, GPT-NeoX residual form) has two
 //     independent chains, attention (QKV -> attention -> dense) and MLP
 //     (up -> down); their tiles are interleaved
 //         QKV | up | attention | down | dense
-//     so that the wait for "all q/k/v written" is covered by the up-projection
-//     stream, "all m written" by the attention stream and "all heads combined"
-//     by the down-projection stream.  Only "layer output complete" (needed by
-//     the next LayerNorm) is exposed, and prefetched tiles cover most of it.
+//     so that "q/k/v of my heads written" is covered by the up-projection
+//     stream, "all of m written" by the attention stream and "all heads
+//     combined" by the down-projection stream.  Only "layer output complete"
+//     (needed by the next LayerNorm) is exposed, and prefetched tiles cover most
+//     of it.
+//   * Small exchanged vectors (layer output, q/k/v of the new token, split-KV
+//     partials, attention output) travel as 8-byte words (fp32 value, epoch
+//     tag) written with one device-scope store each; a consumer polls the words
+//     it needs until they all carry the current epoch, which costs one memory
+//     hop and needs no counters.  The large GELU(up) vector keeps plain fp32 and
+//     is announced by a two-level counter event.
 //
 // Exchange data uses device-scope (sc1) loads/stores (see device_utils.h); all
 // reductions run in a fixed order, so results are bit-identical run to run.
@@ -42,7 +49,7 @@ constexpr int kStreamThreads = 512;
 
 // ---- LDS control words ---------------------------------------------------------
 enum { cFlagY = 0, cFlagQ, cFlagM, cFlagO, cAbort, cCnt2, cCnt3, cCnt5, cCnt6, cCntA0, cCntA1, cCntA2,
-       cCtrlWords = 16 };
+       cStage, cFlagXr, cGatherX, cFlagOr, cGatherO, cCtrlWords = 24 };
 
 __device__ __forceinline__ int lds_ld(const int *p)
 {
@@ -70,63 +77,165 @@ __device__ __forceinline__ bool lds_wait_ge(int *ctrl, int word, int target, uns
     return true;
 }
 
-// ---- cross-workgroup events ------------------------------------------------------
-// Four event types (Q, M, O, X).  Each has a two-level counter tree that only
-// grows: workgroups add to their group's counter (groups of 16), the last of a
-// group adds to the top counter, waiters poll the top counter.  The k-th
-// instance of a type since the counters were zeroed is complete when
-// top >= ngroups * k.  (A full X event separates successive instances of every
-// type, so instances cannot mix.)
-struct Events {
-    unsigned long long *base;     // [4][1 + 64] counters, one per 64-byte slot
-    unsigned long long top0[4];   // top counter value this launch started from (multiple of ngroups)
+// ---- cross-workgroup signalling ----------------------------------------------------
+// (a) Tagged words: see the file header.  The epoch of layer l of this launch is
+//     E0 + l + 1 with E0 = number of M events completed before the launch, so
+//     epochs never repeat while the counters are not zeroed (the host zeroes the
+//     tagged buffers together with the counters).
+__device__ __forceinline__ void xwg_store_tagged(float *p, float v, unsigned tag)
+{
+    const unsigned long long w = ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
+    __hip_atomic_store(as_global(reinterpret_cast<unsigned long long *>(p)), w, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct Abort {
+    int *ctrl;
+    unsigned *err;
+    unsigned long long t0;
+    unsigned spins;
+    __device__ __forceinline__ void start() { t0 = wall_clock64(); spins = 0; }
+    // call once per unsuccessful poll; true = give up
+    __device__ __forceinline__ bool tick()
+    {
+        if ((++spins & 63u) == 0) {
+            if (lds_ld(ctrl + cAbort)) return true;
+            if (wall_clock64() - t0 > 200000000ull) {       // 2 s at 100 MHz
+                lds_st(ctrl + cAbort, 1);
+                __hip_atomic_store(err, (unsigned)kErrBarrierTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return true;
+            }
+        }
+        return false;
+    }
+};
+
+// One wavefront fetches n tagged words starting at buf (lane handles words
+// lane, lane + 64, ...) until every one carries `epoch`; values go to dst
+// through `put(i, value)`.  MAXJ*64 >= n.
+template <int MAXJ, class Put>
+__device__ __forceinline__ bool poll_tagged(const float *buf, int n, unsigned epoch, Abort &ab, Put put)
+{
+    const int lane = threadIdx.x & 63;
+    ab.start();
+    // cheap first: one word per lane, spread over the range, until those are there
+    while (true) {
+        const int i = (int)(((long long)lane * n) >> 6);
+        const float2 w = xwg_load2(buf + 2 * i);
+        if (__all(i >= n || __float_as_uint(w.y) == epoch)) break;
+        if (ab.tick()) return false;
+        __builtin_amdgcn_s_sleep(2);
+    }
+    while (true) {
+        float2 w[MAXJ];
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) {
+            const int i = lane + 64 * j;
+            w[j] = i < n ? xwg_load2(buf + 2 * i) : float2{0.f, __uint_as_float(epoch)};
+        }
+        bool ok = true;
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) ok &= __float_as_uint(w[j].y) == epoch;
+        if (__all(ok)) {
+#pragma unroll
+            for (int j = 0; j < MAXJ; ++j) {
+                const int i = lane + 64 * j;
+                if (i < n) put(i, w[j].x);
+            }
+            return true;
+        }
+        if (ab.tick()) return false;
+    }
+}
+
+// One wavefront of `nparts` fetches its share of n tagged words (words
+// (j*nparts + part)*64 + lane) until all carry `epoch`, passing values to put.
+template <class Put>
+__device__ __forceinline__ bool gather_tagged_share(const float *buf, int n, unsigned epoch, int part, int nparts,
+                                                    Abort &ab, Put put)
+{
+    const int lane = threadIdx.x & 63;
+    constexpr int UB = 4;
+    ab.start();
+    for (int base = 0; base < n; base += UB * nparts * 64) {
+        while (true) {
+            float2 w[UB];
+#pragma unroll
+            for (int j = 0; j < UB; ++j) {
+                const int i = base + (j * nparts + part) * 64 + lane;
+                w[j] = i < n ? xwg_load2(buf + 2 * i) : float2{0.f, __uint_as_float(epoch)};
+            }
+            bool ok = true;
+#pragma unroll
+            for (int j = 0; j < UB; ++j) ok &= __float_as_uint(w[j].y) == epoch;
+            if (__all(ok)) {
+#pragma unroll
+                for (int j = 0; j < UB; ++j) {
+                    const int i = base + (j * nparts + part) * 64 + lane;
+                    if (i < n) put(i, w[j].x);
+                }
+                break;
+            }
+            if (ab.tick()) return false;
+        }
+    }
+    return true;
+}
+
+// wait until one word per lane, spread over the n words, carries `epoch`
+__device__ __forceinline__ bool sentinel_tagged(const float *buf, int n, unsigned epoch, Abort &ab)
+{
+    const int lane = threadIdx.x & 63;
+    ab.start();
+    while (true) {
+        const int i = (int)(((long long)lane * n) >> 6);
+        const float2 w = xwg_load2(buf + 2 * i);
+        if (__all(__float_as_uint(w.y) == epoch)) return true;
+        if (ab.tick()) return false;
+        __builtin_amdgcn_s_sleep(2);
+    }
+}
+
+// (b) The M event ("every workgroup has written its rows of GELU(up)"): a
+//     two-level counter tree that only grows.  Workgroups add to their group's
+//     counter (groups of 16), the last of a group adds to the top counter,
+//     waiters poll the top counter; the k-th instance since the counters were
+//     zeroed is complete when top >= ngroups * k.
+struct MEvent {
+    unsigned long long *base;     // [1 top + 64 groups] counters, one per 64-byte slot
+    unsigned long long top0;      // top counter this launch started from (multiple of ngroups)
     int ngroups, gsize, g;
 
-    __device__ __forceinline__ unsigned long long *top(int type) const { return base + (size_t)type * 65 * 8; }
-    __device__ __forceinline__ unsigned long long *group(int type) const
-    {
-        return base + ((size_t)type * 65 + 1 + (g >> 4)) * 8;
-    }
+    __device__ __forceinline__ unsigned long long *top() const { return base; }
+    __device__ __forceinline__ unsigned long long *group() const { return base + (size_t)(1 + (g >> 4)) * 8; }
     __device__ __forceinline__ void init(unsigned long long *b, int G, int wg)
     {
         base = b;
         g = wg;
         ngroups = (G + 15) >> 4;
-        const int first = (wg >> 4) << 4;
-        gsize = min(16, G - first);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const unsigned long long v = __hip_atomic_load(top(t), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            top0[t] = v - v % (unsigned long long)ngroups;
-        }
+        gsize = min(16, G - ((wg >> 4) << 4));
+        const unsigned long long v = __hip_atomic_load(as_global(top()), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        top0 = v - v % (unsigned long long)ngroups;
     }
+    __device__ __forceinline__ unsigned epoch0() const { return (unsigned)(top0 / (unsigned long long)ngroups); }
     // all of this wavefront's earlier exchange stores must be acknowledged first
-    __device__ __forceinline__ void arrive(int type)
+    __device__ __forceinline__ void arrive()
     {
         xwg_wait_stores();
         if ((threadIdx.x & 63) == 0) {
             const unsigned long long old =
-                __hip_atomic_fetch_add(group(type), 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(as_global(group()), 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((old + 1) % (unsigned long long)gsize == 0)
-                __hip_atomic_fetch_add(top(type), 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(as_global(top()), 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    // instance: 1-based count of this type within the launch
-    __device__ __forceinline__ bool wait(int type, int instance, int *ctrl, unsigned *err)
+    __device__ __forceinline__ bool wait(int instance, Abort &ab)
     {
-        const unsigned long long target = top0[type] + (unsigned long long)ngroups * instance;
-        const unsigned long long t0 = wall_clock64();
-        unsigned spins = 0;
-        while (__hip_atomic_load(top(type), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            if ((++spins & 255u) == 0) {
-                if (lds_ld(ctrl + cAbort)) return false;
-                if (wall_clock64() - t0 > 200000000ull) {       // 2 s at 100 MHz
-                    lds_st(ctrl + cAbort, 1);
-                    __hip_atomic_store(err, (unsigned)kErrBarrierTimeout, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-                    return false;
-                }
-            }
+        const unsigned long long target = top0 + (unsigned long long)ngroups * instance;
+        ab.start();
+        while (__hip_atomic_load(as_global(top()), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            if (ab.tick()) return false;
+            __builtin_amdgcn_s_sleep(2);
         }
         return true;
     }
@@ -194,11 +303,20 @@ struct Work {
 
 // LDS offsets (in floats), filled in by the host
 struct StreamLds {
-    int ctrl, y1, y2, qs, kn, vn, m, o, res2, res3, res5, res6, gloc, wpart, total;
+    int ctrl, y1, y2, xs, qs, kn, vn, m, o, res2, res3, res5, res6, gloc, wpart, comb, total;
+};
+
+// tagged exchange buffers in the workspace (8 bytes per value)
+struct StreamTagged {
+    float *xt;      // [2][h]  layer output (ping-pong by layer parity)
+    float *qt;      // [3][h]  q, k, v of the new token, (head, dim) order
+    float *ot;      // [h]     attention output
+    float *part;    // [H][part_slots][d+2] split-KV partials
 };
 
 struct StreamParams {
     StreamLds L;
+    StreamTagged T;
     unsigned long long *events;
 };
 
@@ -243,7 +361,7 @@ __device__ __forceinline__ void consume_gemv(const u32x4 (&buf)[TL], const float
 }
 
 template <int D, int CTH, int RTH, int CTF, int RTF>
-__device__ void streamer_main(const StepParams &P, const LayerPtrs *__restrict__ ptrs, const StreamParams &SP,
+__device__ __forceinline__ void streamer_main(const StepParams &P, const LayerPtrs *__restrict__ ptrs, const StreamParams &SP,
                               const Work<D, CTH, RTH, CTF, RTF> &W, int pos, float *lds, int wave, int NS)
 {
     using WK = Work<D, CTH, RTH, CTF, RTF>;
@@ -328,9 +446,8 @@ __device__ void streamer_main(const StepParams &P, const LayerPtrs *__restrict__
     float mrun = -INFINITY, lrun = 0.f;
     bool active = false;
     int act_sl = 0;
-    int flushed_layers = 0;      // layers whose segments this wavefront has all flushed
-    int next_flush = 0;          // next segment to flush in layer `flushed_layers`
-    int knownY = 0, knownQ = 0, knownM = 0, knownO = 0;
+    int next_flush = 0;          // next segment of the current layer to flush
+    int knownY = 0, knownQ = 0, knownM = 0;
     bool ok = true;
 
     auto need_flag = [&](int &known, int word, int target) {
@@ -371,14 +488,95 @@ __device__ void streamer_main(const StepParams &P, const LayerPtrs *__restrict__
         if (lane == 0)
             __hip_atomic_fetch_add(ctrl + cCntA0 + sl, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     };
-    // every layer below `upto_layer` fully flushed, then segments below upto_sl of that layer
-    auto flush_until = [&](int upto_layer, int upto_sl) {
-        while (ok && (flushed_layers < upto_layer || (flushed_layers == upto_layer && next_flush < upto_sl))) {
-            if (next_flush >= W.nseg) { ++flushed_layers; next_flush = 0; continue; }
-            need_flag(knownQ, cFlagQ, flushed_layers + 1);     // never ahead of that layer's q/k/v
+    // flush of layer `layer`: segments next_flush .. upto_sl-1 (a null partial where this
+    // wavefront had no row); never ahead of that layer's q/k/v
+    auto flush_layer = [&](int layer, int upto_sl) {
+        while (ok && next_flush < upto_sl) {
+            need_flag(knownQ, cFlagQ, layer + 1);
             if (!ok) break;
             flush_seg(next_flush);
             ++next_flush;
+        }
+    };
+
+    // Layer inputs x (layers 1..upto_layer) and attention outputs o (layers below
+    // upto) arrive as tagged words; once the service wavefront has seen them
+    // (nearly) complete, every streamer fetches its share into LDS.
+    Abort ab;
+    ab.ctrl = ctrl;
+    ab.err = err;
+    unsigned E0 = 0;
+    {
+        const unsigned long long v = __hip_atomic_load(as_global(SP.events), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long ng = (unsigned long long)((gridDim.x + 15) >> 4);
+        E0 = (unsigned)((v - v % ng) / ng);
+    }
+    float *xs = lds + SP.L.xs, *olw = lds + SP.L.o;
+    // x input of `layer` (> 0): this wavefront's share into LDS
+    auto gather_x = [&](int layer) {
+        int kf = 0;
+        need_flag(kf, cFlagXr, layer);
+        if (!ok) return;
+        const float *xin_t = SP.T.xt + (size_t)((layer - 1) & 1) * 2 * h;
+        ok = gather_tagged_share(xin_t, h, E0 + (unsigned)layer, wave, NS, ab, [&](int i, float v) { xs[i] = v; });
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (lane == 0) __hip_atomic_fetch_add(ctrl + cGatherX, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    // attention output of `layer`: share into LDS, then wait for the other streamers' shares
+    auto gather_o = [&](int layer) {
+        int kf = 0;
+        need_flag(kf, cFlagOr, layer + 1);
+        if (!ok) return;
+        const int hp = (h + kChunk - 1) / kChunk * kChunk;
+        ok = gather_tagged_share(SP.T.ot, h, E0 + (unsigned)layer + 1u, wave, NS, ab,
+                                 [&](int i, float v) { olw[lds_perm(i)] = v; });
+        for (int i = h + wave * 64 + lane; i < hp; i += NS * 64) olw[lds_perm(i)] = 0.f;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (lane == 0) __hip_atomic_fetch_add(ctrl + cGatherO, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (ok) ok = lds_wait_ge(ctrl, cGatherO, NS * (layer + 1), err);
+    };
+    // GELU(up) of `layer`: share into LDS once the service wavefront has seen the M event,
+    // then wait for the other streamers' shares
+    auto stage_m = [&](int layer) {
+        need_flag(knownM, cFlagM, layer + 1);
+        if (!ok) return;
+        constexpr int UNM = 8;
+        const int n2 = f >> 1, np2 = ((f + kChunk - 1) / kChunk * kChunk) >> 1;
+        float *mw = lds + SP.L.m;
+        for (int base = 0; base < np2; base += UNM * NS * 64) {
+            float2 v[UNM];
+#pragma unroll
+            for (int j = 0; j < UNM; ++j) {
+                const int i2 = base + (j * NS + wave) * 64 + lane;
+                v[j] = i2 < n2 ? xwg_load2(P.m + 2 * i2) : float2{0.f, 0.f};
+            }
+#pragma unroll
+            for (int j = 0; j < UNM; ++j) {
+                const int i2 = base + (j * NS + wave) * 64 + lane;
+                if (i2 < np2) *reinterpret_cast<float2 *>(mw + lds_perm(i2 * 2)) = v[j];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (lane == 0) __hip_atomic_fetch_add(ctrl + cStage, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        tr.mark(300);
+        ok = lds_wait_ge(ctrl, cStage, NS * (layer + 1), err);
+        tr.mark(301);
+    };
+
+    // Every streamer performs the same chain of obligations, in the order the
+    // data become available: for each layer  0: fetch x (layers > 0)  1: flush
+    // attention partials  2: stage m  3: fetch o.  `ob` = number completed
+    // (index = 4 * layer + kind).  A tile may only need obligations that precede
+    // it in this chain, so no streamer can wait on something that waits on it.
+    int ob = 0;
+    auto advance = [&](int target) {
+        while (ok && ob < target) {
+            const int layer = ob >> 2, kind = ob & 3;
+            if (kind == 0) { if (layer > 0) gather_x(layer); }
+            else if (kind == 1) { flush_layer(layer, W.nseg); next_flush = 0; }
+            else if (kind == 2) stage_m(layer);
+            else gather_o(layer);
+            ++ob;
         }
     };
 
@@ -394,7 +592,8 @@ __device__ void streamer_main(const StepParams &P, const LayerPtrs *__restrict__
             const int rho = (int)W.r0 + idx;
             const int s = rho / W.R, row = rho - s * W.R;
             const int sl = s - W.s_first;
-            flush_until(layer, sl);
+            advance(4 * layer + 1);
+            flush_layer(layer, sl);
             need_flag(knownQ, cFlagQ, layer + 1);
             if (!ok) return;
             if (!active) {                                   // first row of this wavefront in this head
@@ -444,7 +643,7 @@ __device__ void streamer_main(const StepParams &P, const LayerPtrs *__restrict__
             return;
         }
         // a GEMV tile; steps 5 and 6 come after this layer's attention rows
-        flush_until(step > 4 ? layer + 1 : layer, 0);
+        advance(4 * layer + (step <= 3 ? 1 : step == 5 ? 3 : 4));
         if (!ok) return;
         if (step == 2) {
             need_flag(knownY, cFlagY, layer + 1);
@@ -457,14 +656,10 @@ __device__ void streamer_main(const StepParams &P, const LayerPtrs *__restrict__
             consume_gemv<CTH, RTH, TL>(buf, y2, 0, res3, idx * RTH, W.u_n - idx * RTH, 1, 0, lane);
             done_tile(cCnt3);
         } else if (step == 5) {
-            need_flag(knownM, cFlagM, layer + 1);
-            if (!ok) return;
             const int rg = idx / W.nsl_f, sl = idx - rg * W.nsl_f;
             consume_gemv<CTF, RTF, TL>(buf, ml, sl * CTF, res5, rg * RTF, W.r_n - rg * RTF, W.nsl_f, sl, lane);
             done_tile(cCnt5);
         } else {
-            need_flag(knownO, cFlagO, layer + 1);
-            if (!ok) return;
             consume_gemv<CTH, RTH, TL>(buf, ol, 0, res6, idx * RTH, W.r_n - idx * RTH, 1, 0, lane);
             done_tile(cCnt6);
         }
@@ -483,29 +678,33 @@ __device__ void streamer_main(const StepParams &P, const LayerPtrs *__restrict__
         consume(bufB, Tt);
         Tt += NS;
     }
-    if (ok) flush_until(L, 0);
+    advance(4 * L);
     tr.mark(999);
 }
 
 // ---- service wavefront ---------------------------------------------------------------
 template <int D, int CTH, int RTH, int CTF, int RTF>
-__device__ void service_main(const StepParams &P, const LayerPtrs *__restrict__ ptrs, const StreamParams &SP,
+__device__ __forceinline__ void service_main(const StepParams &P, const LayerPtrs *__restrict__ ptrs, const StreamParams &SP,
                              const Work<D, CTH, RTH, CTF, RTF> &W, int pos, float *lds, int NS)
 {
-    using A = AttnShape<D>;
     const Dims &dm = P.dm;
     const int lane = threadIdx.x & 63, g = blockIdx.x;
-    const int h = dm.h, f = dm.f, d = dm.d, r = dm.r, L = P.n_layers;
+    const int h = dm.h, d = dm.d, r = dm.r, L = P.n_layers;
     int *ctrl = reinterpret_cast<int *>(lds + SP.L.ctrl);
     unsigned *err = P.sync + kSyncErr;
-    float *y1 = lds + SP.L.y1, *y2 = lds + SP.L.y2, *ml = lds + SP.L.m, *ol = lds + SP.L.o;
+    float *y1 = lds + SP.L.y1, *y2 = lds + SP.L.y2;
     const float *res2 = lds + SP.L.res2, *res3 = lds + SP.L.res3, *res5 = lds + SP.L.res5, *res6 = lds + SP.L.res6;
-    float *qs = lds + SP.L.qs, *gloc = lds + SP.L.gloc;
-    unsigned *kn = reinterpret_cast<unsigned *>(lds + SP.L.kn), *vn = reinterpret_cast<unsigned *>(lds + SP.L.vn);
+    float *qs = lds + SP.L.qs, *gloc = lds + SP.L.gloc, *comb = lds + SP.L.comb, *xs = lds + SP.L.xs;
+    __half *kn = reinterpret_cast<__half *>(lds + SP.L.kn), *vn = reinterpret_cast<__half *>(lds + SP.L.vn);
     const float *wpart = lds + SP.L.wpart;
+    float *qt = SP.T.qt, *kt = SP.T.qt + 2 * (size_t)h, *vt = SP.T.qt + 4 * (size_t)h;
 
-    Events ev;
+    MEvent ev;
     ev.init(SP.events, gridDim.x, g);
+    const unsigned E0 = ev.epoch0();
+    Abort ab;
+    ab.ctrl = ctrl;
+    ab.err = err;
     Tracer tr;
     tr.init(P, NS);
 
@@ -513,8 +712,9 @@ __device__ void service_main(const StepParams &P, const LayerPtrs *__restrict__ 
         const __half *w = ptrs->w[layer];
         __half *kv = ptrs->kv[layer];
         const bool first = layer == 0, last = layer == L - 1;
-        const float *xin32 = first ? nullptr : P.xres + (size_t)((layer - 1) & 1) * h;
-        float *xout32 = last ? nullptr : P.xres + (size_t)(layer & 1) * h;
+        const unsigned epoch = E0 + (unsigned)layer + 1u;
+        const float *xin_t = SP.T.xt + (size_t)((layer - 1) & 1) * 2 * h;    // tagged input of layers > 0
+        float *xout_t = SP.T.xt + (size_t)(layer & 1) * 2 * h;
 
         // ---- C1: layer input complete -> LayerNorm 1 and 2 into LDS ----
         {
@@ -531,7 +731,21 @@ __device__ void service_main(const StepParams &P, const LayerPtrs *__restrict__ 
                 }
             }
             tr.mark(10);
-            if (!first && !ev.wait(3, layer, ctrl, err)) return;
+            // x into LDS scratch (natural order), then registers by 8-element group
+            if (first) {
+                for (int gi = lane; gi < ngrp; gi += 64) {
+                    const u32x4 xr = load16(P.x_in + gi * 8);
+                    const float2 a = unpack_h2(xr.x), b = unpack_h2(xr.y), c = unpack_h2(xr.z), e2 = unpack_h2(xr.w);
+                    *reinterpret_cast<float4 *>(xs + gi * 8) = float4{a.x, a.y, b.x, b.y};
+                    *reinterpret_cast<float4 *>(xs + gi * 8 + 4) = float4{c.x, c.y, e2.x, e2.y};
+                }
+            } else {
+                // tell the streamers when the previous layer's output looks complete; they
+                // fetch it into LDS together
+                if (!sentinel_tagged(xin_t, h, epoch - 1u, ab)) return;
+                if (lane == 0) lds_st(ctrl + cFlagXr, layer);
+                if (!lds_wait_ge(ctrl, cGatherX, NS * layer, err)) return;
+            }
             tr.mark(11);
             float xv[CTH][8];
             float s = 0.f;
@@ -541,17 +755,10 @@ __device__ void service_main(const StepParams &P, const LayerPtrs *__restrict__ 
 #pragma unroll
                 for (int e = 0; e < 8; ++e) xv[j][e] = 0.f;
                 if (gi < ngrp) {
-                    if (first) {
-                        const u32x4 xr = load16(P.x_in + gi * 8);
-                        const float2 a = unpack_h2(xr.x), b = unpack_h2(xr.y), c = unpack_h2(xr.z), e2 = unpack_h2(xr.w);
-                        xv[j][0] = a.x; xv[j][1] = a.y; xv[j][2] = b.x; xv[j][3] = b.y;
-                        xv[j][4] = c.x; xv[j][5] = c.y; xv[j][6] = e2.x; xv[j][7] = e2.y;
-                    } else {
-                        const float *xp = xin32 + gi * 8;
-                        const float2 a = xwg_load2(xp), b = xwg_load2(xp + 2), c = xwg_load2(xp + 4), e2 = xwg_load2(xp + 6);
-                        xv[j][0] = a.x; xv[j][1] = a.y; xv[j][2] = b.x; xv[j][3] = b.y;
-                        xv[j][4] = c.x; xv[j][5] = c.y; xv[j][6] = e2.x; xv[j][7] = e2.y;
-                    }
+                    const float4 a = *reinterpret_cast<const float4 *>(xs + gi * 8);
+                    const float4 b = *reinterpret_cast<const float4 *>(xs + gi * 8 + 4);
+                    xv[j][0] = a.x; xv[j][1] = a.y; xv[j][2] = a.z; xv[j][3] = a.w;
+                    xv[j][4] = b.x; xv[j][5] = b.y; xv[j][6] = b.z; xv[j][7] = b.w;
                 }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) s += xv[j][e];
@@ -597,11 +804,11 @@ __device__ void service_main(const StepParams &P, const LayerPtrs *__restrict__ 
             tr.mark(12);
         }
 
-        // ---- F2: QKV rows done -> bias, rotary, q to workspace, k/v appended ----
+        // ---- F2: QKV rows done -> bias, rotary; q, k, v as tagged words; k, v appended ----
         {
             const __half *bq = w + P.lay.b_qkv;
             const int npair = W.q_n >> 1;
-            for (int base = 0; base < npair; base += 64) {
+            for (int base = 0; base < npair || base == 0; base += 64) {
                 const int pr = base + lane;
                 const bool act = pr < npair;
                 const int p = W.q_begin + 2 * (act ? pr : 0);
@@ -625,87 +832,64 @@ __device__ void service_main(const StepParams &P, const LayerPtrs *__restrict__ 
                         d0 = i >> 1; d1 = (i >> 1) + (r >> 1);
                     }
                     if (c == 0) {
-                        xwg_store(P.q + n * d + d0, v0);
+                        xwg_store_tagged(qt + 2 * (n * d + d0), v0, epoch);
+                        xwg_store_tagged(qt + 2 * (n * d + d1), v1, epoch);
+                        xwg_store(P.q + n * d + d0, v0);             // test tap
                         xwg_store(P.q + n * d + d1, v1);
                     } else {
-                        xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d0, pos), v0);
-                        xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d1, pos), v1);
+                        // the cache gets the fp16 value; the tagged copy carries exactly that value
+                        const __half h0 = __float2half_rn(v0), h1 = __float2half_rn(v1);
+                        float *tb = c == 1 ? kt : vt;
+                        xwg_store_tagged(tb + 2 * (n * d + d0), __half2float(h0), epoch);
+                        xwg_store_tagged(tb + 2 * (n * d + d1), __half2float(h1), epoch);
+                        xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d0, pos), __half2float(h0));
+                        xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d1, pos), __half2float(h1));
                     }
                 }
             }
-            if (npair == 0 && !lds_wait_ge(ctrl, cCnt2, (layer + 1) * W.n2, err)) return;
             tr.mark(20);
-            ev.arrive(0);
-            tr.mark(21);
         }
 
-        // ---- C4: all q/k/v written -> this workgroup's heads into LDS ----
+        // ---- C4: q, k, v of this workgroup's heads -> LDS ----
         {
-            if (!ev.wait(0, layer + 1, ctrl, err)) return;
-            tr.mark(30);
             for (int sl = 0; sl < W.nseg; ++sl) {
                 const int s = W.s_first + sl;
-                for (int i2 = lane; i2 < D / 2; i2 += 64) {
-                    const float2 v = xwg_load2(P.q + s * D + 2 * i2);
-                    *reinterpret_cast<float2 *>(qs + sl * D + 2 * i2) = v;
-                }
-                // new K and V rows of head s: D halves each, fetched as 8-byte words (4 dims)
-                for (int i4 = lane; i4 < D / 4; i4 += 64) {
-                    const int dim = 4 * i4;
-                    const float2 kw = xwg_load2(reinterpret_cast<const float *>(kv + kv_offset(dm, 0, P.b, s, dim, pos)));
-                    const float2 vw = xwg_load2(reinterpret_cast<const float *>(kv + kv_offset(dm, 1, P.b, s, dim, pos)));
-                    kn[sl * (D / 2) + 2 * i4] = __float_as_uint(kw.x);
-                    kn[sl * (D / 2) + 2 * i4 + 1] = __float_as_uint(kw.y);
-                    vn[sl * (D / 2) + 2 * i4] = __float_as_uint(vw.x);
-                    vn[sl * (D / 2) + 2 * i4 + 1] = __float_as_uint(vw.y);
-                }
+                if (!poll_tagged<(D + 63) / 64>(qt + 2 * (size_t)s * D, D, epoch, ab,
+                                                [&](int i, float v) { qs[sl * D + i] = v; })) return;
+                if (!poll_tagged<(D + 63) / 64>(kt + 2 * (size_t)s * D, D, epoch, ab,
+                                                [&](int i, float v) { kn[sl * D + i] = __float2half_rn(v); })) return;
+                if (!poll_tagged<(D + 63) / 64>(vt + 2 * (size_t)s * D, D, epoch, ab,
+                                                [&](int i, float v) { vn[sl * D + i] = __float2half_rn(v); })) return;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             if (lane == 0) lds_st(ctrl + cFlagQ, layer + 1);
             tr.mark(31);
         }
 
-        // ---- F3: up rows done -> bias, GELU, m to workspace ----
+        // ---- F3: up rows done -> bias, GELU, m to workspace; M event ----
         {
             const __half *bu = w + P.lay.b_up;
-            for (int base = 0; base < W.u_n; base += 64) {
+            for (int base = 0; base < W.u_n || base == 0; base += 64) {
                 const int t = base + lane;
                 const bool act = t < W.u_n;
                 const float bias = act ? __half2float(bu[W.u_begin + t]) : 0.f;
                 if (base == 0 && !lds_wait_ge(ctrl, cCnt3, (layer + 1) * W.n3, err)) return;
                 if (act) xwg_store(P.m + W.u_begin + t, gelu_erf(res3[t] + bias));
             }
-            if (W.u_n == 0 && !lds_wait_ge(ctrl, cCnt3, (layer + 1) * W.n3, err)) return;
             tr.mark(40);
-            ev.arrive(1);
+            ev.arrive();
             tr.mark(41);
         }
 
-        // ---- C5: all of m written -> LDS ----
+        // ---- C5: all of m written -> tell the streamers (they copy it into LDS together) ----
         {
-            if (!ev.wait(1, layer + 1, ctrl, err)) return;
-            tr.mark(50);
-            constexpr int UN = 16;
-            const int n2 = f >> 1, np2 = ((f + kChunk - 1) / kChunk * kChunk) >> 1;
-            for (int base = 0; base < np2; base += UN * 64) {
-                float2 v[UN];
-#pragma unroll
-                for (int j = 0; j < UN; ++j) {
-                    const int i2 = base + lane + j * 64;
-                    v[j] = i2 < n2 ? xwg_load2(P.m + 2 * i2) : float2{0.f, 0.f};
-                }
-#pragma unroll
-                for (int j = 0; j < UN; ++j) {
-                    const int i2 = base + lane + j * 64;
-                    if (i2 < np2) *reinterpret_cast<float2 *>(ml + lds_perm(i2 * 2)) = v[j];
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (!ev.wait(layer + 1, ab)) return;
             if (lane == 0) lds_st(ctrl + cFlagM, layer + 1);
-            tr.mark(51);
+            tr.mark(50);
         }
 
-        // ---- F4: split-KV merge of this workgroup's heads, last arriver combines ----
+        // ---- F4: split-KV merge of this workgroup's heads -> tagged partial slots;
+        //      the first workgroup covering a head combines that head's slots ----
         {
             for (int sl = 0; sl < W.nseg; ++sl) {
                 const int s = W.s_first + sl;
@@ -715,16 +899,14 @@ __device__ void service_main(const StepParams &P, const LayerPtrs *__restrict__ 
                 float M = -INFINITY;
                 for (int wv = 0; wv < NS; ++wv) M = fmaxf(M, wp[wv * (D + 2) + D]);
                 const long long g_lo = (((long long)s * W.R + 1) * W.Geff - 1) / W.T;
-                const long long g_hi = (((long long)(s + 1) * W.R) * W.Geff - 1) / W.T;
-                const int ncover = (int)(g_hi - g_lo + 1);
-                float *slot = P.part + ((size_t)s * P.part_slots + (size_t)(g - g_lo)) * (D + 2);
+                float *slot = SP.T.part + 2 * ((size_t)s * P.part_slots + (size_t)(g - g_lo)) * (D + 2);
                 for (int i = lane; i < D; i += 64) {
                     float O = 0.f;
                     for (int wv = 0; wv < NS; ++wv) {
                         const float mv = wp[wv * (D + 2) + D];
                         if (mv != -INFINITY) O += wp[wv * (D + 2) + i] * expf(mv - M);
                     }
-                    xwg_store(slot + i, O);
+                    xwg_store_tagged(slot + 2 * i, O, epoch);
                 }
                 if (lane == 0) {
                     float Ls = 0.f;
@@ -732,68 +914,50 @@ __device__ void service_main(const StepParams &P, const LayerPtrs *__restrict__ 
                         const float mv = wp[wv * (D + 2) + D];
                         if (mv != -INFINITY) Ls += wp[wv * (D + 2) + D + 1] * expf(mv - M);
                     }
-                    xwg_store(slot + D, M);
-                    xwg_store(slot + D + 1, Ls);
-                }
-                xwg_wait_stores();
-                unsigned old = 0;
-                if (lane == 0)
-                    old = __hip_atomic_fetch_add(&P.seg_cnt[s], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                old = (unsigned)__builtin_amdgcn_readfirstlane((int)old);
-                if (old == (unsigned)(ncover - 1)) {          // this workgroup delivered the last partial
-                    const float *base = P.part + (size_t)s * P.part_slots * (D + 2);
-                    float Mx = -INFINITY;
-                    for (int j = 0; j < ncover; ++j) Mx = fmaxf(Mx, xwg_load(base + (size_t)j * (D + 2) + D));
-                    float Lx = 0.f;
-                    for (int j = 0; j < ncover; ++j) {
-                        const float *sj = base + (size_t)j * (D + 2);
-                        Lx += xwg_load(sj + D + 1) * expf(xwg_load(sj + D) - Mx);
-                    }
-                    for (int i = lane; i < D; i += 64) {
-                        float O = 0.f;
-                        for (int j = 0; j < ncover; ++j) {
-                            const float *sj = base + (size_t)j * (D + 2);
-                            O += xwg_load(sj + i) * expf(xwg_load(sj + D) - Mx);
-                        }
-                        xwg_store(P.o + s * D + i, O / Lx);
-                    }
-                    if (lane == 0)
-                        __hip_atomic_store(&P.seg_cnt[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    xwg_store_tagged(slot + 2 * D, M, epoch);
+                    xwg_store_tagged(slot + 2 * (D + 1), Ls, epoch);
                 }
             }
             tr.mark(65);
-            ev.arrive(2);
+            for (int sl = 0; sl < W.nseg; ++sl) {
+                const int s = W.s_first + sl;
+                const long long g_lo = (((long long)s * W.R + 1) * W.Geff - 1) / W.T;
+                if (g_lo != g) continue;
+                const long long g_hi = (((long long)(s + 1) * W.R) * W.Geff - 1) / W.T;
+                const int ncover = (int)(g_hi - g_lo + 1);
+                const float *base = SP.T.part + 2 * (size_t)s * P.part_slots * (D + 2);
+                const int nwords = ncover * (D + 2);
+                // slots of a head are contiguous; 16 words per lane per pass
+                for (int w0 = 0; w0 < nwords; w0 += 1024) {
+                    if (!poll_tagged<16>(base + 2 * w0, min(1024, nwords - w0), epoch, ab,
+                                         [&](int i, float v) { comb[w0 + i] = v; })) return;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                float Mx = -INFINITY;
+                for (int j = 0; j < ncover; ++j) Mx = fmaxf(Mx, comb[j * (D + 2) + D]);
+                float Lx = 0.f;
+                for (int j = 0; j < ncover; ++j) Lx += comb[j * (D + 2) + D + 1] * expf(comb[j * (D + 2) + D] - Mx);
+                for (int i = lane; i < D; i += 64) {
+                    float O = 0.f;
+                    for (int j = 0; j < ncover; ++j) O += comb[j * (D + 2) + i] * expf(comb[j * (D + 2) + D] - Mx);
+                    xwg_store_tagged(SP.T.ot + 2 * (s * D + i), O / Lx, epoch);
+                    xwg_store(P.o + s * D + i, O / Lx);          // test tap
+                }
+            }
             tr.mark(66);
         }
 
-        // ---- C6: all heads combined -> attention output into LDS ----
+        // ---- C6: attention output of all heads present -> the streamers fetch it into LDS ----
         {
-            if (!ev.wait(2, layer + 1, ctrl, err)) return;
-            tr.mark(70);
-            constexpr int UN = 16;
-            const int n2 = h >> 1, np2 = ((h + kChunk - 1) / kChunk * kChunk) >> 1;
-            for (int base = 0; base < np2; base += UN * 64) {
-                float2 v[UN];
-#pragma unroll
-                for (int j = 0; j < UN; ++j) {
-                    const int i2 = base + lane + j * 64;
-                    v[j] = i2 < n2 ? xwg_load2(P.o + 2 * i2) : float2{0.f, 0.f};
-                }
-#pragma unroll
-                for (int j = 0; j < UN; ++j) {
-                    const int i2 = base + lane + j * 64;
-                    if (i2 < np2) *reinterpret_cast<float2 *>(ol + lds_perm(i2 * 2)) = v[j];
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            if (lane == 0) lds_st(ctrl + cFlagO, layer + 1);
+            if (!sentinel_tagged(SP.T.ot, h, epoch, ab)) return;
+            if (lane == 0) lds_st(ctrl + cFlagOr, layer + 1);
             tr.mark(71);
         }
 
         // ---- F5: down rows done -> g (kept in LDS, only this workgroup needs its rows) ----
         {
             const __half *bd = w + P.lay.b_down;
-            for (int base = 0; base < W.r_n; base += 64) {
+            for (int base = 0; base < W.r_n || base == 0; base += 64) {
                 const int t = base + lane;
                 const bool act = t < W.r_n;
                 const float bias = act ? __half2float(bd[W.r_begin + t]) : 0.f;
@@ -804,33 +968,29 @@ __device__ void service_main(const StepParams &P, const LayerPtrs *__restrict__ 
                     gloc[t] = a + bias;
                 }
             }
-            if (W.r_n == 0 && !lds_wait_ge(ctrl, cCnt5, (layer + 1) * W.n5, err)) return;
             tr.mark(80);
         }
 
         // ---- F6: dense rows done -> out = x + (W_d o + b_d) + g ----
         {
             const __half *bd = w + P.lay.b_dense;
-            for (int base = 0; base < W.r_n; base += 64) {
+            for (int base = 0; base < W.r_n || base == 0; base += 64) {
                 const int t = base + lane;
                 const bool act = t < W.r_n;
                 float bias = 0.f, xval = 0.f;
                 if (act) {
                     bias = __half2float(bd[W.r_begin + t]);
-                    xval = first ? __half2float(P.x_in[W.r_begin + t]) : xwg_load(xin32 + W.r_begin + t);
+                    xval = first ? __half2float(P.x_in[W.r_begin + t]) : xwg_load2(xin_t + 2 * (W.r_begin + t)).x;
                 }
                 if (base == 0 && !lds_wait_ge(ctrl, cCnt6, (layer + 1) * W.n6, err)) return;
                 if (act) {
                     const float a = res6[t] + bias;
                     const float resv = (xval + a) + gloc[t];
                     if (last) P.out[W.r_begin + t] = __float2half_rn(resv);
-                    else xwg_store(xout32 + W.r_begin + t, resv);
+                    else xwg_store_tagged(xout_t + 2 * (W.r_begin + t), resv, epoch);
                 }
             }
-            if (W.r_n == 0 && !lds_wait_ge(ctrl, cCnt6, (layer + 1) * W.n6, err)) return;
             tr.mark(90);
-            ev.arrive(3);
-            tr.mark(91);
         }
     }
 }
@@ -885,13 +1045,14 @@ size_t stream_lds_bytes(const Dims &dm, const StepParams &P, int threads, Stream
     int o = 0;
     auto take = [&](int n) { int at = o; o = (o + n + 3) & ~3; return at; };
     L.ctrl = take(cCtrlWords);
-    L.y1 = take(Kph); L.y2 = take(Kph);
+    L.y1 = take(Kph); L.y2 = take(Kph); L.xs = take(Kph);
     L.qs = take(3 * dm.d); L.kn = take(3 * dm.d / 2); L.vn = take(3 * dm.d / 2);
     L.m = take(Kpf); L.o = take(Kph);
     L.res2 = take(P.rows_qkv + 8); L.res3 = take(P.rows_up + 8);
     L.res5 = take((P.rows_h + 8) * (nsl_f > 0 ? nsl_f : 1)); L.res6 = take(P.rows_h + 8);
     L.gloc = take(P.rows_h + 8);
     L.wpart = take(3 * NS * (dm.d + 2));
+    L.comb = take(part_slots_for(dm.H) * (dm.d + 2));
     L.total = o;
     if (out) *out = L;
     return (size_t)o * 4;
@@ -907,10 +1068,15 @@ static hipError_t launch_stream_t(const StepParams &P, const LayerPtrs *ptrs, co
 }
 
 hipError_t launch_stack_stream(const StepParams &P, const LayerPtrs *ptrs, unsigned long long *events,
-                               int grid, int threads, hipStream_t s)
+                               float *tagged, int grid, int threads, hipStream_t s)
 {
     StreamParams SP;
     SP.events = events;
+    const size_t h = P.dm.h;
+    SP.T.xt = tagged;
+    SP.T.qt = SP.T.xt + 2 * 2 * h;
+    SP.T.ot = SP.T.qt + 3 * 2 * h;
+    SP.T.part = SP.T.ot + 2 * h;
     stream_lds_bytes(P.dm, P, threads, &SP.L);
     switch (stream_shape_class(P.dm)) {
     case 0: return launch_stream_t<80, 5, 2, 10, 1>(P, ptrs, SP, grid, threads, s);
