@@ -81,6 +81,9 @@ def main():
     ap.add_argument("--threads", type=int, default=int(os.environ.get("CFPP_THREADS", "512")))
     ap.add_argument("--ctx", type=int, default=4096, help="cached positions per layer")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="instead of the benchmark, run the plain copy kernel (1 GiB read + 1 GiB written per "
+                         "launch, 5 launches) used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
@@ -92,6 +95,18 @@ def main():
     import synth
     import paper_2604_23553_amd as cf
     from paper_2604_23553_amd.harness import DeviceStack
+
+    if args.calibrate:
+        n = 1 << 30
+        src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            cf.cfpp_stream_copy(src, dst, n, 256, 512, None)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "cfpp_stream_copy", "bytes_read_per_launch": n,
+                          "bytes_written_per_launch": n, "launches": 5}))
+        return
 
     shape = synth.PYTHIA_2_8B
     S, cap = args.ctx, args.ctx + 1
