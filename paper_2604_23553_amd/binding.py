@@ -42,7 +42,8 @@ class _LayerSrc(C.Structure):
 
 
 def library_path() -> str:
-    return os.path.join(_PKG, "libcfpp.so")
+    """The in-tree library, or the build named by CFPP_LIBRARY (kernel experiments)."""
+    return os.environ.get("CFPP_LIBRARY") or os.path.join(_PKG, "libcfpp.so")
 
 
 _lib = None

@@ -336,15 +336,18 @@ static cfpp_status launch_shape(const cfpp_ctx *ctx, Shape *sh)
     const int nch_h = ceil_div(dm.h, kChunk), nch_f = ceil_div(dm.f, kChunk);
     sh->nsl_down = pick_slices(sh->rows_h, nch_f, nw);
     sh->nsl_dense = pick_slices(sh->rows_h, nch_h, nw);
-    const size_t a = 2 * (size_t)nch_h * kChunk + sh->rows_qkv + sh->rows_up + 16;
-    const size_t b = (size_t)nch_f * kChunk + (size_t)sh->rows_h * sh->nsl_down + (size_t)nw * (dm.d + 2) + 4;
-    const size_t c = (size_t)nch_h * kChunk + (size_t)sh->rows_h * sh->nsl_dense;
+    const size_t a = 2 * (size_t)nch_h * kChunk + (size_t)(sh->rows_qkv + sh->rows_up) * nw + 16 + 16;
+    const size_t b = (size_t)nch_f * kChunk + (size_t)sh->rows_h * nw + 16 + (size_t)nw * (dm.d + 2) + 4 + 2 * (size_t)dm.d;
+    const size_t c = (size_t)nch_h * kChunk + (size_t)sh->rows_h * nw + 16;
     size_t m = a > b ? a : b;
     m = m > c ? m : c;
     m = (m + 63) / 64 * 64;
     if (m * 4 > 160 * 1024) return fail(CFPP_EUNSUPPORTED, "needs %zu bytes of LDS (> 160 KiB)", m * 4);
     if ((size_t)dm.h > (size_t)32 * sh->threads)    // the LayerNorm keeps 32 values per thread
         return fail(CFPP_EUNSUPPORTED, "hidden %d needs more than 32 values per thread at %d threads", dm.h,
+                    sh->threads);
+    if ((size_t)dm.f > (size_t)32 * sh->threads)    // the MLP intermediate is staged with 32 values per thread
+        return fail(CFPP_EUNSUPPORTED, "ffn %d needs more than 32 values per thread at %d threads", dm.f,
                     sh->threads);
     sh->lds_floats = (unsigned)m;
     return CFPP_OK;

@@ -28,122 +28,285 @@
 namespace cfpp {
 
 constexpr int kMaxThreads = 512;
+// After the attention the first wavefront still merges and publishes the partial
+// while the others already stream the down projection: it takes a smaller share.
+constexpr int kShare0AfterAttention = 0;
+constexpr int kStageM = 16;       // the MLP intermediate is staged with up to 16 float2 per thread
 
 // ---------------------------------------------------------------------------
-// Row-split GEMV over this workgroup's rows.  Work unit = (row, K-slice), slice
-// fastest, handed to wavefronts round-robin; a wavefront streams its slice with
-// 16-byte loads per lane (1 KiB contiguous per instruction), multiplies with the
-// activation vector held in LDS (fp32, lds_perm order, zero padded to a chunk
-// multiple) and leaves the slice's partial sum in part[unit].
-template <int U>
-__device__ __forceinline__ void gemv_issue(u32x4 (&wv)[U], const __half *p)
+// Row-split GEMV over this workgroup's rows.
+//
+// The rows a workgroup owns are contiguous in the packed layout, so its block of
+// a matrix is one span of rows*K/512 "units" of 512 weights (1 KiB: one 16-byte
+// load per lane).  Up to two such blocks (QKV rows then MLP-up rows) form one
+// line of N units that is cut evenly over the wavefronts: wavefront w streams
+// units [N*w/nw, N*(w+1)/nw) - a contiguous range of memory - and leaves one
+// partial sum per row it touches in part[row*nw + w].  The epilogue adds the
+// partials of a row in wavefront order.  The activation vector is in LDS (fp32,
+// lds_perm order, zero padded to a unit multiple).
+//
+// Loads run two blocks of U units ahead of the arithmetic, and the first two
+// blocks can be issued by the caller long before the activations exist (before a
+// grid barrier, before the attention merges): weights depend on nothing.
+#ifndef CFPP_GEMV_U
+#define CFPP_GEMV_U 8
+#endif
+constexpr int kGemvU = CFPP_GEMV_U;
+// the down projection's first blocks are in flight during the attention arithmetic, which
+// needs most of the register file: smaller blocks there
+constexpr int kGemvUDown = 4;
+
+// The thread index as a value the optimiser cannot see through.  Inside the
+// whole-stack kernel everything derived from the plain thread index is invariant
+// across layers and would be hoisted out of the layer loop - dozens of
+// precomputed addresses held in registers (or spilled) for the whole launch.
+__device__ __forceinline__ int opaque_thread_index()
 {
-#pragma unroll
-    for (int i = 0; i < U; ++i) wv[i] = load16_stream(p + (size_t)i * kChunk);
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
 }
 
-template <int U>
-__device__ __forceinline__ float gemv_consume(const u32x4 (&wv)[U], const float *yl, float acc)
-{
-    float a0 = acc, a1 = 0.f;
-#pragma unroll
-    for (int i = 0; i < U; ++i) {
-        const float4 ya = *reinterpret_cast<const float4 *>(yl + i * kChunk);
-        const float4 yb = *reinterpret_cast<const float4 *>(yl + i * kChunk + 256);
-        if (i & 1) a1 = dot8(wv[i], ya, yb, a1);
-        else a0 = dot8(wv[i], ya, yb, a0);
-    }
-    return a0 + a1;
-}
+struct GemvSeg {
+    const __half *W;     // first row of this workgroup's block
+    const float *y;      // activations in LDS
+    int K;               // row length
+    int rows;            // rows in the block (may be 0)
+};
 
-// Fast path: K a multiple of 512 and every slice a whole number of U-chunk
-// steps.  The wavefront walks its (unit, step) sequence with the loads of the
-// next step already in flight while it multiplies the current one, so the
-// reduction at the end of a unit never drains the memory pipeline.
-template <int U>
-__device__ __forceinline__ void wg_gemv_pipelined(const __half *__restrict__ Wm, int K, int row_begin,
-                                                  int nrows, int nsl, int cps, const float *y, float *part)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    const int spu = cps / U;                         // steps per unit
-    const int nunits = nrows * nsl;
-    const __half *wl = Wm + (size_t)row_begin * K + lane * 8;
-    const float *yl = y + lane * 4;
-    int u = wave, step = 0;
-    if (u >= nunits) return;
-    u32x4 cur[U], nxt[U];
+template <int U_>
+struct GemvSpan {
+    static constexpr int U = U_;
+    u32x4 a[U], b[U];
+    const __half *w0, *w1;          // block bases (uniform)
+    const __half *p0, *p1;          // the same, or `safe` when this wavefront streams nothing
+    unsigned lane_off;              // this lane's byte offset inside a unit
+    const float *y0, *y1;           // lane-adjusted activation bases
+    int nch0, nch1, rows0, rows1, K0, K1;
+    int n0, N, lo, hi, last, nw, wave, lane;
+    const __half *safe;             // any readable 1 KiB: target of loads that are issued but not used
+    int *bnd;
+    bool regular;
+    // walking state of consume()
+    const float *yc;
+    int c, nchc, rowg;
+    float acc0, acc1;
+
+    // bounds: nw + 1 ints of LDS (range starts of the wavefronts, then N).
+    // share0: the first wavefront's share of the units in quarters of a full
+    // share (4 = equal split); callers lower it when that wavefront has other
+    // work to finish first.
+    __device__ __forceinline__ void init(const GemvSeg &s0, const GemvSeg &s1, const __half *safe_, int tid,
+                                         int *bounds, int share0 = 4)
     {
-        const int rl = u / nsl, sl = u - rl * nsl;
-        gemv_issue<U>(cur, wl + (size_t)rl * K + (size_t)(sl * cps) * kChunk);
-    }
-    float acc = 0.f;
-    while (u < nunits) {
-        int un = u, stn = step + 1;
-        if (stn == spu) { stn = 0; un = u + nw; }
-        if (un < nunits) {
-            const int rl = un / nsl, sl = un - rl * nsl;
-            gemv_issue<U>(nxt, wl + (size_t)rl * K + (size_t)(sl * cps + stn * U) * kChunk);
-        }
+        safe = safe_;
+        bnd = bounds;
+        lane = tid & 63; wave = __builtin_amdgcn_readfirstlane(tid >> 6); nw = blockDim.x >> 6;
+        w0 = s0.W; w1 = s1.W;
+        lane_off = (unsigned)lane * 16u;
+        y0 = s0.y + lane * 4; y1 = s1.y + lane * 4;
+        K0 = s0.K; K1 = s1.K;
+        rows0 = s0.rows; rows1 = s1.rows;
+        regular = (s0.rows == 0 || s0.K % kChunk == 0) && (s1.rows == 0 || s1.K % kChunk == 0);
+        nch0 = s0.K / kChunk; nch1 = s1.K / kChunk;
+        n0 = rows0 * nch0;
+        N = n0 + rows1 * nch1;
+#ifdef CFPP_GEMV_INTERLEAVE
+        // blocks of U units go round-robin over the wavefronts: the workgroup reads one moving window
+        regular = regular && nch0 <= (nw - 1) * U && nch1 <= (nw - 1) * U;
+        lo = regular ? wave * U : 0;
+        hi = regular ? N : 0;
+        last = regular && N > 0 ? N - 1 : -1;
+#else
         {
-            const int sl = u % nsl;
-            acc = gemv_consume<U>(cur, yl + (sl * cps + step * U) * kChunk, acc);
+            const int wtot = share0 + 4 * (nw - 1);
+            const int c0 = wave == 0 ? 0 : share0 + 4 * (wave - 1), c1 = share0 + 4 * wave;
+            lo = regular ? (int)((unsigned)N * (unsigned)c0 / (unsigned)wtot) : 0;
+            hi = regular ? (int)((unsigned)N * (unsigned)c1 / (unsigned)wtot) : 0;
         }
-        if (stn == 0) {
-            const float tot = wave_sum(acc);
-            if (lane == 0) part[u] = tot;
-            acc = 0.f;
-        }
+        last = hi > lo ? hi - 1 : (regular && N > 0 ? (lo < N ? lo : N - 1) : -1);
+#endif
+        p0 = w0; p1 = w1;
+        if (last < 0) { p0 = safe; p1 = safe; last = 0; }  // nothing to stream: loads go to the safe block
+        const bool in1 = lo >= n0;
+        nchc = in1 ? nch1 : nch0;
+        const int local = in1 ? lo - n0 : lo;
+        const int row = nchc ? local / nchc : 0;
+        c = local - row * nchc;
+        rowg = in1 ? rows0 + row : row;
+        yc = in1 ? y1 : y0;
+        acc0 = 0.f; acc1 = 0.f;
+    }
+
+    // Always exactly U load instructions on a single code path, so that the
+    // hardware's in-order load counter (and the compiler's model of it) tells
+    // precisely when an older block has landed while this one is still in
+    // flight; a skipped or differently-routed load would force every wait to
+    // drain the queue.  Units past the end of the range re-read its last unit.
+    __device__ __forceinline__ const __half *unit_ptr(int u) const
+    {
+        const int uc = u < last ? u : last;
+        const bool in0 = uc < n0;
+        return (in0 ? p0 : p1) + (size_t)(in0 ? uc : uc - n0) * kChunk;
+    }
+    __device__ __forceinline__ void issue(u32x4 (&r)[U], int i) const
+    {
 #pragma unroll
-        for (int i = 0; i < U; ++i) cur[i] = nxt[i];
-        u = un;
-        step = stn;
+        for (int j = 0; j < U; ++j) r[j] = load16_stream_at(unit_ptr(i + j), lane_off);
+        // keep the instruction scheduler from sinking these loads towards their use
+        __builtin_amdgcn_sched_barrier(0);
     }
-}
+    __device__ __forceinline__ void issue_first() { issue(a, lo); }
+#ifdef CFPP_GEMV_INTERLEAVE
+    __device__ __forceinline__ void issue_second() { issue(b, lo + nw * U); }
+    __device__ __forceinline__ void seek(int i)
+    {
+        const bool in1 = i >= n0;
+        nchc = in1 ? nch1 : nch0;
+        const int local = in1 ? i - n0 : i;
+        const int row = nchc ? local / nchc : 0;
+        c = local - row * nchc;
+        rowg = in1 ? rows0 + row : row;
+        yc = in1 ? y1 : y0;
+    }
+#else
+    __device__ __forceinline__ void issue_second() { issue(b, lo + U); }
+#endif
 
-// General path: any K that is a multiple of 8 (ragged last chunk), any slicing.
-__device__ __forceinline__ void wg_gemv_general(const __half *__restrict__ Wm, int K, int row_begin,
-                                                int nrows, int nsl, const float *y, float *part)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    const int nchunk = (K + kChunk - 1) / kChunk;
-    const int cps = (nchunk + nsl - 1) / nsl;
-    const int nunits = nrows * nsl;
-    for (int u = wave; u < nunits; u += nw) {
-        const int rl = u / nsl, sl = u - rl * nsl;
-        const int c0 = sl * cps;
-        const int c1 = min(nchunk, c0 + cps);
-        const __half *wrow = Wm + (size_t)(row_begin + rl) * K + lane * 8;
-        const float *yl = y + lane * 4;
-        float acc = 0.f;
-        for (int c = c0; c < c1; ++c) {
-            u32x4 wv = {0u, 0u, 0u, 0u};
-            if (c * kChunk + lane * 8 < K) wv = load16_stream(wrow + (size_t)c * kChunk);
-            const float4 ya = *reinterpret_cast<const float4 *>(yl + c * kChunk);
-            const float4 yb = *reinterpret_cast<const float4 *>(yl + c * kChunk + 256);
-            acc = dot8(wv, ya, yb, acc);
+    __device__ __forceinline__ void consume(const u32x4 (&r)[U], int i, float *part)
+    {
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            const int u = i + j;
+            if (u < hi) {
+                const float4 ya = *reinterpret_cast<const float4 *>(yc + c * kChunk);
+                const float4 yb = *reinterpret_cast<const float4 *>(yc + c * kChunk + 256);
+                if (j & 1) acc1 = dot8(r[j], ya, yb, acc1);
+                else acc0 = dot8(r[j], ya, yb, acc0);
+                ++c;
+#ifdef CFPP_GEMV_INTERLEAVE
+                if (c == nchc || u == hi - 1 || j == U - 1) {
+#else
+                if (c == nchc || u == hi - 1) {              // end of a row, or of this wavefront's range
+#endif
+                    const float tot = wave_sum(acc0 + acc1);
+                    if (lane == 0) part[rowg * nw + wave] = tot;
+                    acc0 = 0.f; acc1 = 0.f;
+#ifdef CFPP_GEMV_INTERLEAVE
+                    if (c == nchc) {
+                        c = 0;
+                        ++rowg;
+                        if (rowg == rows0) { nchc = nch1; yc = y1; }
+                    }
+#else
+                    c = 0;
+                    ++rowg;
+                    if (rowg == rows0) { nchc = nch1; yc = y1; }
+#endif
+                }
+            }
         }
-        const float tot = wave_sum(acc);
-        if (lane == 0) part[u] = tot;
     }
+
+    // rows with a ragged last unit (K not a multiple of 512): whole rows round-robin
+    __device__ __forceinline__ void run_general(float *part) const
+    {
+        const int nrows = rows0 + rows1;
+        for (int rg = wave; rg < nrows; rg += nw) {
+            const bool in1 = rg >= rows0;
+            const int K = in1 ? K1 : K0;
+            const __half *wrow = (in1 ? w1 + (size_t)(rg - rows0) * K : w0 + (size_t)rg * K) + lane * 8;
+            const float *yl = in1 ? y1 : y0;
+            const int nchunk = (K + kChunk - 1) / kChunk;
+            float acc = 0.f;
+            for (int cc = 0; cc < nchunk; ++cc) {
+                u32x4 wv = {0u, 0u, 0u, 0u};
+                if (cc * kChunk + lane * 8 < K) wv = load16_stream(wrow + (size_t)cc * kChunk);
+                const float4 ya = *reinterpret_cast<const float4 *>(yl + cc * kChunk);
+                const float4 yb = *reinterpret_cast<const float4 *>(yl + cc * kChunk + 256);
+                acc = dot8(wv, ya, yb, acc);
+            }
+            const float tot = wave_sum(acc);
+            if (lane == 0) part[rg * nw] = tot;
+        }
+    }
+
+    // consume everything; issue_first() and issue_second() have been called
+    __device__ __forceinline__ void run(float *part)
+    {
+        if (!regular) { run_general(part); return; }
+        int i = lo;
+#ifdef CFPP_GEMV_INTERLEAVE
+        const int st = nw * U;
+        while (i < hi) {
+            seek(i); consume(a, i, part); issue(a, i + 2 * st); i += st;
+            if (i >= hi) break;
+            seek(i); consume(b, i, part); issue(b, i + 2 * st); i += st;
+        }
+#else
+        // Steady state: consume the older block, refill it two blocks ahead.  The
+        // last two blocks are consumed without issuing anything, so that no load
+        // is left in flight when the epilogue (or a grid barrier) waits on memory.
+        bool a_older = true;
+        while (i + 2 * U < hi) {
+            consume(a, i, part); issue(a, i + 2 * U); i += U;
+            a_older = false;
+            if (i + 2 * U >= hi) break;
+            consume(b, i, part); issue(b, i + 2 * U); i += U;
+            a_older = true;
+        }
+        if (a_older) { consume(a, i, part); consume(b, i + U, part); }
+        else { consume(b, i, part); consume(a, i + U, part); }
+#endif
+    }
+
+    // after run() and a workgroup barrier: the dot product of global row rg
+    // (0..rows0-1 first block, then the second block's rows).  Every wavefront
+    // slot of the row is added, in wavefront order; slots of wavefronts that did
+    // not touch the row hold the zero written by clear_partials().
+    __device__ __forceinline__ float row_total(const float *part, int rg) const
+    {
+        const float *pr = part + rg * nw;
+        float t = 0.f;
+        for (int w = 0; w < nw; w += 4) {
+            const float4 v = *reinterpret_cast<const float4 *>(pr + w);
+            t = (((t + v.x) + v.y) + v.z) + v.w;
+        }
+        return t;
+    }
+};
+
+// zero the (rows * nw) partial-sum slots; a workgroup barrier must follow before run()
+__device__ __forceinline__ void clear_partials(float *part, int nslots, int tid)
+{
+    for (int i = tid; i < nslots; i += blockDim.x) part[i] = 0.f;
 }
 
-__device__ __forceinline__ void wg_gemv(const __half *__restrict__ Wm, int K, int row_begin,
-                                        int nrows, int nsl, const float *y, float *part)
+// Epilogue work items are dealt to lanes wavefront-major (item i -> wavefront
+// i % nw), so that a few dozen rows are finished by all wavefronts together
+// rather than by the first one alone.
+__device__ __forceinline__ int spread_index(int tid)
 {
-    if (nrows <= 0) return;
-    const int nchunk = (K + kChunk - 1) / kChunk;
-    const int cps = (nchunk + nsl - 1) / nsl;
-    const bool regular = (K % kChunk) == 0 && cps * nsl == nchunk;
-    if (regular && cps % 8 == 0) wg_gemv_pipelined<8>(Wm, K, row_begin, nrows, nsl, cps, y, part);
-    else if (regular && cps % 5 == 0) wg_gemv_pipelined<5>(Wm, K, row_begin, nrows, nsl, cps, y, part);
-    else if (regular && cps % 4 == 0) wg_gemv_pipelined<4>(Wm, K, row_begin, nrows, nsl, cps, y, part);
-    else wg_gemv_general(Wm, K, row_begin, nrows, nsl, y, part);
+    return (tid & 63) * (int)(blockDim.x >> 6) + (tid >> 6);
 }
+
+struct NoSync {
+    static constexpr bool kInputsReady = true;    // everything this launch reads was written before it started
+
+    __device__ __forceinline__ void wait() {}
+    __device__ __forceinline__ void arrive() {}
+};
+struct GridSync {
+    static constexpr bool kInputsReady = false;   // inputs appear behind a grid barrier
+    GridBarrier &bar;
+    __device__ __forceinline__ void wait() { bar.wait(); }
+    __device__ __forceinline__ void arrive() { bar.arrive(); }
+};
 
 // sum of a value over the workgroup, fixed order; red: >= 16 floats of LDS
-__device__ __forceinline__ float block_sum(float v, float *red)
+__device__ __forceinline__ float block_sum(float v, float *red, int tid)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const int lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
     v = wave_sum(v);
     __syncthreads();                 // red may still be read from a previous use
     if (lane == 0) red[wave] = v;
@@ -179,17 +342,52 @@ __device__ __forceinline__ float load_x(const LayerIO &io, int i)
 __device__ __forceinline__ int round_up_chunk(int k) { return (k + kChunk - 1) / kChunk * kChunk; }
 
 // ---------------------------------------------------------------------------
-// Phase A.  LDS: y1[Kp] y2[Kp] part[rows_qkv + rows_up] red[16]
-__device__ void phase_a(const StepParams &P, const __half *__restrict__ w, __half *__restrict__ kv,
-                        int layer, int pos, float *lds)
+// Phase A.  LDS: y1[Kp] y2[Kp] part[(rows_qkv + rows_up) * nw] bounds[16] red[16]
+template <class Sync>
+__device__ __forceinline__ void phase_a(const StepParams &P, const __half *__restrict__ w, __half *__restrict__ kv,
+                                        int layer, int pos, float *lds, Sync &sync)
 {
     const Dims &dm = P.dm;
     const int h = dm.h, f = dm.f, d = dm.d, r = dm.r;
-    const int tid = threadIdx.x, nt = blockDim.x, g = blockIdx.x;
+    const int tid = opaque_thread_index(), nt = blockDim.x, g = blockIdx.x;
     const int Kp = round_up_chunk(h);
     float *y1 = lds, *y2 = lds + Kp, *part = lds + 2 * Kp;
-    float *red = part + P.rows_qkv + P.rows_up;
+    int *bnd = reinterpret_cast<int *>(part + (P.rows_qkv + P.rows_up) * (nt >> 6));
+    float *red = reinterpret_cast<float *>(bnd + 16);
     const LayerIO io = layer_io(P, layer);
+
+    // weights first: they depend on nothing, so their loads overlap the wait for x
+    const int q_begin = g * P.rows_qkv, q_n = max(0, min(P.rows_qkv, 3 * h - q_begin));
+    const int u_begin = g * P.rows_up, u_n = max(0, min(P.rows_up, f - u_begin));
+    GemvSpan<kGemvU> gs;
+    gs.init(GemvSeg{w + P.lay.w_qkv + (size_t)q_begin * h, y1, h, q_n},
+            GemvSeg{w + P.lay.w_up + (size_t)u_begin * h, y2, h, u_n}, w, tid, bnd);
+    clear_partials(part, (P.rows_qkv + P.rows_up) * (nt >> 6), tid);
+    // Epilogue items: the lower half of the wavefronts finishes pairs of QKV
+    // rows, the upper half MLP-up rows, items dealt wavefront-major inside a
+    // half.  What an item adds (biases, the rotary cos/sin) is requested now: a
+    // load issued after the GEMV would cost a full memory round trip with
+    // nothing left to hide it.
+    const __half *bq = w + P.lay.b_qkv, *bu = w + P.lay.b_up;
+    const int hw = nt >> 7, estride = 64 * hw;           // wavefronts per half, items per pass
+    const bool up_half = (tid >> 6) >= hw;
+    const int item0 = (tid & 63) * hw + ((tid >> 6) - (up_half ? hw : 0));
+    float bq0 = 0.f, bq1 = 0.f, bu0 = 0.f;
+    float2 cs0 = {1.f, 0.f};
+    if (!up_half && item0 < q_n / 2) {
+        const int p = q_begin + 2 * item0;
+        const int i = p % d, c = (p / d) % 3;
+        bq0 = __half2float(bq[p]); bq1 = __half2float(bq[p + 1]);
+        if (c < 2 && i < r) cs0 = P.rope[(size_t)pos * (r >> 1) + (i >> 1)];
+    }
+    if (up_half && item0 < u_n) bu0 = __half2float(bu[u_begin + item0]);
+
+    Tracer tr;
+    tr.init(P, gs.wave, 0);
+    tr.mark(1);
+    if constexpr (!Sync::kInputsReady) gs.issue_first();   // weights stream while x is waited for
+    sync.wait();
+    tr.mark(2);
 
     // Both LayerNorms read the block input.  A thread owns up to GU groups of 8
     // consecutive elements; x and the four parameter vectors are fetched with
@@ -224,12 +422,14 @@ __device__ void phase_a(const StepParams &P, const __half *__restrict__ w, __hal
             pg2[j] = load16(g2 + gi * 8); pb2[j] = load16(b2 + gi * 8);
         }
     }
+    if constexpr (Sync::kInputsReady) gs.issue_first();    // x is already on its way: it returns first
+    gs.issue_second();
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < GU; ++j)
 #pragma unroll
         for (int e = 0; e < 8; ++e) s += xv[j][e];
-    const float mean = block_sum(s, red) / (float)h;
+    const float mean = block_sum(s, red, tid) / (float)h;
     float v = 0.f;
 #pragma unroll
     for (int j = 0; j < GU; ++j) {
@@ -241,7 +441,7 @@ __device__ void phase_a(const StepParams &P, const __half *__restrict__ w, __hal
             }
         }
     }
-    const float var = block_sum(v, red) / (float)h;
+    const float var = block_sum(v, red, tid) / (float)h;
     const float inv = 1.0f / sqrtf(var + dm.ln_eps);
 #pragma unroll
     for (int j = 0; j < GU; ++j) {
@@ -271,41 +471,52 @@ __device__ void phase_a(const StepParams &P, const __half *__restrict__ w, __hal
         }
     }
     __syncthreads();
+    tr.mark(3);
 
-    const int q_begin = g * P.rows_qkv, q_n = max(0, min(P.rows_qkv, 3 * h - q_begin));
-    const int u_begin = g * P.rows_up, u_n = max(0, min(P.rows_up, f - u_begin));
-    wg_gemv(w + P.lay.w_qkv, h, q_begin, q_n, 1, y1, part);
-    wg_gemv(w + P.lay.w_up, h, u_begin, u_n, 1, y2, part + P.rows_qkv);
+    gs.run(part);
+    tr.mark(4);
     __syncthreads();
+    tr.mark(5);
 
-    // QKV epilogue: one thread per pair of adjacent packed rows
-    const __half *bq = w + P.lay.b_qkv;
-    for (int pr = tid; pr < q_n / 2; pr += nt) {
-        const int p = q_begin + 2 * pr;                 // packed row, even
-        const int n = p / (3 * d), rem = p - n * 3 * d;
-        const int c = rem / d, i = rem - c * d;          // i even
-        float v0 = part[2 * pr] + __half2float(bq[p]);
-        float v1 = part[2 * pr + 1] + __half2float(bq[p + 1]);
-        int d0 = i, d1 = i + 1;
-        if (c < 2 && i < r) {                            // rotary pair (j, j + r/2)
-            const int j = i >> 1;
-            const float2 cs = P.rope[(size_t)pos * (r >> 1) + j];
-            const float lo = v0 * cs.x - v1 * cs.y;
-            const float hi = v1 * cs.x + v0 * cs.y;
-            v0 = lo; v1 = hi;
-            d0 = j; d1 = j + (r >> 1);
+    if (!up_half) {
+        // QKV epilogue: one thread per pair of adjacent packed rows
+        for (int pr = item0; pr < q_n / 2; pr += estride) {
+            const int p = q_begin + 2 * pr;             // packed row, even
+            const int pd = p / d, i = p - pd * d;       // i even
+            const int n = pd / 3, c = pd - 3 * n;
+            const bool rotary = c < 2 && i < r;         // rotary pair (j, j + r/2)
+            float b0 = bq0, b1 = bq1;
+            float2 cs = cs0;
+            if (pr != item0) {                          // more pairs than threads: tiny grids only
+                b0 = __half2float(bq[p]); b1 = __half2float(bq[p + 1]);
+                if (rotary) cs = P.rope[(size_t)pos * (r >> 1) + (i >> 1)];
+            }
+            float v0 = gs.row_total(part, 2 * pr) + b0;
+            float v1 = gs.row_total(part, 2 * pr + 1) + b1;
+            int d0 = i, d1 = i + 1;
+            if (rotary) {
+                const int j = i >> 1;
+                const float lo = v0 * cs.x - v1 * cs.y;
+                const float hi = v1 * cs.x + v0 * cs.y;
+                v0 = lo; v1 = hi;
+                d0 = j; d1 = j + (r >> 1);
+            }
+            if (c == 0) {
+                xwg_store(P.q + n * d + d0, v0);
+                xwg_store(P.q + n * d + d1, v1);
+            } else {
+                xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d0, pos), v0);
+                xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d1, pos), v1);
+            }
         }
-        if (c == 0) {
-            xwg_store(P.q + n * d + d0, v0);
-            xwg_store(P.q + n * d + d1, v1);
-        } else {
-            xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d0, pos), v0);
-            xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d1, pos), v1);
+    } else {
+        for (int t = item0; t < u_n; t += estride) {
+            const float b = t == item0 ? bu0 : __half2float(bu[u_begin + t]);
+            xwg_store(P.m + u_begin + t, gelu_erf(gs.row_total(part, q_n + t) + b));
         }
     }
-    const __half *bu = w + P.lay.b_up;
-    for (int t = tid; t < u_n; t += nt)
-        xwg_store(P.m + u_begin + t, gelu_erf(part[P.rows_qkv + t] + __half2float(bu[u_begin + t])));
+    tr.mark(6);
+    sync.arrive();
 }
 
 // ---------------------------------------------------------------------------
@@ -325,90 +536,155 @@ __device__ void phase_a(const StepParams &P, const __half *__restrict__ w, __hal
 // workgroup that delivers the last partial of a head combines all of that
 // head's partials in slot order.  K/V loads of the next row are issued before
 // the current row is processed.
-// scr: nw*(D+2) + 4 floats of LDS.
-template <int D>
-__device__ void attn_share(const StepParams &P, const __half *__restrict__ kv, int n_tok, float *scr)
+// scr: nw*(D+2) + 4 + 2*D floats of LDS.
+// pre(): called once, after the first row of already-cached K/V has been
+// requested and before anything written during this launch (q, the new token's
+// K/V) is read.  early(): called once, when every K/V load of the first two rows
+// has been requested (the caller requests what it wants in flight during the
+// arithmetic).  mid(): called once, ahead of the first workgroup barrier (the
+// caller finishes staging its LDS vectors there).  tail(): called once, when the last K/V rows have been consumed,
+// ahead of the last merges.
+template <int D, class Pre, class Early, class Mid, class Tail>
+__device__ __forceinline__ void attn_share(const StepParams &P, const __half *__restrict__ kv, int n_tok,
+                                           float *scr, int tid, Pre &&pre, Early &&early, Mid &&mid, Tail &&tail,
+                                           Tracer &tr)
 {
     using A = AttnShape<D>;
     constexpr int LPP = A::LPP, PPW = A::PPW, NP = A::NP, NV = A::NV;
     const Dims &dm = P.dm;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = blockDim.x >> 6;
     const int sub = lane & (LPP - 1), tl = lane / LPP;
     const int H = dm.H;
-    const long long g = blockIdx.x;
+    const int g = blockIdx.x;
+    // (host-checked: rows * workgroups stays far below 2^31)
     const int R = (n_tok + PPW - 1) / PPW;
-    const long long T = (long long)R * H;
+    const int T = R * H;
     // with fewer rows than workgroups only the first T workgroups take part, so
     // that every participant owns at least one row (no empty ranges in between)
-    const long long G = min((long long)gridDim.x, T);
-    const long long r0 = g < G ? T * g / G : 0, r1 = g < G ? T * (g + 1) / G : 0;
+    const int G = min((int)gridDim.x, T);
+    const int r0 = g < G ? (int)((long long)T * g / G) : 0, r1 = g < G ? (int)((long long)T * (g + 1) / G) : 0;
     const float scale = 1.0f / sqrtf((float)D);
     const size_t hs = kv_head_stride(dm);
     const __half *Kb = kv + kv_offset(dm, 0, P.b, 0, 0, 0);
     const __half *Vb = kv + kv_offset(dm, 1, P.b, 0, 0, 0);
     float *wp = scr, *wm = scr + nw * D, *wl = wm + nw;
-    int *flag = reinterpret_cast<int *>(wl + nw);
+    float *qs = wl + nw + 4;                               // this head's query
+    __half *kn = reinterpret_cast<__half *>(qs + D);       // the new token's K and V rows of this head
+    __half *vn = kn + D;
 
-    // element offset of this lane's piece k inside a head, for position 0
-    size_t koff[NP];
+    if (r0 >= r1) {                                        // no rows for this workgroup
+        pre();
+        early();
+        mid();
+        __syncthreads();
+        tail();
+        return;
+    }
+
+    // byte offset of this lane's piece k inside a head, for position 0 (a head's
+    // K or V is d * max_seq * 2 bytes, far below 4 GiB)
+    unsigned koff[NP];
 #pragma unroll
     for (int k = 0; k < NP; ++k) {
         const int pc = sub + LPP * k;
-        koff[k] = (size_t)(pc >> 1) * dm.max_seq * 16 + (pc & 1) * 8;
+        koff[k] = ((unsigned)(pc >> 1) * (unsigned)dm.max_seq * 16u + (unsigned)(pc & 1) * 8u) * 2u;
     }
 
-    for (long long sb = r0; sb < r1;) {
-        const int s = (int)(sb / R);                       // head
-        const long long se = min(r1, (long long)(s + 1) * R);
-        const int row_lo = (int)(sb - (long long)s * R), row_hi = (int)(se - (long long)s * R);
+    // K/V of one row into registers: always exactly 2*NP load instructions with
+    // every lane active, so that the in-order load counter tells when this row
+    // has landed while the next one is still in flight.  Lanes past the last
+    // cached position re-read it (their weight is zero); the new token's row
+    // comes from LDS (kn, vn), not from here.
+    const int t_last = n_tok >= 2 ? n_tok - 2 : 0;
+    // (row < 0: nothing is needed, every lane reads the same record)
+    auto issue = [&](u32x4 (&kk)[NP], u32x4 (&vv)[NP], const __half *Kh, const __half *Vh, int row) {
+        const int t = row < 0 ? t_last : row * PPW + tl;
+        const unsigned tb = (unsigned)(t < t_last ? t : t_last) * 32u;
+#pragma unroll
+        for (int k = 0; k < NP; ++k) kk[k] = load16_stream_at(Kh, koff[k] + tb);
+#pragma unroll
+        for (int k = 0; k < NP; ++k) vv[k] = load16_stream_at(Vh, koff[k] + tb);
+        __builtin_amdgcn_sched_barrier(0);                 // the loads stay here, ahead of the arithmetic
+    };
+
+    // this head's query and the new token's K/V rows -> registers -> LDS
+    float q_r = 0.f;
+    __half kn_r = __float2half(0.f), vn_r = kn_r;
+    auto head_issue = [&](int s) {
+        if (tid < D) {
+            q_r = xwg_load(P.q + s * D + tid);
+            kn_r = xwg_load_half(kv + kv_offset(dm, 0, P.b, s, tid, n_tok - 1));
+            vn_r = xwg_load_half(kv + kv_offset(dm, 1, P.b, s, tid, n_tok - 1));
+        }
+    };
+    auto head_commit = [&] {
+        if (tid < D) { qs[tid] = q_r; kn[tid] = kn_r; vn[tid] = vn_r; }
+    };
+
+    // Order of the requests: first row of cached K/V (needs nothing), then -
+    // behind the caller's wait - the small vectors written during this launch,
+    // then the second row and the caller's next weights.  The small loads return
+    // while the bulk behind them is still streaming.
+    u32x4 kA[NP], vA[NP], kB[NP], vB[NP];
+    bool first = true;
+    {
+        const int s = r0 / R;
+        const int se = min(r1, (s + 1) * R);
+        const int row_lo = r0 - s * R, row_hi = se - s * R;
+        const int row = row_lo + wave;
+        issue(kA, vA, Kb + (size_t)s * hs, Vb + (size_t)s * hs, row < row_hi ? row : -1);
+        pre();
+        head_issue(s);
+        issue(kB, vB, Kb + (size_t)s * hs, Vb + (size_t)s * hs, row + nw < row_hi ? row + nw : -1);
+        early();
+        head_commit();
+        mid();
+    }
+
+    for (int sb = r0; sb < r1;) {
+        const int s = sb / R;                              // head
+        const int se = min(r1, (s + 1) * R);
+        const int row_lo = sb - s * R, row_hi = se - s * R;
         const __half *Kh = Kb + (size_t)s * hs;
         const __half *Vh = Vb + (size_t)s * hs;
 
-        float q[NP][8];
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-            const float *qp = P.q + s * D + 8 * (sub + LPP * k);
-            const float2 a = xwg_load2(qp), b = xwg_load2(qp + 2), c = xwg_load2(qp + 4), e = xwg_load2(qp + 6);
-            q[k][0] = a.x; q[k][1] = a.y; q[k][2] = b.x; q[k][3] = b.y;
-            q[k][4] = c.x; q[k][5] = c.y; q[k][6] = e.x; q[k][7] = e.y;
+        int row = row_lo + wave;
+        if (!first) {
+            issue(kA, vA, Kh, Vh, row < row_hi ? row : -1);
+            head_issue(s);
+            issue(kB, vB, Kh, Vh, row + nw < row_hi ? row + nw : -1);
+            head_commit();
         }
+        first = false;
+        __syncthreads();
         float acc[NV];
 #pragma unroll
         for (int i = 0; i < NV; ++i) acc[i] = 0.f;
         float mrun = -INFINITY, lrun = 0.f;
 
-        auto issue = [&](u32x4 (&kk)[NP], u32x4 (&vv)[NP], int row) {
-            const int t = row * PPW + tl;
+        const bool last_seg = se == r1;
+        // one row: scores, online softmax, weighted V.  kk/vv have landed when read.
+        auto process = [&](u32x4 (&kk)[NP], u32x4 (&vv)[NP], int row_now) {
+            const int t = row_now * PPW + tl;
+            const bool valid = t < n_tok;
+            if (t >= n_tok - 1) {                          // only in the last row of a head
 #pragma unroll
-            for (int k = 0; k < NP; ++k) {
-                kk[k] = u32x4{0u, 0u, 0u, 0u};
-                vv[k] = u32x4{0u, 0u, 0u, 0u};
+                for (int k = 0; k < NP; ++k) {
+                    const int pc = sub + LPP * k;
+                    kk[k] = t == n_tok - 1 ? *reinterpret_cast<const u32x4 *>(kn + 8 * pc) : u32x4{0u, 0u, 0u, 0u};
+                    vv[k] = t == n_tok - 1 ? *reinterpret_cast<const u32x4 *>(vn + 8 * pc) : u32x4{0u, 0u, 0u, 0u};
+                }
             }
-            if (t < n_tok - 1) {
-#pragma unroll
-                for (int k = 0; k < NP; ++k) kk[k] = load16_stream(Kh + koff[k] + (size_t)t * 16);
-#pragma unroll
-                for (int k = 0; k < NP; ++k) vv[k] = load16_stream(Vh + koff[k] + (size_t)t * 16);
-            } else if (t == n_tok - 1) {               // appended during this launch by other workgroups
-#pragma unroll
-                for (int k = 0; k < NP; ++k) kk[k] = xwg_load16(Kh + koff[k] + (size_t)t * 16);
-#pragma unroll
-                for (int k = 0; k < NP; ++k) vv[k] = xwg_load16(Vh + koff[k] + (size_t)t * 16);
-            }
-        };
-
-        u32x4 kA[NP], vA[NP], kB[NP], vB[NP];
-        int row = row_lo + wave;
-        if (row < row_hi) issue(kA, vA, row);
-        for (; row < row_hi; row += nw) {
-            if (row + nw < row_hi) issue(kB, vB, row + nw);
-            const bool valid = row * PPW + tl < n_tok;
+            // q is re-read from LDS for every row: the opaque offset keeps the reads
+            // from being hoisted into 8*NP registers for the whole loop
+            int qoff = 8 * sub;
+            asm volatile("" : "+v"(qoff));
             float sp = 0.f;
 #pragma unroll
             for (int k = 0; k < NP; ++k) {
-                const float4 qa = {q[k][0], q[k][1], q[k][2], q[k][3]};
-                const float4 qb = {q[k][4], q[k][5], q[k][6], q[k][7]};
-                sp = dot8(kA[k], qa, qb, sp);
+                const float4 qa = *reinterpret_cast<const float4 *>(qs + qoff + 8 * LPP * k);
+                const float4 qb = *reinterpret_cast<const float4 *>(qs + qoff + 8 * LPP * k + 4);
+                sp = dot8(kk[k], qa, qb, sp);
             }
             sp += lane_xor<1>(sp);                         // the lanes sharing this position
             if constexpr (LPP == 4) sp += lane_xor<2>(sp);
@@ -419,8 +695,8 @@ __device__ void attn_share(const StepParams &P, const __half *__restrict__ kv, i
             lrun = lrun * corr + p;
 #pragma unroll
             for (int k = 0; k < NP; ++k) {
-                const float2 a = unpack_h2(vA[k].x), b = unpack_h2(vA[k].y);
-                const float2 c = unpack_h2(vA[k].z), e = unpack_h2(vA[k].w);
+                const float2 a = unpack_h2(vv[k].x), b = unpack_h2(vv[k].y);
+                const float2 c = unpack_h2(vv[k].z), e = unpack_h2(vv[k].w);
                 float *ac = acc + 8 * k;
                 ac[0] = fmaf(p, a.x, ac[0] * corr); ac[1] = fmaf(p, a.y, ac[1] * corr);
                 ac[2] = fmaf(p, b.x, ac[2] * corr); ac[3] = fmaf(p, b.y, ac[3] * corr);
@@ -428,9 +704,26 @@ __device__ void attn_share(const StepParams &P, const __half *__restrict__ kv, i
                 ac[6] = fmaf(p, e.x, ac[6] * corr); ac[7] = fmaf(p, e.y, ac[7] * corr);
             }
             mrun = mn;
-#pragma unroll
-            for (int k = 0; k < NP; ++k) { kA[k] = kB[k]; vA[k] = vB[k]; }
+        };
+        // Two rows are in flight per wavefront; a register set is refilled as soon
+        // as its row is consumed.  The sets swap roles instead of being copied: a
+        // copy of a set whose loads are still in flight would have to wait for them.
+        while (row < row_hi) {
+            process(kA, vA, row);
+            issue(kA, vA, Kh, Vh, row + 2 * nw < row_hi ? row + 2 * nw : -1);
+            row += nw;
+            if (row >= row_hi) break;
+            process(kB, vB, row);
+            issue(kB, vB, Kh, Vh, row + 2 * nw < row_hi ? row + 2 * nw : -1);
+            row += nw;
         }
+
+        // The first wavefront alone merges the wavefronts' states, publishes the
+        // workgroup's partial and, if it was the last of the head, combines the head;
+        // the others go on (to the caller's next weights) after one barrier.  Its own
+        // next weights are requested only after its stores are acknowledged: that
+        // wait covers every outstanding memory operation of the wavefront.
+        if (last_seg && wave != 0) tail();
 
         // lanes -> wavefront
         const float mw = wave_max(mrun);
@@ -449,125 +742,218 @@ __device__ void attn_share(const StepParams &P, const __half *__restrict__ kv, i
             }
         }
         if (lane == 0) { wm[wave] = mw; wl[wave] = lw; }
+        tr.mark(14);
         __syncthreads();
 
-        // wavefronts -> workgroup partial, slot = rank of this workgroup among
-        // those covering head s
-        const long long g_lo = (((long long)s * R + 1) * G - 1) / T;
-        const long long g_hi = (((long long)(s + 1) * R) * G - 1) / T;
-        const int ncover = (int)(g_hi - g_lo + 1);
-        float *slot = P.part + ((size_t)s * P.part_slots + (size_t)(g - g_lo)) * (D + 2);
-        if (tid < D) {
-            float M = -INFINITY;
-            for (int wv = 0; wv < nw; ++wv) M = fmaxf(M, wm[wv]);
-            float L = 0.f, O = 0.f;
-            for (int wv = 0; wv < nw; ++wv) {
-                const float e = wm[wv] == -INFINITY ? 0.f : expf(wm[wv] - M);
-                L += wl[wv] * e;
-                O += wp[wv * D + tid] * e;
-            }
-            xwg_store(slot + tid, O);
-            if (tid == 0) { xwg_store(slot + D, M); xwg_store(slot + D + 1, L); }
-        }
-        if (P.debug & 8) { __syncthreads(); sb = se; continue; }
-        xwg_wait_stores();
-        __syncthreads();
-        if (tid == 0) {
-            const unsigned old = __hip_atomic_fetch_add(&P.seg_cnt[s], 1u, __ATOMIC_RELAXED,
-                                                        __HIP_MEMORY_SCOPE_AGENT);
-            *flag = old == (unsigned)(ncover - 1);
-        }
-        __syncthreads();
-        if (*flag) {                                       // this workgroup delivered the last partial
-            if (tid < D) {
-                const float *base = P.part + (size_t)s * P.part_slots * (D + 2);
+        if (wave == 0) {
+            // wavefronts -> workgroup partial, slot = rank of this workgroup among
+            // those covering head s.  A lane owns elements lane and lane + 64.
+            constexpr int NE = (D + 63) / 64;
+            const int g_lo = (int)((((long long)s * R + 1) * G - 1) / T);
+            const int g_hi = (int)((((long long)(s + 1) * R) * G - 1) / T);
+            const int ncover = g_hi - g_lo + 1;
+            float *slot = P.part + ((size_t)s * P.part_slots + (size_t)(g - g_lo)) * (D + 2);
+            {
                 float M = -INFINITY;
-                for (int j = 0; j < ncover; ++j) M = fmaxf(M, xwg_load(base + (size_t)j * (D + 2) + D));
-                float L = 0.f, O = 0.f;
-                for (int j = 0; j < ncover; ++j) {
-                    const float *sj = base + (size_t)j * (D + 2);
-                    const float e = expf(xwg_load(sj + D) - M);
-                    L += xwg_load(sj + D + 1) * e;
-                    O += xwg_load(sj + tid) * e;
+                for (int wv = 0; wv < nw; ++wv) M = fmaxf(M, wm[wv]);
+                float L = 0.f, O[NE];
+#pragma unroll
+                for (int e = 0; e < NE; ++e) O[e] = 0.f;
+                for (int wv = 0; wv < nw; ++wv) {
+                    const float ew = wm[wv] == -INFINITY ? 0.f : expf(wm[wv] - M);
+                    L += wl[wv] * ew;
+#pragma unroll
+                    for (int e = 0; e < NE; ++e)
+                        if (lane + 64 * e < D) O[e] += wp[wv * D + lane + 64 * e] * ew;
                 }
-                xwg_store(P.o + s * D + tid, O / L);
+#pragma unroll
+                for (int e = 0; e < NE; ++e)
+                    if (lane + 64 * e < D) xwg_store(slot + lane + 64 * e, O[e]);
+                if (lane == 0) { xwg_store(slot + D, M); xwg_store(slot + D + 1, L); }
             }
-            if (tid == 0)
-                __hip_atomic_store(&P.seg_cnt[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (!(P.debug & 8)) {
+                xwg_wait_stores();
+                tr.mark(15);
+                if (last_seg) tail();
+                unsigned old = 0;
+                if (lane == 0)
+                    old = __hip_atomic_fetch_add(&P.seg_cnt[s], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const bool is_last = __builtin_amdgcn_readfirstlane(old) == (unsigned)(ncover - 1);
+                if (is_last) {                             // this workgroup delivered the last partial
+                    const float *base = P.part + (size_t)s * P.part_slots * (D + 2);
+                    // loads of up to CB partials are in flight together (one round trip per batch)
+                    constexpr int CB = 8;
+                    float M = -INFINITY, L = 0.f, O[NE];
+#pragma unroll
+                    for (int e = 0; e < NE; ++e) O[e] = 0.f;
+                    for (int j0 = 0; j0 < ncover; j0 += CB) {
+                        float mj[CB], lj[CB], oj[CB][NE];
+#pragma unroll
+                        for (int j = 0; j < CB; ++j) {
+                            const int jj = j0 + j < ncover ? j0 + j : ncover - 1;
+                            const float *sj = base + (size_t)jj * (D + 2);
+                            mj[j] = xwg_load(sj + D);
+                            lj[j] = xwg_load(sj + D + 1);
+#pragma unroll
+                            for (int e = 0; e < NE; ++e) oj[j][e] = xwg_load(sj + (lane + 64 * e < D ? lane + 64 * e : 0));
+                        }
+#pragma unroll
+                        for (int j = 0; j < CB; ++j) {
+                            if (j0 + j < ncover) {         // running merge in slot order
+                                const float mn = fmaxf(M, mj[j]);
+                                const float c0 = M == -INFINITY ? 0.f : expf(M - mn);
+                                const float c1 = mj[j] == -INFINITY ? 0.f : expf(mj[j] - mn);
+                                L = L * c0 + lj[j] * c1;
+#pragma unroll
+                                for (int e = 0; e < NE; ++e) O[e] = O[e] * c0 + oj[j][e] * c1;
+                                M = mn;
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < NE; ++e)
+                        if (lane + 64 * e < D) xwg_store(P.o + s * D + lane + 64 * e, O[e] / L);
+                    if (lane == 0)
+                        __hip_atomic_store(&P.seg_cnt[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            } else if (last_seg) {
+                tail();
+            }
         }
-        __syncthreads();
+        if (!last_seg) __syncthreads();                    // the scratch is reused by the next head
+        tr.mark(16);
         sb = se;
     }
 }
 
-// copy an exchanged workspace vector (n a multiple of 8) into LDS in GEMV order,
-// zero padded to a chunk multiple; coherent 8-byte loads, a batch in flight
-// together
-__device__ __forceinline__ void stage_vector(const float *__restrict__ src, int n, float *dst)
-{
-    constexpr int UN = 10;
-    const int n2 = n >> 1, np2 = round_up_chunk(n) >> 1;
-    const int tid = threadIdx.x, nt = blockDim.x;
-    for (int base = 0; base < np2; base += UN * nt) {
-        float2 v[UN];
+// Copy of an exchanged workspace vector (n a multiple of 8, at most
+// 2 * UN * blockDim.x elements) into LDS in GEMV order, zero padded to a unit
+// multiple: coherent 8-byte loads that are all in flight together, split into
+// the request and the LDS write so that other loads can be queued in between.
+template <int UN>
+struct StagedVector {
+    float2 v[UN];
+    __device__ __forceinline__ void issue(const float *__restrict__ src, int n, int tid)
+    {
+        const int n2 = n >> 1, nt = blockDim.x;
 #pragma unroll
         for (int j = 0; j < UN; ++j) {
-            const int i2 = base + tid + j * nt;
-            v[j] = i2 < n2 ? xwg_load2(src + 2 * i2) : float2{0.f, 0.f};
-        }
-#pragma unroll
-        for (int j = 0; j < UN; ++j) {
-            const int i2 = base + tid + j * nt;
-            if (i2 < np2) *reinterpret_cast<float2 *>(dst + lds_perm(i2 * 2)) = v[j];
+            const int i2 = tid + j * nt;
+            v[j] = float2{0.f, 0.f};
+            if (j * nt < n2) v[j] = xwg_load2(src + 2 * (i2 < n2 ? i2 : 0));
         }
     }
-}
+    __device__ __forceinline__ void commit(int n, float *dst, int tid) const
+    {
+        const int n2 = n >> 1, np2 = round_up_chunk(n) >> 1, nt = blockDim.x;
+#pragma unroll
+        for (int j = 0; j < UN; ++j) {
+            const int i2 = tid + j * nt;
+            if (i2 < np2) *reinterpret_cast<float2 *>(dst + lds_perm(i2 * 2)) = i2 < n2 ? v[j] : float2{0.f, 0.f};
+        }
+    }
+};
 
-// Phase B.  LDS: m[Kp_f] part[rows_h*nsl_down] scr[nw*(D+2)+4]
-template <int D>
-__device__ void phase_b(const StepParams &P, const __half *__restrict__ w, const __half *__restrict__ kv,
-                        int pos, float *lds)
+// Phase B.  LDS: m[Kp_f] part[rows_h*nw] bounds[16] scr[nw*(D+2)+4+2*D]
+template <int D, class Sync>
+__device__ __forceinline__ void phase_b(const StepParams &P, const __half *__restrict__ w,
+                                        const __half *__restrict__ kv, int pos, float *lds, Sync &sync)
 {
     const Dims &dm = P.dm;
-    const int h = dm.h, f = dm.f, tid = threadIdx.x, nt = blockDim.x, g = blockIdx.x;
+    const int h = dm.h, f = dm.f, tid = opaque_thread_index(), nt = blockDim.x, g = blockIdx.x;
     const int Kp = round_up_chunk(f);
-    float *ml = lds, *part = lds + Kp, *scr = part + P.rows_h * P.nsl_down;
-    if (!(P.debug & 1)) stage_vector(P.m, f, ml);
-    if (!(P.debug & 2)) attn_share<D>(P, kv, pos + 1, scr);
-    __syncthreads();
+    float *ml = lds, *part = lds + Kp;
+    int *bnd = reinterpret_cast<int *>(part + P.rows_h * (nt >> 6));
+    float *scr = reinterpret_cast<float *>(bnd + 16);
     const int r_begin = g * P.rows_h, r_n = max(0, min(P.rows_h, h - r_begin));
-    if (!(P.debug & 4)) wg_gemv(w + P.lay.w_down, f, r_begin, r_n, P.nsl_down, ml, part);
-    __syncthreads();
+    GemvSpan<kGemvUDown> gs;
+    gs.init(GemvSeg{w + P.lay.w_down + (size_t)r_begin * f, ml, f, r_n}, GemvSeg{w + P.lay.w_down, ml, f, 0}, w, tid, bnd, kShare0AfterAttention);
+    // the first down-projection weights are requested behind the last K/V loads,
+    // so that they stream while the attention partials are merged
+    Tracer tr;
+    tr.init(P, gs.wave, 16);
+    tr.mark(10);
+    clear_partials(part, P.rows_h * (nt >> 6), tid);
     const __half *bd = w + P.lay.b_down;
-    for (int t = tid; t < r_n; t += nt) {
-        float a = 0.f;
-        for (int sl = 0; sl < P.nsl_down; ++sl) a += part[t * P.nsl_down + sl];
-        xwg_store(P.g + r_begin + t, a + __half2float(bd[r_begin + t]));
-    }
+    const int item0 = spread_index(tid);
+    const float bd0 = item0 < r_n ? __half2float(bd[r_begin + item0]) : 0.f;   // for the epilogue
+    StagedVector<kStageM> sm;
+    if constexpr (Sync::kInputsReady) sm.issue(P.m, f, tid);
+    attn_share<D>(P, kv, pos + 1, scr, tid,
+                  [&] {
+                      sync.wait();
+                      tr.mark(11);
+                      if constexpr (!Sync::kInputsReady) sm.issue(P.m, f, tid);
+                  },
+                  [&] {
+                      // The first down-projection weights are requested here, behind the
+                      // K/V rows: they stream while the rows are processed and the partials
+                      // merged.  (The first wavefront has no share of the GEMV: its loads
+                      // re-read one cached block and cost nothing to wait for.)
+                      gs.issue_first();
+                      gs.issue_second();
+                  },
+                  [&] { sm.commit(f, ml, tid); tr.mark(12); },
+                  [&] { tr.mark(13); }, tr);
+    tr.mark(17);
+    gs.run(part);            // (m became visible at the barrier inside attn_share)
+    tr.mark(18);
+    __syncthreads();
+    for (int t = item0; t < r_n; t += nt)
+        xwg_store(P.g + r_begin + t, gs.row_total(part, t) + (t == item0 ? bd0 : __half2float(bd[r_begin + t])));
+    tr.mark(19);
+    sync.arrive();
 }
 
-// Phase C.  LDS: o[Kp_h] part[rows_h*nsl_dense]
-__device__ void phase_c(const StepParams &P, const __half *__restrict__ w, int layer, float *lds)
+// Phase C.  LDS: o[Kp_h] part[rows_h*nw] bounds[16]
+template <class Sync>
+__device__ __forceinline__ void phase_c(const StepParams &P, const __half *__restrict__ w, int layer,
+                                        float *lds, Sync &sync)
 {
     const Dims &dm = P.dm;
-    const int h = dm.h, tid = threadIdx.x, nt = blockDim.x, g = blockIdx.x;
+    const int h = dm.h, tid = opaque_thread_index(), nt = blockDim.x, g = blockIdx.x;
     const int Kp = round_up_chunk(h);
     float *ol = lds, *part = lds + Kp;
+    int *bnd = reinterpret_cast<int *>(part + P.rows_h * (nt >> 6));
     const LayerIO io = layer_io(P, layer);
-    stage_vector(P.o, h, ol);
-    __syncthreads();
     const int r_begin = g * P.rows_h, r_n = max(0, min(P.rows_h, h - r_begin));
-    wg_gemv(w + P.lay.w_dense, h, r_begin, r_n, P.nsl_dense, ol, part);
-    __syncthreads();
+    GemvSpan<kGemvU> gs;
+    gs.init(GemvSeg{w + P.lay.w_dense + (size_t)r_begin * h, ol, h, r_n}, GemvSeg{w + P.lay.w_dense, ol, h, 0}, w, tid, bnd);
+    Tracer tr;
+    tr.init(P, gs.wave, 48);
+    tr.mark(20);
+    clear_partials(part, P.rows_h * (nt >> 6), tid);
+    StagedVector<kStageM> so;
+    if constexpr (Sync::kInputsReady) so.issue(P.o, h, tid);
+    gs.issue_first();
+    gs.issue_second();
+    sync.wait();
+    tr.mark(21);
+    if constexpr (!Sync::kInputsReady) so.issue(P.o, h, tid);
+    // epilogue operands of this thread's first row
     const __half *bd = w + P.lay.b_dense;
-    for (int t = tid; t < r_n; t += nt) {
-        float a = 0.f;
-        for (int sl = 0; sl < P.nsl_dense; ++sl) a += part[t * P.nsl_dense + sl];
-        a += __half2float(bd[r_begin + t]);
-        const float res = (load_x(io, r_begin + t) + a) + xwg_load(P.g + r_begin + t);
+    const int item0 = spread_index(tid);
+    float bd0 = 0.f, x0 = 0.f, g0 = 0.f;
+    if (item0 < r_n) {
+        bd0 = __half2float(bd[r_begin + item0]);
+        x0 = load_x(io, r_begin + item0);
+        g0 = xwg_load(P.g + r_begin + item0);
+    }
+    so.commit(h, ol, tid);
+    __syncthreads();
+    tr.mark(22);
+    gs.run(part);
+    tr.mark(23);
+    __syncthreads();
+    for (int t = item0; t < r_n; t += nt) {
+        const bool pre = t == item0;
+        const float a = gs.row_total(part, t) + (pre ? bd0 : __half2float(bd[r_begin + t]));
+        const float res = ((pre ? x0 : load_x(io, r_begin + t)) + a) + (pre ? g0 : xwg_load(P.g + r_begin + t));
         if (io.o16) io.o16[r_begin + t] = __float2half_rn(res);
         else xwg_store(io.o32 + r_begin + t, res);
     }
+    tr.mark(24);
+    sync.arrive();
 }
 
 // position of the new token; out of range raises the error flag (no work is done)
@@ -591,7 +977,8 @@ k_phase_a(StepParams P, const __half *w, __half *kv, int layer)
     extern __shared__ __align__(16) float lds[];
     int pos;
     if (!read_pos(P, &pos)) return;
-    phase_a(P, w, kv, layer, pos, lds);
+    NoSync sync;
+    phase_a(P, w, kv, layer, pos, lds, sync);
 }
 
 template <int D>
@@ -601,7 +988,8 @@ k_phase_b(StepParams P, const __half *w, const __half *kv)
     extern __shared__ __align__(16) float lds[];
     int pos;
     if (!read_pos(P, &pos)) return;
-    phase_b<D>(P, w, kv, pos, lds);
+    NoSync sync;
+    phase_b<D>(P, w, kv, pos, lds, sync);
 }
 
 __global__ void __launch_bounds__(kMaxThreads)
@@ -610,7 +998,8 @@ k_phase_c(StepParams P, const __half *w, int layer)
     extern __shared__ __align__(16) float lds[];
     int pos;
     if (!read_pos(P, &pos)) return;
-    phase_c(P, w, layer, lds);
+    NoSync sync;
+    phase_c(P, w, layer, lds, sync);
 }
 
 template <int D>
@@ -622,11 +1011,11 @@ k_block_persistent(StepParams P, const __half *w, __half *kv, int layer)
     if (!read_pos(P, &pos)) return;
     GridBarrier bar;
     bar.init(P.sync, gridDim.x);
-    phase_a(P, w, kv, layer, pos, lds);
-    bar.wait();
-    phase_b<D>(P, w, kv, pos, lds);
-    bar.wait();
-    phase_c(P, w, layer, lds);
+    GridSync sync{bar};
+    phase_a(P, w, kv, layer, pos, lds, sync);
+    phase_b<D>(P, w, kv, pos, lds, sync);
+    phase_c(P, w, layer, lds, sync);
+    bar.finish();
 }
 
 template <int D>
@@ -638,17 +1027,16 @@ k_stack_persistent(StepParams P, const LayerPtrs *__restrict__ ptrs)
     if (!read_pos(P, &pos)) return;
     GridBarrier bar;
     bar.init(P.sync, gridDim.x);
+    GridSync sync{bar};
 #pragma clang loop unroll(disable)
     for (int layer = 0; layer < P.n_layers; ++layer) {
         const __half *w = ptrs->w[layer];
         __half *kv = ptrs->kv[layer];
-        if (layer) bar.wait();
-        phase_a(P, w, kv, layer, pos, lds);
-        bar.wait();
-        phase_b<D>(P, w, kv, pos, lds);
-        bar.wait();
-        phase_c(P, w, layer, lds);
+        phase_a(P, w, kv, layer, pos, lds, sync);
+        phase_b<D>(P, w, kv, pos, lds, sync);
+        phase_c(P, w, layer, lds, sync);
     }
+    bar.finish();
 }
 
 // ---------------------------------------------------------------------------

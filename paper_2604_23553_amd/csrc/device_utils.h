@@ -9,6 +9,7 @@
 namespace cfpp {
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Pointers that come out of a table in memory (per-layer weights, KV caches) lose
 // their address space; the explicit global address space keeps the compiler from
@@ -100,6 +101,16 @@ __device__ __forceinline__ u32x4 load16_stream(const __half *p)
     return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
 }
 
+// uniform (scalar-register) base + 32-bit per-lane byte offset: one address
+// register per load instead of two, and the base arithmetic stays on the scalar unit
+__device__ __forceinline__ u32x4 load16_stream_at(const __half *ubase, unsigned byte_off)
+{
+    return __builtin_nontemporal_load(
+        as_global(reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(ubase) + byte_off)));
+}
+// wavefront index inside the workgroup, as a scalar
+__device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
+
 // Position of activation element k inside an LDS vector laid out for the GEMV
 // inner loop: per 512-element chunk, lane l reads elements 8l..8l+7 as two
 // float4 at [l*4] and [256 + l*4], so that consecutive lanes touch consecutive
@@ -146,6 +157,11 @@ __device__ __forceinline__ void xwg_store_half(__half *p, float v)
     __hip_atomic_store(as_global(reinterpret_cast<unsigned short *>(p)), __half_as_ushort(hv), __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ __half xwg_load_half(const __half *p)
+{
+    return __ushort_as_half(__hip_atomic_load(as_global(reinterpret_cast<const unsigned short *>(p)),
+                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
 // 16 bytes of fp16 as two coherent 8-byte loads
 __device__ __forceinline__ u32x4 xwg_load16(const __half *p)
 {
@@ -163,48 +179,84 @@ __device__ __forceinline__ void xwg_wait_stores()
 // ---- grid barrier ------------------------------------------------------------
 // All workgroups of a launch must be resident (the host checks the grid against
 // the occupancy limit).  The barrier orders only exchange data (xwg_store /
-// xwg_load): it issues no cache write-back or invalidate.  sync[kSyncCount] returns to 0 after every barrier and
-// sync[kSyncGen] only grows, so nothing needs resetting between launches or
-// graph replays.  The wait is bounded: after ~2 s of wall clock the waiter sets
-// the error flag and every later barrier falls through, so the grid always
-// drains.
+// xwg_load): it issues no cache write-back or invalidate.
+//
+// Two levels: a workgroup arrives at one of up to 16 leaf counters (128 bytes
+// apart, so arrivals at different leaves do not serialise), the last arrival of
+// a leaf arrives at the root, the last arrival of the root publishes the next
+// generation.  Counters count up on even barriers and down on odd ones, so they
+// need no reset (and no ordering between a reset and the release); a launch that
+// has run an odd number of barriers runs one more before it ends, which leaves
+// every counter at zero whatever grid the next launch uses.
+//
+// The barrier is split: arrive() (after this workgroup's exchange stores) and
+// wait().  Loads issued between the two - weights that do not depend on other
+// workgroups - stay in flight across the wait.  Only thread 0 talks to memory;
+// the value its arrival returns is not needed before wait().
+// The wait is bounded: after ~2 s of wall clock the waiter sets the error flag
+// and every later barrier falls through, so the grid always drains.
 struct GridBarrier {
     unsigned *sync;
-    unsigned gen;      // generation this workgroup waits to leave (thread 0 only)
-    unsigned nwg;
+    unsigned gen;        // generation this workgroup waits to leave (thread 0 only)
+    unsigned nbar;       // barriers completed by this launch
+    unsigned nleaf, members;
+    unsigned *leaf;
+    bool pending, last;
 
-    __device__ __forceinline__ void init(unsigned *s, unsigned n)
+    __device__ __forceinline__ void init(unsigned *s, unsigned nwg)
     {
         sync = s;
-        nwg = n;
+        nbar = 0;
+        pending = false;
+        last = false;
+        nleaf = nwg < (unsigned)kSyncLeaves ? nwg : (unsigned)kSyncLeaves;
+        const unsigned l = blockIdx.x % nleaf;
+        members = (nwg - l + nleaf - 1) / nleaf;
+        leaf = s + kSyncLeaf0 + l * kSyncLeafStride;
         gen = 0;
         if (threadIdx.x == 0)
-            gen = __hip_atomic_load(&sync[kSyncGen], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            gen = __hip_atomic_load(as_global(&sync[kSyncGen]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    // true when this arrival was the last of `n` at counter c
+    __device__ __forceinline__ bool count(unsigned *c, unsigned n) const
+    {
+        if (nbar & 1u) {
+            return __hip_atomic_fetch_add(as_global(c), 0xffffffffu, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 1u;
+        }
+        return __hip_atomic_fetch_add(as_global(c), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == n - 1u;
+    }
+
+    __device__ __forceinline__ void arrive()
+    {
+        xwg_wait_stores();          // every wavefront: its exchange stores are in memory
+        __syncthreads();
+        if (threadIdx.x == 0) last = count(leaf, members);
+        pending = true;
     }
 
     __device__ __forceinline__ void wait()
     {
-        xwg_wait_stores();          // every wavefront: its exchange stores are in memory
-        __syncthreads();
+        if (!pending) return;
+        pending = false;
         if (threadIdx.x == 0) {
-            unsigned old = __hip_atomic_fetch_add(&sync[kSyncCount], 1u, __ATOMIC_RELAXED,
-                                                  __HIP_MEMORY_SCOPE_AGENT);
-            if (old == nwg - 1) {
-                __hip_atomic_store(&sync[kSyncCount], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                xwg_wait_stores();  // the reset lands before anyone can leave
-                __hip_atomic_fetch_add(&sync[kSyncGen], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else {
+            bool released = false;
+            if (last && count(sync + kSyncRoot, nleaf)) {
+                __hip_atomic_store(as_global(&sync[kSyncGen]), gen + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                released = true;
+            }
+            if (!released) {
                 const unsigned long long t0 = wall_clock64();
                 unsigned spins = 0;
-                while (__hip_atomic_load(&sync[kSyncGen], __ATOMIC_RELAXED,
+                while (__hip_atomic_load(as_global(&sync[kSyncGen]), __ATOMIC_RELAXED,
                                          __HIP_MEMORY_SCOPE_AGENT) == gen) {
                     __builtin_amdgcn_s_sleep(1);
                     if ((++spins & 1023u) == 0) {
-                        if (__hip_atomic_load(&sync[kSyncErr], __ATOMIC_RELAXED,
+                        if (__hip_atomic_load(as_global(&sync[kSyncErr]), __ATOMIC_RELAXED,
                                               __HIP_MEMORY_SCOPE_AGENT) == kErrBarrierTimeout)
                             break;
                         if (wall_clock64() - t0 > 200000000ull) {   // 100 MHz counter: 2 s
-                            __hip_atomic_store(&sync[kSyncErr], (unsigned)kErrBarrierTimeout,
+                            __hip_atomic_store(as_global(&sync[kSyncErr]), (unsigned)kErrBarrierTimeout,
                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             break;
                         }
@@ -213,7 +265,39 @@ struct GridBarrier {
             }
             gen += 1;
         }
+        nbar += 1;
         __syncthreads();
+    }
+
+    // before the launch ends: leave every counter at zero
+    __device__ __forceinline__ void finish()
+    {
+        wait();
+        if (nbar & 1u) { arrive(); wait(); }
+    }
+};
+
+// ---- timeline trace (profiling aid) --------------------------------------------
+// Workgroup (debug >> 8) records (tag, 100 MHz wall clock) pairs per wavefront
+// when bit 16 of StepParams::debug is set; `first` lets each kernel of a
+// multi-kernel step use its own part of a wavefront's kTraceLen entries.
+struct Tracer {
+    unsigned long long *p;
+    int n;
+    template <class Params>
+    __device__ __forceinline__ void init(const Params &P, int wave, int first = 0)
+    {
+        const bool on = (P.debug & 16) && (int)blockIdx.x == (P.debug >> 8) && wave < kTraceWaves;
+        p = on ? P.trace + (size_t)wave * kTraceLen * 2 : nullptr;
+        n = first;
+    }
+    __device__ __forceinline__ void mark(int tag)
+    {
+        if (p && n < kTraceLen && (threadIdx.x & 63) == 0) {
+            p[2 * n] = (unsigned long long)tag;
+            p[2 * n + 1] = wall_clock64();
+        }
+        if (p) ++n;
     }
 };
 

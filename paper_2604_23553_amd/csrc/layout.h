@@ -76,9 +76,13 @@ CFPP_HD size_t kv_offset(const Dims &m, int which, int b, int n, int dim, int t)
 }
 CFPP_HD size_t kv_layer_elems(const Dims &m) { return 2 * kv_which_stride(m); }
 
+// indices into the sync words (barrier counters 128 bytes apart)
+enum { kSyncGen = 16, kSyncErr = 32, kSyncRoot = 64, kSyncLeaf0 = 96, kSyncLeafStride = 32, kSyncLeaves = 16,
+       kSyncWords = kSyncLeaf0 + kSyncLeaves * kSyncLeafStride };
+
 // Workspace: byte offsets of every static buffer.
 struct WorkspaceLayout {
-    size_t sync;      // uint32[64]: grid-barrier words, device error flag
+    size_t sync;      // uint32[kSyncWords]: grid-barrier words, device error flag
     size_t seg_cnt;   // uint32[max_batch*H]: arrivals per (sequence, head) in the split-KV combine
     size_t layer_ptrs; // device copy of the per-layer pointer table of the stack kernel
     size_t events;    // uint64 counters of the stream kernel's M event: [1 top + 64 groups], 64 B apart
@@ -103,7 +107,7 @@ CFPP_HD WorkspaceLayout workspace_layout(const Dims &m)
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     W.part_slots = part_slots_for(m.H);
-    W.sync = take(64 * 4);
+    W.sync = take((size_t)kSyncWords * 4);
     W.seg_cnt = take((size_t)m.max_batch * m.H * 4);
     W.layer_ptrs = take(2 * kMaxLayers * sizeof(void *));
     W.events = take(65 * 64);
@@ -120,8 +124,7 @@ CFPP_HD WorkspaceLayout workspace_layout(const Dims &m)
     return W;
 }
 
-// indices into the sync words
-enum { kSyncCount = 0, kSyncGen = 16, kSyncErr = 32 };
+
 // device error codes
 enum { kErrNone = 0, kErrBadPos = 1, kErrBarrierTimeout = 2 };
 

@@ -242,25 +242,6 @@ struct MEvent {
 };
 
 // ---- timeline trace (profiling aid) ---------------------------------------------------
-struct Tracer {
-    unsigned long long *p;
-    int n;
-    __device__ __forceinline__ void init(const StepParams &P, int wave)
-    {
-        const bool on = (P.debug & 16) && (int)blockIdx.x == (P.debug >> 8) && wave < kTraceWaves;
-        p = on ? P.trace + (size_t)wave * kTraceLen * 2 : nullptr;
-        n = 0;
-    }
-    __device__ __forceinline__ void mark(int tag)
-    {
-        if (p && n < kTraceLen && (threadIdx.x & 63) == 0) {
-            p[2 * n] = (unsigned long long)tag;
-            p[2 * n + 1] = wall_clock64();
-        }
-        if (p) ++n;
-    }
-};
-
 // ---- work split of one workgroup ---------------------------------------------------
 template <int D, int CTH, int RTH, int CTF, int RTF>
 struct Work {
