@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcfpp.so")
 SOURCES = ["api.hip", "decode_kernels.hip", "stream_kernel.hip", "prep_kernels.hip"]
-HEADERS = ["layout.h", "device_utils.h", "decode_params.h", "attention_common.h"]
+HEADERS = ["layout.h", "device_utils.h", "decode_params.h", "attention_common.h", "decode_blocks.h", "attention_blocks.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -336,9 +336,9 @@ static cfpp_status launch_shape(const cfpp_ctx *ctx, Shape *sh)
     const int nch_h = ceil_div(dm.h, kChunk), nch_f = ceil_div(dm.f, kChunk);
     sh->nsl_down = pick_slices(sh->rows_h, nch_f, nw);
     sh->nsl_dense = pick_slices(sh->rows_h, nch_h, nw);
-    const size_t a = 2 * (size_t)nch_h * kChunk + (size_t)(sh->rows_qkv + sh->rows_up) * nw + 16 + 16;
-    const size_t b = (size_t)nch_f * kChunk + (size_t)sh->rows_h * nw + 16 + (size_t)nw * (dm.d + 2) + 4 + 2 * (size_t)dm.d;
-    const size_t c = (size_t)nch_h * kChunk + (size_t)sh->rows_h * nw + 16;
+    const size_t a = 2 * (size_t)nch_h * kChunk + (size_t)(sh->rows_qkv + sh->rows_up) * nw + 16;
+    const size_t b = (size_t)nch_f * kChunk + (size_t)sh->rows_h * nw + (size_t)nw * (dm.d + 2) + 4 + 2 * (size_t)dm.d;
+    const size_t c = (size_t)nch_h * kChunk + (size_t)sh->rows_h * nw;
     size_t m = a > b ? a : b;
     m = m > c ? m : c;
     m = (m + 63) / 64 * 64;
