@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcfpp.so")
-SOURCES = ["api.hip", "decode_kernels.hip", "stream_kernel.hip", "prep_kernels.hip"]
+SOURCES = ["api.hip", "decode_kernels.hip", "fused_kernel.hip", "stream_kernel.hip", "prep_kernels.hip"]
 HEADERS = ["layout.h", "device_utils.h", "decode_params.h", "attention_common.h", "decode_blocks.h", "attention_blocks.h"]
 
 HIPCC_FLAGS = [

@@ -270,6 +270,16 @@ extern "C" cfpp_status cfpp_set_option(cfpp_ctx *ctx, int32_t option, int64_t va
     switch (option) {
     case CFPP_OPT_MODE:
         if (value < 0 || value > 3) return fail(CFPP_EINVAL, "mode must be 0, 1, 2 or 3");
+        if ((int)value != ctx->mode) {
+            // The modes tag their exchanged words from different counters: start the
+            // new one from zeroed barrier words, counters and tagged words (waits for
+            // the device; not for use inside a stream capture).
+            HIP_OK(hipDeviceSynchronize());
+            HIP_OK(hipMemset(ctx->ws + ctx->wl.sync, 0, ctx->wl.layer_ptrs - ctx->wl.sync));
+            HIP_OK(hipMemset(ctx->ws + ctx->wl.events, 0, ctx->wl.rope - ctx->wl.events));
+            HIP_OK(hipDeviceSynchronize());
+            ctx->events_grid = 0;
+        }
         ctx->mode = (int)value;
         return CFPP_OK;
     case CFPP_OPT_GRID:
@@ -360,6 +370,7 @@ static cfpp_status prepare(cfpp_ctx *ctx)
     if (ctx->prepared) return CFPP_OK;
     HIP_OK(prepare_kernels(160 * 1024));
     HIP_OK(prepare_stream_kernels(160 * 1024));
+    HIP_OK(prepare_fused_kernels(160 * 1024));
     ctx->prepared = true;
     return CFPP_OK;
 }
@@ -382,6 +393,7 @@ static StepParams make_params(const cfpp_ctx *ctx, const Shape &sh, int b, const
     P.o = reinterpret_cast<float *>(ctx->ws + wl.o) + (size_t)b * dm.h;
     P.part = reinterpret_cast<float *>(ctx->ws + wl.part) + (size_t)b * dm.H * wl.part_slots * (dm.d + 2);
     P.part_slots = wl.part_slots;
+    P.tagged = reinterpret_cast<float *>(ctx->ws + wl.tagged);
     P.pos = pos_dev + b;
     P.b = b;
     P.x_in = static_cast<const __half *>(x) + (size_t)b * dm.h;
@@ -402,6 +414,23 @@ static cfpp_status check_persistent(const cfpp_ctx *ctx, const Shape &sh)
     if ((long long)per_cu * ctx->n_cu < sh.grid)
         return fail(CFPP_EUNSUPPORTED,
                     "persistent mode needs all %d workgroups resident, device fits %d x %d", sh.grid,
+                    per_cu, ctx->n_cu);
+    return CFPP_OK;
+}
+
+// Mode 2 (whole stack, hand-overs hidden behind streaming): shape limits and residency.
+static cfpp_status check_fused(const cfpp_ctx *ctx, const Shape &sh, const StepParams &P)
+{
+    if (!fused_supported(ctx->dm, P, sh.grid, sh.threads))
+        return fail(CFPP_EUNSUPPORTED,
+                    "mode 2 needs grid >= n_heads, at most 64 rows of the hidden-size matrices per workgroup, "
+                    "hidden <= 4096 and head_dim 64, 80 or 128; use mode 0 for this shape");
+    const size_t lds = fused_lds_bytes(ctx->dm, P, sh.threads);
+    if (lds > 160 * 1024) return fail(CFPP_EUNSUPPORTED, "mode 2 needs %zu bytes of LDS (> 160 KiB)", lds);
+    int per_cu = 0;
+    HIP_OK(fused_occupancy(ctx->dm.d, sh.threads, lds, &per_cu));
+    if ((long long)per_cu * ctx->n_cu < sh.grid)
+        return fail(CFPP_EUNSUPPORTED, "mode 2 needs all %d workgroups resident, device fits %d x %d", sh.grid,
                     per_cu, ctx->n_cu);
     return CFPP_OK;
 }
@@ -518,6 +547,8 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
         if ((st = stream_residency(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, L))) != CFPP_OK) return st;
         if (store_table && (st = stream_rearm(ctx, sh.grid, s)) != CFPP_OK) return st;
         if (!store_table && ctx->events_grid != sh.grid) return fail(CFPP_ESTATE, "event counters not armed for this grid");
+    } else if (ctx->mode == 2) {
+        if ((st = check_fused(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, L))) != CFPP_OK) return st;
     } else if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
     LayerPtrs ptrs;
     std::memset(&ptrs, 0, sizeof ptrs);
@@ -534,7 +565,7 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
             HIP_OK(launch_stack_stream(P, dev_ptrs, reinterpret_cast<unsigned long long *>(ctx->ws + ctx->wl.events),
                                        reinterpret_cast<float *>(ctx->ws + ctx->wl.tagged), sh.grid, sh.threads, s));
         } else if (ctx->mode == 2) {
-            HIP_OK(launch_stack_persistent(P, dev_ptrs, sh.grid, sh.threads, s));
+            HIP_OK(launch_stack_fused(P, dev_ptrs, sh.grid, sh.threads, s));
         } else {
             for (int l = 0; l < L; ++l) {
                 if (ctx->mode == 0)

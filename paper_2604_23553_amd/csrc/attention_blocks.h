@@ -253,6 +253,95 @@ struct AttnCore {
             __hip_atomic_store(&P.seg_cnt[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return true;
     }
+
+    // The same two steps with tagged words (value, tag pairs in `pt`, laid out like
+    // P.part): the partial is published with single stores and nobody counts;
+    // the first workgroup covering a head re-reads the head's slots until all
+    // carry `tag`, merges them in slot order and stores the head's output into
+    // P.o.  The publishing side waits for no acknowledgement.
+    __device__ __forceinline__ void publish_tagged(const StepParams &P, float *pt, unsigned tag, int s,
+                                                   const float *wp, const float *wm, const float *wl,
+                                                   int nslots) const
+    {
+        int g_lo, ncover;
+        cover(s, g_lo, ncover);
+        float *slot = pt + 2 * ((size_t)s * P.part_slots + (size_t)(g - g_lo)) * (D + 2);
+        float M = -INFINITY;
+        for (int wv = 0; wv < nslots; ++wv) M = fmaxf(M, wm[wv]);
+        float L = 0.f, O[NE];
+#pragma unroll
+        for (int e = 0; e < NE; ++e) O[e] = 0.f;
+        for (int wv = 0; wv < nslots; ++wv) {
+            const float ew = wm[wv] == -INFINITY ? 0.f : expf(wm[wv] - M);
+            L += wl[wv] * ew;
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+                if (lane + 64 * e < D) O[e] += wp[wv * D + lane + 64 * e] * ew;
+        }
+#pragma unroll
+        for (int e = 0; e < NE; ++e)
+            if (lane + 64 * e < D) xwg_store_tagged(slot + 2 * (lane + 64 * e), O[e], tag);
+        if (lane == 0) { xwg_store_tagged(slot + 2 * D, M, tag); xwg_store_tagged(slot + 2 * (D + 1), L, tag); }
+    }
+
+    // true if this workgroup is the one that combines head s
+    __device__ __forceinline__ bool combines(int s) const
+    {
+        int g_lo, ncover;
+        cover(s, g_lo, ncover);
+        return g == g_lo;
+    }
+
+    __device__ __forceinline__ void combine_tagged(const StepParams &P, const float *pt, unsigned tag, int s) const
+    {
+        int g_lo, ncover;
+        cover(s, g_lo, ncover);
+        const float *base = pt + 2 * (size_t)s * P.part_slots * (D + 2);
+        constexpr int CB = 8;
+        float M = -INFINITY, L = 0.f, O[NE];
+#pragma unroll
+        for (int e = 0; e < NE; ++e) O[e] = 0.f;
+        PollGuard pg;
+        pg.start(P.sync);
+        for (int j0 = 0; j0 < ncover; j0 += CB) {
+            float2 mj[CB], lj[CB], oj[CB][NE];
+            bool ok;
+            do {
+#pragma unroll
+                for (int j = 0; j < CB; ++j) {
+                    const int jj = j0 + j < ncover ? j0 + j : ncover - 1;
+                    const float *sj = base + 2 * (size_t)jj * (D + 2);
+                    mj[j] = xwg_load2(sj + 2 * D);
+                    lj[j] = xwg_load2(sj + 2 * (D + 1));
+#pragma unroll
+                    for (int e = 0; e < NE; ++e) oj[j][e] = xwg_load2(sj + 2 * (lane + 64 * e < D ? lane + 64 * e : 0));
+                }
+                ok = true;
+#pragma unroll
+                for (int j = 0; j < CB; ++j) {
+                    ok = ok && __float_as_uint(mj[j].y) == tag && __float_as_uint(lj[j].y) == tag;
+#pragma unroll
+                    for (int e = 0; e < NE; ++e) ok = ok && __float_as_uint(oj[j][e].y) == tag;
+                }
+                ok = __all(ok);
+            } while (!ok && !pg.give_up());
+#pragma unroll
+            for (int j = 0; j < CB; ++j) {
+                if (j0 + j < ncover) {                     // running merge in slot order
+                    const float mn = fmaxf(M, mj[j].x);
+                    const float c0 = M == -INFINITY ? 0.f : expf(M - mn);
+                    const float c1 = mj[j].x == -INFINITY ? 0.f : expf(mj[j].x - mn);
+                    L = L * c0 + lj[j].x * c1;
+#pragma unroll
+                    for (int e = 0; e < NE; ++e) O[e] = O[e] * c0 + oj[j][e].x * c1;
+                    M = mn;
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < NE; ++e)
+            if (lane + 64 * e < D) xwg_store(P.o + s * D + lane + 64 * e, O[e] / L);
+    }
 };
 
 // this head's query and the new token's K/V rows: workspace -> registers -> LDS,

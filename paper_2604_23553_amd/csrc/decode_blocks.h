@@ -173,10 +173,17 @@ struct GemvSpan {
         }
     }
 
-    // consume everything; issue_first() and issue_second() have been called
+    // consume everything; issue_first() and issue_second() have been called.
+    // before_drain(): called once when the last load of this GEMV has been
+    // issued - the place to request whatever should stream next.
     __device__ __forceinline__ void run(float *part)
     {
-        if (!regular) { run_general(part); return; }
+        run(part, [] {});
+    }
+    template <class Hook>
+    __device__ __forceinline__ void run(float *part, Hook &&before_drain)
+    {
+        if (!regular) { before_drain(); run_general(part); return; }
         int i = lo;
         // Steady state: consume the older block, refill it two blocks ahead.  The
         // last two blocks are consumed without issuing anything, so that no load
@@ -189,6 +196,7 @@ struct GemvSpan {
             consume(b, i, part); issue(b, i + 2 * U); i += U;
             a_older = true;
         }
+        before_drain();
         if (a_older) { consume(a, i, part); consume(b, i + U, part); }
         else { consume(b, i, part); consume(a, i + U, part); }
     }
@@ -274,6 +282,20 @@ __device__ __forceinline__ float load_x(const LayerIO &io, int i)
 
 __device__ __forceinline__ int round_up_chunk(int k) { return (k + kChunk - 1) / kChunk * kChunk; }
 
+// position of the new token; out of range raises the error flag (no work is done)
+__device__ __forceinline__ bool read_pos(const StepParams &P, int *pos)
+{
+    const int p = *P.pos;
+    *pos = p;
+    if (p < 0 || p >= P.dm.max_seq) {
+        if (threadIdx.x == 0 && blockIdx.x == 0)
+            __hip_atomic_store(&P.sync[kSyncErr], (unsigned)kErrBadPos, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        return false;
+    }
+    return true;
+}
+
 // Both LayerNorms of a block (they read the same input): load() requests the
 // input and the four parameter vectors, finish() computes the statistics and
 // writes the two normalised vectors to LDS in GEMV order (zero padded); the
@@ -314,6 +336,47 @@ struct LnPair {
                 pg2[j] = load16(g2 + gi * 8); pb2[j] = load16(b2 + gi * 8);
             }
         }
+    }
+
+    // The same with the input given as tagged words xt[h] (value, tag pairs): the
+    // input is re-read until every word carries `tag` - the producers' stores are
+    // the only signal.
+    __device__ __forceinline__ void load_tagged(const StepParams &P, const __half *__restrict__ w, const float *xt,
+                                                unsigned tag, int tid)
+    {
+        const int h = P.dm.h, nt = blockDim.x;
+        const int ngrp = h >> 3;
+        const __half *g1 = w + P.lay.ln1_g, *b1 = w + P.lay.ln1_b;
+        const __half *g2 = w + P.lay.ln2_g, *b2 = w + P.lay.ln2_b;
+#pragma unroll
+        for (int j = 0; j < GU; ++j) {
+            const int gi = tid + j * nt;
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            pg1[j] = z; pb1[j] = z; pg2[j] = z; pb2[j] = z;
+            if (gi < ngrp) {
+                pg1[j] = load16(g1 + gi * 8); pb1[j] = load16(b1 + gi * 8);
+                pg2[j] = load16(g2 + gi * 8); pb2[j] = load16(b2 + gi * 8);
+            }
+        }
+        PollGuard pg;
+        pg.start(P.sync);
+        bool ok;
+        do {
+            ok = true;
+#pragma unroll
+            for (int j = 0; j < GU; ++j) {
+                const int gi = tid + j * nt;
+                const int gc = gi < ngrp ? gi : 0;
+                float2 wd[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) wd[e] = xwg_load2(xt + 2 * (gc * 8 + e));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    xv[j][e] = gi < ngrp ? wd[e].x : 0.f;
+                    ok = ok && (gi >= ngrp || __float_as_uint(wd[e].y) == tag);
+                }
+            }
+        } while (!ok && !pg.give_up());
     }
 
     __device__ __forceinline__ void finish(const StepParams &P, float *y1, float *y2, float *red, int tid)
@@ -378,9 +441,10 @@ struct LnPair {
 template <int UN>
 struct StagedVector {
     float2 v[UN];
-    __device__ __forceinline__ void issue(const float *__restrict__ src, int n, int tid)
+    // tid in [0, nt): the threads that share the copy (default: the workgroup)
+    __device__ __forceinline__ void issue(const float *__restrict__ src, int n, int tid, int nt = blockDim.x)
     {
-        const int n2 = n >> 1, nt = blockDim.x;
+        const int n2 = n >> 1;
 #pragma unroll
         for (int j = 0; j < UN; ++j) {
             const int i2 = tid + j * nt;
@@ -388,9 +452,9 @@ struct StagedVector {
             if (j * nt < n2) v[j] = xwg_load2(src + 2 * (i2 < n2 ? i2 : 0));
         }
     }
-    __device__ __forceinline__ void commit(int n, float *dst, int tid) const
+    __device__ __forceinline__ void commit(int n, float *dst, int tid, int nt = blockDim.x) const
     {
-        const int n2 = n >> 1, np2 = round_up_chunk(n) >> 1, nt = blockDim.x;
+        const int n2 = n >> 1, np2 = round_up_chunk(n) >> 1;
 #pragma unroll
         for (int j = 0; j < UN; ++j) {
             const int i2 = tid + j * nt;

@@ -333,20 +333,6 @@ __device__ __forceinline__ void phase_c(const StepParams &P, const __half *__res
     sync.arrive();
 }
 
-// position of the new token; out of range raises the error flag (no work is done)
-__device__ __forceinline__ bool read_pos(const StepParams &P, int *pos)
-{
-    const int p = *P.pos;
-    *pos = p;
-    if (p < 0 || p >= P.dm.max_seq) {
-        if (threadIdx.x == 0 && blockIdx.x == 0)
-            __hip_atomic_store(&P.sync[kSyncErr], (unsigned)kErrBadPos, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        return false;
-    }
-    return true;
-}
-
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kMaxThreads)
 k_phase_a(StepParams P, const __half *w, __half *kv, int layer)

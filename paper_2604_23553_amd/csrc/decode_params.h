@@ -16,6 +16,7 @@ struct StepParams {
     float *xres;         // [2][h] for this sequence
     float *q, *m, *g, *o;
     float *part;         // [H][part_slots][d+2] for this sequence
+    float *tagged;       // tagged-word region (value, tag pairs): x[2][h], q/k/v[3][h], o[h], part[H][part_slots][d+2]
     int part_slots;
     const int *pos;      // device, this sequence's position
     int b;               // sequence index inside the KV cache
@@ -48,6 +49,13 @@ hipError_t launch_store_layer_ptrs(const LayerPtrs &ptrs, LayerPtrs *dst, int n,
 // most co-resident workgroups per compute unit for the persistent kernels
 hipError_t persistent_occupancy(int head_dim, int threads, size_t lds_bytes, int *blocks_per_cu);
 hipError_t prepare_kernels(size_t lds_bytes);
+
+// implemented in fused_kernel.hip: the whole-stack kernel with hidden hand-overs (mode 2)
+bool fused_supported(const Dims &dm, const StepParams &P, int grid, int threads);
+size_t fused_lds_bytes(const Dims &dm, const StepParams &P, int threads);
+hipError_t launch_stack_fused(const StepParams &P, const LayerPtrs *ptrs, int grid, int threads, hipStream_t s);
+hipError_t fused_occupancy(int head_dim, int threads, size_t lds_bytes, int *blocks_per_cu);
+hipError_t prepare_fused_kernels(size_t lds_bytes);
 
 // implemented in stream_kernel.hip: the wave-specialised whole-stack kernel
 bool stream_supported(const Dims &dm, int grid);

@@ -171,6 +171,15 @@ __device__ __forceinline__ u32x4 xwg_load16(const __half *p)
     return u32x4{(unsigned)(a & 0xffffffffull), (unsigned)(a >> 32), (unsigned)(b & 0xffffffffull),
                  (unsigned)(b >> 32)};
 }
+// Tagged words: an exchanged fp32 value travels with a 32-bit tag in one 8-byte
+// store, so a reader needs no separate flag or ordering: it re-reads a word
+// until the tag is the one it expects.  p: 8-byte aligned pair (value, tag).
+__device__ __forceinline__ void xwg_store_tagged(float *p, float v, unsigned tag)
+{
+    const unsigned long long w = ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
+    __hip_atomic_store(as_global(reinterpret_cast<unsigned long long *>(p)), w, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ void xwg_wait_stores()
 {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -196,15 +205,18 @@ __device__ __forceinline__ void xwg_wait_stores()
 // The wait is bounded: after ~2 s of wall clock the waiter sets the error flag
 // and every later barrier falls through, so the grid always drains.
 struct GridBarrier {
-    unsigned *sync;
+    unsigned *sync, *err;
     unsigned gen;        // generation this workgroup waits to leave (thread 0 only)
     unsigned nbar;       // barriers completed by this launch
     unsigned nleaf, members;
     unsigned *leaf;
     bool pending, last;
 
-    __device__ __forceinline__ void init(unsigned *s, unsigned nwg)
+    // s: the workspace's sync words; which: one of the kSyncBarriers independent barriers
+    __device__ __forceinline__ void init(unsigned *s, unsigned nwg, int which = 0)
     {
+        err = s + kSyncErr;
+        s += kSyncBarrier0 + which * kSyncBarrierWords;
         sync = s;
         nbar = 0;
         pending = false;
@@ -238,6 +250,27 @@ struct GridBarrier {
     __device__ __forceinline__ void wait()
     {
         if (!pending) return;
+        wait_leader();
+        __syncthreads();
+    }
+
+    // The same barrier driven by the first wavefront alone (it has issued all of
+    // the workgroup's exchange stores itself); the other wavefronts learn the
+    // outcome at their next workgroup barrier with it.
+    __device__ __forceinline__ void arrive_wave()
+    {
+        xwg_wait_stores();
+        if (threadIdx.x == 0) last = count(leaf, members);
+        pending = true;
+    }
+    __device__ __forceinline__ void wait_wave()
+    {
+        if (!pending) return;
+        wait_leader();
+    }
+
+    __device__ __forceinline__ void wait_leader()
+    {
         pending = false;
         if (threadIdx.x == 0) {
             bool released = false;
@@ -252,11 +285,11 @@ struct GridBarrier {
                                          __HIP_MEMORY_SCOPE_AGENT) == gen) {
                     __builtin_amdgcn_s_sleep(1);
                     if ((++spins & 1023u) == 0) {
-                        if (__hip_atomic_load(as_global(&sync[kSyncErr]), __ATOMIC_RELAXED,
+                        if (__hip_atomic_load(as_global(err), __ATOMIC_RELAXED,
                                               __HIP_MEMORY_SCOPE_AGENT) == kErrBarrierTimeout)
                             break;
                         if (wall_clock64() - t0 > 200000000ull) {   // 100 MHz counter: 2 s
-                            __hip_atomic_store(as_global(&sync[kSyncErr]), (unsigned)kErrBarrierTimeout,
+                            __hip_atomic_store(as_global(err), (unsigned)kErrBarrierTimeout,
                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             break;
                         }
@@ -266,7 +299,6 @@ struct GridBarrier {
             gen += 1;
         }
         nbar += 1;
-        __syncthreads();
     }
 
     // before the launch ends: leave every counter at zero
@@ -274,6 +306,40 @@ struct GridBarrier {
     {
         wait();
         if (nbar & 1u) { arrive(); wait(); }
+    }
+    __device__ __forceinline__ void finish_wave()
+    {
+        wait_wave();
+        if (nbar & 1u) { arrive_wave(); wait_wave(); }
+    }
+};
+
+// ---- bounded polling -----------------------------------------------------------
+// A reader that re-reads exchanged words until they are current calls give_up()
+// after every unsuccessful pass: after ~2 s of wall clock (or once any other
+// wait of the launch has timed out) it raises the device error flag and returns
+// true, so that every wavefront still runs to the end of the kernel.
+struct PollGuard {
+    unsigned *err;
+    unsigned long long t0;
+    unsigned spins;
+    __device__ __forceinline__ void start(unsigned *sync_words)
+    {
+        err = sync_words + kSyncErr;
+        t0 = wall_clock64();
+        spins = 0;
+    }
+    __device__ __forceinline__ bool give_up()
+    {
+        if ((++spins & 15u) != 0) return false;
+        if (__hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == kErrBarrierTimeout)
+            return true;
+        if (wall_clock64() - t0 > 200000000ull) {           // 100 MHz counter: 2 s
+            __hip_atomic_store(as_global(err), (unsigned)kErrBarrierTimeout, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            return true;
+        }
+        return false;
     }
 };
 

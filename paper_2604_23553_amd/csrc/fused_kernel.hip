@@ -1,0 +1,494 @@
+// Whole-stack decode in one persistent kernel with every grid-wide dependency
+// hidden behind streaming (launch mode 2).
+//
+// The block (paper Sec. 2.2; Sec. 2.3 wraps the stack in one graph) has two
+// independent chains after the LayerNorms - attention and MLP - and each
+// grid-wide hand-over of one chain can be waited for while the other chain's
+// weights stream:
+//
+//   QKV rows   -> q,k,v published      ... waited for behind the MLP-up rows
+//   up rows    -> GELU(up) published   ... waited for behind the attention
+//   attention  -> o published          ... waited for behind the MLP-down rows
+//   down rows  (stay inside the workgroup)
+//   dense rows -> next layer's input   ... the one exposed hand-over per layer
+//
+// Wavefront 0 of every workgroup is the "chain" wavefront: it finishes rows
+// (biases, rotary, GELU, residual), publishes them, drives the four grid
+// barriers (one per hand-over, each independent) and stages the small vectors
+// the next stretch needs.  The split-KV partials travel as tagged words (value
+// and an epoch in one 8-byte store) that the combining workgroup re-reads until
+// they are current - no acknowledgement or counter on that path.  The epoch of
+// layer l is E0 + l + 1 with E0 a counter that every launch advances by more
+// than its layer count when it ends: epochs never repeat until the host zeroes
+// that counter together with the tagged region.
+// Wavefronts 1.. stream weights and K/V; the loads of
+// the next stretch are requested before the current one is drained, so the
+// memory queue never empties at a hand-over.  Both roles meet at a fixed sequence
+// of workgroup barriers.  All reductions are in a fixed order (row-split GEMVs,
+// slot-ordered split-KV merges): the result is bit-identical from run to run
+// (the paper's fp16-atomic output accumulation, Sec. 3, is not).
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include "decode_blocks.h"
+#include "attention_blocks.h"
+
+namespace cfpp {
+
+constexpr int kFusedSegs = 2;       // a workgroup's share of the attention covers at most two heads
+constexpr int kFusedSlots = 8;      // LDS slots for the streaming wavefronts' attention states
+constexpr int kStageMStream = 22;   // float2 per streaming thread when staging GELU(up): ffn <= 44 * 64 * (nw - 1)
+
+// LDS of the fused kernel, in floats
+struct FusedLds {
+    unsigned y1, y2, ml, ol, pq, pu, pd, pc, red, qs, kn, vn, wp, wm, wl, total;
+};
+
+static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qkv, int rows_up, int rows_h, int nw)
+{
+    FusedLds L;
+    const unsigned Kph = (unsigned)((dm.h + kChunk - 1) / kChunk * kChunk);
+    const unsigned Kpf = (unsigned)((dm.f + kChunk - 1) / kChunk * kChunk);
+    unsigned o = 0;
+    auto take = [&](unsigned n) { unsigned at = o; o += (n + 3u) & ~3u; return at; };
+    L.y1 = take(Kph); L.y2 = take(Kph); L.ml = take(Kpf); L.ol = take(Kph);
+    L.pq = take((unsigned)(rows_qkv * nw)); L.pu = take((unsigned)(rows_up * nw));
+    L.pd = take((unsigned)(rows_h * nw)); L.pc = take((unsigned)(rows_h * nw));
+    L.red = take(16);
+    L.qs = take((unsigned)(kFusedSegs * dm.d));
+    L.kn = take((unsigned)(kFusedSegs * dm.d / 2)); L.vn = take((unsigned)(kFusedSegs * dm.d / 2));
+    L.wp = take((unsigned)(kFusedSegs * kFusedSlots * dm.d));
+    L.wm = take(kFusedSegs * kFusedSlots); L.wl = take(kFusedSegs * kFusedSlots);
+    L.total = o;
+    return L;
+}
+
+struct FusedCtx {
+    const StepParams *P;
+    const LayerPtrs *ptrs;
+    float *lds;
+    FusedLds L;
+    int pos, nw;
+    int q_begin, q_n, u_begin, u_n, r_begin, r_n;
+    unsigned E0;                    // epoch base of this launch
+    float *pt;                      // tagged words of the split-KV partials
+};
+
+// first part of every layer, both roles: the two LayerNorms into LDS and the
+// partial-sum slots of the four GEMVs cleared.  Four workgroup barriers inside;
+// the caller adds one after it.
+__device__ __forceinline__ void fused_prologue(const FusedCtx &C, const __half *w, const LayerIO &io, int tid)
+{
+    const StepParams &P = *C.P;
+    LnPair ln;
+    ln.load(P, w, io, tid);
+    ln.finish(P, C.lds + C.L.y1, C.lds + C.L.y2, C.lds + C.L.red, tid);
+    clear_partials(C.lds + C.L.pq, (int)(C.L.red - C.L.pq), tid);
+}
+
+// segments (head, rows) of this workgroup's attention share
+template <int D>
+struct FusedSegs {
+    int n, s[kFusedSegs], row_lo[kFusedSegs], row_hi[kFusedSegs];
+    __device__ __forceinline__ void init(const AttnCore<D> &ac)
+    {
+        n = 0;
+#pragma unroll
+        for (int k = 0; k < kFusedSegs; ++k) { s[k] = 0; row_lo[k] = 0; row_hi[k] = 0; }
+        int sb = ac.r0;
+#pragma unroll
+        for (int k = 0; k < kFusedSegs; ++k) {
+            if (sb < ac.r1) {
+                int se;
+                ac.segment(sb, s[k], se, row_lo[k], row_hi[k]);
+                sb = se;
+                n = k + 1;
+            }
+        }
+    }
+};
+
+// ---- wavefronts 1.. : stream --------------------------------------------------
+template <int D>
+__device__ __forceinline__ void fused_stream(const FusedCtx &C)
+{
+    using AC = AttnCore<D>;
+    constexpr int NP = AC::NP;
+    const StepParams &P = *C.P;
+    const Dims &dm = P.dm;
+    const int h = dm.h, f = dm.f, L = P.n_layers, nw = C.nw, NS = nw - 1;
+    float *lds = C.lds;
+    float *y1 = lds + C.L.y1, *y2 = lds + C.L.y2, *ml = lds + C.L.ml, *ol = lds + C.L.ol;
+    float *pq = lds + C.L.pq, *pu = lds + C.L.pu, *pd = lds + C.L.pd, *pc = lds + C.L.pc;
+    const int n_tok = C.pos + 1;
+
+    GemvSpan<kGemvU> gsQ, gsU, gsD, gsC;
+    {
+        const int tid0 = opaque_thread_index();
+        const __half *w0 = C.ptrs->w[0];
+        gsQ.init(GemvSeg{w0 + P.lay.w_qkv + (size_t)C.q_begin * h, y1, h, C.q_n}, GemvSeg{w0 + P.lay.w_qkv, y1, h, 0},
+                 w0, tid0, 0);
+        gsQ.issue_first();
+        gsQ.issue_second();
+    }
+    Tracer tr;
+    tr.init(P, gsQ.wave, 0);
+
+#pragma clang loop unroll(disable)
+    for (int layer = 0; layer < L; ++layer) {
+        const int tid = opaque_thread_index();
+        const int lane = tid & 63, si = gsQ.wave - 1;
+        const __half *w = C.ptrs->w[layer];
+        const __half *kv = C.ptrs->kv[layer];
+        const LayerIO io = layer_io(P, layer);
+        tr.n = 0;
+        tr.mark(1);
+        __syncthreads();                                   // Sx: the layer input is complete
+        tr.mark(2);
+        fused_prologue(C, w, io, tid);
+        __syncthreads();                                   // S0
+        tr.mark(3);
+
+        gsU.init(GemvSeg{w + P.lay.w_up + (size_t)C.u_begin * h, y2, h, C.u_n}, GemvSeg{w + P.lay.w_up, y2, h, 0},
+                 w, tid, 0);
+        gsQ.run(pq, [&] { gsU.issue_first(); gsU.issue_second(); });
+        tr.mark(4);
+        __syncthreads();                                   // S1: QKV rows done
+        tr.mark(5);
+
+        // attention share: the first two K/V rows are requested behind the last up-projection weights
+        AC ac;
+        ac.init(P, kv, n_tok, lane);
+        FusedSegs<D> sg;
+        sg.init(ac);
+        u32x4 kA[NP], vA[NP], kB[NP], vB[NP];
+        const int row0 = sg.row_lo[0] + si;
+        gsU.run(pu, [&] {
+            ac.issue(kA, vA, sg.s[0], sg.n > 0 && row0 < sg.row_hi[0] ? row0 : -1);
+            ac.issue(kB, vB, sg.s[0], sg.n > 0 && row0 + NS < sg.row_hi[0] ? row0 + NS : -1);
+        });
+        tr.mark(6);
+        __syncthreads();                                   // S2: up rows done; q and the new K/V rows staged
+        tr.mark(10);
+
+        gsD.init(GemvSeg{w + P.lay.w_down + (size_t)C.r_begin * f, ml, f, C.r_n}, GemvSeg{w + P.lay.w_down, ml, f, 0},
+                 w, tid, 0);
+        gsD.issue_first();                                 // streams during the attention arithmetic
+        gsD.issue_second();
+#pragma unroll
+        for (int k = 0; k < kFusedSegs; ++k) {
+            if (k < sg.n) {
+                const float *qs = lds + C.L.qs + k * D;
+                const __half *kn = reinterpret_cast<const __half *>(lds + C.L.kn) + k * D;
+                const __half *vn = reinterpret_cast<const __half *>(lds + C.L.vn) + k * D;
+                const int s = sg.s[k], row_hi = sg.row_hi[k];
+                int row = sg.row_lo[k] + si;
+                if (k > 0) {
+                    ac.issue(kA, vA, s, row < row_hi ? row : -1);
+                    ac.issue(kB, vB, s, row + NS < row_hi ? row + NS : -1);
+                }
+                ac.reset();
+                while (row < row_hi) {
+                    ac.process(kA, vA, row, qs, kn, vn);
+                    ac.issue(kA, vA, s, row + 2 * NS < row_hi ? row + 2 * NS : -1);
+                    row += NS;
+                    if (row >= row_hi) break;
+                    ac.process(kB, vB, row, qs, kn, vn);
+                    ac.issue(kB, vB, s, row + 2 * NS < row_hi ? row + 2 * NS : -1);
+                    row += NS;
+                }
+                ac.wave_merge(lds + C.L.wp + k * kFusedSlots * D, lds + C.L.wm + k * kFusedSlots,
+                              lds + C.L.wl + k * kFusedSlots, si);
+            }
+        }
+        tr.mark(13);
+        __syncthreads();                                   // S3: attention states in LDS; GELU(up) complete everywhere
+        tr.mark(14);
+        {
+            StagedVector<kStageMStream> sm;                // (the chain wavefront is busy with the partials)
+            sm.issue(P.m, f, tid - 64, NS * 64);
+            sm.commit(f, ml, tid - 64, NS * 64);
+        }
+        __syncthreads();                                   // S3b: GELU(up) staged
+        tr.mark(17);
+
+        gsC.init(GemvSeg{w + P.lay.w_dense + (size_t)C.r_begin * h, ol, h, C.r_n}, GemvSeg{w + P.lay.w_dense, ol, h, 0},
+                 w, tid, 0);
+        gsD.run(pd, [&] { gsC.issue_first(); gsC.issue_second(); });
+        tr.mark(18);
+        __syncthreads();                                   // S4: down rows done; attention output staged
+        tr.mark(20);
+
+        {
+            // the next layer's first QKV weights (nothing for the last layer: the loads re-read one block)
+            const bool more = layer + 1 < L;
+            const __half *wn = C.ptrs->w[more ? layer + 1 : layer];
+            gsQ.init(GemvSeg{wn + P.lay.w_qkv + (size_t)C.q_begin * h, y1, h, more ? C.q_n : 0},
+                     GemvSeg{wn + P.lay.w_qkv, y1, h, 0}, wn, tid, 0);
+        }
+        gsC.run(pc, [&] { gsQ.issue_first(); gsQ.issue_second(); });
+        tr.mark(23);
+        __syncthreads();                                   // S6: dense rows done
+        tr.mark(24);
+    }
+}
+
+// ---- wavefront 0 : chain ------------------------------------------------------
+template <int D>
+__device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv_layers)
+{
+    using AC = AttnCore<D>;
+    const StepParams &P = *C.P;
+    const Dims &dm = P.dm;
+    const int h = dm.h, f = dm.f, d = dm.d, r = dm.r, L = P.n_layers, nw = C.nw, NS = nw - 1;
+    float *lds = C.lds;
+    float *ml = lds + C.L.ml, *ol = lds + C.L.ol;
+    const float *pq = lds + C.L.pq, *pu = lds + C.L.pu, *pd = lds + C.L.pd, *pc = lds + C.L.pc;
+    const int pos = C.pos, n_tok = pos + 1;
+    const int q_begin = C.q_begin, q_n = C.q_n, u_begin = C.u_begin, u_n = C.u_n, r_begin = C.r_begin, r_n = C.r_n;
+
+    GridBarrier b1, b2, b3, b4;
+    b1.init(P.sync, gridDim.x, 0);
+    b2.init(P.sync, gridDim.x, 1);
+    b3.init(P.sync, gridDim.x, 2);
+    b4.init(P.sync, gridDim.x, 3);
+    // the partial sums of a row sit in wavefront slots; only the streaming wavefronts fill them
+    GemvSpan<kGemvU> rt;                                  // (row_total() only)
+    rt.nw = nw;
+    Tracer tr;
+    tr.init(P, 0, 0);
+    float x_r = 0.f;                                       // this lane's row of the residual stream
+
+#pragma clang loop unroll(disable)
+    for (int layer = 0; layer < L; ++layer) {
+        const int tid = opaque_thread_index();
+        const int lane = tid & 63;
+        const __half *w = C.ptrs->w[layer];
+        __half *kv = kv_layers[layer];
+        const LayerIO io = layer_io(P, layer);
+        const bool last_layer = layer == L - 1;
+        tr.n = 0;
+        tr.mark(1);
+        b4.wait_wave();                                    // the previous layer's output is complete
+        __syncthreads();                                   // Sx
+        tr.mark(2);
+        fused_prologue(C, w, io, tid);
+        __syncthreads();                                   // S0
+        tr.mark(3);
+
+        // what the epilogues add to this lane's first rows: requested now, used behind the GEMVs
+        const __half *bq = w + P.lay.b_qkv, *bu = w + P.lay.b_up, *bdn = w + P.lay.b_down, *bde = w + P.lay.b_dense;
+        float bq0 = 0.f, bq1 = 0.f, bu0 = 0.f, bdn0 = 0.f, bde0 = 0.f;
+        float2 cs0 = {1.f, 0.f};
+        if (lane < q_n / 2) {
+            const int p = q_begin + 2 * lane;
+            const int i = p % d, c = (p / d) % 3;
+            bq0 = __half2float(bq[p]); bq1 = __half2float(bq[p + 1]);
+            if (c < 2 && i < r) cs0 = P.rope[(size_t)pos * (r >> 1) + (i >> 1)];
+        }
+        if (lane < u_n) bu0 = __half2float(bu[u_begin + lane]);
+        if (lane < r_n) {
+            bdn0 = __half2float(bdn[r_begin + lane]);
+            bde0 = __half2float(bde[r_begin + lane]);
+            if (layer == 0) x_r = __half2float(io.x16[r_begin + lane]);
+        }
+        AC ac;
+        ac.init(P, kv, n_tok, lane);
+        FusedSegs<D> sg;
+        sg.init(ac);
+
+        __syncthreads();                                   // S1: QKV rows done
+        tr.mark(5);
+        // QKV epilogue: one lane per pair of adjacent packed rows
+        for (int pr = lane; pr < q_n / 2; pr += 64) {
+            const int p = q_begin + 2 * pr;                 // packed row, even
+            const int pdv = p / d, i = p - pdv * d;         // i even
+            const int n = pdv / 3, c = pdv - 3 * n;
+            const bool rotary = c < 2 && i < r;             // rotary pair (j, j + r/2)
+            float b0 = bq0, b1v = bq1;
+            float2 cs = cs0;
+            if (pr != lane) {
+                b0 = __half2float(bq[p]); b1v = __half2float(bq[p + 1]);
+                if (rotary) cs = P.rope[(size_t)pos * (r >> 1) + (i >> 1)];
+            }
+            float v0 = rt.row_total(pq, 2 * pr) + b0;
+            float v1 = rt.row_total(pq, 2 * pr + 1) + b1v;
+            int d0 = i, d1 = i + 1;
+            if (rotary) {
+                const int j = i >> 1;
+                const float lo = v0 * cs.x - v1 * cs.y;
+                const float hi = v1 * cs.x + v0 * cs.y;
+                v0 = lo; v1 = hi;
+                d0 = j; d1 = j + (r >> 1);
+            }
+            if (c == 0) {
+                xwg_store(P.q + n * d + d0, v0);
+                xwg_store(P.q + n * d + d1, v1);
+            } else {
+                xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d0, pos), v0);
+                xwg_store_half(kv + kv_offset(dm, c - 1, P.b, n, d1, pos), v1);
+            }
+        }
+        b1.arrive_wave();
+        b1.wait_wave();                                    // q and the new K/V rows are complete everywhere
+        tr.mark(7);
+        {
+            // stage them for the heads of this workgroup's attention share (lanes own elements lane, lane + 64)
+            float qv[kFusedSegs][AC::NE];
+            __half knv[kFusedSegs][AC::NE], vnv[kFusedSegs][AC::NE];
+#pragma unroll
+            for (int k = 0; k < kFusedSegs; ++k)
+#pragma unroll
+                for (int e = 0; e < AC::NE; ++e) {
+                    const int i = lane + 64 * e;
+                    const int ii = i < D ? i : 0, s = sg.s[k];
+                    qv[k][e] = xwg_load(P.q + s * D + ii);
+                    knv[k][e] = xwg_load_half(kv + kv_offset(dm, 0, P.b, s, ii, n_tok - 1));
+                    vnv[k][e] = xwg_load_half(kv + kv_offset(dm, 1, P.b, s, ii, n_tok - 1));
+                }
+#pragma unroll
+            for (int k = 0; k < kFusedSegs; ++k)
+#pragma unroll
+                for (int e = 0; e < AC::NE; ++e) {
+                    const int i = lane + 64 * e;
+                    if (i < D) {
+                        lds[C.L.qs + k * D + i] = qv[k][e];
+                        reinterpret_cast<__half *>(lds + C.L.kn)[k * D + i] = knv[k][e];
+                        reinterpret_cast<__half *>(lds + C.L.vn)[k * D + i] = vnv[k][e];
+                    }
+                }
+        }
+        tr.mark(8);
+        __syncthreads();                                   // S2: up rows done
+        tr.mark(10);
+        for (int t = lane; t < u_n; t += 64) {
+            const float b = t == lane ? bu0 : __half2float(bu[u_begin + t]);
+            xwg_store(P.m + u_begin + t, gelu_erf(rt.row_total(pu, t) + b));
+        }
+        b2.arrive_wave();
+        b2.wait_wave();                                    // GELU(up) is complete everywhere
+        tr.mark(12);
+        __syncthreads();                                   // S3: attention states in LDS
+        tr.mark(14);
+        __syncthreads();                                   // S3b (the streaming wavefronts stage GELU(up))
+        tr.mark(15);
+        // attention: this workgroup's partials; the heads it combines; the whole
+        // attention output into LDS once every head is combined
+        const unsigned epoch = C.E0 + (unsigned)layer + 1u;
+#pragma unroll
+        for (int k = 0; k < kFusedSegs; ++k)
+            if (k < sg.n)
+                ac.publish_tagged(P, C.pt, epoch, sg.s[k], lds + C.L.wp + k * kFusedSlots * D,
+                                  lds + C.L.wm + k * kFusedSlots, lds + C.L.wl + k * kFusedSlots, NS);
+#pragma unroll
+        for (int k = 0; k < kFusedSegs; ++k)
+            if (k < sg.n && ac.combines(sg.s[k])) ac.combine_tagged(P, C.pt, epoch, sg.s[k]);
+        b3.arrive_wave();                                  // (waits for the combined heads' stores first)
+        b3.wait_wave();                                    // the attention output is complete
+        tr.mark(16);
+        {
+            // stage it: this wavefront alone, up to 64 values per lane
+            StagedVector<32> so;
+            so.issue(P.o, h, lane, 64);
+            so.commit(h, ol, lane, 64);
+        }
+        tr.mark(17);
+        __syncthreads();                                   // S4: down rows done
+        tr.mark(20);
+        float g_r = 0.f;
+        if (lane < r_n) g_r = rt.row_total(pd, lane) + bdn0;
+        __syncthreads();                                   // S6: dense rows done
+        tr.mark(24);
+        if (lane < r_n) {
+            const float a = rt.row_total(pc, lane) + bde0;
+            const float res = (x_r + a) + g_r;
+            x_r = res;
+            if (io.o16) io.o16[r_begin + lane] = __float2half_rn(res);
+            else xwg_store(io.o32 + r_begin + lane, res);
+        }
+        if (!last_layer) b4.arrive_wave();
+        tr.mark(25);
+    }
+    b1.finish_wave();
+    b2.finish_wave();
+    b3.finish_wave();
+    b4.finish_wave();
+    // every workgroup has read E0 and finished its layers: the next launch gets fresh epochs
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        __hip_atomic_store(as_global(P.sync + kSyncEpoch), C.E0 + (unsigned)L + 1u, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int D>
+__global__ void __launch_bounds__(kMaxThreads)
+k_stack_fused(StepParams P, const LayerPtrs *__restrict__ ptrs)
+{
+    extern __shared__ __align__(16) float lds[];
+    int pos;
+    if (!read_pos(P, &pos)) return;
+    const Dims &dm = P.dm;
+    FusedCtx C;
+    C.P = &P;
+    C.ptrs = ptrs;
+    C.lds = lds;
+    C.nw = blockDim.x >> 6;
+    C.L = fused_lds(dm, P.rows_qkv, P.rows_up, P.rows_h, C.nw);
+    C.pos = pos;
+    const int g = blockIdx.x;
+    C.q_begin = g * P.rows_qkv; C.q_n = max(0, min(P.rows_qkv, 3 * dm.h - C.q_begin));
+    C.u_begin = g * P.rows_up;  C.u_n = max(0, min(P.rows_up, dm.f - C.u_begin));
+    C.r_begin = g * P.rows_h;   C.r_n = max(0, min(P.rows_h, dm.h - C.r_begin));
+    // (only changed at the very end of a launch, behind the last barriers)
+    C.E0 = __hip_atomic_load(as_global(P.sync + kSyncEpoch), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    C.pt = P.tagged + 2 * (size_t)6 * dm.h;
+    if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0) fused_chain<D>(C, ptrs->kv);
+    else fused_stream<D>(C);
+}
+
+// ---- host side -----------------------------------------------------------------
+size_t fused_lds_bytes(const Dims &dm, const StepParams &P, int threads)
+{
+    return (size_t)fused_lds(dm, P.rows_qkv, P.rows_up, P.rows_h, threads / 64).total * 4;
+}
+
+// grid >= heads (a workgroup's attention share then covers at most two heads),
+// at most 64 rows of the h-row matrices per workgroup (one lane each in the
+// chain wavefront), and at most 8 streaming wavefronts
+bool fused_supported(const Dims &dm, const StepParams &P, int grid, int threads)
+{
+    return grid >= dm.H && P.rows_h <= 64 && dm.h <= 4096 &&
+           (size_t)dm.f <= (size_t)2 * kStageMStream * 64 * (threads / 64 - 1) && threads / 64 - 1 <= kFusedSlots && threads >= 128 &&
+           (dm.d == 64 || dm.d == 80 || dm.d == 128);
+}
+
+hipError_t launch_stack_fused(const StepParams &P, const LayerPtrs *ptrs, int grid, int threads, hipStream_t s)
+{
+    const size_t lds = fused_lds_bytes(P.dm, P, threads);
+    switch (P.dm.d) {
+    case 64: hipLaunchKernelGGL(k_stack_fused<64>, dim3(grid), dim3(threads), lds, s, P, ptrs); break;
+    case 80: hipLaunchKernelGGL(k_stack_fused<80>, dim3(grid), dim3(threads), lds, s, P, ptrs); break;
+    case 128: hipLaunchKernelGGL(k_stack_fused<128>, dim3(grid), dim3(threads), lds, s, P, ptrs); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t fused_occupancy(int head_dim, int threads, size_t lds_bytes, int *blocks_per_cu)
+{
+    switch (head_dim) {
+    case 64: return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, k_stack_fused<64>, threads, lds_bytes);
+    case 80: return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, k_stack_fused<80>, threads, lds_bytes);
+    case 128: return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, k_stack_fused<128>, threads, lds_bytes);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t prepare_fused_kernels(size_t lds_bytes)
+{
+    const int v = (int)lds_bytes;
+    hipError_t e = hipFuncSetAttribute((const void *)k_stack_fused<64>, hipFuncAttributeMaxDynamicSharedMemorySize, v);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_stack_fused<80>, hipFuncAttributeMaxDynamicSharedMemorySize, v);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_stack_fused<128>, hipFuncAttributeMaxDynamicSharedMemorySize, v);
+    return e;
+}
+
+}  // namespace cfpp

@@ -76,9 +76,12 @@ CFPP_HD size_t kv_offset(const Dims &m, int which, int b, int n, int dim, int t)
 }
 CFPP_HD size_t kv_layer_elems(const Dims &m) { return 2 * kv_which_stride(m); }
 
-// indices into the sync words (barrier counters 128 bytes apart)
-enum { kSyncGen = 16, kSyncErr = 32, kSyncRoot = 64, kSyncLeaf0 = 96, kSyncLeafStride = 32, kSyncLeaves = 16,
-       kSyncWords = kSyncLeaf0 + kSyncLeaves * kSyncLeafStride };
+// Sync words: the device error flag, the epoch counter of the tagged words,
+// then kSyncBarriers independent grid barriers of kSyncBarrierWords words each
+// (generation word, root counter and up to 16 leaf counters, 128 bytes apart).
+enum { kSyncErr = 32, kSyncEpoch = 40, kSyncBarrier0 = 64, kSyncGen = 0, kSyncRoot = 32, kSyncLeaf0 = 64,
+       kSyncLeafStride = 32, kSyncLeaves = 16, kSyncBarrierWords = kSyncLeaf0 + kSyncLeaves * kSyncLeafStride,
+       kSyncBarriers = 4, kSyncWords = kSyncBarrier0 + kSyncBarriers * kSyncBarrierWords };
 
 // Workspace: byte offsets of every static buffer.
 struct WorkspaceLayout {

@@ -82,13 +82,6 @@ __device__ __forceinline__ bool lds_wait_ge(int *ctrl, int word, int target, uns
 //     E0 + l + 1 with E0 = number of M events completed before the launch, so
 //     epochs never repeat while the counters are not zeroed (the host zeroes the
 //     tagged buffers together with the counters).
-__device__ __forceinline__ void xwg_store_tagged(float *p, float v, unsigned tag)
-{
-    const unsigned long long w = ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
-    __hip_atomic_store(as_global(reinterpret_cast<unsigned long long *>(p)), w, __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-}
-
 struct Abort {
     int *ctrl;
     unsigned *err;
