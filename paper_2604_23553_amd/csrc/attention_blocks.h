@@ -301,6 +301,8 @@ struct AttnCore {
         float M = -INFINITY, L = 0.f, O[NE];
 #pragma unroll
         for (int e = 0; e < NE; ++e) O[e] = 0.f;
+        // a cheap test first: the word stored last of every slot (one lane each)
+        wait_tagged_sample(base, D + 1, D + 2, ncover, ncover * (D + 2) - 1, tag, P.sync, lane);
         PollGuard pg;
         pg.start(P.sync);
         for (int j0 = 0; j0 < ncover; j0 += CB) {

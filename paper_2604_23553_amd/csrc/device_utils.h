@@ -332,7 +332,9 @@ struct PollGuard {
     __device__ __forceinline__ bool give_up()
     {
         if ((++spins & 15u) != 0) return false;
-        if (__hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == kErrBarrierTimeout)
+        // (the flag costs a memory round trip: looked at rarely; the clock is cheap)
+        if ((spins & 4095u) == 0 &&
+            __hip_atomic_load(as_global(err), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == kErrBarrierTimeout)
             return true;
         if (wall_clock64() - t0 > 200000000ull) {           // 100 MHz counter: 2 s
             __hip_atomic_store(as_global(err), (unsigned)kErrBarrierTimeout, __ATOMIC_RELAXED,
@@ -342,6 +344,51 @@ struct PollGuard {
         return false;
     }
 };
+
+// One wavefront waits until `count` tagged words carry `tag`: word i sits at
+// base[2 * (first + i * stride)] (a sample of a larger vector - one word per
+// producer - serves as a cheap "probably complete" test before the vector is
+// read and verified in full).  Up to 16 words per lane.
+__device__ __forceinline__ void wait_tagged_sample(const float *base, int first, int stride, int count, int last_index,
+                                                   unsigned tag, unsigned *sync_words, int lane)
+{
+    PollGuard pg;
+    pg.start(sync_words);
+    for (int b0 = 0; b0 < count; b0 += 16 * 64) {
+        bool ok;
+        do {
+            ok = true;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int i = b0 + j * 64 + lane;
+                if (b0 + j * 64 < count) {
+                    int idx = first + (i < count ? i : 0) * stride;
+                    idx = idx < last_index ? idx : last_index;
+                    const float2 w = xwg_load2(base + 2 * (size_t)idx);
+                    ok = ok && (i >= count || __float_as_uint(w.y) == tag);
+                }
+            }
+            ok = __all(ok);
+        } while (!ok && !pg.give_up());
+    }
+}
+
+// Rendezvous of `n` wavefronts of a workgroup through an LDS counter that only
+// grows: each adds one and waits until it reaches `target` (the caller's running
+// total).  Orders LDS traffic like a workgroup barrier for those wavefronts, and
+// leaves the others alone.  Bounded like every other wait.
+__device__ __forceinline__ void lds_rendezvous(int *counter, int target, unsigned *sync_words, int lane)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0) __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    PollGuard pg;
+    pg.start(sync_words);
+    while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target) {
+        __builtin_amdgcn_s_sleep(1);
+        if (pg.give_up()) break;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
 
 // ---- timeline trace (profiling aid) --------------------------------------------
 // Workgroup (debug >> 8) records (tag, 100 MHz wall clock) pairs per wavefront

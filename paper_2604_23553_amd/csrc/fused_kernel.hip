@@ -40,7 +40,7 @@ constexpr int kStageMStream = 22;   // float2 per streaming thread when staging 
 
 // LDS of the fused kernel, in floats
 struct FusedLds {
-    unsigned y1, y2, ml, ol, pq, pu, pd, pc, red, qs, kn, vn, wp, wm, wl, total;
+    unsigned y1, y2, ml, ol, pq, pu, pd, pc, red, qs, kn, vn, wp, wm, wl, ctr, total;
 };
 
 static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qkv, int rows_up, int rows_h, int nw)
@@ -58,6 +58,7 @@ static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qk
     L.kn = take((unsigned)(kFusedSegs * dm.d / 2)); L.vn = take((unsigned)(kFusedSegs * dm.d / 2));
     L.wp = take((unsigned)(kFusedSegs * kFusedSlots * dm.d));
     L.wm = take(kFusedSegs * kFusedSlots); L.wl = take(kFusedSegs * kFusedSlots);
+    L.ctr = take(4);
     L.total = o;
     return L;
 }
@@ -208,7 +209,9 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
             sm.issue(P.m, f, tid - 64, NS * 64);
             sm.commit(f, ml, tid - 64, NS * 64);
         }
-        __syncthreads();                                   // S3b: GELU(up) staged
+        // GELU(up) staged: a rendezvous of the streaming wavefronts only (the chain
+        // wavefront is already publishing the attention partials)
+        lds_rendezvous(reinterpret_cast<int *>(lds) + C.L.ctr, NS * (layer + 1), P.sync, lane);
         tr.mark(17);
 
         gsC.init(GemvSeg{w + P.lay.w_dense + (size_t)C.r_begin * h, ol, h, C.r_n}, GemvSeg{w + P.lay.w_dense, ol, h, 0},
@@ -369,7 +372,7 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
         tr.mark(12);
         __syncthreads();                                   // S3: attention states in LDS
         tr.mark(14);
-        __syncthreads();                                   // S3b (the streaming wavefronts stage GELU(up))
+        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 0] = wall_clock64();
         tr.mark(15);
         // attention: this workgroup's partials; the heads it combines; the whole
         // attention output into LDS once every head is combined
@@ -382,8 +385,11 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
 #pragma unroll
         for (int k = 0; k < kFusedSegs; ++k)
             if (k < sg.n && ac.combines(sg.s[k])) ac.combine_tagged(P, C.pt, epoch, sg.s[k]);
+        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 1] = wall_clock64();
         b3.arrive_wave();                                  // (waits for the combined heads' stores first)
+        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 2] = wall_clock64();
         b3.wait_wave();                                    // the attention output is complete
+        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 3] = wall_clock64();
         tr.mark(16);
         {
             // stage it: this wavefront alone, up to 64 values per lane
@@ -392,7 +398,9 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
             so.commit(h, ol, lane, 64);
         }
         tr.mark(17);
+        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 4] = wall_clock64();
         __syncthreads();                                   // S4: down rows done
+        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 5] = wall_clock64();
         tr.mark(20);
         float g_r = 0.f;
         if (lane < r_n) g_r = rt.row_total(pd, lane) + bdn0;
@@ -440,6 +448,7 @@ k_stack_fused(StepParams P, const LayerPtrs *__restrict__ ptrs)
     // (only changed at the very end of a launch, behind the last barriers)
     C.E0 = __hip_atomic_load(as_global(P.sync + kSyncEpoch), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     C.pt = P.tagged + 2 * (size_t)6 * dm.h;
+    if (threadIdx.x == 0) reinterpret_cast<int *>(lds)[C.L.ctr] = 0;    // (a workgroup barrier follows in both roles)
     if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0) fused_chain<D>(C, ptrs->kv);
     else fused_stream<D>(C);
 }
