@@ -148,16 +148,30 @@ void cfpp_destroy(cfpp_ctx *ctx);
  * and replay). */
 #define CFPP_OPT_MODE     1  /* 0: one kernel per phase (3 per block);
                                 1: one persistent kernel per block;
-                                2: one persistent kernel for the whole stack;
+                                2: cfpp_stack_*: one fused persistent kernel for
+                                   the whole stack, every grid-wide hand-over
+                                   but the layer output hidden behind weight
+                                   streaming (fastest; needs grid >= n_heads,
+                                   hidden <= 4096, all workgroups resident,
+                                   else CFPP_EUNSUPPORTED); cfpp_block_decode:
+                                   as mode 1;
                                 3: one wave-specialised streaming kernel for the
-                                   whole stack (split-phase events, prefetched
-                                   tiles; selected shape classes, else
-                                   CFPP_EUNSUPPORTED)                          */
+                                   whole stack (experimental; selected shape
+                                   classes, else CFPP_EUNSUPPORTED).
+                                Changing the mode waits for the device and
+                                zeroes the workspace's synchronisation words:
+                                not between capture and replay, not inside a
+                                stream capture.                                */
 #define CFPP_OPT_GRID     2  /* workgroups; 0 = one per compute unit          */
 #define CFPP_OPT_THREADS  3  /* threads per workgroup: 256 or 512             */
-#define CFPP_OPT_PROFILE_SKIP 100 /* profiling aid only: bit mask of sub-steps to
-                                skip so the others can be timed alone; any
-                                non-zero value makes the results wrong         */
+#define CFPP_OPT_PROFILE_SKIP 100 /* profiling aid only.  Bits 0-3: sub-steps to
+                                skip so that the others can be timed alone
+                                (results are then wrong).  Bit 4 (16): workgroup
+                                (value >> 8) records a per-wavefront timeline,
+                                bit 5 (32): every workgroup records a few time
+                                stamps of the last layer (mode 2); both are read
+                                back with cfpp_debug_read(which = 4) and leave
+                                the results intact.                             */
 cfpp_status cfpp_set_option(cfpp_ctx *ctx, int32_t option, int64_t value);
 cfpp_status cfpp_get_option(const cfpp_ctx *ctx, int32_t option, int64_t *value);
 

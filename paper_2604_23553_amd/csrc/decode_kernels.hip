@@ -16,9 +16,10 @@
 // output is bit-identical from run to run (unlike the fp16-atomic output
 // accumulation the paper describes in Sec. 3).
 //
-// The same phase bodies are launched either as three kernels per block, as one
-// persistent kernel per block, or as one persistent kernel for the whole stack
-// (phases separated by a grid barrier; Sec. 2.3's graph mode wraps any of them).
+// The same phase bodies are launched either as three kernels per block or as
+// one persistent kernel per block (phases separated by a grid barrier); the
+// whole-stack kernel is in fused_kernel.hip.  Sec. 2.3's graph mode wraps any
+// of them.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include "decode_blocks.h"
@@ -381,27 +382,6 @@ k_block_persistent(StepParams P, const __half *w, __half *kv, int layer)
     bar.finish();
 }
 
-template <int D>
-__global__ void __launch_bounds__(kMaxThreads)
-k_stack_persistent(StepParams P, const LayerPtrs *__restrict__ ptrs)
-{
-    extern __shared__ __align__(16) float lds[];
-    int pos;
-    if (!read_pos(P, &pos)) return;
-    GridBarrier bar;
-    bar.init(P.sync, gridDim.x);
-    GridSync sync{bar};
-#pragma clang loop unroll(disable)
-    for (int layer = 0; layer < P.n_layers; ++layer) {
-        const __half *w = ptrs->w[layer];
-        __half *kv = ptrs->kv[layer];
-        phase_a(P, w, kv, layer, pos, lds, sync);
-        phase_b<D>(P, w, kv, pos, lds, sync);
-        phase_c(P, w, layer, lds, sync);
-    }
-    bar.finish();
-}
-
 // ---------------------------------------------------------------------------
 // host-side launchers
 
@@ -459,25 +439,12 @@ hipError_t launch_store_layer_ptrs(const LayerPtrs &ptrs, LayerPtrs *dst, int n,
     return hipGetLastError();
 }
 
-hipError_t launch_stack_persistent(const StepParams &P, const LayerPtrs *ptrs,
-                                   int grid, int threads, hipStream_t s)
-{
-    const size_t lds = (size_t)P.lds_floats * 4;
-    switch (P.dm.d) {
-    case 64: hipLaunchKernelGGL(k_stack_persistent<64>, dim3(grid), dim3(threads), lds, s, P, ptrs); break;
-    case 80: hipLaunchKernelGGL(k_stack_persistent<80>, dim3(grid), dim3(threads), lds, s, P, ptrs); break;
-    case 128: hipLaunchKernelGGL(k_stack_persistent<128>, dim3(grid), dim3(threads), lds, s, P, ptrs); break;
-    default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
-}
-
 hipError_t persistent_occupancy(int head_dim, int threads, size_t lds_bytes, int *blocks_per_cu)
 {
     switch (head_dim) {
-    case 64: return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, k_stack_persistent<64>, threads, lds_bytes);
-    case 80: return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, k_stack_persistent<80>, threads, lds_bytes);
-    case 128: return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, k_stack_persistent<128>, threads, lds_bytes);
+    case 64: return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, k_block_persistent<64>, threads, lds_bytes);
+    case 80: return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, k_block_persistent<80>, threads, lds_bytes);
+    case 128: return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, k_block_persistent<128>, threads, lds_bytes);
     }
     return hipErrorInvalidValue;
 }
@@ -494,9 +461,6 @@ hipError_t prepare_kernels(size_t lds_bytes)
     CFPP_TRY(hipFuncSetAttribute((const void *)k_block_persistent<64>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
     CFPP_TRY(hipFuncSetAttribute((const void *)k_block_persistent<80>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
     CFPP_TRY(hipFuncSetAttribute((const void *)k_block_persistent<128>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
-    CFPP_TRY(hipFuncSetAttribute((const void *)k_stack_persistent<64>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
-    CFPP_TRY(hipFuncSetAttribute((const void *)k_stack_persistent<80>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
-    CFPP_TRY(hipFuncSetAttribute((const void *)k_stack_persistent<128>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
     return hipSuccess;
 }
 

@@ -161,19 +161,25 @@ def test_full_pythia_2_8b_stack_graph_and_argmax(orc):
         print("[case] full 2.8B stack: running", flush=True)
         x = synth.x_input(shape, synth.MASTER_SEED)
         ds.set_inputs(x, S)
-        ds.set_options(mode=0)
-        ds.capture()
-        outs = []
-        for _ in range(5):
-            ds.replay()
-            ds.check()
-            outs.append(ds.result()[0].copy())
-        for o in outs[1:]:
-            assert np.array_equal(o.view(np.uint16), outs[0].view(np.uint16)), "not bit-identical"
+        results = {}
+        for mode in (0, 2):                               # per-phase kernels; fused whole-stack kernel
+            ds.set_options(mode=mode)
+            ds.set_inputs(x, S)
+            ds.capture()
+            outs = []
+            for _ in range(5):
+                ds.replay()
+                ds.check()
+                outs.append(ds.result()[0].copy())
+            for o in outs[1:]:
+                assert np.array_equal(o.view(np.uint16), outs[0].view(np.uint16)), f"mode {mode}: not bit-identical"
+            results[mode] = outs[0]
         print("[case] full 2.8B stack: oracle", flush=True)
         ref16, per, _, _ = oracle_stack(orc, shape, ws, kvs, S, x[0])
-        ma, rl = assert_block_close(outs[0], ref16, "32-layer output")
-        print(f"[result] max-abs {ma:.4e} rel-L2 {rl:.4e}", flush=True)
+        for mode, out in results.items():
+            ma, rl = assert_block_close(out, ref16, f"32-layer output, mode {mode}")
+            print(f"[result] mode {mode}: max-abs {ma:.4e} rel-L2 {rl:.4e}", flush=True)
+        outs = [results[2]]
         head = synth.lm_head(shape, synth.MASTER_SEED)
         lg_ref = orc.lm_head_logits(shape, head, orc.half_to_real(ref16))
         lg_gpu = orc.lm_head_logits(shape, head, orc.half_to_real(outs[0]))
