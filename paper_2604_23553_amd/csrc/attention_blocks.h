@@ -257,8 +257,8 @@ struct AttnCore {
     // The same two steps with tagged words (value, tag pairs in `pt`, laid out like
     // P.part): the partial is published with single stores and nobody counts;
     // the first workgroup covering a head re-reads the head's slots until all
-    // carry `tag`, merges them in slot order and stores the head's output into
-    // P.o.  The publishing side waits for no acknowledgement.
+    // carry `tag`, merges them in slot order and stores the head's output, tagged
+    // again, into ot[h].  Neither side waits for an acknowledgement.
     __device__ __forceinline__ void publish_tagged(const StepParams &P, float *pt, unsigned tag, int s,
                                                    const float *wp, const float *wm, const float *wl,
                                                    int nslots) const
@@ -292,7 +292,8 @@ struct AttnCore {
         return g == g_lo;
     }
 
-    __device__ __forceinline__ void combine_tagged(const StepParams &P, const float *pt, unsigned tag, int s) const
+    __device__ __forceinline__ void combine_tagged(const StepParams &P, const float *pt, float *ot, unsigned tag,
+                                                   int s) const
     {
         int g_lo, ncover;
         cover(s, g_lo, ncover);
@@ -301,8 +302,6 @@ struct AttnCore {
         float M = -INFINITY, L = 0.f, O[NE];
 #pragma unroll
         for (int e = 0; e < NE; ++e) O[e] = 0.f;
-        // a cheap test first: the word stored last of every slot (one lane each)
-        wait_tagged_sample(base, D + 1, D + 2, ncover, ncover * (D + 2) - 1, tag, P.sync, lane);
         PollGuard pg;
         pg.start(P.sync);
         for (int j0 = 0; j0 < ncover; j0 += CB) {
@@ -342,7 +341,7 @@ struct AttnCore {
         }
 #pragma unroll
         for (int e = 0; e < NE; ++e)
-            if (lane + 64 * e < D) xwg_store(P.o + s * D + lane + 64 * e, O[e] / L);
+            if (lane + 64 * e < D) xwg_store_tagged(ot + 2 * (s * D + lane + 64 * e), O[e] / L, tag);
     }
 };
 

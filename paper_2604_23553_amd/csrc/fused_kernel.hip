@@ -35,6 +35,13 @@
 namespace cfpp {
 
 constexpr int kFusedSegs = 2;       // a workgroup's share of the attention covers at most two heads
+#ifndef CFPP_FUSED_UQ
+#define CFPP_FUSED_UQ 4
+#endif
+#ifndef CFPP_FUSED_UD
+#define CFPP_FUSED_UD 4
+#endif
+constexpr int kFusedUQ = CFPP_FUSED_UQ, kFusedUD = CFPP_FUSED_UD;   // (overridable for kernel experiments)
 constexpr int kFusedSlots = 8;      // LDS slots for the streaming wavefronts' attention states
 constexpr int kStageMStream = 22;   // float2 per streaming thread when staging GELU(up): ffn <= 44 * 64 * (nw - 1)
 
@@ -71,7 +78,7 @@ struct FusedCtx {
     int pos, nw;
     int q_begin, q_n, u_begin, u_n, r_begin, r_n;
     unsigned E0;                    // epoch base of this launch
-    float *pt;                      // tagged words of the split-KV partials
+    float *ot, *pt;                 // tagged words: attention output [h], split-KV partials
 };
 
 // first part of every layer, both roles: the two LayerNorms into LDS and the
@@ -122,7 +129,11 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
     float *pq = lds + C.L.pq, *pu = lds + C.L.pu, *pd = lds + C.L.pd, *pc = lds + C.L.pc;
     const int n_tok = C.pos + 1;
 
-    GemvSpan<kGemvU> gsQ, gsU, gsD, gsC;
+    // deeper blocks for the two GEMVs whose first loads must cover a hand-over
+    // (layer boundary, attention arithmetic and GELU(up) staging)
+    GemvSpan<kFusedUQ> gsQ;
+    GemvSpan<kFusedUD> gsD;
+    GemvSpan<kGemvU> gsU, gsC;
     {
         const int tid0 = opaque_thread_index();
         const __half *w0 = C.ptrs->w[0];
@@ -218,17 +229,19 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
                  w, tid, 0);
         gsD.run(pd, [&] { gsC.issue_first(); gsC.issue_second(); });
         tr.mark(18);
-        __syncthreads();                                   // S4: down rows done; attention output staged
-        tr.mark(20);
-
         {
-            // the next layer's first QKV weights (nothing for the last layer: the loads re-read one block)
+            // the next layer's first QKV weights stream while the attention output is waited for
+            // (nothing for the last layer: the loads re-read one block)
             const bool more = layer + 1 < L;
             const __half *wn = C.ptrs->w[more ? layer + 1 : layer];
             gsQ.init(GemvSeg{wn + P.lay.w_qkv + (size_t)C.q_begin * h, y1, h, more ? C.q_n : 0},
                      GemvSeg{wn + P.lay.w_qkv, y1, h, 0}, wn, tid, 0);
+            gsQ.issue_first();
+            gsQ.issue_second();
         }
-        gsC.run(pc, [&] { gsQ.issue_first(); gsQ.issue_second(); });
+        __syncthreads();                                   // S4: down rows done; attention output staged
+        tr.mark(20);
+        gsC.run(pc);
         tr.mark(23);
         __syncthreads();                                   // S6: dense rows done
         tr.mark(24);
@@ -249,10 +262,9 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
     const int pos = C.pos, n_tok = pos + 1;
     const int q_begin = C.q_begin, q_n = C.q_n, u_begin = C.u_begin, u_n = C.u_n, r_begin = C.r_begin, r_n = C.r_n;
 
-    GridBarrier b1, b2, b3, b4;
+    GridBarrier b1, b2, b4;
     b1.init(P.sync, gridDim.x, 0);
     b2.init(P.sync, gridDim.x, 1);
-    b3.init(P.sync, gridDim.x, 2);
     b4.init(P.sync, gridDim.x, 3);
     // the partial sums of a row sit in wavefront slots; only the streaming wavefronts fill them
     GemvSpan<kGemvU> rt;                                  // (row_total() only)
@@ -384,19 +396,39 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
                                   lds + C.L.wm + k * kFusedSlots, lds + C.L.wl + k * kFusedSlots, NS);
 #pragma unroll
         for (int k = 0; k < kFusedSegs; ++k)
-            if (k < sg.n && ac.combines(sg.s[k])) ac.combine_tagged(P, C.pt, epoch, sg.s[k]);
+            if (k < sg.n && ac.combines(sg.s[k])) ac.combine_tagged(P, C.pt, C.ot, epoch, sg.s[k]);
         if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 1] = wall_clock64();
-        b3.arrive_wave();                                  // (waits for the combined heads' stores first)
-        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 2] = wall_clock64();
-        b3.wait_wave();                                    // the attention output is complete
-        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 3] = wall_clock64();
         tr.mark(16);
         {
-            // stage it: this wavefront alone, up to 64 values per lane
-            StagedVector<32> so;
-            so.issue(P.o, h, lane, 64);
-            so.commit(h, ol, lane, 64);
+            // the attention output, tagged: the whole vector is re-read until every word
+            // is current (one round trip after the last head was stored), then staged
+            constexpr int SB = 20;
+            const int hp = round_up_chunk(h);
+            PollGuard pg;
+            pg.start(P.sync);
+            for (int base = 0; base < hp; base += SB * 64) {
+                float2 wd[SB];
+                bool ok;
+                do {
+#pragma unroll
+                    for (int j2 = 0; j2 < SB; ++j2) {
+                        const int i2 = base + j2 * 64 + lane;
+                        wd[j2] = xwg_load2(C.ot + 2 * (i2 < h ? i2 : 0));
+                    }
+                    ok = true;
+#pragma unroll
+                    for (int j2 = 0; j2 < SB; ++j2)
+                        ok = ok && (base + j2 * 64 + lane >= h || __float_as_uint(wd[j2].y) == epoch);
+                    ok = __all(ok);
+                } while (!ok && !pg.give_up());
+#pragma unroll
+                for (int j2 = 0; j2 < SB; ++j2) {
+                    const int i2 = base + j2 * 64 + lane;
+                    if (i2 < hp) ol[lds_perm(i2)] = i2 < h ? wd[j2].x : 0.f;
+                }
+            }
         }
+        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 3] = wall_clock64();
         tr.mark(17);
         if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 4] = wall_clock64();
         __syncthreads();                                   // S4: down rows done
@@ -418,7 +450,6 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
     }
     b1.finish_wave();
     b2.finish_wave();
-    b3.finish_wave();
     b4.finish_wave();
     // every workgroup has read E0 and finished its layers: the next launch gets fresh epochs
     if (blockIdx.x == 0 && threadIdx.x == 0)
@@ -447,6 +478,7 @@ k_stack_fused(StepParams P, const LayerPtrs *__restrict__ ptrs)
     C.r_begin = g * P.rows_h;   C.r_n = max(0, min(P.rows_h, dm.h - C.r_begin));
     // (only changed at the very end of a launch, behind the last barriers)
     C.E0 = __hip_atomic_load(as_global(P.sync + kSyncEpoch), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    C.ot = P.tagged + 2 * (size_t)5 * dm.h;
     C.pt = P.tagged + 2 * (size_t)6 * dm.h;
     if (threadIdx.x == 0) reinterpret_cast<int *>(lds)[C.L.ctr] = 0;    // (a workgroup barrier follows in both roles)
     if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0) fused_chain<D>(C, ptrs->kv);
