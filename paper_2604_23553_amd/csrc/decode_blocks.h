@@ -341,11 +341,10 @@ struct LnPair {
         }
     }
 
-    // The same with the input given as tagged words xt[h] (value, tag pairs): the
-    // input is re-read until every word carries `tag` - the producers' stores are
-    // the only signal.
-    __device__ __forceinline__ void load_tagged(const StepParams &P, const __half *__restrict__ w, const float *xt,
-                                                unsigned tag, int tid)
+    // The two halves of load() on their own: the parameters depend on nothing and
+    // can be requested ahead of a wait; the input may already sit in LDS (fp32,
+    // natural order).
+    __device__ __forceinline__ void load_params(const StepParams &P, const __half *__restrict__ w, int tid)
     {
         const int h = P.dm.h, nt = blockDim.x;
         const int ngrp = h >> 3;
@@ -361,25 +360,43 @@ struct LnPair {
                 pg2[j] = load16(g2 + gi * 8); pb2[j] = load16(b2 + gi * 8);
             }
         }
-        PollGuard pg;
-        pg.start(P.sync);
-        bool ok;
-        do {
-            ok = true;
+    }
+    __device__ __forceinline__ void load_x_global(const StepParams &P, const LayerIO &io, int tid)
+    {
+        const int h = P.dm.h, nt = blockDim.x;
+        const int ngrp = h >> 3;
 #pragma unroll
-            for (int j = 0; j < GU; ++j) {
-                const int gi = tid + j * nt;
-                const int gc = gi < ngrp ? gi : 0;
-                float2 wd[8];
+        for (int j = 0; j < GU; ++j) {
+            const int gi = tid + j * nt;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) wd[e] = xwg_load2(xt + 2 * (gc * 8 + e));
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    xv[j][e] = gi < ngrp ? wd[e].x : 0.f;
-                    ok = ok && (gi >= ngrp || __float_as_uint(wd[e].y) == tag);
+            for (int e = 0; e < 8; ++e) xv[j][e] = 0.f;
+            if (gi < ngrp) {
+                if (io.x16) {
+                    const u32x4 xr = load16(io.x16 + gi * 8);
+                    const float2 a = unpack_h2(xr.x), b = unpack_h2(xr.y), c = unpack_h2(xr.z), e2 = unpack_h2(xr.w);
+                    xv[j][0] = a.x; xv[j][1] = a.y; xv[j][2] = b.x; xv[j][3] = b.y;
+                    xv[j][4] = c.x; xv[j][5] = c.y; xv[j][6] = e2.x; xv[j][7] = e2.y;
+                } else {
+                    const float *xp = io.x32 + gi * 8;
+                    const float2 a = xwg_load2(xp), b = xwg_load2(xp + 2), c = xwg_load2(xp + 4), e2 = xwg_load2(xp + 6);
+                    xv[j][0] = a.x; xv[j][1] = a.y; xv[j][2] = b.x; xv[j][3] = b.y;
+                    xv[j][4] = c.x; xv[j][5] = c.y; xv[j][6] = e2.x; xv[j][7] = e2.y;
                 }
             }
-        } while (!ok && !pg.give_up());
+        }
+    }
+    __device__ __forceinline__ void load_x_lds(const StepParams &P, const float *xs, int tid)
+    {
+        const int h = P.dm.h, nt = blockDim.x;
+        const int ngrp = h >> 3;
+#pragma unroll
+        for (int j = 0; j < GU; ++j) {
+            const int gi = tid + j * nt;
+            const float4 a = gi < ngrp ? *reinterpret_cast<const float4 *>(xs + gi * 8) : float4{0.f, 0.f, 0.f, 0.f};
+            const float4 b = gi < ngrp ? *reinterpret_cast<const float4 *>(xs + gi * 8 + 4) : float4{0.f, 0.f, 0.f, 0.f};
+            xv[j][0] = a.x; xv[j][1] = a.y; xv[j][2] = a.z; xv[j][3] = a.w;
+            xv[j][4] = b.x; xv[j][5] = b.y; xv[j][6] = b.z; xv[j][7] = b.w;
+        }
     }
 
     __device__ __forceinline__ void finish(const StepParams &P, float *y1, float *y2, float *red, int tid)

@@ -47,7 +47,7 @@ constexpr int kStageMStream = 22;   // float2 per streaming thread when staging 
 
 // LDS of the fused kernel, in floats
 struct FusedLds {
-    unsigned y1, y2, ml, ol, pq, pu, pd, pc, red, qs, kn, vn, wp, wm, wl, ctr, total;
+    unsigned y1, y2, ml, ol, xs, pq, pu, pd, pc, red, qs, kn, vn, wp, wm, wl, ctr, total;
 };
 
 static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qkv, int rows_up, int rows_h, int nw)
@@ -57,7 +57,7 @@ static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qk
     const unsigned Kpf = (unsigned)((dm.f + kChunk - 1) / kChunk * kChunk);
     unsigned o = 0;
     auto take = [&](unsigned n) { unsigned at = o; o += (n + 3u) & ~3u; return at; };
-    L.y1 = take(Kph); L.y2 = take(Kph); L.ml = take(Kpf); L.ol = take(Kph);
+    L.y1 = take(Kph); L.y2 = take(Kph); L.ml = take(Kpf); L.ol = take(Kph); L.xs = take(Kph);
     L.pq = take((unsigned)(rows_qkv * nw)); L.pu = take((unsigned)(rows_up * nw));
     L.pd = take((unsigned)(rows_h * nw)); L.pc = take((unsigned)(rows_h * nw));
     L.red = take(16);
@@ -78,17 +78,23 @@ struct FusedCtx {
     int pos, nw;
     int q_begin, q_n, u_begin, u_n, r_begin, r_n;
     unsigned E0;                    // epoch base of this launch
-    float *ot, *pt;                 // tagged words: attention output [h], split-KV partials
+    float *xt, *ot, *pt;            // tagged words: layer outputs [2][h], attention output [h], split-KV partials
 };
 
 // first part of every layer, both roles: the two LayerNorms into LDS and the
-// partial-sum slots of the four GEMVs cleared.  Four workgroup barriers inside;
-// the caller adds one after it.
-__device__ __forceinline__ void fused_prologue(const FusedCtx &C, const __half *w, const LayerIO &io, int tid)
+// partial-sum slots of the four GEMVs cleared.  The parameters are requested
+// ahead of the workgroup barrier behind which the layer input is known to be
+// there (for layers > 0 the chain wavefront has put it into LDS); four more
+// barriers inside, and the caller adds one after it.
+__device__ __forceinline__ void fused_prologue(const FusedCtx &C, const __half *w, const LayerIO &io, int layer,
+                                               int tid)
 {
     const StepParams &P = *C.P;
     LnPair ln;
-    ln.load(P, w, io, tid);
+    ln.load_params(P, w, tid);
+    __syncthreads();                                       // Sx: the layer input is complete
+    if (layer == 0) ln.load_x_global(P, io, tid);
+    else ln.load_x_lds(P, C.lds + C.L.xs, tid);
     ln.finish(P, C.lds + C.L.y1, C.lds + C.L.y2, C.lds + C.L.red, tid);
     clear_partials(C.lds + C.L.pq, (int)(C.L.red - C.L.pq), tid);
 }
@@ -154,9 +160,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
         const LayerIO io = layer_io(P, layer);
         tr.n = 0;
         tr.mark(1);
-        __syncthreads();                                   // Sx: the layer input is complete
-        tr.mark(2);
-        fused_prologue(C, w, io, tid);
+        fused_prologue(C, w, io, layer, tid);
         __syncthreads();                                   // S0
         tr.mark(3);
 
@@ -262,10 +266,9 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
     const int pos = C.pos, n_tok = pos + 1;
     const int q_begin = C.q_begin, q_n = C.q_n, u_begin = C.u_begin, u_n = C.u_n, r_begin = C.r_begin, r_n = C.r_n;
 
-    GridBarrier b1, b2, b4;
+    GridBarrier b1, b2;
     b1.init(P.sync, gridDim.x, 0);
     b2.init(P.sync, gridDim.x, 1);
-    b4.init(P.sync, gridDim.x, 3);
     // the partial sums of a row sit in wavefront slots; only the streaming wavefronts fill them
     GemvSpan<kGemvU> rt;                                  // (row_total() only)
     rt.nw = nw;
@@ -283,10 +286,39 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
         const bool last_layer = layer == L - 1;
         tr.n = 0;
         tr.mark(1);
-        b4.wait_wave();                                    // the previous layer's output is complete
-        __syncthreads();                                   // Sx
+        if (layer > 0) {
+            // the previous layer's output, tagged: re-read until every word is current, then into LDS
+            constexpr int SB = 40;
+            const float *xt = C.xt + 2 * (size_t)((layer - 1) & 1) * h;
+            const unsigned want = C.E0 + (unsigned)layer;
+            float *xs = lds + C.L.xs;
+            PollGuard pg;
+            pg.start(P.sync);
+            for (int base = 0; base < h; base += SB * 64) {
+                float2 wd[SB];
+                bool ok;
+                do {
+#pragma unroll
+                    for (int j2 = 0; j2 < SB; ++j2) {
+                        const int i2 = base + j2 * 64 + lane;
+                        wd[j2] = xwg_load2(xt + 2 * (i2 < h ? i2 : 0));
+                    }
+                    ok = true;
+#pragma unroll
+                    for (int j2 = 0; j2 < SB; ++j2)
+                        ok = ok && (base + j2 * 64 + lane >= h || __float_as_uint(wd[j2].y) == want);
+                    ok = __all(ok);
+                } while (!ok && !pg.give_up());
+#pragma unroll
+                for (int j2 = 0; j2 < SB; ++j2) {
+                    const int i2 = base + j2 * 64 + lane;
+                    if (i2 < h) xs[i2] = wd[j2].x;
+                }
+            }
+        }
         tr.mark(2);
-        fused_prologue(C, w, io, tid);
+        if ((P.debug & 32) && lane == 0 && layer == L - 1) P.trace[blockIdx.x * 8 + 7] = wall_clock64();
+        fused_prologue(C, w, io, layer, tid);
         __syncthreads();                                   // S0
         tr.mark(3);
 
@@ -438,19 +470,18 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
         if (lane < r_n) g_r = rt.row_total(pd, lane) + bdn0;
         __syncthreads();                                   // S6: dense rows done
         tr.mark(24);
+        if ((P.debug & 32) && lane == 0 && layer == L - 2) P.trace[blockIdx.x * 8 + 6] = wall_clock64();
         if (lane < r_n) {
             const float a = rt.row_total(pc, lane) + bde0;
             const float res = (x_r + a) + g_r;
             x_r = res;
-            if (io.o16) io.o16[r_begin + lane] = __float2half_rn(res);
-            else xwg_store(io.o32 + r_begin + lane, res);
+            if (last_layer) io.o16[r_begin + lane] = __float2half_rn(res);
+            else xwg_store_tagged(C.xt + 2 * ((size_t)(layer & 1) * h + r_begin + lane), res, epoch);
         }
-        if (!last_layer) b4.arrive_wave();
         tr.mark(25);
     }
     b1.finish_wave();
     b2.finish_wave();
-    b4.finish_wave();
     // every workgroup has read E0 and finished its layers: the next launch gets fresh epochs
     if (blockIdx.x == 0 && threadIdx.x == 0)
         __hip_atomic_store(as_global(P.sync + kSyncEpoch), C.E0 + (unsigned)L + 1u, __ATOMIC_RELAXED,
@@ -478,6 +509,7 @@ k_stack_fused(StepParams P, const LayerPtrs *__restrict__ ptrs)
     C.r_begin = g * P.rows_h;   C.r_n = max(0, min(P.rows_h, dm.h - C.r_begin));
     // (only changed at the very end of a launch, behind the last barriers)
     C.E0 = __hip_atomic_load(as_global(P.sync + kSyncEpoch), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    C.xt = P.tagged;
     C.ot = P.tagged + 2 * (size_t)5 * dm.h;
     C.pt = P.tagged + 2 * (size_t)6 * dm.h;
     if (threadIdx.x == 0) reinterpret_cast<int *>(lds)[C.L.ctr] = 0;    // (a workgroup barrier follows in both roles)
