@@ -188,8 +188,6 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
 
         gsD.init(GemvSeg{w + P.lay.w_down + (size_t)C.r_begin * f, ml, f, C.r_n}, GemvSeg{w + P.lay.w_down, ml, f, 0},
                  w, tid, 0);
-        gsD.issue_first();                                 // streams during the attention arithmetic
-        gsD.issue_second();
 #pragma unroll
         for (int k = 0; k < kFusedSegs; ++k) {
             if (k < sg.n) {
@@ -216,6 +214,11 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
                               lds + C.L.wl + k * kFusedSlots, si);
             }
         }
+        // the first down-projection weights stream while the attention states are
+        // merged and GELU(up) is staged (requested any earlier they only lengthen the
+        // queue the hand-overs wait in)
+        gsD.issue_first();
+        gsD.issue_second();
         tr.mark(13);
         __syncthreads();                                   // S3: attention states in LDS; GELU(up) complete everywhere
         tr.mark(14);
