@@ -167,7 +167,9 @@ void cfpp_destroy(cfpp_ctx *ctx);
 #define CFPP_OPT_PROFILE_SKIP 100 /* profiling aid only.  Bits 0-3: sub-steps to
                                 skip so that the others can be timed alone
                                 (results are then wrong).  Bit 4 (16): workgroup
-                                (value >> 8) records a per-wavefront timeline,
+                                ((value >> 8) & 0xfff) records a per-wavefront
+                                timeline (mode 2: of layer ((value >> 20) & 255)
+                                - 1, of the last layer when those bits are 0),
                                 bit 5 (32): every workgroup records a few time
                                 stamps of the last layer (mode 2); both are read
                                 back with cfpp_debug_read(which = 4) and leave

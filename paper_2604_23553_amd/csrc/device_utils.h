@@ -400,7 +400,7 @@ struct Tracer {
     template <class Params>
     __device__ __forceinline__ void init(const Params &P, int wave, int first = 0)
     {
-        const bool on = (P.debug & 16) && (int)blockIdx.x == (P.debug >> 8) && wave < kTraceWaves;
+        const bool on = (P.debug & 16) && (int)blockIdx.x == ((P.debug >> 8) & 0xfff) && wave < kTraceWaves;
         p = on ? P.trace + (size_t)wave * kTraceLen * 2 : nullptr;
         n = first;
     }

@@ -35,13 +35,6 @@
 namespace cfpp {
 
 constexpr int kFusedSegs = 2;       // a workgroup's share of the attention covers at most two heads
-#ifndef CFPP_FUSED_UQ
-#define CFPP_FUSED_UQ 4
-#endif
-#ifndef CFPP_FUSED_UD
-#define CFPP_FUSED_UD 4
-#endif
-constexpr int kFusedUQ = CFPP_FUSED_UQ, kFusedUD = CFPP_FUSED_UD;   // (overridable for kernel experiments)
 constexpr int kFusedSlots = 8;      // LDS slots for the streaming wavefronts' attention states
 constexpr int kStageMStream = 22;   // float2 per streaming thread when staging GELU(up): ffn <= 44 * 64 * (nw - 1)
 
@@ -135,11 +128,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
     float *pq = lds + C.L.pq, *pu = lds + C.L.pu, *pd = lds + C.L.pd, *pc = lds + C.L.pc;
     const int n_tok = C.pos + 1;
 
-    // deeper blocks for the two GEMVs whose first loads must cover a hand-over
-    // (layer boundary, attention arithmetic and GELU(up) staging)
-    GemvSpan<kFusedUQ> gsQ;
-    GemvSpan<kFusedUD> gsD;
-    GemvSpan<kGemvU> gsU, gsC;
+    GemvSpan<kGemvU> gsQ, gsU, gsD, gsC;
     {
         const int tid0 = opaque_thread_index();
         const __half *w0 = C.ptrs->w[0];
@@ -158,7 +147,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
         const __half *w = C.ptrs->w[layer];
         const __half *kv = C.ptrs->kv[layer];
         const LayerIO io = layer_io(P, layer);
-        tr.n = 0;
+        tr.n = layer == (((P.debug >> 20) & 255) ? ((P.debug >> 20) & 255) - 1 : L - 1) ? 0 : kTraceLen;   // the traced layer
         tr.mark(1);
         fused_prologue(C, w, io, layer, tid);
         __syncthreads();                                   // S0
@@ -262,9 +251,9 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
     using AC = AttnCore<D>;
     const StepParams &P = *C.P;
     const Dims &dm = P.dm;
-    const int h = dm.h, f = dm.f, d = dm.d, r = dm.r, L = P.n_layers, nw = C.nw, NS = nw - 1;
+    const int h = dm.h, d = dm.d, r = dm.r, L = P.n_layers, nw = C.nw, NS = nw - 1;
     float *lds = C.lds;
-    float *ml = lds + C.L.ml, *ol = lds + C.L.ol;
+    float *ol = lds + C.L.ol;
     const float *pq = lds + C.L.pq, *pu = lds + C.L.pu, *pd = lds + C.L.pd, *pc = lds + C.L.pc;
     const int pos = C.pos, n_tok = pos + 1;
     const int q_begin = C.q_begin, q_n = C.q_n, u_begin = C.u_begin, u_n = C.u_n, r_begin = C.r_begin, r_n = C.r_n;
@@ -287,7 +276,7 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
         __half *kv = kv_layers[layer];
         const LayerIO io = layer_io(P, layer);
         const bool last_layer = layer == L - 1;
-        tr.n = 0;
+        tr.n = layer == (((P.debug >> 20) & 255) ? ((P.debug >> 20) & 255) - 1 : L - 1) ? 0 : kTraceLen;   // the traced layer
         tr.mark(1);
         if (layer > 0) {
             // the previous layer's output, tagged: re-read until every word is current, then into LDS
