@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--grid", type=int, default=int(os.environ.get("CFPP_GRID", "0")))
     ap.add_argument("--threads", type=int, default=int(os.environ.get("CFPP_THREADS", "512")))
     ap.add_argument("--ctx", type=int, default=4096, help="cached positions per layer")
+    ap.add_argument("--shape", choices=["2.8b", "6.9b"], default="2.8b",
+                    help="model shape of the stack (the headline metric is quoted on 2.8b, ctx 4096)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--calibrate", action="store_true",
                     help="instead of the benchmark, run the plain copy kernel (1 GiB read + 1 GiB written per "
@@ -108,7 +110,8 @@ def main():
                           "bytes_written_per_launch": n, "launches": 5}))
         return
 
-    shape = synth.PYTHIA_2_8B
+    shape = synth.PYTHIA_2_8B if args.shape == "2.8b" else synth.PYTHIA_6_9B
+    headline = args.shape == "2.8b" and args.ctx == 4096
     S, cap = args.ctx, args.ctx + 1
     seed = synth.MASTER_SEED
     t_gen = time.perf_counter()
@@ -152,7 +155,7 @@ def main():
     achieved = alg_bytes / (us_launch * 1e-6) / 1e9
     grid = cf.cfpp_get_option(ds.ctx, cf.OPT_GRID)
     out = {
-        "metric": "us_per_token_decode_32L_pythia2.8b_bs1",
+        "metric": f"us_per_token_decode_32L_pythia{args.shape}_bs1",
         "value": us_wall,
         "unit": "us/token",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -162,7 +165,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f16 weights/KV, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": f"32-layer Pythia-2.8B-shaped decode step, ctx {S}, batch 1, one HIP graph replay",
+        "config": {"workload": f"32-layer Pythia-{args.shape.upper()}-shaped decode step, ctx {S}, batch 1, one HIP graph replay",
                    "hidden": shape.hidden, "n_heads": shape.n_heads, "head_dim": shape.head_dim,
                    "ffn": shape.ffn, "n_layers": shape.n_layers, "ctx": S, "batch": 1,
                    "launch_mode": args.mode, "grid": grid, "threads": args.threads},
@@ -172,9 +175,9 @@ def main():
                                  "min": float(per.min()), "p95": float(np.percentile(per, 95))},
         "achieved_hbm_GBps": achieved,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic_note(),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic_note() if headline and args.mode == 2 else None,
                      "algorithmic_bytes_per_launch": alg_bytes,
-                     "kernel": "k_stack_fused<80> (the whole 32-layer step is one launch)" if args.mode == 2
+                     "kernel": f"k_stack_fused<{shape.head_dim}> (the whole 32-layer step is one launch)" if args.mode == 2
                      else "all kernels of one graph replay",
                      "launch": "one graph replay of the 32-layer step"},
         "context": PAPER_CONTEXT,
