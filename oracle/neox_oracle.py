@@ -174,6 +174,33 @@ class Oracle:
                              C.c_double(shape.ln_eps if eps is None else eps), self._rp(logits))
         return logits
 
+    # -- greedy generation (the steps either side of the stack: paper Sec. 2.3
+    #    replays one graph per generated token; Sec. 4 decodes greedily) ------
+    def next_token(self, shape, head: dict, hidden_f16):
+        """Final LayerNorm + LM head on the stack's fp16 output, then the index of
+        the largest logit (the lowest index among equal maxima)."""
+        logits = self.lm_head_logits(shape, head, self.half_to_real(np.asarray(hidden_f16).reshape(-1)))
+        return int(np.argmax(logits)), logits
+
+    def generate(self, shape, layers, Ks, Vs, head: dict, embed: np.ndarray, tokens, pos: int,
+                 n_steps: int, trace: list | None = None):
+        """n_steps greedy decode steps for one sequence.  tokens[pos] is the token
+        whose K/V rows are appended at row `pos`; each step embeds it (fp16 table
+        row), runs the stack, and picks tokens[pos + 1].  Ks, Vs are updated in
+        place.  Returns the token list extended by n_steps entries; `trace`
+        (optional) receives (hidden_f16, logits) of every step."""
+        tokens = list(tokens)
+        assert len(tokens) == pos + 1
+        for _ in range(n_steps):
+            x = np.ascontiguousarray(embed[tokens[pos]])
+            hidden16, _ = self.stack_decode(shape, layers, Ks, Vs, pos, x)
+            tok, logits = self.next_token(shape, head, hidden16)
+            if trace is not None:
+                trace.append((hidden16.copy(), logits))
+            tokens.append(tok)
+            pos += 1
+        return tokens
+
 
 _cache = {}
 

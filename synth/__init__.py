@@ -29,7 +29,7 @@ _TID = {
     "w_qkv": 5, "b_qkv": 6, "w_dense": 7, "b_dense": 8,
     "w_up": 9, "b_up": 10, "w_down": 11, "b_down": 12,
     "k_cache": 13, "v_cache": 14, "x": 15,
-    "lnf_g": 16, "lnf_b": 17, "w_lm": 18, "seq_lens": 19,
+    "lnf_g": 16, "lnf_b": 17, "w_lm": 18, "seq_lens": 19, "embed": 20,
 }
 LAYER_TENSORS = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv",
                  "w_dense", "b_dense", "w_up", "b_up", "w_down", "b_down")
@@ -126,6 +126,11 @@ def lm_head(shape: ModelShape, seed: int = MASTER_SEED, vocab: int = VOCAB) -> d
         "lnf_b": _normal_f16(_rng(seed, 0, "lnf_b"), (shape.hidden,), 0.02),
         "w_lm": _normal_f16(_rng(seed, 0, "w_lm"), (vocab, shape.hidden), 0.02),
     }
+
+
+def embedding(shape: ModelShape, seed: int = MASTER_SEED, vocab: int = VOCAB) -> np.ndarray:
+    """Random token embedding table [vocab, hidden], rows ~ N(0, 1) like the block input x."""
+    return _normal_f16(_rng(seed, 0, "embed"), (vocab, shape.hidden))
 
 
 def seq_lens(seed: int, batch: int, lo: int, hi: int) -> np.ndarray:
