@@ -213,6 +213,48 @@ cfpp_status cfpp_stack_capture(cfpp_ctx *ctx, const void *const *packed_layers,
                                cfpp_stream stream);
 cfpp_status cfpp_stack_replay(cfpp_ctx *ctx, cfpp_stream stream);
 
+/* ---- generation loop: the steps either side of the stack ---------------------
+ * (paper Sec. 2.3 replays one graph per generated token with static buffers;
+ * Sec. 4 decodes greedily.)  One sequence.  The token sequence lives in DEVICE
+ * memory indexed by position: tokens_dev[p] is the token whose K/V rows are
+ * appended at cache row p; int32[max_seq + 1].
+ *
+ * cfpp_lm: DEVICE fp16 tensors, 16-byte aligned, owned by the caller:
+ *   embed [vocab, hidden]   token embedding rows
+ *   lnf_g, lnf_b [hidden]   final LayerNorm (eps = cfg.ln_eps, biased variance)
+ *   w_lm  [vocab, hidden]   bias-free LM head, rows contiguous                  */
+typedef struct cfpp_lm {
+    const void *embed, *lnf_g, *lnf_b, *w_lm;
+    int32_t vocab;
+} cfpp_lm;
+
+/* x[hidden] (DEVICE fp16) = embed[tokens_dev[*pos_dev]].  A token outside
+ * [0, vocab) raises the device error flag (row 0 is used); a position outside
+ * [0, max_seq) makes this and the next call do nothing (the stack step raises
+ * the flag for it). */
+cfpp_status cfpp_lm_embed(cfpp_ctx *ctx, const cfpp_lm *lm, const int32_t *tokens_dev,
+                          const int32_t *pos_dev, void *x, cfpp_stream stream);
+
+/* logits = w_lm LayerNorm(hidden) in fp32 (hidden: DEVICE fp16 [hidden], the
+ * stack's output); tokens_dev[*pos_dev + 1] = index of the largest logit, the
+ * lowest index among equal ones; then *pos_dev += 1.  logits_dev: DEVICE
+ * float[vocab] that receives every logit, or NULL.  Uses the context's launch
+ * shape (CFPP_OPT_GRID / CFPP_OPT_THREADS); CFPP_EUNSUPPORTED if vocab / grid rows
+ * do not fit a workgroup's LDS. */
+cfpp_status cfpp_lm_next(cfpp_ctx *ctx, const cfpp_lm *lm, const void *hidden, int32_t *tokens_dev,
+                         int32_t *pos_dev, float *logits_dev, cfpp_stream stream);
+
+/* Records embed -> stack step (batch 1, current launch mode) -> next token for
+ * these exact pointers into the context's graph, replacing any captured one;
+ * every cfpp_stack_replay then generates one token: it reads tokens_dev[pos],
+ * appends the K/V rows at pos, writes tokens_dev[pos + 1] and advances *pos_dev.
+ * x_buf, hidden_buf: DEVICE fp16 [hidden] scratch owned by the caller.  Replays
+ * past the end of the cache (pos = max_seq) do nothing and raise the flag. */
+cfpp_status cfpp_generate_capture(cfpp_ctx *ctx, const void *const *packed_layers,
+                                  void *const *kv_layers, const cfpp_lm *lm, int32_t *tokens_dev,
+                                  int32_t *pos_dev, void *x_buf, void *hidden_buf,
+                                  cfpp_stream stream);
+
 /* Synchronises `stream` and reports (and clears) the device error flag:
  * CFPP_OK, or CFPP_EDEVICE with the reason in cfpp_last_error(). */
 cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream);

@@ -178,6 +178,33 @@ def cfpp_stack_replay(ctx: int, stream):
     _check(lib().cfpp_stack_replay(C.c_void_p(ctx), _ptr(stream)), "cfpp_stack_replay")
 
 
+class Lm(C.Structure):
+    """cfpp_lm: device pointers of the embedding table, final LayerNorm and LM head."""
+    _fields_ = [("embed", C.c_void_p), ("lnf_g", C.c_void_p), ("lnf_b", C.c_void_p), ("w_lm", C.c_void_p),
+                ("vocab", C.c_int32)]
+
+    @classmethod
+    def of(cls, embed, lnf_g, lnf_b, w_lm, vocab: int):
+        return cls(_ptr(embed).value, _ptr(lnf_g).value, _ptr(lnf_b).value, _ptr(w_lm).value, int(vocab))
+
+
+def cfpp_lm_embed(ctx: int, lm: Lm, tokens_dev, pos_dev, x, stream=None):
+    _check(lib().cfpp_lm_embed(C.c_void_p(ctx), C.byref(lm), _ptr(tokens_dev), _ptr(pos_dev), _ptr(x),
+                               _ptr(stream)), "cfpp_lm_embed")
+
+
+def cfpp_lm_next(ctx: int, lm: Lm, hidden, tokens_dev, pos_dev, logits_dev=None, stream=None):
+    _check(lib().cfpp_lm_next(C.c_void_p(ctx), C.byref(lm), _ptr(hidden), _ptr(tokens_dev), _ptr(pos_dev),
+                              _ptr(logits_dev), _ptr(stream)), "cfpp_lm_next")
+
+
+def cfpp_generate_capture(ctx: int, packed_layers, kv_layers, lm: Lm, tokens_dev, pos_dev, x_buf, hidden_buf,
+                          stream):
+    _check(lib().cfpp_generate_capture(C.c_void_p(ctx), _ptr_array(packed_layers), _ptr_array(kv_layers),
+                                       C.byref(lm), _ptr(tokens_dev), _ptr(pos_dev), _ptr(x_buf),
+                                       _ptr(hidden_buf), _ptr(stream)), "cfpp_generate_capture")
+
+
 def cfpp_device_error(ctx: int, stream=None):
     """Synchronises the stream; raises CfppError if a kernel flagged an error."""
     _check(lib().cfpp_device_error(C.c_void_p(ctx), _ptr(stream)), "cfpp_device_error")

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "cfpp.h"
+#include "lm_params.h"
 #include "decode_params.h"
 
 using namespace cfpp;
@@ -186,7 +187,7 @@ struct cfpp_ctx {
     int mode, grid, threads, debug;
     int events_grid;   // grid size the stream kernel's event counters are consistent with (0: zeroed)
     size_t lds_limit;
-    bool prepared;
+    bool prepared, lm_prepared;
     hipGraph_t graph;
     hipGraphExec_t exec;
     int last_batch;
@@ -225,6 +226,7 @@ extern "C" cfpp_status cfpp_create(const cfpp_config *c, void *workspace, size_t
     ctx->events_grid = 0;
     ctx->lds_limit = prop.sharedMemPerBlock > 0 ? (size_t)prop.sharedMemPerBlock : 65536;
     ctx->prepared = false;
+    ctx->lm_prepared = false;
     ctx->graph = nullptr;
     ctx->exec = nullptr;
     ctx->last_batch = 1;
@@ -631,6 +633,123 @@ extern "C" cfpp_status cfpp_stack_replay(cfpp_ctx *ctx, cfpp_stream stream)
     return CFPP_OK;
 }
 
+// ---- generation loop: embedding lookup, LM head, next token -----------------
+static cfpp_status make_lm_params(cfpp_ctx *ctx, const cfpp_lm *lm, const int32_t *tokens_dev,
+                                  const int32_t *pos_dev, Shape *sh, LmParams *L)
+{
+    if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
+    if (!lm) return fail(CFPP_EINVAL, "lm is NULL");
+    if (lm->vocab < 1) return fail(CFPP_EINVAL, "vocab %d < 1", lm->vocab);
+    if (!aligned16(lm->embed) || !aligned16(lm->lnf_g) || !aligned16(lm->lnf_b) || !aligned16(lm->w_lm))
+        return fail(CFPP_EINVAL, "an lm tensor is NULL or not 16-byte aligned");
+    if (!tokens_dev || (reinterpret_cast<uintptr_t>(tokens_dev) & 3u) || !pos_dev ||
+        (reinterpret_cast<uintptr_t>(pos_dev) & 3u))
+        return fail(CFPP_EINVAL, "tokens_dev or pos_dev is NULL or misaligned");
+    cfpp_status st = launch_shape(ctx, sh);
+    if (st != CFPP_OK) return st;
+    const Dims &dm = ctx->dm;
+    std::memset(L, 0, sizeof *L);
+    L->h = dm.h; L->vocab = lm->vocab; L->max_seq = dm.max_seq; L->eps = dm.ln_eps;
+    L->embed = static_cast<const __half *>(lm->embed);
+    L->lnf_g = static_cast<const __half *>(lm->lnf_g);
+    L->lnf_b = static_cast<const __half *>(lm->lnf_b);
+    L->w_lm = static_cast<const __half *>(lm->w_lm);
+    L->tokens = tokens_dev; L->tokens_out = const_cast<int32_t *>(tokens_dev);
+    L->pos = pos_dev; L->pos_out = const_cast<int32_t *>(pos_dev);
+    L->best = reinterpret_cast<float *>(ctx->ws + ctx->wl.lm_best);
+    L->sync = reinterpret_cast<unsigned *>(ctx->ws + ctx->wl.sync);
+    L->rows = ceil_div(lm->vocab, sh->grid);
+    if ((size_t)ceil_div(dm.h, kChunk) * kChunk > (size_t)kLmPerThread * sh->threads)
+        return fail(CFPP_EUNSUPPORTED, "hidden %d needs more than %d values per thread at %d threads", dm.h,
+                    kLmPerThread, sh->threads);
+    const size_t lds = lm_head_lds_bytes(*L, sh->threads);
+    if (lds > 160 * 1024)
+        return fail(CFPP_EUNSUPPORTED, "the LM head needs %zu bytes of LDS with %d workgroups (> 160 KiB)", lds,
+                    sh->grid);
+    return CFPP_OK;
+}
+
+static cfpp_status prepare_lm(cfpp_ctx *ctx)
+{
+    if (ctx->lm_prepared) return CFPP_OK;
+    HIP_OK(prepare_lm_kernels(160 * 1024));
+    ctx->lm_prepared = true;
+    return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_lm_embed(cfpp_ctx *ctx, const cfpp_lm *lm, const int32_t *tokens_dev,
+                                     const int32_t *pos_dev, void *x, cfpp_stream stream)
+{
+    Shape sh;
+    LmParams L;
+    cfpp_status st = make_lm_params(ctx, lm, tokens_dev, pos_dev, &sh, &L);
+    if (st != CFPP_OK) return st;
+    if (!aligned16(x)) return fail(CFPP_EINVAL, "x is NULL or not 16-byte aligned");
+    L.x = static_cast<__half *>(x);
+    HIP_OK(launch_lm_embed(L, static_cast<hipStream_t>(stream)));
+    return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_lm_next(cfpp_ctx *ctx, const cfpp_lm *lm, const void *hidden, int32_t *tokens_dev,
+                                    int32_t *pos_dev, float *logits_dev, cfpp_stream stream)
+{
+    Shape sh;
+    LmParams L;
+    cfpp_status st = make_lm_params(ctx, lm, tokens_dev, pos_dev, &sh, &L);
+    if (st != CFPP_OK) return st;
+    if (!aligned16(hidden)) return fail(CFPP_EINVAL, "hidden is NULL or not 16-byte aligned");
+    if (logits_dev && (reinterpret_cast<uintptr_t>(logits_dev) & 3u)) return fail(CFPP_EINVAL, "logits_dev is misaligned");
+    if ((st = prepare_lm(ctx)) != CFPP_OK) return st;
+    L.hidden = static_cast<const __half *>(hidden);
+    L.logits = logits_dev;
+    HIP_OK(launch_lm_head(L, sh.grid, sh.threads, static_cast<hipStream_t>(stream)));
+    return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_generate_capture(cfpp_ctx *ctx, const void *const *packed_layers,
+                                             void *const *kv_layers, const cfpp_lm *lm, int32_t *tokens_dev,
+                                             int32_t *pos_dev, void *x_buf, void *hidden_buf, cfpp_stream stream)
+{
+    if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!s) return fail(CFPP_EINVAL, "capture needs a non-default stream");
+    Shape sh;
+    LmParams L;
+    cfpp_status st = make_lm_params(ctx, lm, tokens_dev, pos_dev, &sh, &L);
+    if (st != CFPP_OK) return st;
+    if (!aligned16(x_buf) || !aligned16(hidden_buf)) return fail(CFPP_EINVAL, "x_buf or hidden_buf is NULL or not 16-byte aligned");
+    L.x = static_cast<__half *>(x_buf);
+    L.hidden = static_cast<const __half *>(hidden_buf);
+    if ((st = prepare(ctx)) != CFPP_OK) return st;
+    if ((st = prepare_lm(ctx)) != CFPP_OK) return st;
+    if (ctx->exec) { (void)hipGraphExecDestroy(ctx->exec); ctx->exec = nullptr; }
+    if (ctx->graph) { (void)hipGraphDestroy(ctx->graph); ctx->graph = nullptr; }
+    // validate and store the pointer table first (executes now, not captured)
+    st = enqueue_stack(ctx, packed_layers, kv_layers, x_buf, pos_dev, 1, hidden_buf, s, true, false);
+    if (st != CFPP_OK) return st;
+    HIP_OK(hipStreamSynchronize(s));
+    HIP_OK(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+    hipError_t e = launch_lm_embed(L, s);
+    if (e == hipSuccess) {
+        st = enqueue_stack(ctx, packed_layers, kv_layers, x_buf, pos_dev, 1, hidden_buf, s, false, true);
+        if (st == CFPP_OK) e = launch_lm_head(L, sh.grid, sh.threads, s);
+    }
+    hipGraph_t graph = nullptr;
+    const hipError_t e2 = hipStreamEndCapture(s, &graph);
+    if (st != CFPP_OK || e != hipSuccess || e2 != hipSuccess) {
+        if (graph) (void)hipGraphDestroy(graph);
+        if (st != CFPP_OK) return st;
+        return fail(CFPP_EHIP, "capturing the generation step failed: %s", hipGetErrorString(e != hipSuccess ? e : e2));
+    }
+    ctx->graph = graph;
+    e = hipGraphInstantiate(&ctx->exec, graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        ctx->exec = nullptr;
+        return fail(CFPP_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+    }
+    return CFPP_OK;
+}
+
 extern "C" cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream)
 {
     if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
@@ -646,6 +765,7 @@ extern "C" cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream)
     HIP_OK(hipDeviceSynchronize());
     if (err == kErrBadPos) return fail(CFPP_EDEVICE, "a position in pos_dev was outside [0, max_seq)");
     if (err == kErrBarrierTimeout) return fail(CFPP_EDEVICE, "grid barrier timed out (workgroups not co-resident?)");
+    if (err == kErrBadToken) return fail(CFPP_EDEVICE, "a token in tokens_dev was outside [0, vocab)");
     return fail(CFPP_EDEVICE, "device error code %u", err);
 }
 

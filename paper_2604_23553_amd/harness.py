@@ -117,6 +117,38 @@ class DeviceStack:
     def replay(self):
         B.cfpp_stack_replay(self.ctx, self.s)
 
+    # -- generation loop ---------------------------------------------------
+    def load_lm(self, head: dict, embed: np.ndarray):
+        """head: final LayerNorm + LM head (fp16 numpy: lnf_g, lnf_b, w_lm); embed: [vocab, hidden]."""
+        self.vocab = int(head["w_lm"].shape[0])
+        self.lm_t = {n: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
+                     for n, a in (("embed", embed), ("lnf_g", head["lnf_g"]), ("lnf_b", head["lnf_b"]),
+                                  ("w_lm", head["w_lm"]))}
+        self.lm = B.Lm.of(self.lm_t["embed"], self.lm_t["lnf_g"], self.lm_t["lnf_b"], self.lm_t["w_lm"], self.vocab)
+        self.tokens = torch.zeros(self.max_seq + 1, dtype=torch.int32, device=self.dev)
+        self.logits = torch.zeros(self.vocab, dtype=torch.float32, device=self.dev)
+        self.batch = 1
+        torch.cuda.synchronize()
+
+    def set_tokens(self, tokens, pos: int):
+        """tokens[0..pos] are known; generation continues from position pos."""
+        t = np.zeros(self.max_seq + 1, dtype=np.int32)
+        t[: pos + 1] = np.asarray(tokens[: pos + 1], dtype=np.int32)
+        self.tokens.copy_(torch.from_numpy(t))
+        self.pos[:1].copy_(torch.tensor([pos], dtype=torch.int32))
+        torch.cuda.synchronize()
+
+    def generate_step(self, want_logits: bool = False):
+        """One token, call by call (no graph): embed, stack, next token."""
+        B.cfpp_lm_embed(self.ctx, self.lm, self.tokens, self.pos, self.x, self.s)
+        B.cfpp_stack_decode(self.ctx, self.packed, self.kv, self.x, self.pos, 1, self.out, self.s)
+        B.cfpp_lm_next(self.ctx, self.lm, self.out, self.tokens, self.pos,
+                       self.logits if want_logits else None, self.s)
+
+    def generate_capture(self):
+        B.cfpp_generate_capture(self.ctx, self.packed, self.kv, self.lm, self.tokens, self.pos, self.x,
+                                self.out, self.s)
+
     def check(self):
         B.cfpp_device_error(self.ctx, self.s)
 
