@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--shape", choices=["2.8b", "6.9b"], default="2.8b",
                     help="model shape of the stack (the headline metric is quoted on 2.8b, ctx 4096)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--gen-steps", type=int, default=64,
+                    help="tokens of the generation-loop measurement reported beside the headline (0: skip)")
     ap.add_argument("--calibrate", action="store_true",
                     help="instead of the benchmark, run the plain copy kernel (1 GiB read + 1 GiB written per "
                          "launch, 5 launches) used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -112,7 +114,7 @@ def main():
 
     shape = synth.PYTHIA_2_8B if args.shape == "2.8b" else synth.PYTHIA_6_9B
     headline = args.shape == "2.8b" and args.ctx == 4096
-    S, cap = args.ctx, args.ctx + 1
+    S, cap = args.ctx, args.ctx + 1 + (args.gen_steps + 8 if args.gen_steps > 0 else 0)
     seed = synth.MASTER_SEED
     t_gen = time.perf_counter()
     layers = synth.stack_weights(shape, seed, workers=16)
@@ -183,6 +185,31 @@ def main():
         "context": PAPER_CONTEXT,
         "input_generation_s": t_gen,
     }
+    if args.gen_steps > 0:
+        # the same stack inside a true generation loop: embedding row of the current
+        # token -> stack -> final LayerNorm + LM head (50304 rows) + argmax; the position
+        # advances on the device and every replay appends one row to the caches
+        head = synth.lm_head(shape, seed)
+        ds.load_lm(head, synth.embedding(shape, seed))
+        ds.set_tokens([1] * (S + 1), S)
+        ds.generate_capture()
+        for _ in range(8):
+            ds.replay()
+        ds.check()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.gen_steps):
+            ds.replay()
+        ds.stream.synchronize()
+        torch.cuda.synchronize()
+        gen_us = (time.perf_counter() - t0) / args.gen_steps * 1e6
+        ds.check()
+        lm_bytes = 2 * synth.VOCAB * shape.hidden
+        out["generation"] = {"us_per_token": gen_us, "tokens_per_s": 1e6 / gen_us, "steps": args.gen_steps,
+                             "vocab": synth.VOCAB, "first_position": S + 8,
+                             "achieved_hbm_GBps": (alg_bytes + lm_bytes) / (gen_us * 1e-6) / 1e9,
+                             "what": "one graph replay per token: embedding row, the stack step, final LayerNorm, "
+                                     "LM head and argmax; position advanced on the device"}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(shape, layers, kvs, x, S, 4)
     ds.close()

@@ -190,6 +190,17 @@ def test_full_pythia_2_8b_stack_graph_and_argmax(orc):
             assert int(np.argmax(lg_gpu)) == int(np.argmax(lg_ref))
         else:   # a near-tie: either of the two leaders is a correct greedy choice
             assert int(np.argmax(lg_gpu)) in np.argsort(lg_ref)[-2:]
+        # the library's own LM head at the full vocabulary (50304 rows) on that output:
+        # every logit against the oracle's, and its pick against its own logits
+        print("[case] full 2.8B stack: LM head on the GPU", flush=True)
+        import paper_2604_23553_amd as cf
+        ds.load_lm(head, synth.embedding(shape, synth.MASTER_SEED, vocab=64))    # (the table is not used here)
+        ds.set_tokens([0] * (S + 1), S - 1)                 # picks tokens[S]
+        cf.cfpp_lm_next(ds.ctx, ds.lm, ds.out, ds.tokens, ds.pos, ds.logits, ds.s)
+        ds.check()
+        lg_dev = ds.logits.cpu().numpy()
+        assert np.abs(lg_dev.astype(np.float64) - lg_gpu).max() <= 2e-4
+        assert int(ds.tokens[S].item()) == int(np.argmax(lg_dev)) and int(ds.pos[0].item()) == S
     finally:
         ds.close()
 
