@@ -298,3 +298,37 @@ def test_api_misuse_on_the_gpu():
         assert e.value.status == -2
     finally:
         ds.close()
+
+
+@pytest.mark.parametrize("grid,threads", [(8, 512), (33, 512), (100, 256), (128, 512), (256, 256)])
+def test_fused_kernel_across_launch_shapes(orc, grid, threads):
+    """The whole-stack kernel with other workgroup counts and sizes than the
+    default (ragged row shares, 3 instead of 7 streaming wavefronts, attention
+    shares spanning two heads), and the LM head split the same way."""
+    S, cap = 133, 140
+    print(f"[case] fused kernel grid={grid} threads={threads}", flush=True)
+    ds, ws, kvs = build_stack(TINY_STACK, 31, S, cap)
+    try:
+        ds.set_options(mode=2, grid=grid, threads=threads)
+        x = synth.x_input(TINY_STACK, 131)
+        ds.set_inputs(x, S)
+        outs = []
+        for _ in range(2):
+            ds.stack_decode()
+            ds.check()
+            outs.append(ds.result()[0].copy())
+        assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
+        ref16, _, Ks, Vs = oracle_stack(orc, TINY_STACK, ws, kvs, S, x[0])
+        assert_block_close(outs[0], ref16, f"grid {grid} x {threads}")
+        head = synth.lm_head(TINY_STACK, 31, vocab=777)
+        ds.load_lm(head, synth.embedding(TINY_STACK, 31, vocab=777))
+        ds.set_tokens([5] * (S + 1), S)
+        import paper_2604_23553_amd as cf
+        cf.cfpp_lm_next(ds.ctx, ds.lm, ds.out, ds.tokens, ds.pos, ds.logits, ds.s)
+        ds.check()
+        lg = ds.logits.cpu().numpy()
+        want = orc.lm_head_logits(TINY_STACK, head, orc.half_to_real(outs[0]))
+        assert np.abs(lg.astype(np.float64) - want).max() <= 1e-4
+        assert int(ds.tokens[S + 1].item()) == int(np.argmax(lg))
+    finally:
+        ds.close()
