@@ -30,6 +30,14 @@
  *     theta_i = base^(-2i/r), angle = pos * theta_i, applied to q and k.
  *   - Softmax scale 1/sqrt(head_dim); no mask (every cached t <= pos).
  *   - GELU is the exact erf form.
+ * The other readings of two of these points are available behind flags of
+ * orc_block_decode_flags (they change nothing unless set):
+ *   - ORC_TANH_GELU: the tanh approximation of GELU (the paper only says
+ *     "accelerated GELU", Sec. 2.2, without naming the flavour);
+ *   - ORC_SEQUENTIAL_RESIDUAL: the chain read literally in the order Sec. 2.2
+ *     lists it - output projection with residual, then the post-attention
+ *     LayerNorm on that sum, then the MLP with residual:
+ *         x1 = x + Dense(Attn(LN1(x)));  out = x1 + Down(GELU(Up(LN2(x1))))
  *   - Cached K rows are already rotated.
  *
  * Loops over output rows / heads carry an OpenMP pragma; that only spreads
@@ -211,6 +219,18 @@ void orc_gelu_n(const real *z, real *out, int64_t n)
     for (int64_t i = 0; i < n; ++i) out[i] = orc_gelu(z[i]);
 }
 
+/* tanh form: z/2 * (1 + tanh(sqrt(2/pi) * (z + 0.044715 z^3))) */
+real orc_gelu_tanh(real z)
+{
+    const double t = (double)z;
+    return (real)(0.5 * t * (1.0 + tanh(0.79788456080286535588 * (t + 0.044715 * t * t * t))));
+}
+
+void orc_gelu_tanh_n(const real *z, real *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = orc_gelu_tanh(z[i]);
+}
+
 /* ---- the block -------------------------------------------------------- */
 
 /*
@@ -220,9 +240,11 @@ void orc_gelu_n(const real *z, real *out, int64_t n)
  *   x    : [hidden] block input;  out: [hidden] block output, NOT rounded.
  * Returns 0, or -1 on a bad argument.
  */
-int orc_block_decode(const orc_shape *sh, const orc_layer *w,
-                     uint16_t *K, uint16_t *V, int capacity, int pos,
-                     const real *x, real *out, const orc_taps *taps)
+enum { ORC_TANH_GELU = 1, ORC_SEQUENTIAL_RESIDUAL = 2 };
+
+int orc_block_decode_flags(const orc_shape *sh, const orc_layer *w,
+                           uint16_t *K, uint16_t *V, int capacity, int pos,
+                           const real *x, real *out, const orc_taps *taps, int flags)
 {
     const int h = sh->hidden, H = sh->n_heads, d = sh->head_dim;
     const int r = sh->rotary_dims, f = sh->ffn;
@@ -234,9 +256,9 @@ int orc_block_decode(const orc_shape *sh, const orc_layer *w,
     real *m = malloc(sizeof(real) * f), *g = malloc(sizeof(real) * h);
     real *qrot = malloc(sizeof(real) * h);
 
-    /* 1. both LayerNorms read the block input */
+    /* 1. both LayerNorms read the block input (sequential form: the second one later) */
     orc_layernorm(x, w->ln1_g, w->ln1_b, h, sh->ln_eps, y1);
-    orc_layernorm(x, w->ln2_g, w->ln2_b, h, sh->ln_eps, y2);
+    if (!(flags & ORC_SEQUENTIAL_RESIDUAL)) orc_layernorm(x, w->ln2_g, w->ln2_b, h, sh->ln_eps, y2);
 
     /* 2. fused QKV projection, rows (head, {q,k,v}, dim) */
     orc_gemv(w->w_qkv, w->b_qkv, y1, 3 * h, h, qkv);
@@ -262,13 +284,28 @@ int orc_block_decode(const orc_shape *sh, const orc_layer *w,
     /* 6. output projection */
     orc_gemv(w->w_dense, w->b_dense, attn, h, h, a);
 
+    /* sequential form: the attention branch joins the residual first, and the
+       post-attention LayerNorm reads that sum */
+    real *x1 = NULL;
+    if (flags & ORC_SEQUENTIAL_RESIDUAL) {
+        x1 = malloc(sizeof(real) * h);
+        for (int i = 0; i < h; ++i) x1[i] = x[i] + a[i];
+        orc_layernorm(x1, w->ln2_g, w->ln2_b, h, sh->ln_eps, y2);
+    }
+
     /* 7-8. MLP */
     orc_gemv(w->w_up, w->b_up, y2, f, h, up);
-    orc_gelu_n(up, m, f);
+    if (flags & ORC_TANH_GELU) orc_gelu_tanh_n(up, m, f);
+    else orc_gelu_n(up, m, f);
     orc_gemv(w->w_down, w->b_down, m, h, f, g);
 
     /* 9. residual */
-    for (int i = 0; i < h; ++i) out[i] = x[i] + a[i] + g[i];
+    if (x1) {
+        for (int i = 0; i < h; ++i) out[i] = x1[i] + g[i];
+        free(x1);
+    } else {
+        for (int i = 0; i < h; ++i) out[i] = x[i] + a[i] + g[i];
+    }
 
     if (taps) {
         if (taps->y1) memcpy(taps->y1, y1, sizeof(real) * h);
@@ -281,6 +318,13 @@ int orc_block_decode(const orc_shape *sh, const orc_layer *w,
     }
     free(y1); free(y2); free(qkv); free(attn); free(a); free(up); free(m); free(g); free(qrot);
     return 0;
+}
+
+int orc_block_decode(const orc_shape *sh, const orc_layer *w,
+                     uint16_t *K, uint16_t *V, int capacity, int pos,
+                     const real *x, real *out, const orc_taps *taps)
+{
+    return orc_block_decode_flags(sh, w, K, V, capacity, pos, x, out, taps, 0);
 }
 
 /* final LayerNorm + bias-free LM head: logits = W_lm LN(x) */

@@ -59,6 +59,7 @@ class Oracle:
         L.orc_gelu.restype = self._creal
         L.orc_gelu.argtypes = [self._creal]
         L.orc_block_decode.restype = C.c_int
+        L.orc_block_decode_flags.restype = C.c_int
 
     # -- helpers ---------------------------------------------------------
     def _r(self, a):
@@ -125,8 +126,14 @@ class Oracle:
         return out
 
     # -- the block -------------------------------------------------------
+    def gelu_tanh(self, z):
+        z = self._r(z)
+        out = np.empty_like(z)
+        self.lib.orc_gelu_tanh_n(self._rp(z), self._rp(out), C.c_int64(z.size))
+        return out
+
     def block_decode(self, shape, w: dict, K: np.ndarray, V: np.ndarray, pos: int, x,
-                     taps: bool = False):
+                     taps: bool = False, flags: int | None = None):
         """One sequence.  K, V: fp16 [n_heads, capacity, head_dim], updated in
         place at row `pos`.  x: [hidden] (any float dtype; used as given).
         Returns the unrounded block output (and a dict of intermediates)."""
@@ -144,8 +151,11 @@ class Oracle:
             sizes["m"] = shape.ffn
             tap_arrays = {n: np.empty(sizes[n], dtype=self.real) for n in _TAP_FIELDS}
             tp = C.byref(_Taps(*[self._rp(tap_arrays[n]) for n in _TAP_FIELDS]))
-        rc = self.lib.orc_block_decode(C.byref(sh), C.byref(lay), _u16(K), _u16(V),
-                                       C.c_int(cap), C.c_int(pos), self._rp(x), self._rp(out), tp)
+        if flags is None:
+            flags = int(getattr(shape, "flags", 0))      # 1: tanh GELU, 2: sequential residual
+        rc = self.lib.orc_block_decode_flags(C.byref(sh), C.byref(lay), _u16(K), _u16(V),
+                                             C.c_int(cap), C.c_int(pos), self._rp(x), self._rp(out), tp,
+                                             C.c_int(flags))
         if rc != 0:
             raise ValueError("orc_block_decode: bad argument")
         return (out, tap_arrays) if taps else out

@@ -35,6 +35,10 @@ LAYER_TENSORS = ("ln1_g", "ln1_b", "ln2_g", "ln2_b", "w_qkv", "b_qkv",
                  "w_dense", "b_dense", "w_up", "b_up", "w_down", "b_down")
 
 
+FLAG_TANH_GELU = 1               # GELU by its tanh approximation instead of erf
+FLAG_SEQUENTIAL_RESIDUAL = 2     # x1 = x + attention; out = x1 + MLP(LN2(x1)) instead of the parallel form
+
+
 @dataclass(frozen=True)
 class ModelShape:
     """Shape of one GPT-NeoX decoder block (names follow the model family)."""
@@ -47,6 +51,7 @@ class ModelShape:
     rope_base: float = 10000.0
     ln_eps: float = 1e-5
     name: str = ""
+    flags: int = 0          # FLAG_* bits: which reading of the block is meant (0 = GPT-NeoX / Pythia)
 
     def __post_init__(self):
         assert self.hidden == self.n_heads * self.head_dim

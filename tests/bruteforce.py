@@ -52,7 +52,16 @@ def block(shape, w, K, V, pos, x, round_half):
         den = math.fsum(e)
         attn += [math.fsum(e[t] / den * vals[t][i] for t in range(len(vals))) for i in range(d)]
     a = matvec(w["w_dense"], w["b_dense"], attn)
+    flags = getattr(shape, "flags", 0)
+    if flags & 2:       # sequential reading: the post-attention LayerNorm sees x + attention
+        x1 = [x[i] + a[i] for i in range(h)]
+        y2 = layernorm(x1, w["ln2_g"], w["ln2_b"], shape.ln_eps)
     up = matvec(w["w_up"], w["b_up"], y2)
-    m = [0.5 * z * (1.0 + math.erf(z / math.sqrt(2.0))) for z in up]
+    if flags & 1:       # tanh form of GELU
+        m = [0.5 * z * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * (z + 0.044715 * z ** 3))) for z in up]
+    else:
+        m = [0.5 * z * (1.0 + math.erf(z / math.sqrt(2.0))) for z in up]
     g = matvec(w["w_down"], w["b_down"], m)
+    if flags & 2:
+        return [x1[i] + g[i] for i in range(h)], k_new, v_new
     return [x[i] + a[i] + g[i] for i in range(h)], k_new, v_new
