@@ -63,8 +63,20 @@ typedef struct cfpp_config {
     int32_t max_batch;    /* sequences the KV cache and workspace are sized for */
     float   rope_base;    /* 10000 for Pythia                                */
     float   ln_eps;       /* 1e-5 for Pythia                                 */
-    int32_t flags;        /* reserved, must be 0                             */
+    int32_t flags;        /* CFPP_FLAG_* bits; 0 = the GPT-NeoX / Pythia block */
 } cfpp_config;
+
+/* The other readings of two points the paper leaves open (Sec. 2.2 says
+ * "accelerated GELU" without naming the flavour, and lists the chain as output
+ * projection with residual -> post-attention LayerNorm -> MLP with residual):
+ *   CFPP_FLAG_TANH_GELU            gelu(z) = z/2 (1 + tanh(sqrt(2/pi)(z + 0.044715 z^3)))
+ *                                  instead of the exact erf form (all launch modes)
+ *   CFPP_FLAG_SEQUENTIAL_RESIDUAL  x1 = x + Dense(Attn(LN1(x))); out = x1 + Down(GELU(Up(LN2(x1))))
+ *                                  instead of the parallel form (launch mode 0 only: the
+ *                                  other modes overlap the two branches, which this form
+ *                                  forbids; they return CFPP_EUNSUPPORTED)             */
+#define CFPP_FLAG_TANH_GELU 1
+#define CFPP_FLAG_SEQUENTIAL_RESIDUAL 2
 
 /* The 12 canonical fp16 tensors of one GPT-NeoX block, DEVICE pointers,
  * row-major.  w_qkv rows are interleaved per head (paper Sec. 2.2): row

@@ -34,7 +34,7 @@ class Config(C.Structure):
     def from_shape(cls, shape, max_seq: int, max_batch: int = 1, n_layers: int | None = None):
         return cls(shape.hidden, shape.n_heads, shape.head_dim, shape.rotary_dims, shape.ffn,
                    shape.n_layers if n_layers is None else n_layers, max_seq, max_batch,
-                   float(shape.rope_base), float(shape.ln_eps), 0)
+                   float(shape.rope_base), float(shape.ln_eps), int(getattr(shape, "flags", 0)))
 
 
 class _LayerSrc(C.Structure):

@@ -65,7 +65,8 @@ extern "C" cfpp_status cfpp_validate_config(const cfpp_config *c)
                     c->head_dim);
     if ((c->rotary_dims & 1) || c->rotary_dims > c->head_dim)
         return fail(CFPP_EINVAL, "rotary_dims (%d) must be even and <= head_dim", c->rotary_dims);
-    if (c->flags != 0) return fail(CFPP_EINVAL, "flags must be 0");
+    if (c->flags & ~(CFPP_FLAG_TANH_GELU | CFPP_FLAG_SEQUENTIAL_RESIDUAL))
+        return fail(CFPP_EINVAL, "unknown bits in flags (0x%x)", c->flags);
     if (!(c->ln_eps >= 0.f) || !(c->rope_base > 0.f))
         return fail(CFPP_EINVAL, "ln_eps must be >= 0 and rope_base > 0");
     if (c->head_dim != 64 && c->head_dim != 80 && c->head_dim != 128)
@@ -85,6 +86,7 @@ static Dims dims_of(const cfpp_config &c)
     Dims m;
     m.h = c.hidden; m.H = c.n_heads; m.d = c.head_dim; m.r = c.rotary_dims; m.f = c.ffn;
     m.max_seq = c.max_seq; m.max_batch = c.max_batch; m.ln_eps = c.ln_eps;
+    m.flags = c.flags;
     return m;
 }
 
@@ -401,12 +403,37 @@ static StepParams make_params(const cfpp_ctx *ctx, const Shape &sh, int b, const
     P.x_in = static_cast<const __half *>(x) + (size_t)b * dm.h;
     P.out = static_cast<__half *>(out) + (size_t)b * dm.h;
     P.n_layers = n_layers;
+    P.parts = kPartAll;
     P.rows_qkv = sh.rows_qkv; P.rows_up = sh.rows_up; P.rows_h = sh.rows_h;
     P.nsl_down = sh.nsl_down; P.nsl_dense = sh.nsl_dense;
     P.lds_floats = sh.lds_floats;
     P.debug = ctx->debug;
     P.trace = reinterpret_cast<unsigned long long *>(ctx->ws + wl.trace);
     return P;
+}
+
+// One block with the phase kernels.  Parallel residual: one pass.  Sequential
+// residual: two passes over the same kernels - the attention half (LayerNorm,
+// QKV, attention, output projection, x1 = x + a) and the MLP half (LayerNorm of
+// x1, up, down, out = x1 + g) - as two consecutive slots of the fp32 residual
+// ping-pong; P.n_layers counts slots.
+static hipError_t launch_block_phases(const StepParams &P, const __half *w, __half *kv, int l, int grid,
+                                      int threads, hipStream_t s)
+{
+    if (!(P.dm.flags & kFlagSequentialResidual)) return launch_phases(P, w, kv, l, grid, threads, s);
+    StepParams Q = P;
+    Q.parts = kPartQkv | kPartAttention | kPartDense;
+    hipError_t e = launch_phases(Q, w, kv, 2 * l, grid, threads, s);
+    if (e != hipSuccess) return e;
+    Q.parts = kPartUp | kPartDown;
+    return launch_phases(Q, w, kv, 2 * l + 1, grid, threads, s);
+}
+
+static cfpp_status check_form(const cfpp_ctx *ctx)
+{
+    if ((ctx->dm.flags & kFlagSequentialResidual) && ctx->mode != 0)
+        return fail(CFPP_EUNSUPPORTED, "the sequential residual form runs in launch mode 0 only");
+    return CFPP_OK;
 }
 
 static cfpp_status check_persistent(const cfpp_ctx *ctx, const Shape &sh)
@@ -494,8 +521,10 @@ extern "C" cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer
         return fail(CFPP_EINVAL, "packed_layer or kv_layer is NULL or not 16-byte aligned");
     Shape sh;
     if ((st = launch_shape(ctx, &sh)) != CFPP_OK) return st;
+    if ((st = check_form(ctx)) != CFPP_OK) return st;
     if ((st = prepare(ctx)) != CFPP_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const int slots = (ctx->dm.flags & kFlagSequentialResidual) ? 2 : 1;   // residual slots per block
     if (ctx->mode == 3) {
         if ((st = stream_check(ctx, &sh)) != CFPP_OK) return st;
         if ((st = stream_residency(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, 1))) != CFPP_OK) return st;
@@ -516,10 +545,10 @@ extern "C" cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer
     }
     if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
     for (int b = 0; b < batch; ++b) {
-        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, 1);
+        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, ctx->mode == 0 ? slots : 1);
         if (ctx->mode == 0)
-            HIP_OK(launch_phases(P, static_cast<const __half *>(packed_layer), static_cast<__half *>(kv_layer),
-                                 0, sh.grid, sh.threads, s));
+            HIP_OK(launch_block_phases(P, static_cast<const __half *>(packed_layer), static_cast<__half *>(kv_layer),
+                                       0, sh.grid, sh.threads, s));
         else
             HIP_OK(launch_block_persistent(P, static_cast<const __half *>(packed_layer),
                                            static_cast<__half *>(kv_layer), 0, sh.grid, sh.threads, s));
@@ -544,6 +573,7 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
             return fail(CFPP_EINVAL, "layer %d: NULL or misaligned pointer", l);
     Shape sh;
     if ((st = launch_shape(ctx, &sh)) != CFPP_OK) return st;
+    if ((st = check_form(ctx)) != CFPP_OK) return st;
     if (ctx->mode == 3) {
         if ((st = stream_check(ctx, &sh)) != CFPP_OK) return st;
         if ((st = stream_residency(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, L))) != CFPP_OK) return st;
@@ -561,8 +591,9 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
     LayerPtrs *dev_ptrs = reinterpret_cast<LayerPtrs *>(ctx->ws + ctx->wl.layer_ptrs);
     if (store_table && ctx->mode >= 2) HIP_OK(launch_store_layer_ptrs(ptrs, dev_ptrs, L, s));
     if (!launch) return CFPP_OK;
+    const int slots = (ctx->dm.flags & kFlagSequentialResidual) ? 2 : 1;   // (mode 0 only, checked above)
     for (int b = 0; b < batch; ++b) {
-        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, L);
+        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, L * slots);
         if (ctx->mode == 3) {
             HIP_OK(launch_stack_stream(P, dev_ptrs, reinterpret_cast<unsigned long long *>(ctx->ws + ctx->wl.events),
                                        reinterpret_cast<float *>(ctx->ws + ctx->wl.tagged), sh.grid, sh.threads, s));
@@ -571,7 +602,7 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
         } else {
             for (int l = 0; l < L; ++l) {
                 if (ctx->mode == 0)
-                    HIP_OK(launch_phases(P, ptrs.w[l], ptrs.kv[l], l, sh.grid, sh.threads, s));
+                    HIP_OK(launch_block_phases(P, ptrs.w[l], ptrs.kv[l], l, sh.grid, sh.threads, s));
                 else
                     HIP_OK(launch_block_persistent(P, ptrs.w[l], ptrs.kv[l], l, sh.grid, sh.threads, s));
             }

@@ -42,8 +42,8 @@ __device__ __forceinline__ void phase_a(const StepParams &P, const __half *__res
     const LayerIO io = layer_io(P, layer);
 
     // weights first: they depend on nothing, so their loads overlap the wait for x
-    const int q_begin = g * P.rows_qkv, q_n = max(0, min(P.rows_qkv, 3 * h - q_begin));
-    const int u_begin = g * P.rows_up, u_n = max(0, min(P.rows_up, f - u_begin));
+    const int q_begin = g * P.rows_qkv, q_n = (P.parts & kPartQkv) ? max(0, min(P.rows_qkv, 3 * h - q_begin)) : 0;
+    const int u_begin = g * P.rows_up, u_n = (P.parts & kPartUp) ? max(0, min(P.rows_up, f - u_begin)) : 0;
     GemvSpan<kGemvU> gs;
     gs.init(GemvSeg{w + P.lay.w_qkv + (size_t)q_begin * h, y1, h, q_n},
             GemvSeg{w + P.lay.w_up + (size_t)u_begin * h, y2, h, u_n}, w, tid);
@@ -121,7 +121,7 @@ __device__ __forceinline__ void phase_a(const StepParams &P, const __half *__res
     } else {
         for (int t = item0; t < u_n; t += estride) {
             const float b = t == item0 ? bu0 : __half2float(bu[u_begin + t]);
-            xwg_store(P.m + u_begin + t, gelu_erf(gs.row_total(part, q_n + t) + b));
+            xwg_store(P.m + u_begin + t, gelu_act(gs.row_total(part, q_n + t) + b, dm.flags));
         }
     }
     tr.mark(6);
@@ -154,7 +154,7 @@ __device__ __forceinline__ void attn_share(const StepParams &P, const __half *__
     AC ac;
     ac.init(P, kv, n_tok, lane);
 
-    if (ac.r0 >= ac.r1) {                                  // no rows for this workgroup
+    if (ac.r0 >= ac.r1 || !(P.parts & kPartAttention)) {   // no rows for this workgroup, or no attention in this launch
         pre();
         early();
         mid();
@@ -244,7 +244,7 @@ __device__ __forceinline__ void phase_b(const StepParams &P, const __half *__res
     const int Kp = round_up_chunk(f);
     float *ml = lds, *part = lds + Kp;
     float *scr = part + P.rows_h * (nt >> 6);
-    const int r_begin = g * P.rows_h, r_n = max(0, min(P.rows_h, h - r_begin));
+    const int r_begin = g * P.rows_h, r_n = (P.parts & kPartDown) ? max(0, min(P.rows_h, h - r_begin)) : 0;
     GemvSpan<kGemvUDown> gs;
     gs.init(GemvSeg{w + P.lay.w_down + (size_t)r_begin * f, ml, f, r_n}, GemvSeg{w + P.lay.w_down, ml, f, 0}, w, tid, kShare0AfterAttention);
     // the first down-projection weights are requested behind the last K/V loads,
@@ -295,8 +295,9 @@ __device__ __forceinline__ void phase_c(const StepParams &P, const __half *__res
     float *ol = lds, *part = lds + Kp;
     const LayerIO io = layer_io(P, layer);
     const int r_begin = g * P.rows_h, r_n = max(0, min(P.rows_h, h - r_begin));
+    const bool dense = P.parts & kPartDense, down = P.parts & kPartDown;   // branches this launch adds to the residual
     GemvSpan<kGemvU> gs;
-    gs.init(GemvSeg{w + P.lay.w_dense + (size_t)r_begin * h, ol, h, r_n}, GemvSeg{w + P.lay.w_dense, ol, h, 0}, w, tid);
+    gs.init(GemvSeg{w + P.lay.w_dense + (size_t)r_begin * h, ol, h, dense ? r_n : 0}, GemvSeg{w + P.lay.w_dense, ol, h, 0}, w, tid);
     Tracer tr;
     tr.init(P, gs.wave, 48);
     tr.mark(20);
@@ -315,7 +316,7 @@ __device__ __forceinline__ void phase_c(const StepParams &P, const __half *__res
     if (item0 < r_n) {
         bd0 = __half2float(bd[r_begin + item0]);
         x0 = load_x(io, r_begin + item0);
-        g0 = xwg_load(P.g + r_begin + item0);
+        g0 = down ? xwg_load(P.g + r_begin + item0) : 0.f;
     }
     so.commit(h, ol, tid);
     __syncthreads();
@@ -325,8 +326,8 @@ __device__ __forceinline__ void phase_c(const StepParams &P, const __half *__res
     __syncthreads();
     for (int t = item0; t < r_n; t += nt) {
         const bool pre = t == item0;
-        const float a = gs.row_total(part, t) + (pre ? bd0 : __half2float(bd[r_begin + t]));
-        const float res = ((pre ? x0 : load_x(io, r_begin + t)) + a) + (pre ? g0 : xwg_load(P.g + r_begin + t));
+        const float a = dense ? gs.row_total(part, t) + (pre ? bd0 : __half2float(bd[r_begin + t])) : 0.f;
+        const float res = ((pre ? x0 : load_x(io, r_begin + t)) + a) + (pre ? g0 : (down ? xwg_load(P.g + r_begin + t) : 0.f));
         if (io.o16) io.o16[r_begin + t] = __float2half_rn(res);
         else xwg_store(io.o32 + r_begin + t, res);
     }

@@ -23,6 +23,7 @@ struct StepParams {
     const __half *x_in;  // fp16 [h] input of layer 0
     __half *out;         // fp16 [h] output of the last layer
     int n_layers;
+    int parts;           // kPart* bits: what a phase launch performs (kPartAll unless the block runs in two halves)
     // work split (chosen on the host from the grid and the workgroup size)
     int rows_qkv, rows_up, rows_h;   // matrix rows per workgroup (rows_qkv even)
     int nsl_down, nsl_dense;         // K-slices per row for the two GEMVs with few rows

@@ -121,10 +121,21 @@ __device__ __forceinline__ int lds_perm(int k)
     return (c << 9) + ((e >> 2) << 8) + (l << 2) + (e & 3);
 }
 
+// tanh form of GELU
+__device__ __forceinline__ float gelu_tanh(float z)
+{
+    return 0.5f * z * (1.0f + tanhf(0.79788456080286535588f * (z + 0.044715f * z * z * z)));
+}
+
 // exact (erf) GELU
 __device__ __forceinline__ float gelu_erf(float z)
 {
     return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
+}
+// the activation the configuration asks for (flags: Dims::flags)
+__device__ __forceinline__ float gelu_act(float z, int flags)
+{
+    return (flags & 1) ? gelu_tanh(z) : gelu_erf(z);
 }
 
 // ---- data exchanged between workgroups --------------------------------------

@@ -401,7 +401,7 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
         tr.mark(10);
         for (int t = lane; t < u_n; t += 64) {
             const float b = t == lane ? bu0 : __half2float(bu[u_begin + t]);
-            xwg_store(P.m + u_begin + t, gelu_erf(rt.row_total(pu, t) + b));
+            xwg_store(P.m + u_begin + t, gelu_act(rt.row_total(pu, t) + b, dm.flags));
         }
         b2.arrive_wave();
         b2.wait_wave();                                    // GELU(up) is complete everywhere

@@ -23,7 +23,12 @@ struct Dims {
     int h, H, d, r, f;
     int max_seq, max_batch;
     float ln_eps;
+    int flags;       // kFlagTanhGelu, kFlagSequentialResidual
 };
+
+enum { kFlagTanhGelu = 1, kFlagSequentialResidual = 2 };
+// parts of a block a phase launch performs (the sequential residual form runs a block in two halves)
+enum { kPartQkv = 1, kPartUp = 2, kPartAttention = 4, kPartDown = 8, kPartDense = 16, kPartAll = 31 };
 
 // Offsets (in fp16 elements) of every section of a packed layer.  Each section
 // starts on a 256-byte boundary.  Matrices are row-major [rows][cols]; w_qkv and

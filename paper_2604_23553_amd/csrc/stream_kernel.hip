@@ -848,7 +848,7 @@ __device__ __forceinline__ void service_main(const StepParams &P, const LayerPtr
                 const bool act = t < W.u_n;
                 const float bias = act ? __half2float(bu[W.u_begin + t]) : 0.f;
                 if (base == 0 && !lds_wait_ge(ctrl, cCnt3, (layer + 1) * W.n3, err)) return;
-                if (act) xwg_store(P.m + W.u_begin + t, gelu_erf(res3[t] + bias));
+                if (act) xwg_store(P.m + W.u_begin + t, gelu_act(res3[t] + bias, P.dm.flags));
             }
             tr.mark(40);
             ev.arrive();

@@ -332,3 +332,56 @@ def test_fused_kernel_across_launch_shapes(orc, grid, threads):
         assert int(ds.tokens[S + 1].item()) == int(np.argmax(lg))
     finally:
         ds.close()
+
+
+@pytest.mark.parametrize("flags,mode", [(1, 0), (1, 1), (1, 2), (1, 3), (2, 0), (3, 0)])
+def test_other_readings_of_the_block(orc, flags, mode):
+    """tanh GELU (every launch mode) and the sequential residual form (launch
+    mode 0, two passes per block) against the oracle's variants."""
+    import dataclasses
+    shape = dataclasses.replace(TINY_STACK, flags=flags)
+    S, cap = 90, 96
+    print(f"[case] block variants flags={flags} mode={mode}", flush=True)
+    ds, ws, kvs = build_stack(shape, 41, S, cap)
+    try:
+        ds.set_options(mode=mode)
+        x = synth.x_input(shape, 141)
+        ds.set_inputs(x, S)
+        outs = []
+        for _ in range(2):
+            ds.stack_decode()
+            ds.check()
+            outs.append(ds.result()[0].copy())
+        assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
+        ref16, _, Ks, Vs = oracle_stack(orc, shape, ws, kvs, S, x[0])
+        assert_block_close(outs[0], ref16, f"flags {flags} mode {mode}")
+        # the variant is really in effect: the default reading gives another result
+        ref_default, _, _, _ = oracle_stack(orc, TINY_STACK, ws, kvs, S, x[0])
+        assert np.abs(ref16.astype(np.float64) - ref_default.astype(np.float64)).max() > 1e-3
+        for l in range(shape.n_layers):
+            kg, vg = ds.export_kv(l, 0, S, 1)
+            assert_fp16_rows_match(kg[:, 0], Ks[l][:, S], f"layer {l} appended K")
+            assert_fp16_rows_match(vg[:, 0], Vs[l][:, S], f"layer {l} appended V")
+        # one block on its own
+        ds.set_inputs(x, S)
+        ds.block_decode(0)
+        ds.check()
+        Ko, Vo = kvs[0][0][0].copy(), kvs[0][1][0].copy()
+        assert_block_close(ds.result()[0], orc.block_decode_f16(shape, ws[0], Ko, Vo, S, x[0]), "single block")
+    finally:
+        ds.close()
+
+
+def test_sequential_form_is_refused_by_the_overlapping_modes():
+    import dataclasses
+    from paper_2604_23553_amd import CfppError
+    shape = dataclasses.replace(TINY_STACK, flags=synth.FLAG_SEQUENTIAL_RESIDUAL)
+    ds, ws, kvs = build_stack(shape, 42, 10, 12)
+    try:
+        ds.set_inputs(synth.x_input(shape, 1), 10)
+        for mode in (1, 2, 3):
+            ds.set_options(mode=mode)
+            with pytest.raises(CfppError):
+                ds.stack_decode()
+    finally:
+        ds.close()
