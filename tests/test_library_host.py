@@ -72,7 +72,7 @@ def test_batch_bytes_count_each_sequence():
     (dict(hidden=513), -1),                      # hidden != heads * head_dim
     (dict(rotary_dims=17), -1),                  # odd rotary width
     (dict(rotary_dims=66), -1),                  # wider than the head
-    (dict(flags=1), -1),
+    (dict(flags=4), -1),                         # unknown flag bit
     (dict(max_seq=0), -1),
     (dict(n_heads=4, head_dim=96, hidden=384), -2),   # head_dim without a kernel
     (dict(ffn=2052), -2),                        # not a multiple of 8
