@@ -139,3 +139,45 @@ def test_bad_token_and_end_of_cache_raise_the_flag(orc):
         assert int(ds.pos[0].item()) == cap
     finally:
         ds.close()
+
+
+@pytest.mark.parametrize("vocab", [1, 7, 100, 4096])
+def test_lm_head_with_fewer_rows_than_workgroups_and_ties(orc, vocab):
+    """Vocabularies smaller than the grid (workgroups without rows), a single
+    row, and duplicated rows (equal logits: the lowest index wins)."""
+    import paper_2604_23553_amd as cf
+    from paper_2604_23553_amd.harness import DeviceStack
+    print(f"[case] LM head vocab={vocab}", flush=True)
+    head = synth.lm_head(SHAPE, 9, vocab=vocab)
+    if vocab >= 7:
+        head["w_lm"][vocab - 1] = head["w_lm"][2]          # two equal logits
+        head["w_lm"][5] = head["w_lm"][2]
+    hidden = synth.x_input(SHAPE, 9)
+    ds = DeviceStack(SHAPE, 8, 1, 1)
+    try:
+        ds.load_lm(head, synth.embedding(SHAPE, 9, vocab=vocab))
+        ds.set_tokens([0, 0], 1)
+        import torch
+        ds.out[:1].copy_(torch.from_numpy(hidden))
+        cf.cfpp_lm_next(ds.ctx, ds.lm, ds.out, ds.tokens, ds.pos, ds.logits, ds.s)
+        ds.check()
+        lg = ds.logits.cpu().numpy()
+        want = orc.lm_head_logits(SHAPE, head, orc.half_to_real(hidden[0]))
+        assert np.abs(lg.astype(np.float64) - want).max() <= 1e-4
+        if vocab >= 7:
+            assert lg[2] == lg[5] == lg[vocab - 1]
+        assert int(ds.tokens[2].item()) == int(np.argmax(lg))      # numpy: first of equal maxima
+        if vocab >= 7:
+            # make the tied rows the winners: the pick must be row 2
+            z = orc.layernorm(orc.half_to_real(hidden[0]), head["lnf_g"], head["lnf_b"], SHAPE.ln_eps)
+            row = (z / np.abs(z).max()).astype(np.float16)          # aligned with the normalised vector: largest logit
+            head["w_lm"][[2, 5, vocab - 1]] = row * np.float16(4.0)
+            ds.load_lm(head, synth.embedding(SHAPE, 9, vocab=vocab))
+            ds.set_tokens([0, 0], 1)
+            cf.cfpp_lm_next(ds.ctx, ds.lm, ds.out, ds.tokens, ds.pos, ds.logits, ds.s)
+            ds.check()
+            lg = ds.logits.cpu().numpy()
+            assert lg[2] == lg.max() and lg[5] == lg[2] == lg[vocab - 1]
+            assert int(ds.tokens[2].item()) == 2
+    finally:
+        ds.close()
