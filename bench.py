@@ -70,6 +70,70 @@ def cpu_baseline(shape, layers, kvs, x, S, n_layers_sample):
             "seconds_measured": dt}
 
 
+def bench_block(args):
+    """The single-block workloads of the measurement table (not the headline):
+    one block at batch 1, warm (one copy replayed) and cold (enough copies in
+    rotation that their weights and caches exceed the 256 MB Infinity Cache), or
+    one block at batch 8 with ragged lengths.  Prints one JSON line."""
+    import numpy as np
+    import torch
+    import synth
+    import paper_2604_23553_amd as cf
+    from paper_2604_23553_amd.harness import DeviceStack
+
+    shape = {"small": synth.SMALL_BLOCK, "2.8b": synth.PYTHIA_2_8B, "6.9b": synth.PYTHIA_6_9B}[args.shape]
+    seed = synth.MASTER_SEED
+    batch = args.batch
+    if batch > 1:
+        lens = synth.seq_lens(seed, batch, 1024, 8192)
+        cap = int(lens.max()) + 1
+    else:
+        lens = np.array([args.ctx], dtype=np.int32)
+        cap = args.ctx + 1
+    w = synth.layer_weights(shape, seed, 0)
+    kv = synth.kv_cache(shape, seed, 0, lens, cap, batch, poison=False)
+    x = synth.x_input(shape, seed, batch)
+    copies = []
+    for _ in range(args.copies):
+        ds = DeviceStack(shape, cap, batch, 1)
+        ds.load_layer(0, w)
+        ds.load_kv(0, kv[0], kv[1], lens)
+        ds.set_inputs(x, lens)
+        ds.set_options(mode=args.mode, grid=args.grid, threads=args.threads)
+        ds.capture()
+        copies.append(ds)
+    alg_bytes = cf.cfpp_algorithmic_bytes(copies[0].cfg, [int(v) for v in lens], 1)
+    footprint = args.copies * (cf.cfpp_packed_layer_bytes(copies[0].cfg) + cf.cfpp_kv_layer_bytes(copies[0].cfg))
+    # every replay on ONE stream: the persistent kernels need the whole GPU to themselves
+    one = copies[0].s
+    for i in range(args.warmup):
+        cf.cfpp_stack_replay(copies[i % args.copies].ctx, one)
+    torch.cuda.synchronize()
+    for ds in copies:
+        ds.check()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        cf.cfpp_stack_replay(copies[i % args.copies].ctx, one)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / args.steps * 1e6
+    for ds in copies:
+        ds.check()
+        ds.close()
+    achieved = alg_bytes / (us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": f"us_per_block_decode_{args.shape}_bs{batch}", "value": us, "unit": "us/block", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "data": "synthetic",
+        "dtype": "f16 weights/KV, f32 accumulate",
+        "config": {"workload": f"one {shape.name} block, batch {batch}, cached positions {[int(v) for v in lens]}, "
+                               f"{args.copies} cop{'y' if args.copies == 1 else 'ies'} replayed in rotation "
+                               f"({footprint / 1e6:.0f} MB of weights and caches)",
+                   "launch_mode": args.mode, "copies": args.copies},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": alg_bytes},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -80,7 +144,11 @@ def main():
     ap.add_argument("--grid", type=int, default=int(os.environ.get("CFPP_GRID", "0")))
     ap.add_argument("--threads", type=int, default=int(os.environ.get("CFPP_THREADS", "512")))
     ap.add_argument("--ctx", type=int, default=4096, help="cached positions per layer")
-    ap.add_argument("--shape", choices=["2.8b", "6.9b"], default="2.8b",
+    ap.add_argument("--workload", choices=["stack", "block"], default="stack",
+                    help="stack: the headline (32 layers, batch 1); block: one block, see --copies / --batch")
+    ap.add_argument("--copies", type=int, default=1, help="block workload: copies replayed in rotation (cold when large)")
+    ap.add_argument("--batch", type=int, default=1, help="block workload: sequences (ragged lengths 1024..8192 when > 1)")
+    ap.add_argument("--shape", choices=["small", "2.8b", "6.9b"], default="2.8b",
                     help="model shape of the stack (the headline metric is quoted on 2.8b, ctx 4096)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--gen-steps", type=int, default=64,
@@ -100,6 +168,12 @@ def main():
     import paper_2604_23553_amd as cf
     from paper_2604_23553_amd.harness import DeviceStack
 
+    if args.workload == "block":
+        bench_block(args)
+        return
+    if args.shape == "small":
+        print("bench.py: --shape small is a single-block workload (--workload block)", file=sys.stderr)
+        sys.exit(2)
     if args.calibrate:
         n = 1 << 30
         src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
