@@ -157,7 +157,15 @@ cfpp_status cfpp_create(const cfpp_config *cfg, void *workspace, size_t workspac
 void cfpp_destroy(cfpp_ctx *ctx);
 
 /* Launch tuning.  Options may be changed between calls (not between capture
- * and replay). */
+ * and replay).
+ * Modes 1-3 launch persistent kernels whose workgroups wait for each other:
+ * every workgroup of a launch must be resident at the same time.  The library
+ * checks that one launch fits the device; the caller must not run them next to
+ * other work on the same GPU (another stream or process): workgroups that do
+ * not get a compute unit then stall the rest until a wait times out (after
+ * about 2 s the step is abandoned and the device error flag raised, see
+ * cfpp_device_error).  Calls of one context, and of contexts sharing a GPU,
+ * belong on one stream. */
 #define CFPP_OPT_MODE     1  /* 0: one kernel per phase (3 per block);
                                 1: one persistent kernel per block;
                                 2: cfpp_stack_*: one fused persistent kernel for
