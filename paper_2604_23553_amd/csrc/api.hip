@@ -12,6 +12,7 @@
 
 #include "cfpp.h"
 #include "lm_params.h"
+#include "batched_params.h"
 #include "decode_params.h"
 
 using namespace cfpp;
@@ -375,6 +376,7 @@ static cfpp_status prepare(cfpp_ctx *ctx)
     HIP_OK(prepare_kernels(160 * 1024));
     HIP_OK(prepare_stream_kernels(160 * 1024));
     HIP_OK(prepare_fused_kernels(160 * 1024));
+    HIP_OK(prepare_bat_kernels(160 * 1024));
     ctx->prepared = true;
     return CFPP_OK;
 }
@@ -427,6 +429,47 @@ static hipError_t launch_block_phases(const StepParams &P, const __half *w, __ha
     if (e != hipSuccess) return e;
     Q.parts = kPartUp | kPartDown;
     return launch_phases(Q, w, kv, 2 * l + 1, grid, threads, s);
+}
+
+// Launch mode 0 with several sequences: the projections of a layer run once for
+// groups of up to kBatMax sequences (weights streamed once per group, matrix
+// cores), the attention per sequence in between.
+static bool batched_path(const cfpp_ctx *ctx, const Shape &sh, int batch)
+{
+    return ctx->mode == 0 && batch > 1 && !(ctx->dm.flags & kFlagSequentialResidual) &&
+           bat_supported(ctx->dm, sh.grid, sh.threads);
+}
+
+static cfpp_status launch_batched_layer(const cfpp_ctx *ctx, const Shape &sh, const __half *w, __half *kv, int l,
+                                        int n_layers, const void *x, const int32_t *pos_dev, int batch, void *out,
+                                        hipStream_t s)
+{
+    const Dims &dm = ctx->dm;
+    const WorkspaceLayout &wl = ctx->wl;
+    for (int b0 = 0; b0 < batch; b0 += kBatMax) {
+        BatParams B;
+        std::memset(&B, 0, sizeof B);
+        B.dm = dm; B.lay = ctx->lay; B.w = w; B.kv = kv;
+        B.pos = pos_dev + b0;
+        B.nb = batch - b0 < kBatMax ? batch - b0 : kBatMax;
+        B.b0 = b0; B.layer = l; B.n_layers = n_layers;
+        B.x_in = static_cast<const __half *>(x) + (size_t)b0 * dm.h;
+        B.out = static_cast<__half *>(out) + (size_t)b0 * dm.h;
+        B.xres = reinterpret_cast<float *>(ctx->ws + wl.xres) + (size_t)b0 * 2 * dm.h;
+        B.q = reinterpret_cast<float *>(ctx->ws + wl.q) + (size_t)b0 * dm.h;
+        B.m = reinterpret_cast<float *>(ctx->ws + wl.m) + (size_t)b0 * dm.f;
+        B.o = reinterpret_cast<float *>(ctx->ws + wl.o) + (size_t)b0 * dm.h;
+        B.rope = reinterpret_cast<const float2 *>(ctx->ws + wl.rope);
+        B.sync = reinterpret_cast<unsigned *>(ctx->ws + wl.sync);
+        HIP_OK(launch_bat_qkv(B, sh.grid, s));
+        HIP_OK(launch_bat_up(B, sh.grid, s));
+        for (int b = b0; b < b0 + B.nb; ++b) {
+            const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, n_layers);
+            HIP_OK(launch_attention_only(P, w, kv, sh.grid, sh.threads, s));
+        }
+        HIP_OK(launch_bat_out(B, sh.grid, s));
+    }
+    return CFPP_OK;
 }
 
 static cfpp_status check_form(const cfpp_ctx *ctx)
@@ -544,6 +587,11 @@ extern "C" cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer
         return CFPP_OK;
     }
     if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
+    if (batched_path(ctx, sh, batch)) {
+        ctx->last_batch = batch;
+        return launch_batched_layer(ctx, sh, static_cast<const __half *>(packed_layer), static_cast<__half *>(kv_layer),
+                                    0, 1, x, pos_dev, batch, out, s);
+    }
     for (int b = 0; b < batch; ++b) {
         const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, ctx->mode == 0 ? slots : 1);
         if (ctx->mode == 0)
@@ -591,6 +639,13 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
     LayerPtrs *dev_ptrs = reinterpret_cast<LayerPtrs *>(ctx->ws + ctx->wl.layer_ptrs);
     if (store_table && ctx->mode >= 2) HIP_OK(launch_store_layer_ptrs(ptrs, dev_ptrs, L, s));
     if (!launch) return CFPP_OK;
+    if (batched_path(ctx, sh, batch)) {
+        for (int l = 0; l < L; ++l)
+            if ((st = launch_batched_layer(ctx, sh, ptrs.w[l], ptrs.kv[l], l, L, x, pos_dev, batch, out, s)) != CFPP_OK)
+                return st;
+        ctx->last_batch = batch;
+        return CFPP_OK;
+    }
     const int slots = (ctx->dm.flags & kFlagSequentialResidual) ? 2 : 1;   // (mode 0 only, checked above)
     for (int b = 0; b < batch; ++b) {
         const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, L * slots);

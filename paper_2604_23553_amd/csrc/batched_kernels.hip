@@ -1,0 +1,383 @@
+// Several sequences per step (launch mode 0, batch > 1): the four projections
+// of the block (paper Sec. 2.2) with the weights streamed ONCE for up to 8
+// sequences.  Here the path is a dense contraction - rows x K weights times K x
+// batch activations - so it runs on the matrix cores: v_mfma_f32_16x16x16_f16
+// with a 16-row tile of the weight matrix as the A operand, straight from its
+// row-major layout (one 16-byte load per lane: 16 rows x 32 columns per
+// wavefront instruction), and the activations of the batch as the B operand
+// from LDS.  Activations are fp32 values: each is split into an fp16 head and an
+// fp16 remainder (y = hi + lo exactly to ~2^-22), two MFMAs per tile, fp32
+// accumulation - the result matches the fp32 FMA path to rounding.
+//
+//   k_bat_proj<T, MODE> : LayerNorm of every sequence (one wavefront each), then
+//                         MODE 0: QKV rows + bias, rotary, K/V append, q
+//                         MODE 1: MLP-up rows + bias + GELU
+//   k_bat_out<T>        : output projection of the attention output, then the
+//                         MLP-down rows (K in slices of `hidden` through the same
+//                         LDS), + biases + residual -> the block output
+//
+// Attention stays per sequence (every sequence has its own cache) and runs the
+// attention part of the per-sequence phase kernel in between.
+//
+// A workgroup owns `rows` consecutive rows (T = ceil(rows/16) tiles, T <= 4);
+// its 8 wavefronts split K; their accumulators are added in wavefront order
+// through LDS: one bit pattern per build.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include "decode_blocks.h"
+#include "batched_params.h"
+
+namespace cfpp {
+
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBatPad = 16;          // halves between the activation rows in LDS (spreads the banks)
+
+__device__ __forceinline__ f16x4 lo_halves(u32x4 v)
+{
+    union { unsigned u[2]; f16x4 h; } c;
+    c.u[0] = v.x; c.u[1] = v.y;
+    return c.h;
+}
+__device__ __forceinline__ f16x4 hi_halves(u32x4 v)
+{
+    union { unsigned u[2]; f16x4 h; } c;
+    c.u[0] = v.z; c.u[1] = v.w;
+    return c.h;
+}
+
+// input of this layer for sequence b, element i
+__device__ __forceinline__ float bat_x(const BatParams &P, int b, int i)
+{
+    if (P.layer == 0) return __half2float(P.x_in[(size_t)b * P.dm.h + i]);
+    return P.xres[((size_t)b * 2 + ((P.layer - 1) & 1)) * P.dm.h + i];
+}
+
+// all positions of the group inside the cache?  (uniform over the grid)
+__device__ __forceinline__ bool bat_positions_ok(const BatParams &P)
+{
+    bool ok = true;
+    for (int b = 0; b < P.nb; ++b) {
+        const int p = P.pos[b];
+        ok = ok && p >= 0 && p < P.dm.max_seq;
+    }
+    if (!ok && threadIdx.x == 0 && blockIdx.x == 0)
+        __hip_atomic_store(&P.sync[kSyncErr], (unsigned)kErrBadPos, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return ok;
+}
+
+// fp32 value -> fp16 head and remainder in the two LDS arrays
+__device__ __forceinline__ void bat_put(__half *yh, __half *yl, int at, float v)
+{
+    const __half hi = __float2half_rn(v);
+    yh[at] = hi;
+    yl[at] = __float2half_rn(v - __half2float(hi));
+}
+
+// Streams rows [r_begin, r_begin + 16 T) x columns [k_off, k_off + klen) of the
+// row-major matrix W (row length K) against the activations in LDS (columns
+// 0..klen of yh/yl, row stride Ks) and adds into acc[T].  Rows past r_last
+// re-read row r_last (their results are not used).  The 8 wavefronts split klen.
+// Loads run two sets of NS ahead of the MFMAs; every set is exactly NS load
+// instructions on one code path (see GemvSpan).
+template <int T>
+__device__ __forceinline__ void bat_stream(const __half *__restrict__ W, int K, int r_begin, int r_last, int k_off,
+                                           int klen, const __half *yh, const __half *yl, int Ks, int nb,
+                                           f32x4 (&acc)[T], int tid)
+{
+    constexpr int NS = T == 3 ? 3 : 4;                    // loads per set; NS % T == 0
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, q = lane >> 4;
+    const int kslice = klen >> 3, steps = kslice >> 5;    // per wavefront: steps of 32 columns
+    const int M = steps * T;                              // loads of this wavefront
+    const int k_lo = wave * kslice;
+    int arow[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) arow[t] = min(r_begin + 16 * t + n, r_last);
+    const bool has_b = n < nb;
+
+    auto issue = [&](u32x4 (&r)[NS], int m0) {
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            int step = m0 / T + j / T;
+            step = step < steps ? step : steps - 1;       // past the end: re-read the last block
+            const __half *p = W + (size_t)arow[j % T] * K + k_off + k_lo + 32 * step + 8 * q;
+            r[j] = __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto consume = [&](const u32x4 (&r)[NS], int m0) {
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const int step = m0 / T + j / T;
+            if (m0 + j < M) {                             // (uniform)
+                const int at = n * Ks + k_lo + 32 * step + 8 * q;
+                u32x4 bh = {0u, 0u, 0u, 0u}, bl = {0u, 0u, 0u, 0u};
+                if (has_b) {
+                    bh = *reinterpret_cast<const u32x4 *>(yh + at);
+                    bl = *reinterpret_cast<const u32x4 *>(yl + at);
+                }
+                f32x4 c = acc[j % T];
+                c = __builtin_amdgcn_mfma_f32_16x16x16f16(lo_halves(r[j]), lo_halves(bh), c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_16x16x16f16(hi_halves(r[j]), hi_halves(bh), c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_16x16x16f16(lo_halves(r[j]), lo_halves(bl), c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_16x16x16f16(hi_halves(r[j]), hi_halves(bl), c, 0, 0, 0);
+                acc[j % T] = c;
+            }
+        }
+    };
+
+    if (steps <= 0) return;
+    u32x4 ra[NS], rb[NS];
+    issue(ra, 0);
+    issue(rb, NS);
+    int m0 = 0;
+    bool a_older = true;
+    while (m0 + 2 * NS < M) {
+        consume(ra, m0); issue(ra, m0 + 2 * NS); m0 += NS;
+        a_older = false;
+        if (m0 + 2 * NS >= M) break;
+        consume(rb, m0); issue(rb, m0 + 2 * NS); m0 += NS;
+        a_older = true;
+    }
+    if (a_older) { consume(ra, m0); consume(rb, m0 + NS); }
+    else { consume(rb, m0); consume(ra, m0 + NS); }
+}
+
+// accumulators of the 8 wavefronts -> LDS red[wave][tile][row in tile][sequence]
+template <int T>
+__device__ __forceinline__ void bat_spill(float *red, const f32x4 (&acc)[T], int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6, n = lane & 15, q = lane >> 4;
+    if (n < kBatMax) {
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[((wave * T + t) * 16 + 4 * q + i) * kBatMax + n] = acc[t][i];
+    }
+}
+// row (0..16T-1) of sequence b, wavefronts added in order
+template <int T>
+__device__ __forceinline__ float bat_total(const float *red, int row, int b)
+{
+    float s = 0.f;
+    for (int w = 0; w < 8; ++w) s += red[((w * T + (row >> 4)) * 16 + (row & 15)) * kBatMax + b];
+    return s;
+}
+
+// LayerNorm of sequence `wave` (two passes in registers) -> hi/lo rows in LDS
+__device__ __forceinline__ void bat_layernorm(const BatParams &P, const __half *gam, const __half *bet, __half *yh,
+                                              __half *yl, int Ks, int tid)
+{
+    const int lane = tid & 63, b = tid >> 6, h = P.dm.h;
+    if (b >= P.nb) return;                                 // (wavefront-uniform)
+    // every load is issued (clamped index) before the first one is used
+    float xv[kBatLnPerLane];
+    if (P.layer == 0) {
+        const __half *xs = P.x_in + (size_t)b * h;
+#pragma unroll
+        for (int j = 0; j < kBatLnPerLane; ++j) xv[j] = __half2float(xs[min(lane + 64 * j, h - 1)]);
+    } else {
+        const float *xs = P.xres + ((size_t)b * 2 + ((P.layer - 1) & 1)) * h;
+#pragma unroll
+        for (int j = 0; j < kBatLnPerLane; ++j) xv[j] = xs[min(lane + 64 * j, h - 1)];
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < kBatLnPerLane; ++j) {
+        if (lane + 64 * j >= h) xv[j] = 0.f;
+        s += xv[j];
+    }
+    const float mean = wave_sum(s) / (float)h;
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < kBatLnPerLane; ++j) {
+        const float dlt = lane + 64 * j < h ? xv[j] - mean : 0.f;
+        v += dlt * dlt;
+    }
+    const float inv = 1.0f / sqrtf(wave_sum(v) / (float)h + P.dm.ln_eps);
+#pragma unroll
+    for (int j = 0; j < kBatLnPerLane; ++j) {
+        const int i = lane + 64 * j, ic = min(i, h - 1);
+        const float yv = (xv[j] - mean) * inv * __half2float(gam[ic]) + __half2float(bet[ic]);
+        if (i < h) bat_put(yh, yl, b * Ks + i, yv);
+    }
+}
+
+template <int T, int MODE>
+__global__ void __launch_bounds__(512) k_bat_proj(BatParams P)
+{
+    extern __shared__ __align__(16) float lds[];
+    if (!bat_positions_ok(P)) return;
+    const Dims &dm = P.dm;
+    const int h = dm.h, tid = threadIdx.x, Ks = h + kBatPad;
+    __half *yh = reinterpret_cast<__half *>(lds), *yl = yh + kBatMax * Ks;
+    const int total = MODE == 0 ? 3 * h : dm.f;
+    const int r_begin = blockIdx.x * P.rows, r_n = max(0, min(P.rows, total - r_begin));
+    if (r_n == 0) return;                                  // (whole workgroup)
+    const __half *w = P.w;
+    bat_layernorm(P, w + (MODE == 0 ? P.lay.ln1_g : P.lay.ln2_g), w + (MODE == 0 ? P.lay.ln1_b : P.lay.ln2_b), yh, yl,
+                  Ks, tid);
+    __syncthreads();
+    f32x4 acc[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bat_stream<T>(w + (MODE == 0 ? P.lay.w_qkv : P.lay.w_up), h, r_begin, r_begin + r_n - 1, 0, h, yh, yl, Ks, P.nb, acc,
+                  tid);
+    __syncthreads();                                       // the activations are no longer read: the space is reused
+    float *red = lds;
+    bat_spill<T>(red, acc, tid);
+    __syncthreads();
+    const int b = tid & (kBatMax - 1);
+    if (b >= P.nb) return;
+    if (MODE == 1) {
+        const __half *bu = w + P.lay.b_up;
+        for (int row = tid >> 3; row < r_n; row += 64)
+            P.m[(size_t)b * dm.f + r_begin + row] =
+                gelu_act(bat_total<T>(red, row, b) + __half2float(bu[r_begin + row]), dm.flags);
+    } else {
+        // pairs of adjacent packed rows (a rotary pair sits in one), as in the per-sequence epilogue
+        const __half *bq = w + P.lay.b_qkv;
+        const int d = dm.d, r = dm.r, pos = P.pos[b];
+        for (int pr = tid >> 3; 2 * pr < r_n; pr += 64) {
+            const int p = r_begin + 2 * pr;                // packed row, even (rows is even)
+            const int pd = p / d, i = p - pd * d;
+            const int nh = pd / 3, c = pd - 3 * nh;
+            float v0 = bat_total<T>(red, 2 * pr, b) + __half2float(bq[p]);
+            float v1 = bat_total<T>(red, 2 * pr + 1, b) + __half2float(bq[p + 1]);
+            int d0 = i, d1 = i + 1;
+            if (c < 2 && i < r) {
+                const float2 cs = P.rope[(size_t)pos * (r >> 1) + (i >> 1)];
+                const float lo = v0 * cs.x - v1 * cs.y, hi = v1 * cs.x + v0 * cs.y;
+                v0 = lo; v1 = hi;
+                d0 = i >> 1; d1 = (i >> 1) + (r >> 1);
+            }
+            if (c == 0) {
+                P.q[(size_t)b * h + nh * d + d0] = v0;
+                P.q[(size_t)b * h + nh * d + d1] = v1;
+            } else {
+                P.kv[kv_offset(dm, c - 1, P.b0 + b, nh, d0, pos)] = __float2half_rn(v0);
+                P.kv[kv_offset(dm, c - 1, P.b0 + b, nh, d1, pos)] = __float2half_rn(v1);
+            }
+        }
+    }
+}
+
+template <int T>
+__global__ void __launch_bounds__(512) k_bat_out(BatParams P)
+{
+    extern __shared__ __align__(16) float lds[];
+    if (!bat_positions_ok(P)) return;
+    const Dims &dm = P.dm;
+    const int h = dm.h, f = dm.f, tid = threadIdx.x, nt = blockDim.x, Ks = h + kBatPad;
+    __half *yh = reinterpret_cast<__half *>(lds), *yl = yh + kBatMax * Ks;
+    const int r_begin = blockIdx.x * P.rows, r_n = max(0, min(P.rows, h - r_begin));
+    if (r_n == 0) return;
+    const __half *w = P.w;
+    f32x4 acc[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // attention output of every sequence -> output projection
+    for (int b = 0; b < P.nb; ++b)
+        for (int i = tid; i < h; i += nt) bat_put(yh, yl, b * Ks + i, P.o[(size_t)b * h + i]);
+    __syncthreads();
+    bat_stream<T>(w + P.lay.w_dense, h, r_begin, r_begin + r_n - 1, 0, h, yh, yl, Ks, P.nb, acc, tid);
+    // GELU(up) in slices of at most h columns -> down projection, same accumulators
+    for (int k_off = 0; k_off < f; k_off += h) {
+        const int klen = min(h, f - k_off);
+        __syncthreads();
+        for (int b = 0; b < P.nb; ++b)
+            for (int i = tid; i < klen; i += nt) bat_put(yh, yl, b * Ks + i, P.m[(size_t)b * f + k_off + i]);
+        __syncthreads();
+        bat_stream<T>(w + P.lay.w_down, f, r_begin, r_begin + r_n - 1, k_off, klen, yh, yl, Ks, P.nb, acc, tid);
+    }
+    __syncthreads();
+    float *red = lds;
+    bat_spill<T>(red, acc, tid);
+    __syncthreads();
+    const int b = tid & (kBatMax - 1);
+    if (b >= P.nb) return;
+    const __half *bde = w + P.lay.b_dense, *bdn = w + P.lay.b_down;
+    const bool last = P.layer == P.n_layers - 1;
+    for (int row = tid >> 3; row < r_n; row += 64) {
+        const int i = r_begin + row;
+        const float branches = (bat_total<T>(red, row, b) + __half2float(bde[i])) + __half2float(bdn[i]);
+        const float res = bat_x(P, b, i) + branches;
+        if (last) P.out[(size_t)b * h + i] = __float2half_rn(res);
+        else P.xres[((size_t)b * 2 + (P.layer & 1)) * h + i] = res;
+    }
+}
+
+size_t bat_lds_bytes(const Dims &dm)
+{
+    return (size_t)2 * kBatMax * (dm.h + kBatPad) * sizeof(__half);
+}
+
+bool bat_supported(const Dims &dm, int grid, int threads)
+{
+    // 8 wavefronts split K in steps of 32 columns; rows per workgroup fit 4 tiles; the
+    // LayerNorm keeps hidden / 64 values per lane; the reduction space fits under the activations
+    const int rows_max = (dm.f + grid - 1) / grid > (3 * dm.h + grid - 1) / grid ? (dm.f + grid - 1) / grid
+                                                                                 : (3 * dm.h + grid - 1) / grid;
+    return threads == 512 && dm.h % 256 == 0 && dm.f % 256 == 0 && dm.h <= 64 * kBatLnPerLane && rows_max + 1 <= 64 &&
+           bat_lds_bytes(dm) <= 160 * 1024 && (size_t)8 * 4 * 16 * kBatMax * 4 <= bat_lds_bytes(dm);
+}
+
+template <int MODE>
+static hipError_t launch_proj(const BatParams &P, int grid, size_t lds, hipStream_t s)
+{
+    const int T = (P.rows + 15) / 16;
+    switch (T) {
+    case 1: hipLaunchKernelGGL((k_bat_proj<1, MODE>), dim3(grid), dim3(512), lds, s, P); break;
+    case 2: hipLaunchKernelGGL((k_bat_proj<2, MODE>), dim3(grid), dim3(512), lds, s, P); break;
+    case 3: hipLaunchKernelGGL((k_bat_proj<3, MODE>), dim3(grid), dim3(512), lds, s, P); break;
+    case 4: hipLaunchKernelGGL((k_bat_proj<4, MODE>), dim3(grid), dim3(512), lds, s, P); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_bat_qkv(BatParams P, int grid, hipStream_t s)
+{
+    P.rows = (((3 * P.dm.h + grid - 1) / grid) + 1) & ~1;   // even: a rotary pair stays in one workgroup
+    return launch_proj<0>(P, grid, bat_lds_bytes(P.dm), s);
+}
+
+hipError_t launch_bat_up(BatParams P, int grid, hipStream_t s)
+{
+    P.rows = (P.dm.f + grid - 1) / grid;
+    return launch_proj<1>(P, grid, bat_lds_bytes(P.dm), s);
+}
+
+hipError_t launch_bat_out(BatParams P, int grid, hipStream_t s)
+{
+    P.rows = (P.dm.h + grid - 1) / grid;
+    const size_t lds = bat_lds_bytes(P.dm);
+    const int T = (P.rows + 15) / 16;
+    switch (T) {
+    case 1: hipLaunchKernelGGL(k_bat_out<1>, dim3(grid), dim3(512), lds, s, P); break;
+    case 2: hipLaunchKernelGGL(k_bat_out<2>, dim3(grid), dim3(512), lds, s, P); break;
+    case 3: hipLaunchKernelGGL(k_bat_out<3>, dim3(grid), dim3(512), lds, s, P); break;
+    case 4: hipLaunchKernelGGL(k_bat_out<4>, dim3(grid), dim3(512), lds, s, P); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t prepare_bat_kernels(size_t lds_bytes)
+{
+#define CFPP_BAT_ATTR(k) \
+    do { \
+        hipError_t e_ = hipFuncSetAttribute(reinterpret_cast<const void *>(k), \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); \
+        if (e_ != hipSuccess) return e_; \
+    } while (0)
+    CFPP_BAT_ATTR((k_bat_proj<1, 0>)); CFPP_BAT_ATTR((k_bat_proj<2, 0>)); CFPP_BAT_ATTR((k_bat_proj<3, 0>));
+    CFPP_BAT_ATTR((k_bat_proj<4, 0>)); CFPP_BAT_ATTR((k_bat_proj<1, 1>)); CFPP_BAT_ATTR((k_bat_proj<2, 1>));
+    CFPP_BAT_ATTR((k_bat_proj<3, 1>)); CFPP_BAT_ATTR((k_bat_proj<4, 1>));
+    CFPP_BAT_ATTR(k_bat_out<1>); CFPP_BAT_ATTR(k_bat_out<2>); CFPP_BAT_ATTR(k_bat_out<3>); CFPP_BAT_ATTR(k_bat_out<4>);
+#undef CFPP_BAT_ATTR
+    return hipSuccess;
+}
+
+}  // namespace cfpp

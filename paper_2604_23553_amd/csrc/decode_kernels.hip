@@ -412,6 +412,20 @@ hipError_t launch_phases(const StepParams &P, const __half *w, __half *kv, int l
     return hipErrorInvalidValue;
 }
 
+// the attention of one sequence alone (the batched path runs the projections for all sequences at once)
+hipError_t launch_attention_only(StepParams P, const __half *w, const __half *kv, int grid, int threads, hipStream_t s)
+{
+    P.parts = kPartAttention;
+    const size_t lds = (size_t)P.lds_floats * 4;
+    switch (P.dm.d) {
+    case 64: hipLaunchKernelGGL(k_phase_b<64>, dim3(grid), dim3(threads), lds, s, P, w, kv); break;
+    case 80: hipLaunchKernelGGL(k_phase_b<80>, dim3(grid), dim3(threads), lds, s, P, w, kv); break;
+    case 128: hipLaunchKernelGGL(k_phase_b<128>, dim3(grid), dim3(threads), lds, s, P, w, kv); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_block_persistent(const StepParams &P, const __half *w, __half *kv, int layer,
                                    int grid, int threads, hipStream_t s)
 {

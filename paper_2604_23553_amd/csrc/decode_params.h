@@ -43,6 +43,7 @@ hipError_t launch_phases(const StepParams &P, const __half *w, __half *kv, int l
                          int grid, int threads, hipStream_t s);
 hipError_t launch_block_persistent(const StepParams &P, const __half *w, __half *kv, int layer,
                                    int grid, int threads, hipStream_t s);
+hipError_t launch_attention_only(StepParams P, const __half *w, const __half *kv, int grid, int threads, hipStream_t s);
 // stores the per-layer pointer table in device memory (the whole-stack kernels read it there)
 hipError_t launch_store_layer_ptrs(const LayerPtrs &ptrs, LayerPtrs *dst, int n, hipStream_t s);
 // most co-resident workgroups per compute unit for the persistent kernels

@@ -385,3 +385,45 @@ def test_sequential_form_is_refused_by_the_overlapping_modes():
                 ds.stack_decode()
     finally:
         ds.close()
+
+
+@pytest.mark.parametrize("shape,B,layers", [
+    (TINY_STACK, 8, 4),
+    (synth.ModelShape(2560, 32, 80, 20, 10240, n_layers=2, name="pythia-2.8b-x2"), 5, 2),
+    (synth.ModelShape(4096, 32, 128, 32, 16384, n_layers=1, name="pythia-6.9b-block"), 8, 1),
+    (TINY_STACK, 11, 2),                      # more sequences than one group of 8
+])
+def test_batched_projections_on_the_matrix_cores(orc, shape, B, layers):
+    """Launch mode 0 with several sequences: the projections run once per group
+    of up to 8 sequences (MFMA, activations split into fp16 head + remainder),
+    the attention per sequence.  Every sequence against the oracle; the appended
+    K/V rows; bit-identical reruns."""
+    lens = synth.seq_lens(77, B, 3, 300)
+    cap = int(lens.max()) + 1
+    print(f"[case] batched projections {shape.name} B={B} lens={list(lens)}", flush=True)
+    from paper_2604_23553_amd.harness import DeviceStack
+    ds = DeviceStack(shape, cap, B, layers)
+    try:
+        ds.set_options(mode=0)
+        ws = [synth.layer_weights(shape, 51, l) for l in range(layers)]
+        kvs = [synth.kv_cache(shape, 51, l, lens, cap, B) for l in range(layers)]
+        for l in range(layers):
+            ds.load_layer(l, ws[l])
+            ds.load_kv(l, kvs[l][0], kvs[l][1], lens)
+        x = synth.x_input(shape, 51, B)
+        ds.set_inputs(x, lens)
+        outs = []
+        for _ in range(2):
+            ds.stack_decode()
+            ds.check()
+            outs.append(ds.result().copy())
+        assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
+        for b in range(B):
+            ref16, _, Ks, Vs = oracle_stack(orc, shape, ws, kvs, lens[b], x[b], b)
+            assert_block_close(outs[0][b], ref16, f"sequence {b}")
+            for l in range(layers):
+                kg, vg = ds.export_kv(l, b, int(lens[b]), 1)
+                assert_fp16_rows_match(kg[:, 0], Ks[l][:, lens[b]], f"sequence {b} layer {l} appended K")
+                assert_fp16_rows_match(vg[:, 0], Vs[l][:, lens[b]], f"sequence {b} layer {l} appended V")
+    finally:
+        ds.close()
