@@ -406,6 +406,8 @@ static StepParams make_params(const cfpp_ctx *ctx, const Shape &sh, int b, const
     P.out = static_cast<__half *>(out) + (size_t)b * dm.h;
     P.n_layers = n_layers;
     P.parts = kPartAll;
+    P.attn_g0 = 0;
+    P.attn_G = 0;
     P.rows_qkv = sh.rows_qkv; P.rows_up = sh.rows_up; P.rows_h = sh.rows_h;
     P.nsl_down = sh.nsl_down; P.nsl_dense = sh.nsl_dense;
     P.lds_floats = sh.lds_floats;
@@ -463,9 +465,14 @@ static cfpp_status launch_batched_layer(const cfpp_ctx *ctx, const Shape &sh, co
         B.sync = reinterpret_cast<unsigned *>(ctx->ws + wl.sync);
         HIP_OK(launch_bat_qkv(B, sh.grid, s));
         HIP_OK(launch_bat_up(B, sh.grid, s));
-        for (int b = b0; b < b0 + B.nb; ++b) {
-            const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, n_layers);
-            HIP_OK(launch_attention_only(P, w, kv, sh.grid, sh.threads, s));
+        if (sh.grid >= B.nb) {
+            const StepParams P = make_params(ctx, sh, b0, x, pos_dev, out, n_layers);
+            HIP_OK(launch_attention_batched(P, B.nb, w, kv, sh.grid, sh.threads, s));
+        } else {
+            for (int b = b0; b < b0 + B.nb; ++b) {
+                const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, n_layers);
+                HIP_OK(launch_attention_only(P, w, kv, sh.grid, sh.threads, s));
+            }
         }
         HIP_OK(launch_bat_out(B, sh.grid, s));
     }

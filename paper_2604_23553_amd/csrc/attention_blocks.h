@@ -44,13 +44,13 @@ struct AttnCore {
         lane = lane_;
         sub = lane & (LPP - 1);
         tl = lane / LPP;
-        g = blockIdx.x;
+        g = (int)blockIdx.x - P.attn_g0;
         // (host-checked: rows * workgroups stays far below 2^31)
         R = (n_tok + PPW - 1) / PPW;
         T = R * dm->H;
         // with fewer rows than workgroups only the first T workgroups take part, so
         // that every participant owns at least one row (no empty ranges in between)
-        G = min((int)gridDim.x, T);
+        G = min(P.attn_G > 0 ? P.attn_G : (int)gridDim.x, T);
         r0 = g < G ? (int)((long long)T * g / G) : 0;
         r1 = g < G ? (int)((long long)T * (g + 1) / G) : 0;
         scale = 1.0f / sqrtf((float)D);

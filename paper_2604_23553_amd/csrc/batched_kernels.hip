@@ -66,14 +66,6 @@ __device__ __forceinline__ bool bat_positions_ok(const BatParams &P)
     return ok;
 }
 
-// fp32 value -> fp16 head and remainder in the two LDS arrays
-__device__ __forceinline__ void bat_put(__half *yh, __half *yl, int at, float v)
-{
-    const __half hi = __float2half_rn(v);
-    yh[at] = hi;
-    yl[at] = __float2half_rn(v - __half2float(hi));
-}
-
 // Streams rows [r_begin, r_begin + 16 T) x columns [k_off, k_off + klen) of the
 // row-major matrix W (row length K) against the activations in LDS (columns
 // 0..klen of yh/yl, row stride Ks) and adds into acc[T].  Rows past r_last
@@ -94,7 +86,10 @@ __device__ __forceinline__ void bat_stream(const __half *__restrict__ W, int K, 
     int arow[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) arow[t] = min(r_begin + 16 * t + n, r_last);
-    const bool has_b = n < nb;
+    // Lanes of columns without a sequence read some sequence's activations: their
+    // products land in columns of the result that are never looked at.
+    const int brow = (n & (kBatMax - 1)) * Ks + k_lo + 8 * q;
+    (void)nb;
 
     auto issue = [&](u32x4 (&r)[NS], int m0) {
 #pragma unroll
@@ -106,17 +101,14 @@ __device__ __forceinline__ void bat_stream(const __half *__restrict__ W, int K, 
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto consume = [&](const u32x4 (&r)[NS], int m0) {
+    // guard: sets at the end of the range may be partly past it (their loads were clamped)
+    auto consume = [&](const u32x4 (&r)[NS], int m0, bool guard) {
 #pragma unroll
         for (int j = 0; j < NS; ++j) {
             const int step = m0 / T + j / T;
-            if (m0 + j < M) {                             // (uniform)
-                const int at = n * Ks + k_lo + 32 * step + 8 * q;
-                u32x4 bh = {0u, 0u, 0u, 0u}, bl = {0u, 0u, 0u, 0u};
-                if (has_b) {
-                    bh = *reinterpret_cast<const u32x4 *>(yh + at);
-                    bl = *reinterpret_cast<const u32x4 *>(yl + at);
-                }
+            if (!guard || m0 + j < M) {                   // (uniform)
+                const u32x4 bh = *reinterpret_cast<const u32x4 *>(yh + brow + 32 * step);
+                const u32x4 bl = *reinterpret_cast<const u32x4 *>(yl + brow + 32 * step);
                 f32x4 c = acc[j % T];
                 c = __builtin_amdgcn_mfma_f32_16x16x16f16(lo_halves(r[j]), lo_halves(bh), c, 0, 0, 0);
                 c = __builtin_amdgcn_mfma_f32_16x16x16f16(hi_halves(r[j]), hi_halves(bh), c, 0, 0, 0);
@@ -131,17 +123,19 @@ __device__ __forceinline__ void bat_stream(const __half *__restrict__ W, int K, 
     u32x4 ra[NS], rb[NS];
     issue(ra, 0);
     issue(rb, NS);
+    // Both sets are consumed and refilled per round, no exit from the middle of
+    // the loop (the wait counts at its top would have to cover a path that is never
+    // taken); inside the loop every consumed set lies wholly inside the range.
     int m0 = 0;
-    bool a_older = true;
-    while (m0 + 2 * NS < M) {
-        consume(ra, m0); issue(ra, m0 + 2 * NS); m0 += NS;
-        a_older = false;
-        if (m0 + 2 * NS >= M) break;
-        consume(rb, m0); issue(rb, m0 + 2 * NS); m0 += NS;
-        a_older = true;
+    while (m0 + 3 * NS < M) {
+        consume(ra, m0, false); issue(ra, m0 + 2 * NS);
+        consume(rb, m0 + NS, false); issue(rb, m0 + 3 * NS);
+        m0 += 2 * NS;
     }
-    if (a_older) { consume(ra, m0); consume(rb, m0 + NS); }
-    else { consume(rb, m0); consume(ra, m0 + NS); }
+    const bool one_more = m0 + 2 * NS < M;
+    if (one_more) { consume(ra, m0, false); issue(ra, m0 + 2 * NS); }
+    if (one_more) { consume(rb, m0 + NS, true); consume(ra, m0 + 2 * NS, true); }
+    else { consume(ra, m0, true); consume(rb, m0 + NS, true); }
 }
 
 // accumulators of the 8 wavefronts -> LDS red[wave][tile][row in tile][sequence]
@@ -165,42 +159,127 @@ __device__ __forceinline__ float bat_total(const float *red, int row, int b)
     return s;
 }
 
-// LayerNorm of sequence `wave` (two passes in registers) -> hi/lo rows in LDS
-__device__ __forceinline__ void bat_layernorm(const BatParams &P, const __half *gam, const __half *bet, __half *yh,
-                                              __half *yl, int Ks, int tid)
+// 8 consecutive fp32 values -> fp16 heads and remainders, one 16-byte LDS write each
+__device__ __forceinline__ void bat_put8(__half *yh, __half *yl, int at, const float (&v)[8])
 {
-    const int lane = tid & 63, b = tid >> 6, h = P.dm.h;
-    if (b >= P.nb) return;                                 // (wavefront-uniform)
-    // every load is issued (clamped index) before the first one is used
-    float xv[kBatLnPerLane];
+    union { __half h[8]; u32x4 u; } hi, lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        hi.h[e] = __float2half_rn(v[e]);
+        lo.h[e] = __float2half_rn(v[e] - __half2float(hi.h[e]));
+    }
+    *reinterpret_cast<u32x4 *>(yh + at) = hi.u;
+    *reinterpret_cast<u32x4 *>(yl + at) = lo.u;
+}
+
+// src[b * stride + 0..klen) (fp32, klen <= 4096 a multiple of 8) of every sequence -> hi/lo rows in
+// LDS: a thread owns one group of 8 values of every sequence; all loads are issued first
+__device__ __forceinline__ void bat_stage(const float *src, size_t stride, int klen, __half *yh, __half *yl, int Ks,
+                                          int nb, int tid)
+{
+    const int c = tid < (klen >> 3) ? tid : 0;
+    f32x4 v[kBatMax][2];
+#pragma unroll
+    for (int b = 0; b < kBatMax; ++b) {
+        const float *p = src + (size_t)(b < nb ? b : 0) * stride + 8 * c;
+        v[b][0] = *as_global(reinterpret_cast<const f32x4 *>(p));
+        v[b][1] = *as_global(reinterpret_cast<const f32x4 *>(p + 4));
+    }
+    if (tid < (klen >> 3)) {
+#pragma unroll
+        for (int b = 0; b < kBatMax; ++b) {
+            if (b < nb) {
+                const float e[8] = {v[b][0][0], v[b][0][1], v[b][0][2], v[b][0][3], v[b][1][0], v[b][1][1], v[b][1][2], v[b][1][3]};
+                bat_put8(yh, yl, b * Ks + 8 * c, e);
+            }
+        }
+    }
+}
+
+// LayerNorm of every sequence (two passes, biased variance) -> hi/lo rows in
+// LDS.  A thread owns one group of 8 elements of every sequence (hidden <= 4096);
+// the sums go through `red` (2 * 8 * kBatMax floats) in wavefront order.
+__device__ __forceinline__ void bat_layernorm(const BatParams &P, const __half *gam, const __half *bet, __half *yh,
+                                              __half *yl, int Ks, float *red, int tid)
+{
+    const int h = P.dm.h, nchunk = h >> 3, lane = tid & 63, wave = tid >> 6;
+    const bool active = tid < nchunk;
+    const int c = active ? tid : 0;
+    float xv[kBatMax][8];
     if (P.layer == 0) {
-        const __half *xs = P.x_in + (size_t)b * h;
+        u32x4 raw[kBatMax];
 #pragma unroll
-        for (int j = 0; j < kBatLnPerLane; ++j) xv[j] = __half2float(xs[min(lane + 64 * j, h - 1)]);
+        for (int b = 0; b < kBatMax; ++b)
+            raw[b] = *as_global(reinterpret_cast<const u32x4 *>(P.x_in + (size_t)(b < P.nb ? b : 0) * h + 8 * c));
+#pragma unroll
+        for (int b = 0; b < kBatMax; ++b) {
+            const float2 a0 = unpack_h2(raw[b].x), a1 = unpack_h2(raw[b].y), a2 = unpack_h2(raw[b].z), a3 = unpack_h2(raw[b].w);
+            xv[b][0] = a0.x; xv[b][1] = a0.y; xv[b][2] = a1.x; xv[b][3] = a1.y;
+            xv[b][4] = a2.x; xv[b][5] = a2.y; xv[b][6] = a3.x; xv[b][7] = a3.y;
+        }
     } else {
-        const float *xs = P.xres + ((size_t)b * 2 + ((P.layer - 1) & 1)) * h;
+        f32x4 raw[kBatMax][2];
 #pragma unroll
-        for (int j = 0; j < kBatLnPerLane; ++j) xv[j] = xs[min(lane + 64 * j, h - 1)];
+        for (int b = 0; b < kBatMax; ++b) {
+            const float *p = P.xres + ((size_t)(b < P.nb ? b : 0) * 2 + ((P.layer - 1) & 1)) * h + 8 * c;
+            raw[b][0] = *as_global(reinterpret_cast<const f32x4 *>(p));
+            raw[b][1] = *as_global(reinterpret_cast<const f32x4 *>(p + 4));
+        }
+#pragma unroll
+        for (int b = 0; b < kBatMax; ++b)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xv[b][e] = raw[b][e >> 2][e & 3];
     }
-    float s = 0.f;
+    const u32x4 graw = *as_global(reinterpret_cast<const u32x4 *>(gam + 8 * c));
+    const u32x4 braw = *as_global(reinterpret_cast<const u32x4 *>(bet + 8 * c));
+    // pass 1: means
 #pragma unroll
-    for (int j = 0; j < kBatLnPerLane; ++j) {
-        if (lane + 64 * j >= h) xv[j] = 0.f;
-        s += xv[j];
+    for (int b = 0; b < kBatMax; ++b) {
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += xv[b][e];
+        s = wave_sum(active ? s : 0.f);
+        if (lane == 0) red[wave * kBatMax + b] = s;
     }
-    const float mean = wave_sum(s) / (float)h;
-    float v = 0.f;
+    __syncthreads();
+    float mean[kBatMax];
 #pragma unroll
-    for (int j = 0; j < kBatLnPerLane; ++j) {
-        const float dlt = lane + 64 * j < h ? xv[j] - mean : 0.f;
-        v += dlt * dlt;
+    for (int b = 0; b < kBatMax; ++b) {
+        float s = 0.f;
+        for (int w = 0; w < 8; ++w) s += red[w * kBatMax + b];
+        mean[b] = s / (float)h;
     }
-    const float inv = 1.0f / sqrtf(wave_sum(v) / (float)h + P.dm.ln_eps);
+    // pass 2: variances
+    float *red2 = red + 8 * kBatMax;
 #pragma unroll
-    for (int j = 0; j < kBatLnPerLane; ++j) {
-        const int i = lane + 64 * j, ic = min(i, h - 1);
-        const float yv = (xv[j] - mean) * inv * __half2float(gam[ic]) + __half2float(bet[ic]);
-        if (i < h) bat_put(yh, yl, b * Ks + i, yv);
+    for (int b = 0; b < kBatMax; ++b) {
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float dlt = xv[b][e] - mean[b];
+            s += dlt * dlt;
+        }
+        s = wave_sum(active ? s : 0.f);
+        if (lane == 0) red2[wave * kBatMax + b] = s;
+    }
+    __syncthreads();
+    if (!active) return;
+    const unsigned gw[4] = {graw.x, graw.y, graw.z, graw.w}, bw[4] = {braw.x, braw.y, braw.z, braw.w};
+#pragma unroll
+    for (int b = 0; b < kBatMax; ++b) {
+        if (b < P.nb) {
+            float s = 0.f;
+            for (int w = 0; w < 8; ++w) s += red2[w * kBatMax + b];
+            const float inv = 1.0f / sqrtf(s / (float)h + P.dm.ln_eps);
+            float yv[8];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const float2 g2 = unpack_h2(gw[e2]), b2 = unpack_h2(bw[e2]);
+                yv[2 * e2] = (xv[b][2 * e2] - mean[b]) * inv * g2.x + b2.x;
+                yv[2 * e2 + 1] = (xv[b][2 * e2 + 1] - mean[b]) * inv * g2.y + b2.y;
+            }
+            bat_put8(yh, yl, b * Ks + 8 * c, yv);
+        }
     }
 }
 
@@ -216,8 +295,9 @@ __global__ void __launch_bounds__(512) k_bat_proj(BatParams P)
     const int r_begin = blockIdx.x * P.rows, r_n = max(0, min(P.rows, total - r_begin));
     if (r_n == 0) return;                                  // (whole workgroup)
     const __half *w = P.w;
+    float *stat = reinterpret_cast<float *>(yl + kBatMax * Ks);     // behind the activations
     bat_layernorm(P, w + (MODE == 0 ? P.lay.ln1_g : P.lay.ln2_g), w + (MODE == 0 ? P.lay.ln1_b : P.lay.ln2_b), yh, yl,
-                  Ks, tid);
+                  Ks, stat, tid);
     __syncthreads();
     f32x4 acc[T];
 #pragma unroll
@@ -269,7 +349,7 @@ __global__ void __launch_bounds__(512) k_bat_out(BatParams P)
     extern __shared__ __align__(16) float lds[];
     if (!bat_positions_ok(P)) return;
     const Dims &dm = P.dm;
-    const int h = dm.h, f = dm.f, tid = threadIdx.x, nt = blockDim.x, Ks = h + kBatPad;
+    const int h = dm.h, f = dm.f, tid = threadIdx.x, Ks = h + kBatPad;
     __half *yh = reinterpret_cast<__half *>(lds), *yl = yh + kBatMax * Ks;
     const int r_begin = blockIdx.x * P.rows, r_n = max(0, min(P.rows, h - r_begin));
     if (r_n == 0) return;
@@ -278,16 +358,14 @@ __global__ void __launch_bounds__(512) k_bat_out(BatParams P)
 #pragma unroll
     for (int t = 0; t < T; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
     // attention output of every sequence -> output projection
-    for (int b = 0; b < P.nb; ++b)
-        for (int i = tid; i < h; i += nt) bat_put(yh, yl, b * Ks + i, P.o[(size_t)b * h + i]);
+    bat_stage(P.o, (size_t)h, h, yh, yl, Ks, P.nb, tid);
     __syncthreads();
     bat_stream<T>(w + P.lay.w_dense, h, r_begin, r_begin + r_n - 1, 0, h, yh, yl, Ks, P.nb, acc, tid);
     // GELU(up) in slices of at most h columns -> down projection, same accumulators
     for (int k_off = 0; k_off < f; k_off += h) {
         const int klen = min(h, f - k_off);
         __syncthreads();
-        for (int b = 0; b < P.nb; ++b)
-            for (int i = tid; i < klen; i += nt) bat_put(yh, yl, b * Ks + i, P.m[(size_t)b * f + k_off + i]);
+        bat_stage(P.m + k_off, (size_t)f, klen, yh, yl, Ks, P.nb, tid);
         __syncthreads();
         bat_stream<T>(w + P.lay.w_down, f, r_begin, r_begin + r_n - 1, k_off, klen, yh, yl, Ks, P.nb, acc, tid);
     }
@@ -310,16 +388,16 @@ __global__ void __launch_bounds__(512) k_bat_out(BatParams P)
 
 size_t bat_lds_bytes(const Dims &dm)
 {
-    return (size_t)2 * kBatMax * (dm.h + kBatPad) * sizeof(__half);
+    return (size_t)2 * kBatMax * (dm.h + kBatPad) * sizeof(__half) + 2 * 8 * kBatMax * sizeof(float);
 }
 
 bool bat_supported(const Dims &dm, int grid, int threads)
 {
     // 8 wavefronts split K in steps of 32 columns; rows per workgroup fit 4 tiles; the
     // LayerNorm keeps hidden / 64 values per lane; the reduction space fits under the activations
-    const int rows_max = (dm.f + grid - 1) / grid > (3 * dm.h + grid - 1) / grid ? (dm.f + grid - 1) / grid
-                                                                                 : (3 * dm.h + grid - 1) / grid;
-    return threads == 512 && dm.h % 256 == 0 && dm.f % 256 == 0 && dm.h <= 64 * kBatLnPerLane && rows_max + 1 <= 64 &&
+    const int rows_up = (dm.f + grid - 1) / grid, rows_qkv = (((3 * dm.h + grid - 1) / grid) + 1) & ~1;
+    const int rows_max = rows_up > rows_qkv ? rows_up : rows_qkv;
+    return threads == 512 && dm.h % 256 == 0 && dm.f % 256 == 0 && dm.h <= 64 * kBatLnPerLane && rows_max <= 64 &&
            bat_lds_bytes(dm) <= 160 * 1024 && (size_t)8 * 4 * 16 * kBatMax * 4 <= bat_lds_bytes(dm);
 }
 

@@ -367,6 +367,65 @@ k_phase_c(StepParams P, const __half *w, int layer)
     phase_c(P, w, layer, lds, sync);
 }
 
+// The attention of several sequences in one launch.  P holds the parameters of
+// the first sequence; sequence i follows at the workspace's usual strides.
+// Every workgroup works out the split from the positions in device memory:
+// workgroups are dealt in proportion to the cache rows of each sequence, at
+// least one each (grid >= nb).
+constexpr int kAttnBatchMax = 8;
+template <int D>
+__global__ void __launch_bounds__(kMaxThreads)
+k_attention_batched(StepParams P, int nb, const __half *w, const __half *kv)
+{
+    extern __shared__ __align__(16) float lds[];
+    constexpr int PPW = AttnShape<D>::PPW;
+    const Dims &dm = P.dm;
+    int rows[kAttnBatchMax];
+    long long total = 0;
+    bool ok = true;
+#pragma unroll
+    for (int i = 0; i < kAttnBatchMax; ++i) {
+        rows[i] = 0;
+        if (i < nb) {
+            const int p = P.pos[i];
+            ok = ok && p >= 0 && p < dm.max_seq;
+            rows[i] = dm.H * ((p + 1 + PPW - 1) / PPW);
+            total += rows[i];
+        }
+    }
+    if (!ok) {
+        if (threadIdx.x == 0 && blockIdx.x == 0)
+            __hip_atomic_store(&P.sync[kSyncErr], (unsigned)kErrBadPos, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+    const int spare = (int)gridDim.x - nb, g = blockIdx.x;
+    long long before = 0;
+    int mine = -1, g0 = 0, g1 = 0;
+#pragma unroll
+    for (int i = 0; i < kAttnBatchMax; ++i) {
+        if (i < nb) {
+            const int lo = (int)(spare * before / total) + i;
+            before += rows[i];
+            const int hi = (int)(spare * before / total) + i + 1;
+            if (g >= lo && g < hi) { mine = i; g0 = lo; g1 = hi; }
+        }
+    }
+    if (mine < 0) return;
+    StepParams Q = P;
+    Q.b = P.b + mine;
+    Q.pos = P.pos + mine;
+    Q.q = P.q + (size_t)mine * dm.h;
+    Q.o = P.o + (size_t)mine * dm.h;
+    Q.m = P.m + (size_t)mine * dm.f;
+    Q.part = P.part + (size_t)mine * dm.H * P.part_slots * (dm.d + 2);
+    Q.seg_cnt = P.seg_cnt + (size_t)mine * dm.H;
+    Q.attn_g0 = g0;
+    Q.attn_G = g1 - g0;
+    Q.parts = kPartAttention;
+    NoSync sync;
+    phase_b<D>(Q, w, kv, *Q.pos, lds, sync);
+}
+
 template <int D>
 __global__ void __launch_bounds__(kMaxThreads)
 k_block_persistent(StepParams P, const __half *w, __half *kv, int layer)
@@ -426,6 +485,20 @@ hipError_t launch_attention_only(StepParams P, const __half *w, const __half *kv
     return hipGetLastError();
 }
 
+hipError_t launch_attention_batched(StepParams P, int nb, const __half *w, const __half *kv, int grid, int threads,
+                                    hipStream_t s)
+{
+    if (nb < 1 || nb > kAttnBatchMax || grid < nb) return hipErrorInvalidValue;
+    const size_t lds = (size_t)P.lds_floats * 4;
+    switch (P.dm.d) {
+    case 64: hipLaunchKernelGGL(k_attention_batched<64>, dim3(grid), dim3(threads), lds, s, P, nb, w, kv); break;
+    case 80: hipLaunchKernelGGL(k_attention_batched<80>, dim3(grid), dim3(threads), lds, s, P, nb, w, kv); break;
+    case 128: hipLaunchKernelGGL(k_attention_batched<128>, dim3(grid), dim3(threads), lds, s, P, nb, w, kv); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_block_persistent(const StepParams &P, const __half *w, __half *kv, int layer,
                                    int grid, int threads, hipStream_t s)
 {
@@ -473,6 +546,9 @@ hipError_t prepare_kernels(size_t lds_bytes)
     CFPP_TRY(hipFuncSetAttribute((const void *)k_phase_b<64>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
     CFPP_TRY(hipFuncSetAttribute((const void *)k_phase_b<80>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
     CFPP_TRY(hipFuncSetAttribute((const void *)k_phase_b<128>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
+    CFPP_TRY(hipFuncSetAttribute((const void *)k_attention_batched<64>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
+    CFPP_TRY(hipFuncSetAttribute((const void *)k_attention_batched<80>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
+    CFPP_TRY(hipFuncSetAttribute((const void *)k_attention_batched<128>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
     CFPP_TRY(hipFuncSetAttribute((const void *)k_block_persistent<64>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
     CFPP_TRY(hipFuncSetAttribute((const void *)k_block_persistent<80>, hipFuncAttributeMaxDynamicSharedMemorySize, v));
     CFPP_TRY(hipFuncSetAttribute((const void *)k_block_persistent<128>, hipFuncAttributeMaxDynamicSharedMemorySize, v));

@@ -23,6 +23,7 @@ struct StepParams {
     const __half *x_in;  // fp16 [h] input of layer 0
     __half *out;         // fp16 [h] output of the last layer
     int n_layers;
+    int attn_g0, attn_G; // attention: the workgroups [attn_g0, attn_g0 + attn_G) share this sequence (attn_G 0: the whole grid)
     int parts;           // kPart* bits: what a phase launch performs (kPartAll unless the block runs in two halves)
     // work split (chosen on the host from the grid and the workgroup size)
     int rows_qkv, rows_up, rows_h;   // matrix rows per workgroup (rows_qkv even)
@@ -44,6 +45,9 @@ hipError_t launch_phases(const StepParams &P, const __half *w, __half *kv, int l
 hipError_t launch_block_persistent(const StepParams &P, const __half *w, __half *kv, int layer,
                                    int grid, int threads, hipStream_t s);
 hipError_t launch_attention_only(StepParams P, const __half *w, const __half *kv, int grid, int threads, hipStream_t s);
+// the attention of nb sequences (P: the first one's parameters) in one launch, workgroups dealt by cache length
+hipError_t launch_attention_batched(StepParams P, int nb, const __half *w, const __half *kv, int grid, int threads,
+                                    hipStream_t s);
 // stores the per-layer pointer table in device memory (the whole-stack kernels read it there)
 hipError_t launch_store_layer_ptrs(const LayerPtrs &ptrs, LayerPtrs *dst, int n, hipStream_t s);
 // most co-resident workgroups per compute unit for the persistent kernels
