@@ -82,7 +82,9 @@ __device__ __forceinline__ void bat_stream(const __half *__restrict__ W, int K, 
     const int n = lane & 15, q = lane >> 4;
     const int kslice = klen >> 3, steps = kslice >> 5;    // per wavefront: steps of 32 columns
     const int M = steps * T;                              // loads of this wavefront
-    const int k_lo = wave * kslice;
+    // the 8 wavefronts interleave blocks of 32 columns: together they read 512 contiguous
+    // bytes of every row per step (kinder to the DRAM pages than 8 slices far apart)
+    const int k_lo = 32 * wave;
     int arow[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) arow[t] = min(r_begin + 16 * t + n, r_last);
@@ -96,7 +98,7 @@ __device__ __forceinline__ void bat_stream(const __half *__restrict__ W, int K, 
         for (int j = 0; j < NS; ++j) {
             int step = m0 / T + j / T;
             step = step < steps ? step : steps - 1;       // past the end: re-read the last block
-            const __half *p = W + (size_t)arow[j % T] * K + k_off + k_lo + 32 * step + 8 * q;
+            const __half *p = W + (size_t)arow[j % T] * K + k_off + k_lo + 256 * step + 8 * q;
             r[j] = __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -107,8 +109,8 @@ __device__ __forceinline__ void bat_stream(const __half *__restrict__ W, int K, 
         for (int j = 0; j < NS; ++j) {
             const int step = m0 / T + j / T;
             if (!guard || m0 + j < M) {                   // (uniform)
-                const u32x4 bh = *reinterpret_cast<const u32x4 *>(yh + brow + 32 * step);
-                const u32x4 bl = *reinterpret_cast<const u32x4 *>(yl + brow + 32 * step);
+                const u32x4 bh = *reinterpret_cast<const u32x4 *>(yh + brow + 256 * step);
+                const u32x4 bl = *reinterpret_cast<const u32x4 *>(yl + brow + 256 * step);
                 f32x4 c = acc[j % T];
                 c = __builtin_amdgcn_mfma_f32_16x16x16f16(lo_halves(r[j]), lo_halves(bh), c, 0, 0, 0);
                 c = __builtin_amdgcn_mfma_f32_16x16x16f16(hi_halves(r[j]), hi_halves(bh), c, 0, 0, 0);
