@@ -66,78 +66,107 @@ __device__ __forceinline__ bool bat_positions_ok(const BatParams &P)
     return ok;
 }
 
+// One 16-row tile: its `steps` blocks of 32 columns (per wavefront) against the
+// activations in LDS, into one accumulator.  A and B already hold the tile's
+// first two sets of kBatSet loads; when the last load of the tile has been
+// issued, the first two sets of the next tile (row `row_next`, if has_next) are
+// requested into C and D, so the queue stays full across tiles.  Every set is
+// exactly kBatSet load instructions on one code path; no exit from the middle
+// of the loop (see GemvSpan for why).
+constexpr int kBatSet = 4;
+
+struct BatStreamCtx {
+    const __half *W;          // matrix, offset to the first column of the range
+    size_t K;                 // row length
+    int col;                  // this lane's first column: 32 * wave + 8 * (lane / 16)
+    int steps;                // blocks per tile and wavefront (256 columns apart)
+    const __half *yh, *yl;    // this lane's activation row in LDS, at column `col`
+};
+
+__device__ __forceinline__ void bat_issue(const BatStreamCtx &C, u32x4 (&r)[kBatSet], int row, int m0)
+{
+#pragma unroll
+    for (int j = 0; j < kBatSet; ++j) {
+        const int step = m0 + j < C.steps ? m0 + j : C.steps - 1;     // past the end: re-read the last block
+        const __half *p = C.W + (size_t)row * C.K + C.col + 256 * step;
+        r[j] = __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// guard: a set at the end of the tile may be partly past it (its loads were clamped)
+__device__ __forceinline__ void bat_consume(const BatStreamCtx &C, const u32x4 (&r)[kBatSet], f32x4 &acc, int m0,
+                                            bool guard)
+{
+#pragma unroll
+    for (int j = 0; j < kBatSet; ++j) {
+        if (!guard || m0 + j < C.steps) {                 // (uniform)
+            const u32x4 bh = *reinterpret_cast<const u32x4 *>(C.yh + 256 * (m0 + j));
+            const u32x4 bl = *reinterpret_cast<const u32x4 *>(C.yl + 256 * (m0 + j));
+            f32x4 c = acc;
+            c = __builtin_amdgcn_mfma_f32_16x16x16f16(lo_halves(r[j]), lo_halves(bh), c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_16x16x16f16(hi_halves(r[j]), hi_halves(bh), c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_16x16x16f16(lo_halves(r[j]), lo_halves(bl), c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_16x16x16f16(hi_halves(r[j]), hi_halves(bl), c, 0, 0, 0);
+            acc = c;
+        }
+    }
+}
+
+__device__ __forceinline__ void bat_tile(const BatStreamCtx &C, u32x4 (&A)[kBatSet], u32x4 (&B)[kBatSet],
+                                         u32x4 (&Cn)[kBatSet], u32x4 (&Dn)[kBatSet], f32x4 &acc, int row,
+                                         int row_next, bool has_next)
+{
+    constexpr int NS = kBatSet;
+    int m0 = 0;
+    while (m0 + 3 * NS < C.steps) {
+        bat_consume(C, A, acc, m0, false); bat_issue(C, A, row, m0 + 2 * NS);
+        bat_consume(C, B, acc, m0 + NS, false); bat_issue(C, B, row, m0 + 3 * NS);
+        m0 += 2 * NS;
+    }
+    const bool one_more = m0 + 2 * NS < C.steps;
+    if (one_more) { bat_consume(C, A, acc, m0, false); bat_issue(C, A, row, m0 + 2 * NS); }
+    if (has_next) { bat_issue(C, Cn, row_next, 0); bat_issue(C, Dn, row_next, NS); }
+    if (one_more) { bat_consume(C, B, acc, m0 + NS, true); bat_consume(C, A, acc, m0 + 2 * NS, true); }
+    else { bat_consume(C, A, acc, m0, true); bat_consume(C, B, acc, m0 + NS, true); }
+}
+
 // Streams rows [r_begin, r_begin + 16 T) x columns [k_off, k_off + klen) of the
 // row-major matrix W (row length K) against the activations in LDS (columns
 // 0..klen of yh/yl, row stride Ks) and adds into acc[T].  Rows past r_last
-// re-read row r_last (their results are not used).  The 8 wavefronts split klen.
-// Loads run two sets of NS ahead of the MFMAs; every set is exactly NS load
-// instructions on one code path (see GemvSpan).
+// re-read row r_last (their results are not used).  The 8 wavefronts interleave
+// blocks of 32 columns and work on one tile at a time: together they read every
+// row of the tile in 512-byte steps with up to 4 KiB per row in flight - long
+// runs for the DRAM pages.  Lanes of columns without a sequence read some
+// sequence's activations: their products land in columns of the result that are
+// never looked at.
 template <int T>
 __device__ __forceinline__ void bat_stream(const __half *__restrict__ W, int K, int r_begin, int r_last, int k_off,
                                            int klen, const __half *yh, const __half *yl, int Ks, int nb,
                                            f32x4 (&acc)[T], int tid)
 {
-    constexpr int NS = T == 3 ? 3 : 4;                    // loads per set; NS % T == 0
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, q = lane >> 4;
-    const int kslice = klen >> 3, steps = kslice >> 5;    // per wavefront: steps of 32 columns
-    const int M = steps * T;                              // loads of this wavefront
-    // the 8 wavefronts interleave blocks of 32 columns: together they read 512 contiguous
-    // bytes of every row per step (kinder to the DRAM pages than 8 slices far apart)
-    const int k_lo = 32 * wave;
-    int arow[T];
-#pragma unroll
-    for (int t = 0; t < T; ++t) arow[t] = min(r_begin + 16 * t + n, r_last);
-    // Lanes of columns without a sequence read some sequence's activations: their
-    // products land in columns of the result that are never looked at.
-    const int brow = (n & (kBatMax - 1)) * Ks + k_lo + 8 * q;
     (void)nb;
-
-    auto issue = [&](u32x4 (&r)[NS], int m0) {
+    BatStreamCtx C;
+    C.K = (size_t)K;
+    C.col = 32 * wave + 8 * q;
+    C.W = W + k_off;
+    C.steps = klen >> 8;
+    C.yh = yh + (n & (kBatMax - 1)) * Ks + C.col;
+    C.yl = yl + (n & (kBatMax - 1)) * Ks + C.col;
+    if (C.steps <= 0) return;
+    int arow[T + 1];
 #pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            int step = m0 / T + j / T;
-            step = step < steps ? step : steps - 1;       // past the end: re-read the last block
-            const __half *p = W + (size_t)arow[j % T] * K + k_off + k_lo + 256 * step + 8 * q;
-            r[j] = __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    // guard: sets at the end of the range may be partly past it (their loads were clamped)
-    auto consume = [&](const u32x4 (&r)[NS], int m0, bool guard) {
+    for (int t = 0; t <= T; ++t) arow[t] = min(r_begin + 16 * (t < T ? t : T - 1) + n, r_last);
+    u32x4 r0[kBatSet], r1[kBatSet], r2[kBatSet], r3[kBatSet];
+    bat_issue(C, r0, arow[0], 0);
+    bat_issue(C, r1, arow[0], kBatSet);
 #pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            const int step = m0 / T + j / T;
-            if (!guard || m0 + j < M) {                   // (uniform)
-                const u32x4 bh = *reinterpret_cast<const u32x4 *>(yh + brow + 256 * step);
-                const u32x4 bl = *reinterpret_cast<const u32x4 *>(yl + brow + 256 * step);
-                f32x4 c = acc[j % T];
-                c = __builtin_amdgcn_mfma_f32_16x16x16f16(lo_halves(r[j]), lo_halves(bh), c, 0, 0, 0);
-                c = __builtin_amdgcn_mfma_f32_16x16x16f16(hi_halves(r[j]), hi_halves(bh), c, 0, 0, 0);
-                c = __builtin_amdgcn_mfma_f32_16x16x16f16(lo_halves(r[j]), lo_halves(bl), c, 0, 0, 0);
-                c = __builtin_amdgcn_mfma_f32_16x16x16f16(hi_halves(r[j]), hi_halves(bl), c, 0, 0, 0);
-                acc[j % T] = c;
-            }
-        }
-    };
-
-    if (steps <= 0) return;
-    u32x4 ra[NS], rb[NS];
-    issue(ra, 0);
-    issue(rb, NS);
-    // Both sets are consumed and refilled per round, no exit from the middle of
-    // the loop (the wait counts at its top would have to cover a path that is never
-    // taken); inside the loop every consumed set lies wholly inside the range.
-    int m0 = 0;
-    while (m0 + 3 * NS < M) {
-        consume(ra, m0, false); issue(ra, m0 + 2 * NS);
-        consume(rb, m0 + NS, false); issue(rb, m0 + 3 * NS);
-        m0 += 2 * NS;
+    for (int t = 0; t < T; ++t) {
+        if (t & 1) bat_tile(C, r2, r3, r0, r1, acc[t], arow[t], arow[t + 1], t + 1 < T);
+        else bat_tile(C, r0, r1, r2, r3, acc[t], arow[t], arow[t + 1], t + 1 < T);
     }
-    const bool one_more = m0 + 2 * NS < M;
-    if (one_more) { consume(ra, m0, false); issue(ra, m0 + 2 * NS); }
-    if (one_more) { consume(rb, m0 + NS, true); consume(ra, m0 + 2 * NS, true); }
-    else { consume(ra, m0, true); consume(rb, m0 + NS, true); }
 }
 
 // accumulators of the 8 wavefronts -> LDS red[wave][tile][row in tile][sequence]
