@@ -90,20 +90,22 @@ def bench_block(args):
     else:
         lens = np.array([args.ctx], dtype=np.int32)
         cap = args.ctx + 1
-    w = synth.layer_weights(shape, seed, 0)
-    kv = synth.kv_cache(shape, seed, 0, lens, cap, batch, poison=False)
+    L = args.layers
+    ws = [synth.layer_weights(shape, seed, l) for l in range(L)]
     x = synth.x_input(shape, seed, batch)
     copies = []
     for _ in range(args.copies):
-        ds = DeviceStack(shape, cap, batch, 1)
-        ds.load_layer(0, w)
-        ds.load_kv(0, kv[0], kv[1], lens)
+        ds = DeviceStack(shape, cap, batch, L)
+        for l in range(L):
+            ds.load_layer(l, ws[l])
+            kv = synth.kv_cache(shape, seed, l, lens, cap, batch, poison=False)
+            ds.load_kv(l, kv[0], kv[1], lens)
         ds.set_inputs(x, lens)
         ds.set_options(mode=args.mode, grid=args.grid, threads=args.threads)
         ds.capture()
         copies.append(ds)
-    alg_bytes = cf.cfpp_algorithmic_bytes(copies[0].cfg, [int(v) for v in lens], 1)
-    footprint = args.copies * (cf.cfpp_packed_layer_bytes(copies[0].cfg) + cf.cfpp_kv_layer_bytes(copies[0].cfg))
+    alg_bytes = cf.cfpp_algorithmic_bytes(copies[0].cfg, [int(v) for v in lens], L)
+    footprint = args.copies * L * (cf.cfpp_packed_layer_bytes(copies[0].cfg) + cf.cfpp_kv_layer_bytes(copies[0].cfg))
     # every replay on ONE stream: the persistent kernels need the whole GPU to themselves
     one = copies[0].s
     for i in range(args.warmup):
@@ -122,10 +124,11 @@ def bench_block(args):
         ds.close()
     achieved = alg_bytes / (us * 1e-6) / 1e9
     print(json.dumps({
-        "metric": f"us_per_block_decode_{args.shape}_bs{batch}", "value": us, "unit": "us/block", "n_gpus": 1,
+        "metric": f"us_per_step_decode_{L}L_{args.shape}_bs{batch}", "value": us, "unit": "us/step", "n_gpus": 1,
+        "tokens_per_s": batch * 1e6 / us,
         "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "data": "synthetic",
         "dtype": "f16 weights/KV, f32 accumulate",
-        "config": {"workload": f"one {shape.name} block, batch {batch}, cached positions {[int(v) for v in lens]}, "
+        "config": {"workload": f"{L} {shape.name} block(s), batch {batch}, cached positions {[int(v) for v in lens]}, "
                                f"{args.copies} cop{'y' if args.copies == 1 else 'ies'} replayed in rotation "
                                f"({footprint / 1e6:.0f} MB of weights and caches)",
                    "launch_mode": args.mode, "copies": args.copies},
@@ -148,6 +151,7 @@ def main():
                     help="stack: the headline (32 layers, batch 1); block: one block, see --copies / --batch")
     ap.add_argument("--copies", type=int, default=1, help="block workload: copies replayed in rotation (cold when large)")
     ap.add_argument("--batch", type=int, default=1, help="block workload: sequences (ragged lengths 1024..8192 when > 1)")
+    ap.add_argument("--layers", type=int, default=1, help="block workload: blocks in a row (a stack of that many layers)")
     ap.add_argument("--shape", choices=["small", "2.8b", "6.9b"], default="2.8b",
                     help="model shape of the stack (the headline metric is quoted on 2.8b, ctx 4096)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")

@@ -20,7 +20,7 @@ def assert_block_close(got, want, what=""):
     return ma, rl
 
 
-def assert_fp16_rows_match(got, want, what=""):
+def assert_fp16_rows_match(got, want, what="", max_fraction=0.02):
     """Appended K/V rows: both sides round an fp32-or-better value to fp16, so
     they are equal except where the two accumulations straddle a rounding
     boundary; then they differ by one fp16 step."""
@@ -32,4 +32,4 @@ def assert_fp16_rows_match(got, want, what=""):
     # near zero an fp16 step is far below the fp32 accumulation error of an
     # O(1)-magnitude dot product, hence the small absolute term
     assert (np.abs(g.astype(np.float64) - w.astype(np.float64)) <= step + 1e-5).all(), f"{what}: more than one fp16 step apart"
-    assert diff.mean() <= 0.02, f"{what}: {diff.mean():.3%} of appended values differ"
+    assert diff.mean() <= max_fraction, f"{what}: {diff.mean():.3%} of appended values differ"

@@ -394,11 +394,24 @@ def test_sequential_form_is_refused_by_the_overlapping_modes():
     (TINY_STACK, 11, 2),                      # more sequences than one group of 8
 ])
 def test_batched_projections_on_the_matrix_cores(orc, shape, B, layers):
+    _batched_case(orc, shape, B, layers, synth.seq_lens(77, B, 3, 300))
+
+
+def test_batched_attention_split_with_extreme_lengths(orc):
+    """Sequences from an empty cache to thousands of positions in one group: the
+    attention launch gives every sequence at least one workgroup and the long
+    ones nearly all."""
+    # (single rows of 512 values: the share that lands on the other side of an fp16
+    # rounding boundary fluctuates more than in the long rows of the other cases -
+    # 4.3 % in one row here, the same row in every launch mode)
+    _batched_case(orc, TINY_STACK, 6, 2, np.array([0, 1, 3000, 17, 0, 1500], dtype=np.int32), max_fraction=0.06)
+
+
+def _batched_case(orc, shape, B, layers, lens, max_fraction=0.02):
     """Launch mode 0 with several sequences: the projections run once per group
     of up to 8 sequences (MFMA, activations split into fp16 head + remainder),
     the attention per sequence.  Every sequence against the oracle; the appended
     K/V rows; bit-identical reruns."""
-    lens = synth.seq_lens(77, B, 3, 300)
     cap = int(lens.max()) + 1
     print(f"[case] batched projections {shape.name} B={B} lens={list(lens)}", flush=True)
     from paper_2604_23553_amd.harness import DeviceStack
@@ -423,7 +436,7 @@ def test_batched_projections_on_the_matrix_cores(orc, shape, B, layers):
             assert_block_close(outs[0][b], ref16, f"sequence {b}")
             for l in range(layers):
                 kg, vg = ds.export_kv(l, b, int(lens[b]), 1)
-                assert_fp16_rows_match(kg[:, 0], Ks[l][:, lens[b]], f"sequence {b} layer {l} appended K")
-                assert_fp16_rows_match(vg[:, 0], Vs[l][:, lens[b]], f"sequence {b} layer {l} appended V")
+                assert_fp16_rows_match(kg[:, 0], Ks[l][:, lens[b]], f"sequence {b} layer {l} appended K", max_fraction)
+                assert_fp16_rows_match(vg[:, 0], Vs[l][:, lens[b]], f"sequence {b} layer {l} appended V", max_fraction)
     finally:
         ds.close()
