@@ -63,7 +63,23 @@ def cpu_baseline(shape, layers, kvs, x, S, n_layers_sample):
     if omp:
         cores = min(cores, int(omp))
     per_token_us = dt / n_eval * shape.n_layers * 1e6
+    # the same on one thread (two blocks are enough to time it)
+    single = None
+    try:
+        import ctypes
+        gomp = ctypes.CDLL("libgomp.so.1")
+        n_before = gomp.omp_get_max_threads()
+        gomp.omp_set_num_threads(1)
+        t1 = time.perf_counter()
+        cur = x0
+        for l in range(min(2, n_layers_sample)):
+            cur = orc.block_decode(shape, layers[l], Ks[l], Vs[l], S, cur)
+        single = (time.perf_counter() - t1) / min(2, n_layers_sample) * shape.n_layers * 1e6
+        gomp.omp_set_num_threads(n_before)
+    except OSError:
+        pass
     return {"value": per_token_us, "unit": "us/token", "cores": cores, "kind": "oracle",
+            "single_thread_us_per_token": single,
             "sample": f"layers 0..{n_layers_sample - 1} of the same {shape.n_layers}-layer workload, "
                       f"{n_eval} block evaluations in {dt:.1f} s (fp64 C oracle, OpenMP over rows/heads), "
                       f"scaled to {shape.n_layers} layers per token",
