@@ -210,7 +210,13 @@ cfpp_status cfpp_get_option(const cfpp_ctx *ctx, int32_t option, int64_t *value)
  *                  An out-of-range value makes the kernels skip the step and
  *                  raise the context's device error flag (cfpp_device_error).
  *   out          : DEVICE fp16 [batch, hidden] block output; must not alias x
- * Asynchronous on `stream`. */
+ * Asynchronous on `stream`.
+ * The sequences are independent and share the weights.  Launch mode 0 with
+ * batch > 1 streams the weights once per group of up to 8 sequences (the
+ * projections run on the matrix cores; needs 512 threads, hidden and ffn
+ * multiples of 256, at most 64 matrix rows per workgroup, else - and in the
+ * other launch modes - the sequences run one after the other).  With several
+ * sequences a bad position in any of a group skips the whole group's step. */
 cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer, void *kv_layer,
                               const void *x, const int32_t *pos_dev, int32_t batch,
                               void *out, cfpp_stream stream);
