@@ -440,3 +440,22 @@ def _batched_case(orc, shape, B, layers, lens, max_fraction=0.02):
                 assert_fp16_rows_match(vg[:, 0], Vs[l][:, lens[b]], f"sequence {b} layer {l} appended V", max_fraction)
     finally:
         ds.close()
+
+
+def test_batched_path_reports_a_bad_position():
+    from paper_2604_23553_amd import CfppError
+    B, cap = 3, 20
+    ds, ws, kvs = build_stack(TINY_STACK, 61, np.array([5, 6, 7], dtype=np.int32), cap, batch=B)
+    try:
+        ds.set_options(mode=0)
+        x = synth.x_input(TINY_STACK, 61, B)
+        ds.set_inputs(x, np.array([5, cap, 7], dtype=np.int32))      # the middle one is outside the cache
+        ds.stack_decode()
+        with pytest.raises(CfppError):
+            ds.check()
+        ds.set_inputs(x, np.array([5, 6, 7], dtype=np.int32))        # and the context works again afterwards
+        ds.stack_decode()
+        ds.check()
+        assert np.isfinite(ds.result().astype(np.float32)).all()
+    finally:
+        ds.close()
