@@ -401,16 +401,23 @@ struct LnPair {
 
     __device__ __forceinline__ void finish(const StepParams &P, float *y1, float *y2, float *red, int tid)
     {
-        const Dims &dm = P.dm;
-        const int h = dm.h, nt = blockDim.x;
-        const int Kp = round_up_chunk(h);
-        const int ngrp = h >> 3, ngrp_p = Kp >> 3;
+        const int h = P.dm.h;
         float s = 0.f;
 #pragma unroll
         for (int j = 0; j < GU; ++j)
 #pragma unroll
             for (int e = 0; e < 8; ++e) s += xv[j][e];
         const float mean = block_sum(s, red, tid) / (float)h;
+        finish_with_mean(P, y1, y2, red, mean, tid);
+    }
+
+    // the same with the mean already known (second pass and the affine part)
+    __device__ __forceinline__ void finish_with_mean(const StepParams &P, float *y1, float *y2, float *red, float mean,
+                                                     int tid)
+    {
+        const Dims &dm = P.dm;
+        const int h = dm.h, nt = blockDim.x;
+        const int ngrp = h >> 3;
         float v = 0.f;
 #pragma unroll
         for (int j = 0; j < GU; ++j) {
@@ -424,6 +431,16 @@ struct LnPair {
         }
         const float var = block_sum(v, red, tid) / (float)h;
         const float inv = 1.0f / sqrtf(var + dm.ln_eps);
+        apply(P, y1, y2, mean, inv, tid);
+    }
+
+    // the two normalised vectors into LDS (GEMV order, zero padded to whole units),
+    // given the statistics of the loaded input
+    __device__ __forceinline__ void apply(const StepParams &P, float *y1, float *y2, float mean, float inv, int tid)
+    {
+        const int h = P.dm.h, nt = blockDim.x;
+        const int Kp = round_up_chunk(h);
+        const int ngrp = h >> 3, ngrp_p = Kp >> 3;
 #pragma unroll
         for (int j = 0; j < GU; ++j) {
             const int gi = tid + j * nt;

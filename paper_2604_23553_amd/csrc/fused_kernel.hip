@@ -40,7 +40,7 @@ constexpr int kStageMStream = 22;   // float2 per streaming thread when staging 
 
 // LDS of the fused kernel, in floats
 struct FusedLds {
-    unsigned y1, y2, ml, ol, xs, pq, pu, pd, pc, red, qs, kn, vn, wp, wm, wl, ctr, total;
+    unsigned y1, y2, ml, ol, xs, pq, pu, pd, pc, red, qs, kn, vn, wp, wm, wl, ctr, mu, total;
 };
 
 static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qkv, int rows_up, int rows_h, int nw)
@@ -59,6 +59,7 @@ static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qk
     L.wp = take((unsigned)(kFusedSegs * kFusedSlots * dm.d));
     L.wm = take(kFusedSegs * kFusedSlots); L.wl = take(kFusedSegs * kFusedSlots);
     L.ctr = take(4);
+    L.mu = take(4);                                       // mean of the layer input (from the chain wavefront)
     L.total = o;
     return L;
 }
@@ -86,9 +87,15 @@ __device__ __forceinline__ void fused_prologue(const FusedCtx &C, const __half *
     LnPair ln;
     ln.load_params(P, w, tid);
     __syncthreads();                                       // Sx: the layer input is complete
-    if (layer == 0) ln.load_x_global(P, io, tid);
-    else ln.load_x_lds(P, C.lds + C.L.xs, tid);
-    ln.finish(P, C.lds + C.L.y1, C.lds + C.L.y2, C.lds + C.L.red, tid);
+    if (layer == 0) {
+        ln.load_x_global(P, io, tid);
+        ln.finish(P, C.lds + C.L.y1, C.lds + C.L.y2, C.lds + C.L.red, tid);
+    } else {
+        // (the chain wavefront had every element in registers and left the mean behind the input)
+        ln.load_x_lds(P, C.lds + C.L.xs, tid);
+        const float mean = C.lds[C.L.mu];
+        ln.finish_with_mean(P, C.lds + C.L.y1, C.lds + C.L.y2, C.lds + C.L.red, mean, tid);
+    }
     clear_partials(C.lds + C.L.pq, (int)(C.L.red - C.L.pq), tid);
 }
 
@@ -286,6 +293,7 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
             float *xs = lds + C.L.xs;
             PollGuard pg;
             pg.start(P.sync);
+            float xsum = 0.f;                              // for the mean of both LayerNorms
             for (int base = 0; base < h; base += SB * 64) {
                 float2 wd[SB];
                 bool ok;
@@ -304,9 +312,13 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
 #pragma unroll
                 for (int j2 = 0; j2 < SB; ++j2) {
                     const int i2 = base + j2 * 64 + lane;
-                    if (i2 < h) xs[i2] = wd[j2].x;
+                    if (i2 < h) { xs[i2] = wd[j2].x; xsum += wd[j2].x; }
                 }
             }
+            // (the variance stays with all wavefronts: a second pass here, on the path every
+            // other wavefront waits for, costs more than the workgroup-wide sum it would save)
+            xsum = wave_sum(xsum);
+            if (lane == 0) lds[C.L.mu] = xsum / (float)h;
         }
         tr.mark(2);
         if ((P.debug & 32) && lane == 0 && layer == L - 1) P.trace[blockIdx.x * 8 + 7] = wall_clock64();
