@@ -121,7 +121,11 @@ cfpp_status cfpp_algorithmic_bytes(const cfpp_config *cfg, const int32_t *pos_ho
  * read: one blob with the LayerNorm parameters, the biases, and the four
  * matrices stored row-major so that a wavefront reads 1 KiB contiguous per
  * load; the QKV rows of each head are reordered so that the two rows of a
- * rotary pair (i, i + r/2) are adjacent.  packed_dst: DEVICE,
+ * rotary pair (i, i + r/2) are adjacent.  Behind the tensors the blob carries
+ * two fp32 values per row of the QKV and MLP-up matrices, computed here from
+ * the packed tensors (s = W gamma, c = W beta + b of the LayerNorm in front of
+ * the matrix, paper Sec. 2.2): the whole-stack kernel multiplies by gamma * x
+ * and completes the LayerNorm in the epilogue with them.  packed_dst: DEVICE,
  * cfpp_packed_layer_bytes(cfg) bytes. */
 cfpp_status cfpp_pack_layer(const cfpp_config *cfg, const cfpp_layer_src *src,
                             void *packed_dst, cfpp_stream stream);

@@ -503,7 +503,8 @@ static cfpp_status check_fused(const cfpp_ctx *ctx, const Shape &sh, const StepP
     if (!fused_supported(ctx->dm, P, sh.grid, sh.threads))
         return fail(CFPP_EUNSUPPORTED,
                     "mode 2 needs grid >= n_heads, at most 64 rows of the hidden-size matrices per workgroup, "
-                    "hidden <= 4096 and head_dim 64, 80 or 128; use mode 0 for this shape");
+                    "hidden <= 4096, hidden and ffn multiples of 512 and head_dim 64, 80 or 128; use mode 0 for "
+                    "this shape");
     const size_t lds = fused_lds_bytes(ctx->dm, P, sh.threads);
     if (lds > 160 * 1024) return fail(CFPP_EUNSUPPORTED, "mode 2 needs %zu bytes of LDS (> 160 KiB)", lds);
     int per_cu = 0;

@@ -12,6 +12,14 @@
 //   down rows  (stay inside the workgroup)
 //   dense rows -> next layer's input   ... the one exposed hand-over per layer
 //
+// Nothing but that hand-over stands between two layers: the QKV and MLP-up rows
+// run on gamma * x, which needs no statistics, and the LayerNorm itself (paper
+// Sec. 2.2) is completed in their epilogues from two constants per row that the
+// packing derived (PackedLayout::rc_qkv, rc_up):
+//   W (gamma (x - mu) inv + beta) + b = inv (W (gamma x) - mu s) + c.
+// Mean and variance (two passes, biased) are worked out by the chain wavefront
+// while the QKV rows stream.
+//
 // Wavefront 0 of every workgroup is the "chain" wavefront: it finishes rows
 // (biases, rotary, GELU, residual), publishes them, drives the four grid
 // barriers (one per hand-over, each independent) and stages the small vectors
@@ -40,7 +48,7 @@ constexpr int kStageMStream = 22;   // float2 per streaming thread when staging 
 
 // LDS of the fused kernel, in floats
 struct FusedLds {
-    unsigned y1, y2, ml, ol, xs, pq, pu, pd, pc, red, qs, kn, vn, wp, wm, wl, ctr, mu, total;
+    unsigned y1, y2, ml, ol, xs, pq, pu, pd, pc, pset, qs, kn, vn, wp, wm, wl, ctr, total;
 };
 
 static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qkv, int rows_up, int rows_h, int nw)
@@ -53,13 +61,15 @@ static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qk
     L.y1 = take(Kph); L.y2 = take(Kph); L.ml = take(Kpf); L.ol = take(Kph); L.xs = take(Kph);
     L.pq = take((unsigned)(rows_qkv * nw)); L.pu = take((unsigned)(rows_up * nw));
     L.pd = take((unsigned)(rows_h * nw)); L.pc = take((unsigned)(rows_h * nw));
-    L.red = take(16);
+    // one set of partial-sum slots; a second set follows (layers alternate, so that the
+    // next layer's slots can be cleared while this layer's are still being read)
+    L.pset = o - L.pq;
+    o += L.pset;
     L.qs = take((unsigned)(kFusedSegs * dm.d));
     L.kn = take((unsigned)(kFusedSegs * dm.d / 2)); L.vn = take((unsigned)(kFusedSegs * dm.d / 2));
     L.wp = take((unsigned)(kFusedSegs * kFusedSlots * dm.d));
     L.wm = take(kFusedSegs * kFusedSlots); L.wl = take(kFusedSegs * kFusedSlots);
     L.ctr = take(4);
-    L.mu = take(4);                                       // mean of the layer input (from the chain wavefront)
     L.total = o;
     return L;
 }
@@ -75,28 +85,64 @@ struct FusedCtx {
     float *xt, *ot, *pt;            // tagged words: layer outputs [2][h], attention output [h], split-KV partials
 };
 
-// first part of every layer, both roles: the two LayerNorms into LDS and the
-// partial-sum slots of the four GEMVs cleared.  The parameters are requested
-// ahead of the workgroup barrier behind which the layer input is known to be
-// there (for layers > 0 the chain wavefront has put it into LDS); four more
-// barriers inside, and the caller adds one after it.
-__device__ __forceinline__ void fused_prologue(const FusedCtx &C, const __half *w, const LayerIO &io, int layer,
-                                               int tid)
+// First part of every layer, all wavefronts: the layer input into LDS - as it is
+// (for the statistics) and multiplied by the weights of the two LayerNorms, in
+// GEMV order (the inputs of the QKV and MLP-up rows).  The wavefronts take
+// 64-element pieces of the vector in turn.  Layer 0 reads the step's input;
+// later layers read the previous layer's output, which travels as tagged words:
+// every wavefront re-reads its pieces until each word carries this layer's
+// epoch - one round trip after the last workgroup stored its rows.  The caller
+// places a workgroup barrier behind it.
+__device__ __forceinline__ void fused_input(const FusedCtx &C, const __half *w, int layer, int tid)
 {
+    constexpr int JB = 8;                                  // pieces per wavefront and pass
     const StepParams &P = *C.P;
-    LnPair ln;
-    ln.load_params(P, w, tid);
-    __syncthreads();                                       // Sx: the layer input is complete
-    if (layer == 0) {
-        ln.load_x_global(P, io, tid);
-        ln.finish(P, C.lds + C.L.y1, C.lds + C.L.y2, C.lds + C.L.red, tid);
-    } else {
-        // (the chain wavefront had every element in registers and left the mean behind the input)
-        ln.load_x_lds(P, C.lds + C.L.xs, tid);
-        const float mean = C.lds[C.L.mu];
-        ln.finish_with_mean(P, C.lds + C.L.y1, C.lds + C.L.y2, C.lds + C.L.red, mean, tid);
+    const int h = P.dm.h, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int step = C.nw * 64;
+    const __half *g1 = w + P.lay.ln1_g, *g2 = w + P.lay.ln2_g;
+    float *xs = C.lds + C.L.xs, *y1 = C.lds + C.L.y1, *y2 = C.lds + C.L.y2;
+    const float *xt = C.xt + 2 * (size_t)((layer + 1) & 1) * h;      // written by layer - 1
+    const unsigned want = C.E0 + (unsigned)layer;
+    PollGuard pg;
+    pg.start(P.sync);
+    for (int e0 = wave * 64; e0 < h; e0 += JB * step) {
+        float ga[JB], gb[JB], xv[JB];
+#pragma unroll
+        for (int j = 0; j < JB; ++j) {
+            const int i = e0 + j * step + lane;
+            ga[j] = 0.f; gb[j] = 0.f; xv[j] = 0.f;
+            if (e0 + j * step < h) {
+                ga[j] = __half2float(g1[i]);
+                gb[j] = __half2float(g2[i]);
+                if (layer == 0) xv[j] = __half2float(P.x_in[i]);
+            }
+        }
+        if (layer > 0) {
+            bool ok;
+            do {
+                ok = true;
+#pragma unroll
+                for (int j = 0; j < JB; ++j) {
+                    if (e0 + j * step < h) {
+                        const float2 wd = xwg_load2(xt + 2 * (e0 + j * step + lane));
+                        xv[j] = wd.x;
+                        ok = ok && __float_as_uint(wd.y) == want;
+                    }
+                }
+                ok = __all(ok);
+            } while (!ok && !pg.give_up());
+        }
+#pragma unroll
+        for (int j = 0; j < JB; ++j) {
+            const int i = e0 + j * step + lane;
+            if (e0 + j * step < h) {
+                xs[i] = xv[j];
+                y1[lds_perm(i)] = ga[j] * xv[j];
+                y2[lds_perm(i)] = gb[j] * xv[j];
+            }
+        }
     }
-    clear_partials(C.lds + C.L.pq, (int)(C.L.red - C.L.pq), tid);
 }
 
 // segments (head, rows) of this workgroup's attention share
@@ -132,7 +178,6 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
     const int h = dm.h, f = dm.f, L = P.n_layers, nw = C.nw, NS = nw - 1;
     float *lds = C.lds;
     float *y1 = lds + C.L.y1, *y2 = lds + C.L.y2, *ml = lds + C.L.ml, *ol = lds + C.L.ol;
-    float *pq = lds + C.L.pq, *pu = lds + C.L.pu, *pd = lds + C.L.pd, *pc = lds + C.L.pc;
     const int n_tok = C.pos + 1;
 
     GemvSpan<kGemvU> gsQ, gsU, gsD, gsC;
@@ -153,11 +198,13 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
         const int lane = tid & 63, si = gsQ.wave - 1;
         const __half *w = C.ptrs->w[layer];
         const __half *kv = C.ptrs->kv[layer];
-        const LayerIO io = layer_io(P, layer);
         tr.n = layer == (((P.debug >> 20) & 255) ? ((P.debug >> 20) & 255) - 1 : L - 1) ? 0 : kTraceLen;   // the traced layer
+        // this layer's set of partial-sum slots
+        const unsigned set = (unsigned)(layer & 1) * C.L.pset;
+        float *pq = lds + C.L.pq + set, *pu = lds + C.L.pu + set, *pd = lds + C.L.pd + set, *pc = lds + C.L.pc + set;
         tr.mark(1);
-        fused_prologue(C, w, io, layer, tid);
-        __syncthreads();                                   // S0
+        fused_input(C, w, layer, tid);
+        __syncthreads();                                   // S0: the layer input is in LDS
         tr.mark(3);
 
         gsU.init(GemvSeg{w + P.lay.w_up + (size_t)C.u_begin * h, y2, h, C.u_n}, GemvSeg{w + P.lay.w_up, y2, h, 0},
@@ -248,6 +295,11 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
         tr.mark(23);
         __syncthreads();                                   // S6: dense rows done
         tr.mark(24);
+        {
+            // the next layer's partial-sum slots (the chain wavefront still reads this layer's)
+            float *nx = lds + C.L.pq + (C.L.pset - set);
+            for (int i = tid - 64; i < (int)C.L.pset; i += NS * 64) nx[i] = 0.f;
+        }
     }
 }
 
@@ -261,7 +313,6 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
     const int h = dm.h, d = dm.d, r = dm.r, L = P.n_layers, nw = C.nw, NS = nw - 1;
     float *lds = C.lds;
     float *ol = lds + C.L.ol;
-    const float *pq = lds + C.L.pq, *pu = lds + C.L.pu, *pd = lds + C.L.pd, *pc = lds + C.L.pc;
     const int pos = C.pos, n_tok = pos + 1;
     const int q_begin = C.q_begin, q_n = C.q_n, u_begin = C.u_begin, u_n = C.u_n, r_begin = C.r_begin, r_n = C.r_n;
 
@@ -284,59 +335,31 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
         const LayerIO io = layer_io(P, layer);
         const bool last_layer = layer == L - 1;
         tr.n = layer == (((P.debug >> 20) & 255) ? ((P.debug >> 20) & 255) - 1 : L - 1) ? 0 : kTraceLen;   // the traced layer
+        const unsigned set = (unsigned)(layer & 1) * C.L.pset;   // this layer's partial-sum slots
+        const float *pq = lds + C.L.pq + set, *pu = lds + C.L.pu + set, *pd = lds + C.L.pd + set, *pc = lds + C.L.pc + set;
         tr.mark(1);
-        if (layer > 0) {
-            // the previous layer's output, tagged: re-read until every word is current, then into LDS
-            constexpr int SB = 40;
-            const float *xt = C.xt + 2 * (size_t)((layer - 1) & 1) * h;
-            const unsigned want = C.E0 + (unsigned)layer;
-            float *xs = lds + C.L.xs;
-            PollGuard pg;
-            pg.start(P.sync);
-            float xsum = 0.f;                              // for the mean of both LayerNorms
-            for (int base = 0; base < h; base += SB * 64) {
-                float2 wd[SB];
-                bool ok;
-                do {
-#pragma unroll
-                    for (int j2 = 0; j2 < SB; ++j2) {
-                        const int i2 = base + j2 * 64 + lane;
-                        wd[j2] = xwg_load2(xt + 2 * (i2 < h ? i2 : 0));
-                    }
-                    ok = true;
-#pragma unroll
-                    for (int j2 = 0; j2 < SB; ++j2)
-                        ok = ok && (base + j2 * 64 + lane >= h || __float_as_uint(wd[j2].y) == want);
-                    ok = __all(ok);
-                } while (!ok && !pg.give_up());
-#pragma unroll
-                for (int j2 = 0; j2 < SB; ++j2) {
-                    const int i2 = base + j2 * 64 + lane;
-                    if (i2 < h) { xs[i2] = wd[j2].x; xsum += wd[j2].x; }
-                }
-            }
-            // (the variance stays with all wavefronts: a second pass here, on the path every
-            // other wavefront waits for, costs more than the workgroup-wide sum it would save)
-            xsum = wave_sum(xsum);
-            if (lane == 0) lds[C.L.mu] = xsum / (float)h;
-        }
+        fused_input(C, w, layer, tid);
         tr.mark(2);
         if ((P.debug & 32) && lane == 0 && layer == L - 1) P.trace[blockIdx.x * 8 + 7] = wall_clock64();
-        fused_prologue(C, w, io, layer, tid);
-        __syncthreads();                                   // S0
+        __syncthreads();                                   // S0: the layer input is in LDS
         tr.mark(3);
 
-        // what the epilogues add to this lane's first rows: requested now, used behind the GEMVs
-        const __half *bq = w + P.lay.b_qkv, *bu = w + P.lay.b_up, *bdn = w + P.lay.b_down, *bde = w + P.lay.b_dense;
-        float bq0 = 0.f, bq1 = 0.f, bu0 = 0.f, bdn0 = 0.f, bde0 = 0.f;
+        // what the epilogues need for this lane's first rows: requested now, used behind the GEMVs
+        // (rcq: the constants (s, c) of two adjacent packed QKV rows; rcu: of one MLP-up row)
+        const float4 *rcq = reinterpret_cast<const float4 *>(w + P.lay.rc_qkv) + (q_begin >> 1);
+        const float2 *rcu = reinterpret_cast<const float2 *>(w + P.lay.rc_up) + u_begin;
+        const __half *bdn = w + P.lay.b_down, *bde = w + P.lay.b_dense;
+        float4 rq0 = {0.f, 0.f, 0.f, 0.f};
+        float2 ru0 = {0.f, 0.f};
+        float bdn0 = 0.f, bde0 = 0.f;
         float2 cs0 = {1.f, 0.f};
         if (lane < q_n / 2) {
             const int p = q_begin + 2 * lane;
             const int i = p % d, c = (p / d) % 3;
-            bq0 = __half2float(bq[p]); bq1 = __half2float(bq[p + 1]);
+            rq0 = rcq[lane];
             if (c < 2 && i < r) cs0 = P.rope[(size_t)pos * (r >> 1) + (i >> 1)];
         }
-        if (lane < u_n) bu0 = __half2float(bu[u_begin + lane]);
+        if (lane < u_n) ru0 = rcu[lane];
         if (lane < r_n) {
             bdn0 = __half2float(bdn[r_begin + lane]);
             bde0 = __half2float(bde[r_begin + lane]);
@@ -346,6 +369,24 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
         ac.init(P, kv, n_tok, lane);
         FusedSegs<D> sg;
         sg.init(ac);
+        // mean and 1 / sqrt(variance + eps) of the layer input: both LayerNorms share them
+        float mean, inv;
+        {
+            const float *xs = lds + C.L.xs;
+            float sum = 0.f;
+            for (int i = lane * 4; i < h; i += 256) {
+                const float4 v = *reinterpret_cast<const float4 *>(xs + i);
+                sum += (v.x + v.y) + (v.z + v.w);
+            }
+            mean = wave_sum(sum) / (float)h;
+            float sq = 0.f;
+            for (int i = lane * 4; i < h; i += 256) {
+                const float4 v = *reinterpret_cast<const float4 *>(xs + i);
+                const float d0 = v.x - mean, d1 = v.y - mean, d2 = v.z - mean, d3 = v.w - mean;
+                sq += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+            }
+            inv = 1.0f / sqrtf(wave_sum(sq) / (float)h + dm.ln_eps);
+        }
 
         __syncthreads();                                   // S1: QKV rows done
         tr.mark(5);
@@ -355,14 +396,14 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
             const int pdv = p / d, i = p - pdv * d;         // i even
             const int n = pdv / 3, c = pdv - 3 * n;
             const bool rotary = c < 2 && i < r;             // rotary pair (j, j + r/2)
-            float b0 = bq0, b1v = bq1;
+            float4 rq = rq0;
             float2 cs = cs0;
             if (pr != lane) {
-                b0 = __half2float(bq[p]); b1v = __half2float(bq[p + 1]);
+                rq = rcq[pr];
                 if (rotary) cs = P.rope[(size_t)pos * (r >> 1) + (i >> 1)];
             }
-            float v0 = rt.row_total(pq, 2 * pr) + b0;
-            float v1 = rt.row_total(pq, 2 * pr + 1) + b1v;
+            float v0 = inv * (rt.row_total(pq, 2 * pr) - mean * rq.x) + rq.y;
+            float v1 = inv * (rt.row_total(pq, 2 * pr + 1) - mean * rq.z) + rq.w;
             int d0 = i, d1 = i + 1;
             if (rotary) {
                 const int j = i >> 1;
@@ -412,8 +453,8 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
         __syncthreads();                                   // S2: up rows done
         tr.mark(10);
         for (int t = lane; t < u_n; t += 64) {
-            const float b = t == lane ? bu0 : __half2float(bu[u_begin + t]);
-            xwg_store(P.m + u_begin + t, gelu_act(rt.row_total(pu, t) + b, dm.flags));
+            const float2 ru = t == lane ? ru0 : rcu[t];
+            xwg_store(P.m + u_begin + t, gelu_act(inv * (rt.row_total(pu, t) - mean * ru.x) + ru.y, dm.flags));
         }
         b2.arrive_wave();
         b2.wait_wave();                                    // GELU(up) is complete everywhere
@@ -517,6 +558,7 @@ k_stack_fused(StepParams P, const LayerPtrs *__restrict__ ptrs)
     C.ot = P.tagged + 2 * (size_t)5 * dm.h;
     C.pt = P.tagged + 2 * (size_t)6 * dm.h;
     if (threadIdx.x == 0) reinterpret_cast<int *>(lds)[C.L.ctr] = 0;    // (a workgroup barrier follows in both roles)
+    clear_partials(lds + C.L.pq, (int)C.L.pset, threadIdx.x);          // layer 0's partial-sum slots
     if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0) fused_chain<D>(C, ptrs->kv);
     else fused_stream<D>(C);
 }
@@ -529,10 +571,11 @@ size_t fused_lds_bytes(const Dims &dm, const StepParams &P, int threads)
 
 // grid >= heads (a workgroup's attention share then covers at most two heads),
 // at most 64 rows of the h-row matrices per workgroup (one lane each in the
-// chain wavefront), and at most 8 streaming wavefronts
+// chain wavefront), at most 8 streaming wavefronts, and rows of whole 512-weight
+// units (the streaming wavefronts' balanced split)
 bool fused_supported(const Dims &dm, const StepParams &P, int grid, int threads)
 {
-    return grid >= dm.H && P.rows_h <= 64 && dm.h <= 4096 &&
+    return grid >= dm.H && P.rows_h <= 64 && dm.h <= 4096 && dm.h % kChunk == 0 && dm.f % kChunk == 0 &&
            (size_t)dm.f <= (size_t)2 * kStageMStream * 64 * (threads / 64 - 1) && threads / 64 - 1 <= kFusedSlots && threads >= 128 &&
            (dm.d == 64 || dm.d == 80 || dm.d == 128);
 }

@@ -32,11 +32,17 @@ enum { kPartQkv = 1, kPartUp = 2, kPartAttention = 4, kPartDown = 8, kPartDense 
 
 // Offsets (in fp16 elements) of every section of a packed layer.  Each section
 // starts on a 256-byte boundary.  Matrices are row-major [rows][cols]; w_qkv and
-// b_qkv use the packed row order (see qkv_packed_to_canonical).
+// b_qkv use the packed row order (see qkv_packed_to_canonical).  Behind the
+// tensors themselves sit two fp32 constants per row of the QKV and MLP-up
+// matrices, derived from them when the layer is packed: with them a kernel can
+// run those products on gamma * x before the LayerNorm statistics are known,
+//   W (gamma * (x - mu) * inv + beta) + b = inv * (W (gamma * x) - mu * s) + c,
+//   s = W gamma,  c = W beta + b   (rc_* holds (s, c) per packed row).
 struct PackedLayout {
     size_t ln1_g, ln1_b, ln2_g, ln2_b;
     size_t b_qkv, b_dense, b_up, b_down;
     size_t w_qkv, w_up, w_down, w_dense;
+    size_t rc_qkv, rc_up;   // per-row constants, float2 each (4 fp16 elements per row): see launch_pack_layer
     size_t total;   // fp16 elements
 };
 
@@ -51,6 +57,8 @@ CFPP_HD PackedLayout packed_layout(int h, int f)
     L.w_up = take((size_t)f * h);
     L.w_down = take((size_t)h * f);
     L.w_dense = take((size_t)h * h);
+    L.rc_qkv = take(4 * 3 * (size_t)h);
+    L.rc_up = take(4 * (size_t)f);
     L.total = o;
     return L;
 }

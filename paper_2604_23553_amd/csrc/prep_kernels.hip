@@ -1,7 +1,7 @@
 // One-time data preparation kernels: packing a block's canonical tensors into
 // the streaming layout, and moving KV rows between the canonical layout
-// [n_heads, capacity, head_dim] and the slabbed cache layout.  Pure data
-// movement, off the hot path.
+// [n_heads, capacity, head_dim] and the slabbed cache layout.  Data movement
+// and the per-row constants derived from the packed tensors, off the hot path.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include "decode_params.h"
@@ -32,6 +32,29 @@ __global__ void k_copy_vec(const __half *__restrict__ src, __half *__restrict__ 
         dst[i] = src[qkv_d ? qkv_packed_to_canonical_row(i, qkv_d, qkv_r) : i];
 }
 
+// rc[p] = (sum_j W[p][j] gamma[j],  sum_j W[p][j] beta[j] + bias[p]) for every row of a
+// packed matrix: one wavefront per row, fp64 sums in a fixed order, rounded once to fp32
+__global__ void __launch_bounds__(256) k_row_constants(const __half *__restrict__ W, const __half *__restrict__ gamma,
+                                                        const __half *__restrict__ beta, const __half *__restrict__ bias,
+                                                        float2 *__restrict__ rc, int rows, int K)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const __half *wr = W + (size_t)row * K;
+    double s = 0.0, c = 0.0;
+    for (int j = lane; j < K; j += 64) {
+        const double wv = (double)__half2float(wr[j]);
+        s += wv * (double)__half2float(gamma[j]);
+        c += wv * (double)__half2float(beta[j]);
+    }
+    for (int m = 32; m > 0; m >>= 1) {
+        s += __shfl_xor(s, m, 64);
+        c += __shfl_xor(c, m, 64);
+    }
+    if (lane == 0) rc[row] = float2{(float)s, (float)(c + (double)__half2float(bias[row]))};
+}
+
 hipError_t launch_pack_layer(const Dims &dm, const PackedLayout &lay, const void *const src[12],
                              __half *dst, hipStream_t s)
 {
@@ -51,6 +74,14 @@ hipError_t launch_pack_layer(const Dims &dm, const PackedLayout &lay, const void
     mat(6, lay.w_dense, h, h, false); vec(7, lay.b_dense, h, false);
     mat(8, lay.w_up, f, h, false); vec(9, lay.b_up, f, false);
     mat(10, lay.w_down, h, f, false); vec(11, lay.b_down, h, false);
+    // the row constants of the two products that follow a LayerNorm, from the packed copies
+    // (same stream: behind the copies above)
+    auto consts = [&](size_t w_off, size_t g_off, size_t b_off, size_t bias_off, size_t rc_off, int rows) {
+        hipLaunchKernelGGL(k_row_constants, dim3((rows + 3) / 4), dim3(256), 0, s, dst + w_off, dst + g_off,
+                           dst + b_off, dst + bias_off, reinterpret_cast<float2 *>(dst + rc_off), rows, h);
+    };
+    consts(lay.w_qkv, lay.ln1_g, lay.ln1_b, lay.b_qkv, lay.rc_qkv, 3 * h);
+    consts(lay.w_up, lay.ln2_g, lay.ln2_b, lay.b_up, lay.rc_up, f);
     return hipGetLastError();
 }
 

@@ -97,3 +97,41 @@ def test_odd_shapes(orc, shape):
 
 def test_last_slot_of_the_cache(orc):
     check_block(orc, synth.SMALL_BLOCK, 3, 95, 96, mode=0)
+
+
+def test_packed_row_constants():
+    """Behind the tensors a packed layer carries, per row of the QKV and MLP-up
+    matrices, s = W gamma and c = W beta + b of the LayerNorm in front of them
+    (the whole-stack kernel completes the LayerNorm with them in the epilogue).
+    They are checked here against the plain products in float64; the QKV rows
+    are in the packed order the header documents (per head q | k | v, rotary
+    pair (j, j + r/2) adjacent)."""
+    from paper_2604_23553_amd.harness import DeviceStack
+    shape = synth.ModelShape(640, 8, 80, 20, 2048, name="d80-h640")
+    h, f, d, r = shape.hidden, shape.ffn, shape.head_dim, shape.rotary_dims
+    w = synth.layer_weights(shape, 11, 0)
+    print("[case] packed row constants", flush=True)
+    ds = DeviceStack(shape, 16, 1, 1)
+    try:
+        ds.load_layer(0, w)
+        blob = ds.packed[0].cpu().numpy()
+    finally:
+        ds.close()
+    up256 = lambda n: (n + 255) // 256 * 256
+    off_up = blob.size - up256(8 * f)
+    off_qkv = off_up - up256(8 * 3 * h)
+    rc_qkv = blob[off_qkv:off_qkv + 8 * 3 * h].view(np.float32).reshape(3 * h, 2)
+    rc_up = blob[off_up:off_up + 8 * f].view(np.float32).reshape(f, 2)
+    f64 = lambda a: a.astype(np.float64)
+    rows = np.empty(3 * h, dtype=np.int64)
+    for p in range(3 * h):
+        n, rem = divmod(p, 3 * d)
+        c, i = divmod(rem, d)
+        dim = ((i >> 1) + (r >> 1 if i & 1 else 0)) if (c < 2 and i < r) else i
+        rows[p] = (3 * n + c) * d + dim
+    Wq = f64(w["w_qkv"])[rows]
+    want_q = np.stack([Wq @ f64(w["ln1_g"]), Wq @ f64(w["ln1_b"]) + f64(w["b_qkv"])[rows]], axis=1)
+    Wu = f64(w["w_up"])
+    want_u = np.stack([Wu @ f64(w["ln2_g"]), Wu @ f64(w["ln2_b"]) + f64(w["b_up"])], axis=1)
+    assert np.allclose(rc_qkv, want_q, rtol=1e-6, atol=1e-7)
+    assert np.allclose(rc_up, want_u, rtol=1e-6, atol=1e-7)

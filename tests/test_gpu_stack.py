@@ -387,6 +387,27 @@ def test_sequential_form_is_refused_by_the_overlapping_modes():
         ds.close()
 
 
+def test_whole_stack_kernel_refuses_rows_of_partial_units():
+    """Launch mode 2 splits rows over its streaming wavefronts in whole 512-weight
+    units: a hidden size that is not a multiple of 512 is refused (mode 0 runs it)."""
+    from paper_2604_23553_amd import CfppError
+    shape = synth.ModelShape(640, 8, 80, 20, 2048, n_layers=2, name="d80-h640-x2")
+    S = 10
+    ds, ws, kvs = build_stack(shape, 43, S, 12)
+    try:
+        x = synth.x_input(shape, 2)
+        ds.set_inputs(x, S)
+        ds.set_options(mode=2)
+        with pytest.raises(CfppError) as e:
+            ds.stack_decode()
+        assert e.value.status == -2
+        ds.set_options(mode=0)
+        ds.stack_decode()
+        ds.check()
+    finally:
+        ds.close()
+
+
 @pytest.mark.parametrize("shape,B,layers", [
     (TINY_STACK, 8, 4),
     (synth.ModelShape(2560, 32, 80, 20, 10240, n_layers=2, name="pythia-2.8b-x2"), 5, 2),

@@ -44,8 +44,9 @@ def test_sizes_and_algorithmic_bytes(shape, max_seq, weights, kv_read):
     assert cf.cfpp_validate_config(cfg) == 0
     h, f = shape.hidden, shape.ffn
     assert (12 * h * h + 13 * h) * 2 == weights
-    # every section of the packed blob is 256-byte aligned; for these shapes no padding is needed
-    assert cf.cfpp_packed_layer_bytes(cfg) == weights
+    # every section of the packed blob is 256-byte aligned; for these shapes no padding is needed.
+    # Behind the tensors: two fp32 constants per row of the QKV and MLP-up matrices, derived at packing
+    assert cf.cfpp_packed_layer_bytes(cfg) == weights + (3 * h + f) * 8
     assert cf.cfpp_kv_layer_bytes(cfg) == 2 * h * max_seq * 2
     S = max_seq - 1
     got = cf.cfpp_algorithmic_bytes(cfg, [S], 1)
