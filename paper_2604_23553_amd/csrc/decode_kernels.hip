@@ -200,14 +200,14 @@ __device__ __forceinline__ void attn_share(const StepParams &P, const __half *__
         // Two rows are in flight per wavefront; a register set is refilled as soon
         // as its row is consumed.  The sets swap roles instead of being copied: a
         // copy of a set whose loads are still in flight would have to wait for them.
+        // (no exit between the two halves: with one, the load counter's model loses track of
+        // which set is older and every wait drains the queue)
         while (row < row_hi) {
             ac.process(kA, vA, row, qs, kn, vn);
             ac.issue(kA, vA, s, row + 2 * nw < row_hi ? row + 2 * nw : -1);
-            row += nw;
-            if (row >= row_hi) break;
-            ac.process(kB, vB, row, qs, kn, vn);
-            ac.issue(kB, vB, s, row + 2 * nw < row_hi ? row + 2 * nw : -1);
-            row += nw;
+            if (row + nw < row_hi) ac.process(kB, vB, row + nw, qs, kn, vn);
+            ac.issue(kB, vB, s, row + 3 * nw < row_hi ? row + 3 * nw : -1);
+            row += 2 * nw;
         }
 
         // The first wavefront alone merges the wavefronts' states, publishes the
@@ -380,8 +380,10 @@ k_attention_batched(StepParams P, int nb, const __half *w, const __half *kv)
     extern __shared__ __align__(16) float lds[];
     constexpr int PPW = AttnShape<D>::PPW;
     const Dims &dm = P.dm;
-    int rows[kAttnBatchMax];
-    long long total = 0;
+    // (cache rows per head: every head of a sequence has the same number, so the shares are
+    // the same as by rows of all heads, and spare * sum stays below 2^32: max_seq <= 2^20)
+    unsigned rows[kAttnBatchMax];
+    unsigned total = 0;
     bool ok = true;
 #pragma unroll
     for (int i = 0; i < kAttnBatchMax; ++i) {
@@ -389,7 +391,7 @@ k_attention_batched(StepParams P, int nb, const __half *w, const __half *kv)
         if (i < nb) {
             const int p = P.pos[i];
             ok = ok && p >= 0 && p < dm.max_seq;
-            rows[i] = dm.H * ((p + 1 + PPW - 1) / PPW);
+            rows[i] = (unsigned)((p + 1 + PPW - 1) / PPW);
             total += rows[i];
         }
     }
@@ -398,16 +400,18 @@ k_attention_batched(StepParams P, int nb, const __half *w, const __half *kv)
             __hip_atomic_store(&P.sync[kSyncErr], (unsigned)kErrBadPos, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
-    const int spare = (int)gridDim.x - nb, g = blockIdx.x;
-    long long before = 0;
+    const unsigned spare = gridDim.x - (unsigned)nb;
+    const int g = blockIdx.x;
+    unsigned before = 0;
     int mine = -1, g0 = 0, g1 = 0;
+    int lo = 0;
 #pragma unroll
     for (int i = 0; i < kAttnBatchMax; ++i) {
         if (i < nb) {
-            const int lo = (int)(spare * before / total) + i;
             before += rows[i];
             const int hi = (int)(spare * before / total) + i + 1;
             if (g >= lo && g < hi) { mine = i; g0 = lo; g1 = hi; }
+            lo = hi;
         }
     }
     if (mine < 0) return;
