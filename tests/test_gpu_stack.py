@@ -67,6 +67,24 @@ def test_tiny_stack_direct_and_graph(orc, mode, graph):
         ds.close()
 
 
+@pytest.mark.parametrize("mode", [0, 2])
+def test_bit_identical_over_replays_and_across_processes(mode):
+    """Every reduction runs in a fixed order: 20 graph replays of one process give
+    the same bytes (output and appended K/V rows), and so does a fresh process."""
+    import os
+    import subprocess
+    import sys
+    from tests import fresh_process_run as fp
+    print(f"[case] determinism mode={mode}", flush=True)
+    here = fp.digest(mode, replays=20)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-m", "tests.fresh_process_run", str(mode)], cwd=root,
+                         capture_output=True, text=True, timeout=240)
+    assert out.returncode == 0, out.stderr[-2000:]
+    lines = [l for l in out.stdout.splitlines() if l.startswith("digest ")]
+    assert lines and lines[-1].split()[1] == here
+
+
 def test_graph_follows_position_updates(orc):
     """pos is read from device memory at run time: one captured graph serves
     successive decode positions."""
@@ -167,7 +185,7 @@ def test_full_pythia_2_8b_stack_graph_and_argmax(orc):
             ds.set_inputs(x, S)
             ds.capture()
             outs = []
-            for _ in range(5):
+            for _ in range(20):
                 ds.replay()
                 ds.check()
                 outs.append(ds.result()[0].copy())
