@@ -233,6 +233,28 @@ cfpp_status cfpp_stack_decode(cfpp_ctx *ctx, const void *const *packed_layers,
                               const int32_t *pos_dev, int32_t batch, void *out,
                               cfpp_stream stream);
 
+/* Prompt processing (the paper treats the prefill phase apart from its fused
+ * decode kernel, Sec. 4.2 "Prefill Phase"; what it computes is the block applied
+ * to every prompt token with causal attention, i.e. n_tokens decode steps one
+ * after the other).  The tokens pass through all cfg.n_layers blocks in groups
+ * of up to 8 consecutive positions (min(8, cfg.max_batch): a group uses one
+ * workspace row per token): per group the weights are streamed once and the
+ * projections run on the matrix cores, as for a batch of sequences, but every
+ * row of the group is appended to the cache of sequence `b` before the group's
+ * attention runs, so a token attends to the positions before it.
+ *   x   : DEVICE [n_tokens][hidden] fp16, the tokens' input rows
+ *   pos0: position of the first token (host value); positions below it must be
+ *         cached already; rows pos0 .. pos0 + n_tokens - 1 of sequence b are
+ *         written in every layer
+ *   out : DEVICE [n_tokens][hidden] fp16, the last block's output per token;
+ *         must not overlap x
+ * Launch mode 0 only (CFPP_EUNSUPPORTED otherwise, or for shapes the batched
+ * projections do not cover); CFPP_EINVAL for positions outside the cache.
+ * Asynchronous on `stream`. */
+cfpp_status cfpp_stack_prefill(cfpp_ctx *ctx, const void *const *packed_layers,
+                               void *const *kv_layers, const void *x, int32_t pos0,
+                               int32_t n_tokens, int32_t b, void *out, cfpp_stream stream);
+
 /* Graph mode with static buffers (paper Sec. 2.3): capture records the whole
  * stack step for these exact pointers into one HIP graph (nothing executes);
  * each replay is one graph launch.  Between replays the caller updates the
@@ -245,7 +267,9 @@ cfpp_status cfpp_stack_replay(cfpp_ctx *ctx, cfpp_stream stream);
 
 /* ---- generation loop: the steps either side of the stack ---------------------
  * (paper Sec. 2.3 replays one graph per generated token with static buffers;
- * Sec. 4 decodes greedily.)  One sequence.  The token sequence lives in DEVICE
+ * its Sec. 3 compares the generated tokens with the baseline's and does not name
+ * the rule that picks them: the largest logit, lowest index among equals, is
+ * taken here.)  One sequence.  The token sequence lives in DEVICE
  * memory indexed by position: tokens_dev[p] is the token whose K/V rows are
  * appended at cache row p; int32[max_seq + 1].
  *

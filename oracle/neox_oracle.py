@@ -175,6 +175,21 @@ class Oracle:
                 per_layer.append(x.copy())
         return self.real_to_half(x), x
 
+    # -- prompt processing (paper Sec. 4.2 "Prefill Phase" names it without a
+    #    formula: what it computes is the stack applied to every prompt token
+    #    with causal attention, which is one decode step per token, in order) ---
+    def prefill(self, shape, layers, Ks, Vs, pos0: int, X_f16):
+        """X_f16: fp16 [T, hidden] prompt rows for positions pos0 .. pos0 + T - 1 of
+        one sequence whose first pos0 rows are cached.  Ks, Vs are updated in
+        place.  Returns (fp16 [T, hidden] outputs, unrounded [T, hidden])."""
+        X = np.asarray(X_f16)
+        out16, out = [], []
+        for t in range(X.shape[0]):
+            o16, o = self.stack_decode(shape, layers, Ks, Vs, pos0 + t, X[t])
+            out16.append(o16)
+            out.append(o)
+        return np.stack(out16), np.stack(out)
+
     def lm_head_logits(self, shape, head: dict, x, eps=None):
         x = self._r(x).reshape(-1)
         vocab = head["w_lm"].shape[0]
@@ -185,7 +200,8 @@ class Oracle:
         return logits
 
     # -- greedy generation (the steps either side of the stack: paper Sec. 2.3
-    #    replays one graph per generated token; Sec. 4 decodes greedily) ------
+    #    replays one graph per generated token; Sec. 3 compares generated tokens
+    #    with the baseline's and does not name the picking rule: argmax here) --
     def next_token(self, shape, head: dict, hidden_f16):
         """Final LayerNorm + LM head on the stack's fp16 output, then the index of
         the largest logit (the lowest index among equal maxima)."""

@@ -168,6 +168,13 @@ def cfpp_stack_decode(ctx: int, packed_layers, kv_layers, x, pos_dev, batch: int
            "cfpp_stack_decode")
 
 
+def cfpp_stack_prefill(ctx: int, packed_layers, kv_layers, x, pos0: int, n_tokens: int, b: int, out, stream=None):
+    _check(lib().cfpp_stack_prefill(C.c_void_p(ctx), _ptr_array(packed_layers), _ptr_array(kv_layers),
+                                    _ptr(x), C.c_int32(pos0), C.c_int32(n_tokens), C.c_int32(b), _ptr(out),
+                                    _ptr(stream)),
+           "cfpp_stack_prefill")
+
+
 def cfpp_stack_capture(ctx: int, packed_layers, kv_layers, x, pos_dev, batch: int, out, stream):
     _check(lib().cfpp_stack_capture(C.c_void_p(ctx), _ptr_array(packed_layers), _ptr_array(kv_layers),
                                     _ptr(x), _ptr(pos_dev), C.c_int32(batch), _ptr(out), _ptr(stream)),

@@ -408,6 +408,7 @@ static StepParams make_params(const cfpp_ctx *ctx, const Shape &sh, int b, const
     P.parts = kPartAll;
     P.attn_g0 = 0;
     P.attn_G = 0;
+    P.attn_bstep = 1;
     P.rows_qkv = sh.rows_qkv; P.rows_up = sh.rows_up; P.rows_h = sh.rows_h;
     P.nsl_down = sh.nsl_down; P.nsl_dense = sh.nsl_dense;
     P.lds_floats = sh.lds_floats;
@@ -442,9 +443,14 @@ static bool batched_path(const cfpp_ctx *ctx, const Shape &sh, int batch)
            bat_supported(ctx->dm, sh.grid, sh.threads);
 }
 
+// kv_seq < 0: row i of x / pos / out is sequence i with its own cache (a decode step of
+// `batch` sequences).  kv_seq >= 0: the rows are consecutive positions of sequence kv_seq
+// (a group of prompt tokens): they use the workspace rows 0.. but all append to, and attend
+// over, that one cache - the rows of the group are in the cache before its attention runs,
+// so a token sees the tokens before it.
 static cfpp_status launch_batched_layer(const cfpp_ctx *ctx, const Shape &sh, const __half *w, __half *kv, int l,
                                         int n_layers, const void *x, const int32_t *pos_dev, int batch, void *out,
-                                        hipStream_t s)
+                                        hipStream_t s, int kv_seq = -1)
 {
     const Dims &dm = ctx->dm;
     const WorkspaceLayout &wl = ctx->wl;
@@ -455,6 +461,8 @@ static cfpp_status launch_batched_layer(const cfpp_ctx *ctx, const Shape &sh, co
         B.pos = pos_dev + b0;
         B.nb = batch - b0 < kBatMax ? batch - b0 : kBatMax;
         B.b0 = b0; B.layer = l; B.n_layers = n_layers;
+        B.kv_b0 = kv_seq < 0 ? b0 : kv_seq;
+        B.kv_bstep = kv_seq < 0 ? 1 : 0;
         B.x_in = static_cast<const __half *>(x) + (size_t)b0 * dm.h;
         B.out = static_cast<__half *>(out) + (size_t)b0 * dm.h;
         B.xres = reinterpret_cast<float *>(ctx->ws + wl.xres) + (size_t)b0 * 2 * dm.h;
@@ -466,11 +474,13 @@ static cfpp_status launch_batched_layer(const cfpp_ctx *ctx, const Shape &sh, co
         HIP_OK(launch_bat_qkv(B, sh.grid, s));
         HIP_OK(launch_bat_up(B, sh.grid, s));
         if (sh.grid >= B.nb) {
-            const StepParams P = make_params(ctx, sh, b0, x, pos_dev, out, n_layers);
+            StepParams P = make_params(ctx, sh, b0, x, pos_dev, out, n_layers);
+            if (kv_seq >= 0) { P.b = kv_seq; P.attn_bstep = 0; }
             HIP_OK(launch_attention_batched(P, B.nb, w, kv, sh.grid, sh.threads, s));
         } else {
             for (int b = b0; b < b0 + B.nb; ++b) {
-                const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, n_layers);
+                StepParams P = make_params(ctx, sh, b, x, pos_dev, out, n_layers);
+                if (kv_seq >= 0) P.b = kv_seq;
                 HIP_OK(launch_attention_only(P, w, kv, sh.grid, sh.threads, s));
             }
         }
@@ -684,6 +694,58 @@ extern "C" cfpp_status cfpp_stack_decode(cfpp_ctx *ctx, const void *const *packe
     if (st != CFPP_OK) return st;
     return enqueue_stack(ctx, packed_layers, kv_layers, x, pos_dev, batch, out, static_cast<hipStream_t>(stream),
                          true, true);
+}
+
+// Prompt processing: groups of up to kBatMax consecutive tokens, each group through every
+// layer before the next group starts (the next group attends over this group's rows in
+// every layer's cache).
+extern "C" cfpp_status cfpp_stack_prefill(cfpp_ctx *ctx, const void *const *packed_layers, void *const *kv_layers,
+                                          const void *x, int32_t pos0, int32_t n_tokens, int32_t b, void *out,
+                                          cfpp_stream stream)
+{
+    if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
+    cfpp_status st = prepare(ctx);
+    if (st != CFPP_OK) return st;
+    if (!aligned16(x) || !aligned16(out)) return fail(CFPP_EINVAL, "x or out is NULL or not 16-byte aligned");
+    if (!packed_layers || !kv_layers) return fail(CFPP_EINVAL, "layer pointer arrays are NULL");
+    const int L = ctx->cfg.n_layers;
+    for (int l = 0; l < L; ++l)
+        if (!aligned16(packed_layers[l]) || !aligned16(kv_layers[l]))
+            return fail(CFPP_EINVAL, "layer %d: NULL or misaligned pointer", l);
+    if (b < 0 || b >= ctx->cfg.max_batch) return fail(CFPP_EINVAL, "sequence %d outside [0, max_batch = %d)", b, ctx->cfg.max_batch);
+    if (n_tokens <= 0 || pos0 < 0 || (long long)pos0 + n_tokens > ctx->cfg.max_seq)
+        return fail(CFPP_EINVAL, "positions [%d, %d + %d) outside the cache of %d positions", pos0, pos0, n_tokens,
+                    ctx->cfg.max_seq);
+    {
+        const char *xb = static_cast<const char *>(x), *ob = static_cast<const char *>(out);
+        const size_t n = (size_t)n_tokens * ctx->dm.h * 2;
+        if (xb < ob + n && ob < xb + n) return fail(CFPP_EINVAL, "out overlaps x");
+    }
+    Shape sh;
+    if ((st = launch_shape(ctx, &sh)) != CFPP_OK) return st;
+    if (ctx->mode != 0 || (ctx->dm.flags & kFlagSequentialResidual))
+        return fail(CFPP_EUNSUPPORTED, "prompt processing runs in launch mode 0 with the parallel residual form");
+    if (!bat_supported(ctx->dm, sh.grid, sh.threads) || sh.grid < kBatMax)
+        return fail(CFPP_EUNSUPPORTED, "prompt processing needs the batched projections: 512 threads, grid >= %d, hidden "
+                    "and ffn multiples of 256, at most 64 matrix rows per workgroup", kBatMax);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t *pos_dev = reinterpret_cast<int32_t *>(ctx->ws + ctx->wl.pf_pos);
+    HIP_OK(launch_fill_positions(pos_dev, pos0, n_tokens, s));
+    // a group uses one workspace row per token: as many as the context has
+    const int group = ctx->cfg.max_batch < kBatMax ? ctx->cfg.max_batch : kBatMax;
+    const size_t h = (size_t)ctx->dm.h;
+    for (int t0 = 0; t0 < n_tokens; t0 += group) {
+        const int nb = n_tokens - t0 < group ? n_tokens - t0 : group;
+        const __half *xg = static_cast<const __half *>(x) + (size_t)t0 * h;
+        __half *og = static_cast<__half *>(out) + (size_t)t0 * h;
+        for (int l = 0; l < L; ++l)
+            if ((st = launch_batched_layer(ctx, sh, static_cast<const __half *>(packed_layers[l]),
+                                           static_cast<__half *>(kv_layers[l]), l, L, xg, pos_dev + t0, nb, og, s,
+                                           b)) != CFPP_OK)
+                return st;
+    }
+    ctx->last_batch = 1;
+    return CFPP_OK;
 }
 
 extern "C" cfpp_status cfpp_stack_capture(cfpp_ctx *ctx, const void *const *packed_layers,

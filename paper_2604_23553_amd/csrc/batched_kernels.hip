@@ -367,8 +367,8 @@ __global__ void __launch_bounds__(512) k_bat_proj(BatParams P)
                 P.q[(size_t)b * h + nh * d + d0] = v0;
                 P.q[(size_t)b * h + nh * d + d1] = v1;
             } else {
-                P.kv[kv_offset(dm, c - 1, P.b0 + b, nh, d0, pos)] = __float2half_rn(v0);
-                P.kv[kv_offset(dm, c - 1, P.b0 + b, nh, d1, pos)] = __float2half_rn(v1);
+                P.kv[kv_offset(dm, c - 1, P.kv_b0 + b * P.kv_bstep, nh, d0, pos)] = __float2half_rn(v0);
+                P.kv[kv_offset(dm, c - 1, P.kv_b0 + b * P.kv_bstep, nh, d1, pos)] = __float2half_rn(v1);
             }
         }
     }

@@ -18,6 +18,9 @@ struct BatParams {
     __half *kv;             // the layer's cache (whole, indexed with b0 + b)
     const int *pos;         // [nb]
     int nb, b0;
+    // row i of the group appends to the cache of sequence kv_b0 + i * kv_bstep: its own
+    // sequence (b0, 1), or - consecutive positions of one prompt - all the same one (b, 0)
+    int kv_b0, kv_bstep;
     int layer, n_layers;    // position in the fp32 residual ping-pong
     const __half *x_in;     // [nb][h] fp16: input of layer 0
     __half *out;            // [nb][h] fp16: output of the last layer

@@ -416,7 +416,7 @@ k_attention_batched(StepParams P, int nb, const __half *w, const __half *kv)
     }
     if (mine < 0) return;
     StepParams Q = P;
-    Q.b = P.b + mine;
+    Q.b = P.b + mine * P.attn_bstep;
     Q.pos = P.pos + mine;
     Q.q = P.q + (size_t)mine * dm.h;
     Q.o = P.o + (size_t)mine * dm.h;

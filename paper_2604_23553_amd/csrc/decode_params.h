@@ -24,6 +24,8 @@ struct StepParams {
     __half *out;         // fp16 [h] output of the last layer
     int n_layers;
     int attn_g0, attn_G; // attention: the workgroups [attn_g0, attn_g0 + attn_G) share this sequence (attn_G 0: the whole grid)
+    int attn_bstep;      // batched attention launch: row i reads the cache of sequence b + i * attn_bstep (1, or 0
+                         // when the rows are consecutive positions of one sequence)
     int parts;           // kPart* bits: what a phase launch performs (kPartAll unless the block runs in two halves)
     // work split (chosen on the host from the grid and the workgroup size)
     int rows_qkv, rows_up, rows_h;   // matrix rows per workgroup (rows_qkv even)
@@ -78,6 +80,9 @@ hipError_t launch_kv_import(const Dims &dm, const __half *k_src, const __half *v
                             int n_pos, int b, __half *kv, hipStream_t s);
 hipError_t launch_kv_export(const Dims &dm, const __half *kv, int b, int pos_begin, int n_pos,
                             int dst_cap, __half *k_dst, __half *v_dst, hipStream_t s);
+
+// dst[i] = first + i for i < n (the positions of a prompt's tokens)
+hipError_t launch_fill_positions(int *dst, int first, int n, hipStream_t s);
 
 hipError_t launch_stream_read(const void *src, size_t bytes, unsigned *sink, int grid, int threads,
                               int unroll, hipStream_t s);

@@ -111,6 +111,7 @@ struct WorkspaceLayout {
     size_t o;         // float[max_batch][h]: attention output
     size_t part;      // float[max_batch*H][part_slots][d+2]: split-KV partials (acc[d], max, sum)
     size_t lm_best;   // float[kMaxGrid][2]: (logit, row) of every workgroup of the LM-head kernel
+    size_t pf_pos;    // int32[max_seq]: positions of a prompt's tokens (prompt processing)
     size_t trace;     // uint64[kTraceWaves][kTraceLen][2]: (tag, 100 MHz clock) pairs, profiling aid
     size_t total;
     int part_slots;
@@ -137,6 +138,7 @@ CFPP_HD WorkspaceLayout workspace_layout(const Dims &m)
     W.o = take((size_t)m.max_batch * m.h * 4);
     W.part = take((size_t)m.max_batch * m.H * W.part_slots * (m.d + 2) * 4);
     W.lm_best = take((size_t)kMaxGrid * 8);
+    W.pf_pos = take((size_t)m.max_seq * 4);
     W.trace = take((size_t)kTraceWaves * kTraceLen * 16);
     W.total = o;
     return W;

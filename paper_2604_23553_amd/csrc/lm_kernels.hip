@@ -1,6 +1,7 @@
 // The steps either side of the decode stack in a generation loop (paper Sec.
-// 2.3: one graph replay per generated token with static buffers; Sec. 4 decodes
-// greedily): the embedding row of the current token before it, and behind it
+// 2.3: one graph replay per generated token with static buffers; Sec. 3 compares
+// the generated tokens with the baseline's without naming the rule that picks
+// them - the largest logit is taken here): the embedding row of the current token before it, and behind it
 // the final LayerNorm, the bias-free LM head, and the index of the largest
 // logit (lowest index among equal maxima), which becomes the next token while
 // the position advances by one.

@@ -128,6 +128,18 @@ hipError_t launch_kv_export(const Dims &dm, const __half *kv, int b, int pos_beg
 }
 
 
+__global__ void k_fill_positions(int *dst, int first, int n)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) dst[i] = first + i;
+}
+
+hipError_t launch_fill_positions(int *dst, int first, int n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_positions, dim3((n + 255) / 256), dim3(256), 0, s, dst, first, n);
+    return hipGetLastError();
+}
+
 // ---- plain streaming kernels of known traffic (bandwidth calibration) ---------
 // read: every 16-byte word of src is loaded once and folded into a checksum, one
 // word per workgroup written to sink; copy: dst = src.

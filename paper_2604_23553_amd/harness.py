@@ -111,6 +111,16 @@ class DeviceStack:
     def stack_decode(self):
         B.cfpp_stack_decode(self.ctx, self.packed, self.kv, self.x, self.pos, self.batch, self.out, self.s)
 
+    def prefill(self, x: np.ndarray, pos0: int, b: int = 0) -> np.ndarray:
+        """x: fp16 [T, hidden] prompt rows, appended to sequence b from position pos0 on;
+        returns the last block's fp16 output per token."""
+        xd = torch.from_numpy(np.ascontiguousarray(x)).to(self.dev)
+        od = torch.zeros_like(xd)
+        torch.cuda.synchronize()
+        B.cfpp_stack_prefill(self.ctx, self.packed, self.kv, xd, pos0, x.shape[0], b, od, self.s)
+        self.stream.synchronize()
+        return od.cpu().numpy()
+
     def capture(self):
         B.cfpp_stack_capture(self.ctx, self.packed, self.kv, self.x, self.pos, self.batch, self.out, self.s)
 

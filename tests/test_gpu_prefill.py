@@ -1,0 +1,104 @@
+"""GPU parity of prompt processing (cfpp_stack_prefill) against the CPU oracle,
+through the C ABI: every token's output, the rows appended to every layer's
+cache, and a decode step that continues behind the prompt."""
+import numpy as np
+import pytest
+
+import synth
+from tests.parity import assert_block_close, assert_fp16_rows_match, errors
+
+pytestmark = pytest.mark.gpu
+
+TINY_STACK = synth.ModelShape(512, 8, 64, 16, 2048, n_layers=4, name="neox-h512-x4")
+
+
+def _build(shape, seed, pos0, cap, max_batch):
+    from paper_2604_23553_amd.harness import DeviceStack
+    L = shape.n_layers
+    ds = DeviceStack(shape, cap, max_batch, L)
+    ws = [synth.layer_weights(shape, seed, l) for l in range(L)]
+    kvs = [synth.kv_cache(shape, seed, l, pos0, cap, max_batch) for l in range(L)]
+    for l in range(L):
+        ds.load_layer(l, ws[l])
+        ds.load_kv(l, kvs[l][0], kvs[l][1], pos0)
+    return ds, ws, kvs
+
+
+def _check_prompt(orc, shape, seed, pos0, T, max_batch, b=0, then_decode=True):
+    cap = pos0 + T + 2
+    print(f"[case] prefill shape={shape.name} seed={seed} pos0={pos0} T={T} max_batch={max_batch} b={b}", flush=True)
+    ds, ws, kvs = _build(shape, seed, pos0, cap, max_batch)
+    try:
+        ds.set_options(mode=0)
+        X = synth.x_input(shape, seed + 1, batch=T)
+        got = ds.prefill(X, pos0, b)
+        ds.check()
+        Ks = [kv[0][b].copy() for kv in kvs]
+        Vs = [kv[1][b].copy() for kv in kvs]
+        want16, _ = orc.prefill(shape, ws, Ks, Vs, pos0, X)
+        for t in range(T):
+            assert_block_close(got[t], want16[t], f"token {t}")
+        # rows appended to every layer's cache of sequence b; nothing else of the cache touched
+        for l in range(shape.n_layers):
+            kg, vg = ds.export_kv(l, b, 0, cap)
+            if l == 0:
+                assert_fp16_rows_match(kg[:, pos0:pos0 + T], Ks[l][:, pos0:pos0 + T], "appended K, layer 0")
+                assert_fp16_rows_match(vg[:, pos0:pos0 + T], Vs[l][:, pos0:pos0 + T], "appended V, layer 0")
+            else:   # deeper layers see an input that already carries the earlier layers' rounding
+                for g_, w_ in ((kg, Ks[l]), (vg, Vs[l])):
+                    e = errors(g_[:, pos0:pos0 + T], w_[:, pos0:pos0 + T])
+                    assert e[0] <= 2e-2 and e[1] <= 5e-3, f"appended rows, layer {l}: {e}"
+            assert np.array_equal(np.ascontiguousarray(kg[:, :pos0]).view(np.uint16),
+                                  np.ascontiguousarray(kvs[l][0][b][:, :pos0]).view(np.uint16))
+            assert np.isnan(kg[:, pos0 + T:].astype(np.float32)).all() and np.isnan(vg[:, pos0 + T:].astype(np.float32)).all()
+            for other in range(max_batch):
+                if other != b:
+                    ko, _ = ds.export_kv(l, other, 0, cap)
+                    assert np.isnan(ko[:, pos0:].astype(np.float32)).all(), "another sequence's cache was written"
+        if then_decode and b == 0:
+            # one decode step behind the prompt reads what the prompt left in the caches
+            x1 = synth.x_input(shape, seed + 2)
+            ds.set_inputs(x1, pos0 + T)
+            ds.stack_decode()
+            ds.check()
+            ref16, _ = orc.stack_decode(shape, ws, Ks, Vs, pos0 + T, x1[0])
+            assert_block_close(ds.result()[0], ref16, "decode step behind the prompt")
+    finally:
+        ds.close()
+
+
+@pytest.mark.parametrize("pos0,T,max_batch,b", [
+    (5, 19, 8, 0),        # groups of 8, 8 and 3 behind five cached positions
+    (0, 7, 3, 0),         # groups of 3, 3 and 1 from an empty cache
+    (3, 9, 8, 2),         # into the cache of the third sequence
+    (0, 1, 8, 0),         # a single token
+])
+def test_prompt_through_the_tiny_stack(orc, pos0, T, max_batch, b):
+    _check_prompt(orc, TINY_STACK, 17, pos0, T, max_batch, b)
+
+
+def test_prompt_at_the_2_8b_shape(orc):
+    shape = synth.ModelShape(2560, 32, 80, 20, 10240, n_layers=2, name="pythia-2.8b-x2")
+    _check_prompt(orc, shape, 23, 100, 11, 8)
+
+
+def test_prompt_requests_that_are_refused():
+    from paper_2604_23553_amd import CfppError
+    ds, ws, kvs = _build(TINY_STACK, 1, 0, 12, 8)
+    try:
+        X = synth.x_input(TINY_STACK, 2, batch=4)
+        ds.set_options(mode=2)
+        with pytest.raises(CfppError) as e:
+            ds.prefill(X, 0)
+        assert e.value.status == -2                       # launch mode 0 only
+        ds.set_options(mode=0)
+        with pytest.raises(CfppError) as e:
+            ds.prefill(X, 9)                              # positions 9..12 of a cache of 12
+        assert e.value.status == -1
+        with pytest.raises(CfppError) as e:
+            ds.prefill(X, 0, b=8)                         # no such sequence
+        assert e.value.status == -1
+        ds.prefill(X, 8)                                  # the last four rows fit
+        ds.check()
+    finally:
+        ds.close()

@@ -1,7 +1,8 @@
 """Pins of the oracle's greedy generation loop (the steps either side of the
 decode stack: embedding lookup before it, final LayerNorm + LM head + argmax
-after it; paper Sec. 2.3 replays the graph once per generated token, Sec. 4
-decodes greedily).  CPU only."""
+after it; paper Sec. 2.3 replays the graph once per generated token; the rule
+that picks a token is not named in the paper, the largest logit is taken).
+CPU only."""
 import numpy as np
 
 import synth
