@@ -153,6 +153,59 @@ def bench_block(args):
     }))
 
 
+def bench_prefill(args):
+    """Prompt processing (cfpp_stack_prefill): a prompt of --tokens tokens through the whole stack from an
+    empty cache, groups of 8 tokens per pass over the weights."""
+    import numpy as np
+    import torch
+    import synth
+    import paper_2604_23553_amd as cf
+    from paper_2604_23553_amd.harness import DeviceStack
+
+    shape = {"2.8b": synth.PYTHIA_2_8B, "6.9b": synth.PYTHIA_6_9B}[args.shape]
+    seed, T, G = synth.MASTER_SEED, args.tokens, 8
+    L = shape.n_layers
+    ds = DeviceStack(shape, T + 1, G, L)
+    for l in range(L):
+        ds.load_layer(l, synth.layer_weights(shape, seed, l))
+        kv = synth.kv_cache(shape, seed, l, 0, T + 1, G, poison=False)
+        ds.load_kv(l, kv[0], kv[1], 0)
+    ds.set_options(mode=0, grid=args.grid, threads=args.threads)
+    xd = torch.from_numpy(synth.x_input(shape, seed, T)).to(ds.dev)
+    od = torch.zeros_like(xd)
+    torch.cuda.synchronize()
+    run = lambda: cf.cfpp_stack_prefill(ds.ctx, ds.packed, ds.kv, xd, 0, T, 0, od, ds.s)
+    for _ in range(args.warmup):
+        run()
+    ds.stream.synchronize()
+    ds.check()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    ds.stream.synchronize()
+    us = (time.perf_counter() - t0) / args.steps * 1e6
+    ds.check()
+    # what this path streams: per group of 8 tokens the weights once and every token's K/V rows
+    streamed = sum(cf.cfpp_algorithmic_bytes(ds.cfg, list(range(t0_, min(t0_ + G, T))), L) for t0_ in range(0, T, G))
+    h, f = shape.hidden, shape.ffn
+    flops = 2.0 * (4 * h * h + 2 * h * f) * T * L + 4.0 * h * L * (T * (T + 1) / 2)
+    ds.close()
+    achieved = streamed / (us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": f"us_per_prompt_prefill_{L}L_{args.shape}_T{T}", "value": us, "unit": "us/prompt", "n_gpus": 1,
+        "tokens_per_s": T * 1e6 / us, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False,
+        "data": "synthetic", "dtype": "f16 weights/KV, f32 accumulate",
+        "config": {"workload": f"prompt of {T} tokens through {L} {shape.name} blocks from an empty cache, "
+                               f"groups of {G} tokens (launch mode 0, batched projections)", "launch_mode": 0},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "streamed_bytes_per_prompt": streamed,
+                     "note": "bytes this path streams: the weights once per group of 8 tokens; a prompt-sized "
+                             "GEMM would read them once per prompt and be bound by the matrix cores instead"},
+        "mfma": {"flops_per_prompt": flops, "achieved_TFLOPs": flops / (us * 1e-6) / 1e12,
+                 "frac_of_f16_peak": flops / (us * 1e-6) / 2.5e15},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -163,8 +216,10 @@ def main():
     ap.add_argument("--grid", type=int, default=int(os.environ.get("CFPP_GRID", "0")))
     ap.add_argument("--threads", type=int, default=int(os.environ.get("CFPP_THREADS", "512")))
     ap.add_argument("--ctx", type=int, default=4096, help="cached positions per layer")
-    ap.add_argument("--workload", choices=["stack", "block"], default="stack",
-                    help="stack: the headline (32 layers, batch 1); block: one block, see --copies / --batch")
+    ap.add_argument("--workload", choices=["stack", "block", "prefill"], default="stack",
+                    help="stack: the headline (32 layers, batch 1); block: one block, see --copies / --batch; "
+                         "prefill: a prompt of --tokens tokens through the stack")
+    ap.add_argument("--tokens", type=int, default=512, help="prefill workload: prompt length")
     ap.add_argument("--copies", type=int, default=1, help="block workload: copies replayed in rotation (cold when large)")
     ap.add_argument("--batch", type=int, default=1, help="block workload: sequences (ragged lengths 1024..8192 when > 1)")
     ap.add_argument("--layers", type=int, default=1, help="block workload: blocks in a row (a stack of that many layers)")
@@ -190,6 +245,12 @@ def main():
 
     if args.workload == "block":
         bench_block(args)
+        return
+    if args.workload == "prefill":
+        if args.shape == "small":
+            print("bench.py: the prefill workload runs at the 2.8b or 6.9b shape", file=sys.stderr)
+            sys.exit(2)
+        bench_prefill(args)
         return
     if args.shape == "small":
         print("bench.py: --shape small is a single-block workload (--workload block)", file=sys.stderr)
