@@ -141,33 +141,40 @@ __device__ __forceinline__ void bat_tile(const BatStreamCtx &C, u32x4 (&A)[kBatS
 // sequence's activations: their products land in columns of the result that are
 // never looked at.
 template <int T>
-__device__ __forceinline__ void bat_stream(const __half *__restrict__ W, int K, int r_begin, int r_last, int k_off,
-                                           int klen, const __half *yh, const __half *yl, int Ks, int nb,
-                                           f32x4 (&acc)[T], int tid)
-{
-    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n = lane & 15, q = lane >> 4;
-    (void)nb;
+struct BatStream {
     BatStreamCtx C;
-    C.K = (size_t)K;
-    C.col = 32 * wave + 8 * q;
-    C.W = W + k_off;
-    C.steps = klen >> 8;
-    C.yh = yh + (n & (kBatMax - 1)) * Ks + C.col;
-    C.yl = yl + (n & (kBatMax - 1)) * Ks + C.col;
-    if (C.steps <= 0) return;
     int arow[T + 1];
-#pragma unroll
-    for (int t = 0; t <= T; ++t) arow[t] = min(r_begin + 16 * (t < T ? t : T - 1) + n, r_last);
     u32x4 r0[kBatSet], r1[kBatSet], r2[kBatSet], r3[kBatSet];
-    bat_issue(C, r0, arow[0], 0);
-    bat_issue(C, r1, arow[0], kBatSet);
+
+    // requests the first two sets of the first tile: weights depend on nothing, so this
+    // comes before the activations are even in LDS (yh, yl are only read by run())
+    __device__ __forceinline__ void begin(const __half *__restrict__ W, int K, int r_begin, int r_last, int k_off,
+                                          int klen, const __half *yh, const __half *yl, int Ks, int tid)
+    {
+        const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int n = lane & 15, q = lane >> 4;
+        C.K = (size_t)K;
+        C.col = 32 * wave + 8 * q;
+        C.W = W + k_off;
+        C.steps = klen >> 8;
+        C.yh = yh + (n & (kBatMax - 1)) * Ks + C.col;
+        C.yl = yl + (n & (kBatMax - 1)) * Ks + C.col;
 #pragma unroll
-    for (int t = 0; t < T; ++t) {
-        if (t & 1) bat_tile(C, r2, r3, r0, r1, acc[t], arow[t], arow[t + 1], t + 1 < T);
-        else bat_tile(C, r0, r1, r2, r3, acc[t], arow[t], arow[t + 1], t + 1 < T);
+        for (int t = 0; t <= T; ++t) arow[t] = min(r_begin + 16 * (t < T ? t : T - 1) + n, r_last);
+        if (C.steps <= 0) return;
+        bat_issue(C, r0, arow[0], 0);
+        bat_issue(C, r1, arow[0], kBatSet);
     }
-}
+    __device__ __forceinline__ void run(f32x4 (&acc)[T])
+    {
+        if (C.steps <= 0) return;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            if (t & 1) bat_tile(C, r2, r3, r0, r1, acc[t], arow[t], arow[t + 1], t + 1 < T);
+            else bat_tile(C, r0, r1, r2, r3, acc[t], arow[t], arow[t + 1], t + 1 < T);
+        }
+    }
+};
 
 // accumulators of the 8 wavefronts -> LDS red[wave][tile][row in tile][sequence]
 template <int T>
@@ -204,115 +211,134 @@ __device__ __forceinline__ void bat_put8(__half *yh, __half *yl, int at, const f
 }
 
 // src[b * stride + 0..klen) (fp32, klen <= 4096 a multiple of 8) of every sequence -> hi/lo rows in
-// LDS: a thread owns one group of 8 values of every sequence; all loads are issued first
-__device__ __forceinline__ void bat_stage(const float *src, size_t stride, int klen, __half *yh, __half *yl, int Ks,
-                                          int nb, int tid)
-{
-    const int c = tid < (klen >> 3) ? tid : 0;
+// LDS: a thread owns one group of 8 values of every sequence; load() requests them all,
+// commit() converts and writes (other loads can be queued in between)
+struct BatStage {
     f32x4 v[kBatMax][2];
-#pragma unroll
-    for (int b = 0; b < kBatMax; ++b) {
-        const float *p = src + (size_t)(b < nb ? b : 0) * stride + 8 * c;
-        v[b][0] = *as_global(reinterpret_cast<const f32x4 *>(p));
-        v[b][1] = *as_global(reinterpret_cast<const f32x4 *>(p + 4));
-    }
-    if (tid < (klen >> 3)) {
+    __device__ __forceinline__ void load(const float *src, size_t stride, int klen, int nb, int tid)
+    {
+        const int c = tid < (klen >> 3) ? tid : 0;
 #pragma unroll
         for (int b = 0; b < kBatMax; ++b) {
-            if (b < nb) {
-                const float e[8] = {v[b][0][0], v[b][0][1], v[b][0][2], v[b][0][3], v[b][1][0], v[b][1][1], v[b][1][2], v[b][1][3]};
-                bat_put8(yh, yl, b * Ks + 8 * c, e);
+            const float *p = src + (size_t)(b < nb ? b : 0) * stride + 8 * c;
+            v[b][0] = *as_global(reinterpret_cast<const f32x4 *>(p));
+            v[b][1] = *as_global(reinterpret_cast<const f32x4 *>(p + 4));
+        }
+    }
+    __device__ __forceinline__ void commit(int klen, __half *yh, __half *yl, int Ks, int nb, int tid) const
+    {
+        if (tid < (klen >> 3)) {
+#pragma unroll
+            for (int b = 0; b < kBatMax; ++b) {
+                if (b < nb) {
+                    const float e[8] = {v[b][0][0], v[b][0][1], v[b][0][2], v[b][0][3], v[b][1][0], v[b][1][1], v[b][1][2], v[b][1][3]};
+                    bat_put8(yh, yl, b * Ks + 8 * tid, e);
+                }
             }
         }
     }
-}
+};
 
 // LayerNorm of every sequence (two passes, biased variance) -> hi/lo rows in
 // LDS.  A thread owns one group of 8 elements of every sequence (hidden <= 4096);
-// the sums go through `red` (2 * 8 * kBatMax floats) in wavefront order.
-__device__ __forceinline__ void bat_layernorm(const BatParams &P, const __half *gam, const __half *bet, __half *yh,
-                                              __half *yl, int Ks, float *red, int tid)
-{
-    const int h = P.dm.h, nchunk = h >> 3, lane = tid & 63, wave = tid >> 6;
-    const bool active = tid < nchunk;
-    const int c = active ? tid : 0;
-    float xv[kBatMax][8];
-    if (P.layer == 0) {
-        u32x4 raw[kBatMax];
+// the sums go through `red` (2 * 8 * kBatMax floats) in wavefront order.  load()
+// requests inputs and parameters, finish() does the rest: the first weights are
+// requested in between and stream while the statistics are worked out.
+struct BatLn {
+    u32x4 raw16[kBatMax];          // layer 0: fp16 input
+    f32x4 raw32[kBatMax][2];       // later layers: fp32 residual stream
+    u32x4 graw, braw;
+
+    __device__ __forceinline__ void load(const BatParams &P, const __half *gam, const __half *bet, int tid)
+    {
+        const int h = P.dm.h, nchunk = h >> 3;
+        const int c = tid < nchunk ? tid : 0;
+        if (P.layer == 0) {
 #pragma unroll
-        for (int b = 0; b < kBatMax; ++b)
-            raw[b] = *as_global(reinterpret_cast<const u32x4 *>(P.x_in + (size_t)(b < P.nb ? b : 0) * h + 8 * c));
+            for (int b = 0; b < kBatMax; ++b)
+                raw16[b] = *as_global(reinterpret_cast<const u32x4 *>(P.x_in + (size_t)(b < P.nb ? b : 0) * h + 8 * c));
+        } else {
 #pragma unroll
-        for (int b = 0; b < kBatMax; ++b) {
-            const float2 a0 = unpack_h2(raw[b].x), a1 = unpack_h2(raw[b].y), a2 = unpack_h2(raw[b].z), a3 = unpack_h2(raw[b].w);
-            xv[b][0] = a0.x; xv[b][1] = a0.y; xv[b][2] = a1.x; xv[b][3] = a1.y;
-            xv[b][4] = a2.x; xv[b][5] = a2.y; xv[b][6] = a3.x; xv[b][7] = a3.y;
-        }
-    } else {
-        f32x4 raw[kBatMax][2];
-#pragma unroll
-        for (int b = 0; b < kBatMax; ++b) {
-            const float *p = P.xres + ((size_t)(b < P.nb ? b : 0) * 2 + ((P.layer - 1) & 1)) * h + 8 * c;
-            raw[b][0] = *as_global(reinterpret_cast<const f32x4 *>(p));
-            raw[b][1] = *as_global(reinterpret_cast<const f32x4 *>(p + 4));
-        }
-#pragma unroll
-        for (int b = 0; b < kBatMax; ++b)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) xv[b][e] = raw[b][e >> 2][e & 3];
-    }
-    const u32x4 graw = *as_global(reinterpret_cast<const u32x4 *>(gam + 8 * c));
-    const u32x4 braw = *as_global(reinterpret_cast<const u32x4 *>(bet + 8 * c));
-    // pass 1: means
-#pragma unroll
-    for (int b = 0; b < kBatMax; ++b) {
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s += xv[b][e];
-        s = wave_sum(active ? s : 0.f);
-        if (lane == 0) red[wave * kBatMax + b] = s;
-    }
-    __syncthreads();
-    float mean[kBatMax];
-#pragma unroll
-    for (int b = 0; b < kBatMax; ++b) {
-        float s = 0.f;
-        for (int w = 0; w < 8; ++w) s += red[w * kBatMax + b];
-        mean[b] = s / (float)h;
-    }
-    // pass 2: variances
-    float *red2 = red + 8 * kBatMax;
-#pragma unroll
-    for (int b = 0; b < kBatMax; ++b) {
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float dlt = xv[b][e] - mean[b];
-            s += dlt * dlt;
-        }
-        s = wave_sum(active ? s : 0.f);
-        if (lane == 0) red2[wave * kBatMax + b] = s;
-    }
-    __syncthreads();
-    if (!active) return;
-    const unsigned gw[4] = {graw.x, graw.y, graw.z, graw.w}, bw[4] = {braw.x, braw.y, braw.z, braw.w};
-#pragma unroll
-    for (int b = 0; b < kBatMax; ++b) {
-        if (b < P.nb) {
-            float s = 0.f;
-            for (int w = 0; w < 8; ++w) s += red2[w * kBatMax + b];
-            const float inv = 1.0f / sqrtf(s / (float)h + P.dm.ln_eps);
-            float yv[8];
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const float2 g2 = unpack_h2(gw[e2]), b2 = unpack_h2(bw[e2]);
-                yv[2 * e2] = (xv[b][2 * e2] - mean[b]) * inv * g2.x + b2.x;
-                yv[2 * e2 + 1] = (xv[b][2 * e2 + 1] - mean[b]) * inv * g2.y + b2.y;
+            for (int b = 0; b < kBatMax; ++b) {
+                const float *p = P.xres + ((size_t)(b < P.nb ? b : 0) * 2 + ((P.layer - 1) & 1)) * h + 8 * c;
+                raw32[b][0] = *as_global(reinterpret_cast<const f32x4 *>(p));
+                raw32[b][1] = *as_global(reinterpret_cast<const f32x4 *>(p + 4));
             }
-            bat_put8(yh, yl, b * Ks + 8 * c, yv);
+        }
+        graw = *as_global(reinterpret_cast<const u32x4 *>(gam + 8 * c));
+        braw = *as_global(reinterpret_cast<const u32x4 *>(bet + 8 * c));
+    }
+
+    __device__ __forceinline__ void finish(const BatParams &P, __half *yh, __half *yl, int Ks, float *red, int tid)
+    {
+        const int h = P.dm.h, nchunk = h >> 3, lane = tid & 63, wave = tid >> 6;
+        const bool active = tid < nchunk;
+        const int c = active ? tid : 0;
+        float xv[kBatMax][8];
+        if (P.layer == 0) {
+#pragma unroll
+            for (int b = 0; b < kBatMax; ++b) {
+                const float2 a0 = unpack_h2(raw16[b].x), a1 = unpack_h2(raw16[b].y), a2 = unpack_h2(raw16[b].z), a3 = unpack_h2(raw16[b].w);
+                xv[b][0] = a0.x; xv[b][1] = a0.y; xv[b][2] = a1.x; xv[b][3] = a1.y;
+                xv[b][4] = a2.x; xv[b][5] = a2.y; xv[b][6] = a3.x; xv[b][7] = a3.y;
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < kBatMax; ++b)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xv[b][e] = raw32[b][e >> 2][e & 3];
+        }
+        // pass 1: means
+#pragma unroll
+        for (int b = 0; b < kBatMax; ++b) {
+            float s = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += xv[b][e];
+            s = wave_sum(active ? s : 0.f);
+            if (lane == 0) red[wave * kBatMax + b] = s;
+        }
+        __syncthreads();
+        float mean[kBatMax];
+#pragma unroll
+        for (int b = 0; b < kBatMax; ++b) {
+            float s = 0.f;
+            for (int w = 0; w < 8; ++w) s += red[w * kBatMax + b];
+            mean[b] = s / (float)h;
+        }
+        // pass 2: variances
+        float *red2 = red + 8 * kBatMax;
+#pragma unroll
+        for (int b = 0; b < kBatMax; ++b) {
+            float s = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float dlt = xv[b][e] - mean[b];
+                s += dlt * dlt;
+            }
+            s = wave_sum(active ? s : 0.f);
+            if (lane == 0) red2[wave * kBatMax + b] = s;
+        }
+        __syncthreads();
+        if (!active) return;
+        const unsigned gw[4] = {graw.x, graw.y, graw.z, graw.w}, bw[4] = {braw.x, braw.y, braw.z, braw.w};
+#pragma unroll
+        for (int b = 0; b < kBatMax; ++b) {
+            if (b < P.nb) {
+                float s = 0.f;
+                for (int w = 0; w < 8; ++w) s += red2[w * kBatMax + b];
+                const float inv = 1.0f / sqrtf(s / (float)h + P.dm.ln_eps);
+                float yv[8];
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const float2 g2 = unpack_h2(gw[e2]), b2 = unpack_h2(bw[e2]);
+                    yv[2 * e2] = (xv[b][2 * e2] - mean[b]) * inv * g2.x + b2.x;
+                    yv[2 * e2 + 1] = (xv[b][2 * e2 + 1] - mean[b]) * inv * g2.y + b2.y;
+                }
+                bat_put8(yh, yl, b * Ks + 8 * c, yv);
+            }
         }
     }
-}
+};
 
 template <int T, int MODE>
 __global__ void __launch_bounds__(512) k_bat_proj(BatParams P)
@@ -327,14 +353,18 @@ __global__ void __launch_bounds__(512) k_bat_proj(BatParams P)
     if (r_n == 0) return;                                  // (whole workgroup)
     const __half *w = P.w;
     float *stat = reinterpret_cast<float *>(yl + kBatMax * Ks);     // behind the activations
-    bat_layernorm(P, w + (MODE == 0 ? P.lay.ln1_g : P.lay.ln2_g), w + (MODE == 0 ? P.lay.ln1_b : P.lay.ln2_b), yh, yl,
-                  Ks, stat, tid);
+    // order of the requests: LayerNorm inputs, then the first weights; the statistics are
+    // worked out while those weights arrive
+    BatLn ln;
+    ln.load(P, w + (MODE == 0 ? P.lay.ln1_g : P.lay.ln2_g), w + (MODE == 0 ? P.lay.ln1_b : P.lay.ln2_b), tid);
+    BatStream<T> bs;
+    bs.begin(w + (MODE == 0 ? P.lay.w_qkv : P.lay.w_up), h, r_begin, r_begin + r_n - 1, 0, h, yh, yl, Ks, tid);
+    ln.finish(P, yh, yl, Ks, stat, tid);
     __syncthreads();
     f32x4 acc[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    bat_stream<T>(w + (MODE == 0 ? P.lay.w_qkv : P.lay.w_up), h, r_begin, r_begin + r_n - 1, 0, h, yh, yl, Ks, P.nb, acc,
-                  tid);
+    bs.run(acc);
     __syncthreads();                                       // the activations are no longer read: the space is reused
     float *red = lds;
     bat_spill<T>(red, acc, tid);
@@ -388,17 +418,25 @@ __global__ void __launch_bounds__(512) k_bat_out(BatParams P)
     f32x4 acc[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // attention output of every sequence -> output projection
-    bat_stage(P.o, (size_t)h, h, yh, yl, Ks, P.nb, tid);
+    // attention output of every sequence -> output projection.  In every stretch the
+    // activations are requested first and the first weights right behind them, so the
+    // weights stream while the activations are converted and written to LDS.
+    BatStage st;
+    BatStream<T> bs;
+    st.load(P.o, (size_t)h, h, P.nb, tid);
+    bs.begin(w + P.lay.w_dense, h, r_begin, r_begin + r_n - 1, 0, h, yh, yl, Ks, tid);
+    st.commit(h, yh, yl, Ks, P.nb, tid);
     __syncthreads();
-    bat_stream<T>(w + P.lay.w_dense, h, r_begin, r_begin + r_n - 1, 0, h, yh, yl, Ks, P.nb, acc, tid);
+    bs.run(acc);
     // GELU(up) in slices of at most h columns -> down projection, same accumulators
     for (int k_off = 0; k_off < f; k_off += h) {
         const int klen = min(h, f - k_off);
+        st.load(P.m + k_off, (size_t)f, klen, P.nb, tid);
+        bs.begin(w + P.lay.w_down, f, r_begin, r_begin + r_n - 1, k_off, klen, yh, yl, Ks, tid);
+        __syncthreads();                                   // the previous stretch no longer reads the activations
+        st.commit(klen, yh, yl, Ks, P.nb, tid);
         __syncthreads();
-        bat_stage(P.m + k_off, (size_t)f, klen, yh, yl, Ks, P.nb, tid);
-        __syncthreads();
-        bat_stream<T>(w + P.lay.w_down, f, r_begin, r_begin + r_n - 1, k_off, klen, yh, yl, Ks, P.nb, acc, tid);
+        bs.run(acc);
     }
     __syncthreads();
     float *red = lds;
