@@ -214,7 +214,7 @@ struct AttnCore {
         unsigned old = 0;
         if (lane == 0)
             old = __hip_atomic_fetch_add(&P.seg_cnt[s], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const bool is_last = __builtin_amdgcn_readfirstlane(old) == (unsigned)(ncover - 1);
+        const bool is_last = (unsigned)__builtin_amdgcn_readfirstlane((int)old) == (unsigned)(ncover - 1);
         if (!is_last) return false;
         const float *base = P.part + (size_t)s * P.part_slots * (D + 2);
         // loads of up to CB partials are in flight together (one round trip per batch)
