@@ -56,10 +56,15 @@ struct GemvSeg {
     int rows;            // rows in the block (may be 0)
 };
 
-template <int U_>
+// XB: extra register sets that only ever hold blocks 3 .. 2 + XB of the span - for a
+// GEMV whose first blocks are requested long before its activations exist (ahead of a
+// hand-over with nothing else to stream): the stretch then starts with 2 + XB blocks in
+// registers and the queue is full again by the time they are consumed.
+template <int U_, int XB = 0>
 struct GemvSpan {
     static constexpr int U = U_;
     u32x4 a[U], b[U];
+    u32x4 ex[XB > 0 ? XB : 1][U];
     const __half *w0, *w1;          // block bases (uniform)
     const __half *p0, *p1;          // the same, or `safe` when this wavefront streams nothing
     unsigned lane_off;              // this lane's byte offset inside a unit
@@ -129,6 +134,16 @@ struct GemvSpan {
     }
     __device__ __forceinline__ void issue_first() { issue(a, lo); }
     __device__ __forceinline__ void issue_second() { issue(b, lo + U); }
+    // (XB > 0) blocks 3 .. 2 + XB
+    __device__ __forceinline__ void issue_more()
+    {
+        static_assert(XB > 0, "issue_more() needs the extra register sets");
+#pragma unroll
+        for (int x = 0; x < XB; ++x)
+#pragma unroll
+            for (int j = 0; j < U; ++j) ex[x][j] = load16_stream_at(unit_ptr(lo + (2 + x) * U + j), lane_off);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     __device__ __forceinline__ void consume(const u32x4 (&r)[U], int i, float *part)
     {
@@ -188,6 +203,15 @@ struct GemvSpan {
     {
         if (!regular) { before_drain(); run_general(part); return; }
         int i = lo;
+        if constexpr (XB > 0) {
+            // 2 + XB blocks are in registers: the first two are replaced as they are consumed,
+            // the others just drain
+            consume(a, i, part); issue(a, i + (2 + XB) * U);
+            consume(b, i + U, part); issue(b, i + (3 + XB) * U);
+#pragma unroll
+            for (int x = 0; x < XB; ++x) consume(ex[x], i + (2 + x) * U, part);
+            i += (2 + XB) * U;
+        }
         // Steady state: consume the older block, refill it two blocks ahead.  The
         // last two blocks are consumed without issuing anything, so that no load
         // is left in flight when the epilogue (or a grid barrier) waits on memory.

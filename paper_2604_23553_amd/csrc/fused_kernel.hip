@@ -180,7 +180,14 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
     float *y1 = lds + C.L.y1, *y2 = lds + C.L.y2, *ml = lds + C.L.ml, *ol = lds + C.L.ol;
     const int n_tok = C.pos + 1;
 
-    GemvSpan<kGemvU> gsQ, gsU, gsD, gsC;
+    // The two stretches that follow a gap with nothing to stream start with more blocks in
+    // registers than the usual two: the QKV rows behind the layer-input hand-over (two more,
+    // requested when that hand-over begins), the down rows behind the staging of GELU(up)
+    // (one more, requested behind the staging loads).  Measured: more, or earlier, only
+    // lengthens the queue the hand-over's own loads wait in.
+    GemvSpan<kGemvU, 2> gsQ;
+    GemvSpan<kGemvU, 1> gsD;
+    GemvSpan<kGemvU> gsU, gsC;
     {
         const int tid0 = opaque_thread_index();
         const __half *w0 = C.ptrs->w[0];
@@ -188,6 +195,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
                  w0, tid0, 0);
         gsQ.issue_first();
         gsQ.issue_second();
+        gsQ.issue_more();
     }
     Tracer tr;
     tr.init(P, gsQ.wave, 0);
@@ -268,6 +276,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
         {
             StagedVector<kStageMStream> sm;                // (the chain wavefront is busy with the partials)
             sm.issue(P.m, f, tid - 64, NS * 64);
+            gsD.issue_more();
             sm.commit(f, ml, tid - 64, NS * 64);
         }
         // GELU(up) staged: a rendezvous of the streaming wavefronts only (the chain
@@ -295,6 +304,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
         tr.mark(23);
         __syncthreads();                                   // S6: dense rows done
         tr.mark(24);
+        gsQ.issue_more();                                  // (the last layer's re-read one block)
         {
             // the next layer's partial-sum slots (the chain wavefront still reads this layer's)
             float *nx = lds + C.L.pq + (C.L.pset - set);
