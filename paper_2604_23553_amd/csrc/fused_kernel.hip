@@ -222,20 +222,20 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
         __syncthreads();                                   // S1: QKV rows done
         tr.mark(5);
 
-        // attention share: the first two K/V rows are requested behind the last up-projection weights
+        // attention share: the first K/V row is requested behind the last up-projection weights, the
+        // second behind the barrier (both ahead of it and the chain wavefront's GELU(up) stores
+        // and barrier arrival queue behind 36 MB instead of 18: measured)
         AC ac;
         ac.init(P, kv, n_tok, lane);
         FusedSegs<D> sg;
         sg.init(ac);
         u32x4 kA[NP], vA[NP], kB[NP], vB[NP];
         const int row0 = sg.row_lo[0] + si;
-        gsU.run(pu, [&] {
-            ac.issue(kA, vA, sg.s[0], sg.n > 0 && row0 < sg.row_hi[0] ? row0 : -1);
-            ac.issue(kB, vB, sg.s[0], sg.n > 0 && row0 + NS < sg.row_hi[0] ? row0 + NS : -1);
-        });
+        gsU.run(pu, [&] { ac.issue(kA, vA, sg.s[0], sg.n > 0 && row0 < sg.row_hi[0] ? row0 : -1); });
         tr.mark(6);
         __syncthreads();                                   // S2: up rows done; q and the new K/V rows staged
         tr.mark(10);
+        ac.issue(kB, vB, sg.s[0], sg.n > 0 && row0 + NS < sg.row_hi[0] ? row0 + NS : -1);
 
         gsD.init(GemvSeg{w + P.lay.w_down + (size_t)C.r_begin * f, ml, f, C.r_n}, GemvSeg{w + P.lay.w_down, ml, f, 0},
                  w, tid, 0);
