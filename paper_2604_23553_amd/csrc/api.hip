@@ -471,8 +471,7 @@ static cfpp_status launch_batched_layer(const cfpp_ctx *ctx, const Shape &sh, co
         B.o = reinterpret_cast<float *>(ctx->ws + wl.o) + (size_t)b0 * dm.h;
         B.rope = reinterpret_cast<const float2 *>(ctx->ws + wl.rope);
         B.sync = reinterpret_cast<unsigned *>(ctx->ws + wl.sync);
-        HIP_OK(launch_bat_qkv(B, sh.grid, s));
-        HIP_OK(launch_bat_up(B, sh.grid, s));
+        HIP_OK(launch_bat_qkv_up(B, sh.grid, s));
         if (sh.grid >= B.nb) {
             StepParams P = make_params(ctx, sh, b0, x, pos_dev, out, n_layers);
             if (kv_seq >= 0) { P.b = kv_seq; P.attn_bstep = 0; }

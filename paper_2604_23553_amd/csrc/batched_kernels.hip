@@ -9,9 +9,9 @@
 // fp16 remainder (y = hi + lo exactly to ~2^-22), two MFMAs per tile, fp32
 // accumulation - the result matches the fp32 FMA path to rounding.
 //
-//   k_bat_proj<T, MODE> : LayerNorm of every sequence (one wavefront each), then
-//                         MODE 0: QKV rows + bias, rotary, K/V append, q
-//                         MODE 1: MLP-up rows + bias + GELU
+//   k_bat_qkv_up<TQ, TU>: both LayerNorms of every sequence (input and statistics
+//                         once), QKV rows + bias, rotary, K/V append, q, then the
+//                         MLP-up rows + bias + GELU
 //   k_bat_out<T>        : output projection of the attention output, then the
 //                         MLP-down rows (K in slices of `hidden` through the same
 //                         LDS), + biases + residual -> the block output
@@ -239,17 +239,20 @@ struct BatStage {
     }
 };
 
-// LayerNorm of every sequence (two passes, biased variance) -> hi/lo rows in
-// LDS.  A thread owns one group of 8 elements of every sequence (hidden <= 4096);
-// the sums go through `red` (2 * 8 * kBatMax floats) in wavefront order.  load()
-// requests inputs and parameters, finish() does the rest: the first weights are
-// requested in between and stream while the statistics are worked out.
+// Both LayerNorms of every sequence (they share input and statistics; two passes,
+// biased variance) -> hi/lo rows in LDS.  A thread owns one group of 8 elements of
+// every sequence (hidden <= 4096); the sums go through `red` (2 * 8 * kBatMax floats)
+// in wavefront order.  load() requests the input and both parameter pairs, stats()
+// works out mean and 1/sigma per sequence, write() puts one of the two normalised
+// inputs into LDS: the first weights are requested between load() and stats() and
+// stream while the statistics are worked out.
 struct BatLn {
     u32x4 raw16[kBatMax];          // layer 0: fp16 input
     f32x4 raw32[kBatMax][2];       // later layers: fp32 residual stream
-    u32x4 graw, braw;
+    u32x4 graw[2], braw[2];
+    float xv[kBatMax][8], mean[kBatMax], inv[kBatMax];
 
-    __device__ __forceinline__ void load(const BatParams &P, const __half *gam, const __half *bet, int tid)
+    __device__ __forceinline__ void load(const BatParams &P, int tid)
     {
         const int h = P.dm.h, nchunk = h >> 3;
         const int c = tid < nchunk ? tid : 0;
@@ -265,16 +268,17 @@ struct BatLn {
                 raw32[b][1] = *as_global(reinterpret_cast<const f32x4 *>(p + 4));
             }
         }
-        graw = *as_global(reinterpret_cast<const u32x4 *>(gam + 8 * c));
-        braw = *as_global(reinterpret_cast<const u32x4 *>(bet + 8 * c));
+        const __half *w = P.w;
+        graw[0] = *as_global(reinterpret_cast<const u32x4 *>(w + P.lay.ln1_g + 8 * c));
+        braw[0] = *as_global(reinterpret_cast<const u32x4 *>(w + P.lay.ln1_b + 8 * c));
+        graw[1] = *as_global(reinterpret_cast<const u32x4 *>(w + P.lay.ln2_g + 8 * c));
+        braw[1] = *as_global(reinterpret_cast<const u32x4 *>(w + P.lay.ln2_b + 8 * c));
     }
 
-    __device__ __forceinline__ void finish(const BatParams &P, __half *yh, __half *yl, int Ks, float *red, int tid)
+    __device__ __forceinline__ void stats(const BatParams &P, float *red, int tid)
     {
         const int h = P.dm.h, nchunk = h >> 3, lane = tid & 63, wave = tid >> 6;
         const bool active = tid < nchunk;
-        const int c = active ? tid : 0;
-        float xv[kBatMax][8];
         if (P.layer == 0) {
 #pragma unroll
             for (int b = 0; b < kBatMax; ++b) {
@@ -298,7 +302,6 @@ struct BatLn {
             if (lane == 0) red[wave * kBatMax + b] = s;
         }
         __syncthreads();
-        float mean[kBatMax];
 #pragma unroll
         for (int b = 0; b < kBatMax; ++b) {
             float s = 0.f;
@@ -319,89 +322,120 @@ struct BatLn {
             if (lane == 0) red2[wave * kBatMax + b] = s;
         }
         __syncthreads();
-        if (!active) return;
-        const unsigned gw[4] = {graw.x, graw.y, graw.z, graw.w}, bw[4] = {braw.x, braw.y, braw.z, braw.w};
+#pragma unroll
+        for (int b = 0; b < kBatMax; ++b) {
+            float s = 0.f;
+            for (int w = 0; w < 8; ++w) s += red2[w * kBatMax + b];
+            inv[b] = 1.0f / sqrtf(s / (float)h + P.dm.ln_eps);
+        }
+    }
+
+    // which: 0 = the LayerNorm in front of QKV, 1 = the one in front of the MLP
+    __device__ __forceinline__ void write(const BatParams &P, int which, __half *yh, __half *yl, int Ks, int tid) const
+    {
+        if (tid >= (P.dm.h >> 3)) return;
+        const u32x4 g = graw[which], bt = braw[which];
+        const unsigned gw[4] = {g.x, g.y, g.z, g.w}, bw[4] = {bt.x, bt.y, bt.z, bt.w};
 #pragma unroll
         for (int b = 0; b < kBatMax; ++b) {
             if (b < P.nb) {
-                float s = 0.f;
-                for (int w = 0; w < 8; ++w) s += red2[w * kBatMax + b];
-                const float inv = 1.0f / sqrtf(s / (float)h + P.dm.ln_eps);
                 float yv[8];
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2) {
                     const float2 g2 = unpack_h2(gw[e2]), b2 = unpack_h2(bw[e2]);
-                    yv[2 * e2] = (xv[b][2 * e2] - mean[b]) * inv * g2.x + b2.x;
-                    yv[2 * e2 + 1] = (xv[b][2 * e2 + 1] - mean[b]) * inv * g2.y + b2.y;
+                    yv[2 * e2] = (xv[b][2 * e2] - mean[b]) * inv[b] * g2.x + b2.x;
+                    yv[2 * e2 + 1] = (xv[b][2 * e2 + 1] - mean[b]) * inv[b] * g2.y + b2.y;
                 }
-                bat_put8(yh, yl, b * Ks + 8 * c, yv);
+                bat_put8(yh, yl, b * Ks + 8 * tid, yv);
             }
         }
     }
 };
 
-template <int T, int MODE>
-__global__ void __launch_bounds__(512) k_bat_proj(BatParams P)
+// QKV rows of this workgroup from the summed accumulators: + bias, rotary, K/V append, q.
+// Pairs of adjacent packed rows (a rotary pair sits in one), as in the per-sequence epilogue.
+template <int T>
+__device__ __forceinline__ void bat_finish_qkv(const BatParams &P, const float *red, int r_begin, int r_n, int b,
+                                               int tid)
+{
+    const Dims &dm = P.dm;
+    const __half *bq = P.w + P.lay.b_qkv;
+    const int h = dm.h, d = dm.d, r = dm.r, pos = P.pos[b];
+    for (int pr = tid >> 3; 2 * pr < r_n; pr += 64) {
+        const int p = r_begin + 2 * pr;                    // packed row, even (rows is even)
+        const int pd = p / d, i = p - pd * d;
+        const int nh = pd / 3, c = pd - 3 * nh;
+        float v0 = bat_total<T>(red, 2 * pr, b) + __half2float(bq[p]);
+        float v1 = bat_total<T>(red, 2 * pr + 1, b) + __half2float(bq[p + 1]);
+        int d0 = i, d1 = i + 1;
+        if (c < 2 && i < r) {
+            const float2 cs = P.rope[(size_t)pos * (r >> 1) + (i >> 1)];
+            const float lo = v0 * cs.x - v1 * cs.y, hi = v1 * cs.x + v0 * cs.y;
+            v0 = lo; v1 = hi;
+            d0 = i >> 1; d1 = (i >> 1) + (r >> 1);
+        }
+        if (c == 0) {
+            P.q[(size_t)b * h + nh * d + d0] = v0;
+            P.q[(size_t)b * h + nh * d + d1] = v1;
+        } else {
+            P.kv[kv_offset(dm, c - 1, P.kv_b0 + b * P.kv_bstep, nh, d0, pos)] = __float2half_rn(v0);
+            P.kv[kv_offset(dm, c - 1, P.kv_b0 + b * P.kv_bstep, nh, d1, pos)] = __float2half_rn(v1);
+        }
+    }
+}
+
+// LayerNorms, QKV rows and MLP-up rows of a layer in one launch: the input is read and
+// its statistics are worked out once; the MLP-up weights are requested before the QKV
+// rows are finished, so the stream runs on across the two parts.  A workgroup owns
+// P.rows QKV rows (TQ tiles) and P.rows2 MLP-up rows (TU tiles); either share may be
+// empty at the end of the grid.
+template <int TQ, int TU>
+__global__ void __launch_bounds__(512) k_bat_qkv_up(BatParams P)
 {
     extern __shared__ __align__(16) float lds[];
     if (!bat_positions_ok(P)) return;
     const Dims &dm = P.dm;
     const int h = dm.h, tid = threadIdx.x, Ks = h + kBatPad;
     __half *yh = reinterpret_cast<__half *>(lds), *yl = yh + kBatMax * Ks;
-    const int total = MODE == 0 ? 3 * h : dm.f;
-    const int r_begin = blockIdx.x * P.rows, r_n = max(0, min(P.rows, total - r_begin));
-    if (r_n == 0) return;                                  // (whole workgroup)
+    const int q_begin = blockIdx.x * P.rows, q_n = max(0, min(P.rows, 3 * h - q_begin));
+    const int u_begin = blockIdx.x * P.rows2, u_n = max(0, min(P.rows2, dm.f - u_begin));
+    if (q_n == 0 && u_n == 0) return;                      // (whole workgroup)
     const __half *w = P.w;
     float *stat = reinterpret_cast<float *>(yl + kBatMax * Ks);     // behind the activations
     // order of the requests: LayerNorm inputs, then the first weights; the statistics are
-    // worked out while those weights arrive
+    // worked out while those weights arrive.  Rows past a share's end re-read its last row
+    // (an empty share streams the matrix's first row; its results are not used).
     BatLn ln;
-    ln.load(P, w + (MODE == 0 ? P.lay.ln1_g : P.lay.ln2_g), w + (MODE == 0 ? P.lay.ln1_b : P.lay.ln2_b), tid);
-    BatStream<T> bs;
-    bs.begin(w + (MODE == 0 ? P.lay.w_qkv : P.lay.w_up), h, r_begin, r_begin + r_n - 1, 0, h, yh, yl, Ks, tid);
-    ln.finish(P, yh, yl, Ks, stat, tid);
+    ln.load(P, tid);
+    BatStream<TQ> bq;
+    bq.begin(w + P.lay.w_qkv, h, q_n ? q_begin : 0, q_n ? q_begin + q_n - 1 : 0, 0, h, yh, yl, Ks, tid);
+    ln.stats(P, stat, tid);
+    ln.write(P, 0, yh, yl, Ks, tid);
     __syncthreads();
-    f32x4 acc[T];
+    f32x4 accq[TQ], accu[TU];
 #pragma unroll
-    for (int t = 0; t < T; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    bs.run(acc);
+    for (int t = 0; t < TQ; ++t) accq[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < TU; ++t) accu[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bq.run(accq);
+    BatStream<TU> bu;
+    bu.begin(w + P.lay.w_up, h, u_n ? u_begin : 0, u_n ? u_begin + u_n - 1 : 0, 0, h, yh, yl, Ks, tid);
+    __syncthreads();                                       // the first normalised input is no longer read
+    ln.write(P, 1, yh, yl, Ks, tid);
+    __syncthreads();
+    bu.run(accu);
     __syncthreads();                                       // the activations are no longer read: the space is reused
-    float *red = lds;
-    bat_spill<T>(red, acc, tid);
+    float *redq = lds, *redu = lds + 8 * TQ * 16 * kBatMax;
+    bat_spill<TQ>(redq, accq, tid);
+    bat_spill<TU>(redu, accu, tid);
     __syncthreads();
     const int b = tid & (kBatMax - 1);
     if (b >= P.nb) return;
-    if (MODE == 1) {
-        const __half *bu = w + P.lay.b_up;
-        for (int row = tid >> 3; row < r_n; row += 64)
-            P.m[(size_t)b * dm.f + r_begin + row] =
-                gelu_act(bat_total<T>(red, row, b) + __half2float(bu[r_begin + row]), dm.flags);
-    } else {
-        // pairs of adjacent packed rows (a rotary pair sits in one), as in the per-sequence epilogue
-        const __half *bq = w + P.lay.b_qkv;
-        const int d = dm.d, r = dm.r, pos = P.pos[b];
-        for (int pr = tid >> 3; 2 * pr < r_n; pr += 64) {
-            const int p = r_begin + 2 * pr;                // packed row, even (rows is even)
-            const int pd = p / d, i = p - pd * d;
-            const int nh = pd / 3, c = pd - 3 * nh;
-            float v0 = bat_total<T>(red, 2 * pr, b) + __half2float(bq[p]);
-            float v1 = bat_total<T>(red, 2 * pr + 1, b) + __half2float(bq[p + 1]);
-            int d0 = i, d1 = i + 1;
-            if (c < 2 && i < r) {
-                const float2 cs = P.rope[(size_t)pos * (r >> 1) + (i >> 1)];
-                const float lo = v0 * cs.x - v1 * cs.y, hi = v1 * cs.x + v0 * cs.y;
-                v0 = lo; v1 = hi;
-                d0 = i >> 1; d1 = (i >> 1) + (r >> 1);
-            }
-            if (c == 0) {
-                P.q[(size_t)b * h + nh * d + d0] = v0;
-                P.q[(size_t)b * h + nh * d + d1] = v1;
-            } else {
-                P.kv[kv_offset(dm, c - 1, P.kv_b0 + b * P.kv_bstep, nh, d0, pos)] = __float2half_rn(v0);
-                P.kv[kv_offset(dm, c - 1, P.kv_b0 + b * P.kv_bstep, nh, d1, pos)] = __float2half_rn(v1);
-            }
-        }
-    }
+    bat_finish_qkv<TQ>(P, redq, q_begin, q_n, b, tid);
+    const __half *bup = w + P.lay.b_up;
+    for (int row = tid >> 3; row < u_n; row += 64)
+        P.m[(size_t)b * dm.f + u_begin + row] =
+            gelu_act(bat_total<TU>(redu, row, b) + __half2float(bup[u_begin + row]), dm.flags);
 }
 
 template <int T>
@@ -466,34 +500,38 @@ bool bat_supported(const Dims &dm, int grid, int threads)
     // LayerNorm keeps hidden / 64 values per lane; the reduction space fits under the activations
     const int rows_up = (dm.f + grid - 1) / grid, rows_qkv = (((3 * dm.h + grid - 1) / grid) + 1) & ~1;
     const int rows_max = rows_up > rows_qkv ? rows_up : rows_qkv;
+    // (the accumulators of the QKV and MLP-up tiles are spilled side by side: 8 wavefronts x 16 rows x
+    // kBatMax floats per tile)
+    const size_t tiles = (size_t)(rows_qkv + 15) / 16 + (size_t)(rows_up + 15) / 16;
     return threads == 512 && dm.h % 256 == 0 && dm.f % 256 == 0 && dm.h <= 64 * kBatLnPerLane && rows_max <= 64 &&
-           bat_lds_bytes(dm) <= 160 * 1024 && (size_t)8 * 4 * 16 * kBatMax * 4 <= bat_lds_bytes(dm);
+           bat_lds_bytes(dm) <= 160 * 1024 && tiles * 8 * 16 * kBatMax * 4 <= bat_lds_bytes(dm);
 }
 
-template <int MODE>
-static hipError_t launch_proj(const BatParams &P, int grid, size_t lds, hipStream_t s)
+template <int TQ>
+static hipError_t launch_qkv_up_tq(const BatParams &P, int grid, size_t lds, hipStream_t s)
 {
-    const int T = (P.rows + 15) / 16;
-    switch (T) {
-    case 1: hipLaunchKernelGGL((k_bat_proj<1, MODE>), dim3(grid), dim3(512), lds, s, P); break;
-    case 2: hipLaunchKernelGGL((k_bat_proj<2, MODE>), dim3(grid), dim3(512), lds, s, P); break;
-    case 3: hipLaunchKernelGGL((k_bat_proj<3, MODE>), dim3(grid), dim3(512), lds, s, P); break;
-    case 4: hipLaunchKernelGGL((k_bat_proj<4, MODE>), dim3(grid), dim3(512), lds, s, P); break;
+    switch ((P.rows2 + 15) / 16) {
+    case 1: hipLaunchKernelGGL((k_bat_qkv_up<TQ, 1>), dim3(grid), dim3(512), lds, s, P); break;
+    case 2: hipLaunchKernelGGL((k_bat_qkv_up<TQ, 2>), dim3(grid), dim3(512), lds, s, P); break;
+    case 3: hipLaunchKernelGGL((k_bat_qkv_up<TQ, 3>), dim3(grid), dim3(512), lds, s, P); break;
+    case 4: hipLaunchKernelGGL((k_bat_qkv_up<TQ, 4>), dim3(grid), dim3(512), lds, s, P); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_bat_qkv(BatParams P, int grid, hipStream_t s)
+hipError_t launch_bat_qkv_up(BatParams P, int grid, hipStream_t s)
 {
     P.rows = (((3 * P.dm.h + grid - 1) / grid) + 1) & ~1;   // even: a rotary pair stays in one workgroup
-    return launch_proj<0>(P, grid, bat_lds_bytes(P.dm), s);
-}
-
-hipError_t launch_bat_up(BatParams P, int grid, hipStream_t s)
-{
-    P.rows = (P.dm.f + grid - 1) / grid;
-    return launch_proj<1>(P, grid, bat_lds_bytes(P.dm), s);
+    P.rows2 = (P.dm.f + grid - 1) / grid;
+    const size_t lds = bat_lds_bytes(P.dm);
+    switch ((P.rows + 15) / 16) {
+    case 1: return launch_qkv_up_tq<1>(P, grid, lds, s);
+    case 2: return launch_qkv_up_tq<2>(P, grid, lds, s);
+    case 3: return launch_qkv_up_tq<3>(P, grid, lds, s);
+    case 4: return launch_qkv_up_tq<4>(P, grid, lds, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_bat_out(BatParams P, int grid, hipStream_t s)
@@ -519,9 +557,12 @@ hipError_t prepare_bat_kernels(size_t lds_bytes)
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); \
         if (e_ != hipSuccess) return e_; \
     } while (0)
-    CFPP_BAT_ATTR((k_bat_proj<1, 0>)); CFPP_BAT_ATTR((k_bat_proj<2, 0>)); CFPP_BAT_ATTR((k_bat_proj<3, 0>));
-    CFPP_BAT_ATTR((k_bat_proj<4, 0>)); CFPP_BAT_ATTR((k_bat_proj<1, 1>)); CFPP_BAT_ATTR((k_bat_proj<2, 1>));
-    CFPP_BAT_ATTR((k_bat_proj<3, 1>)); CFPP_BAT_ATTR((k_bat_proj<4, 1>));
+    CFPP_BAT_ATTR((k_bat_qkv_up<1, 1>)); CFPP_BAT_ATTR((k_bat_qkv_up<1, 2>)); CFPP_BAT_ATTR((k_bat_qkv_up<1, 3>));
+    CFPP_BAT_ATTR((k_bat_qkv_up<1, 4>)); CFPP_BAT_ATTR((k_bat_qkv_up<2, 1>)); CFPP_BAT_ATTR((k_bat_qkv_up<2, 2>));
+    CFPP_BAT_ATTR((k_bat_qkv_up<2, 3>)); CFPP_BAT_ATTR((k_bat_qkv_up<2, 4>)); CFPP_BAT_ATTR((k_bat_qkv_up<3, 1>));
+    CFPP_BAT_ATTR((k_bat_qkv_up<3, 2>)); CFPP_BAT_ATTR((k_bat_qkv_up<3, 3>)); CFPP_BAT_ATTR((k_bat_qkv_up<3, 4>));
+    CFPP_BAT_ATTR((k_bat_qkv_up<4, 1>)); CFPP_BAT_ATTR((k_bat_qkv_up<4, 2>)); CFPP_BAT_ATTR((k_bat_qkv_up<4, 3>));
+    CFPP_BAT_ATTR((k_bat_qkv_up<4, 4>));
     CFPP_BAT_ATTR(k_bat_out<1>); CFPP_BAT_ATTR(k_bat_out<2>); CFPP_BAT_ATTR(k_bat_out<3>); CFPP_BAT_ATTR(k_bat_out<4>);
 #undef CFPP_BAT_ATTR
     return hipSuccess;

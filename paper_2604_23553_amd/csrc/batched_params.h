@@ -30,13 +30,13 @@ struct BatParams {
     float *o;               // [nb][h]
     const float2 *rope;
     unsigned *sync;
-    int rows;               // matrix rows per workgroup (set by the launcher)
+    int rows, rows2;        // matrix rows per workgroup (set by the launcher; rows2: the MLP-up rows of the
+                            // launch that also runs the QKV rows)
 };
 
 bool bat_supported(const Dims &dm, int grid, int threads);
 size_t bat_lds_bytes(const Dims &dm);
-hipError_t launch_bat_qkv(BatParams P, int grid, hipStream_t s);
-hipError_t launch_bat_up(BatParams P, int grid, hipStream_t s);
+hipError_t launch_bat_qkv_up(BatParams P, int grid, hipStream_t s);
 hipError_t launch_bat_out(BatParams P, int grid, hipStream_t s);
 hipError_t prepare_bat_kernels(size_t lds_bytes);
 
