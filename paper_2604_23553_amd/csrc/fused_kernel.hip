@@ -44,6 +44,12 @@ namespace cfpp {
 
 constexpr int kFusedSegs = 2;       // a workgroup's share of the attention covers at most two heads
 constexpr int kFusedSlots = 8;      // LDS slots for the streaming wavefronts' attention states
+// units per load block of the down rows: the attention output's hand-overs (partials,
+// combine, the poll for o) queue behind this stretch, and with 3 instead of 4 units per block
+// they gain more than the stream loses (measured at the 2.8B shape; 2 loses more).  The
+// head_dim-128 instance keeps 4: at the 6.9B shape the stretch is 2.5 times longer and the
+// hand-overs end well inside it.
+constexpr int kFusedUDown = 3;
 constexpr int kStageMStream = 22;   // float2 per streaming thread when staging GELU(up): ffn <= 44 * 64 * (nw - 1)
 
 // LDS of the fused kernel, in floats
@@ -186,7 +192,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
     // (one more, requested behind the staging loads).  Measured: more, or earlier, only
     // lengthens the queue the hand-over's own loads wait in.
     GemvSpan<kGemvU, 2> gsQ;
-    GemvSpan<kGemvU, 1> gsD;
+    GemvSpan<(D == 128 ? kGemvU : kFusedUDown), 1> gsD;
     GemvSpan<kGemvU> gsU, gsC;
     {
         const int tid0 = opaque_thread_index();
