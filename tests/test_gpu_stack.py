@@ -405,6 +405,37 @@ def test_sequential_form_is_refused_by_the_overlapping_modes():
         ds.close()
 
 
+@pytest.mark.parametrize("shape,S", [
+    (synth.ModelShape(1536, 24, 64, 16, 6144, n_layers=3, name="d64-h1536-x3"), 301),
+    (synth.ModelShape(2048, 16, 128, 32, 8192, n_layers=2, name="d128-h2048-x2"), 77),
+    (synth.ModelShape(1024, 16, 64, 64, 2048, n_layers=2, name="d64-h1024-f2048-x2"), 5),
+])
+def test_whole_stack_kernel_at_other_shapes(orc, shape, S):
+    """Launch mode 2 away from the three benchmark shapes: other row counts per
+    workgroup and wavefront (shares that end inside the first load blocks), a
+    feed-forward width of twice the hidden size, full rotary."""
+    cap = S + 3
+    print(f"[case] fused kernel shape={shape.name} S={S}", flush=True)
+    ds, ws, kvs = build_stack(shape, 61, S, cap)
+    try:
+        ds.set_options(mode=2)
+        x = synth.x_input(shape, 62)
+        ds.set_inputs(x, S)
+        outs = []
+        for _ in range(2):
+            ds.stack_decode()
+            ds.check()
+            outs.append(ds.result()[0].copy())
+        assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
+        ref16, _, Ks, Vs = oracle_stack(orc, shape, ws, kvs, S, x[0])
+        assert_block_close(outs[0], ref16, shape.name)
+        kg, vg = ds.export_kv(0, 0, 0, cap)
+        assert_fp16_rows_match(kg[:, S], Ks[0][:, S], "appended K, layer 0")
+        assert_fp16_rows_match(vg[:, S], Vs[0][:, S], "appended V, layer 0")
+    finally:
+        ds.close()
+
+
 def test_whole_stack_kernel_refuses_rows_of_partial_units():
     """Launch mode 2 splits rows over its streaming wavefronts in whole 512-weight
     units: a hidden size that is not a multiple of 512 is refused (mode 0 runs it)."""
