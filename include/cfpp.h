@@ -74,7 +74,8 @@ typedef struct cfpp_config {
  *   CFPP_FLAG_SEQUENTIAL_RESIDUAL  x1 = x + Dense(Attn(LN1(x))); out = x1 + Down(GELU(Up(LN2(x1))))
  *                                  instead of the parallel form (launch mode 0 only: the
  *                                  other modes overlap the two branches, which this form
- *                                  forbids; they return CFPP_EUNSUPPORTED)             */
+ *                                  forbids; they return CFPP_EUNSUPPORTED, and
+ *                                  CFPP_MODE_AUTO takes mode 0)                        */
 #define CFPP_FLAG_TANH_GELU 1
 #define CFPP_FLAG_SEQUENTIAL_RESIDUAL 2
 
@@ -162,7 +163,7 @@ void cfpp_destroy(cfpp_ctx *ctx);
 
 /* Launch tuning.  Options may be changed between calls (not between capture
  * and replay).
- * Modes 1-3 launch persistent kernels whose workgroups wait for each other:
+ * Modes 1 and 2 launch persistent kernels whose workgroups wait for each other:
  * every workgroup of a launch must be resident at the same time.  The library
  * checks that one launch fits the device; the caller must not run them next to
  * other work on the same GPU (another stream or process): workgroups that do
@@ -170,34 +171,25 @@ void cfpp_destroy(cfpp_ctx *ctx);
  * about 2 s the step is abandoned and the device error flag raised, see
  * cfpp_device_error).  Calls of one context, and of contexts sharing a GPU,
  * belong on one stream. */
-#define CFPP_OPT_MODE     1  /* 0: one kernel per phase (3 per block);
+#define CFPP_OPT_MODE     1  /* CFPP_MODE_AUTO (the default): the fastest mode
+                                that supports the call - the whole-stack kernel
+                                (2) for a stack step and for a block of hidden
+                                size >= 2048 when the shape and the device allow
+                                it, the batched projections (0) for several
+                                sequences, else the phase kernels (0); never
+                                refuses a call for the mode's sake;
+                                0: one kernel per phase (3 per block);
                                 1: one persistent kernel per block;
-                                2: cfpp_stack_*: one fused persistent kernel for
-                                   the whole stack, every grid-wide hand-over
-                                   but the layer output hidden behind weight
-                                   streaming (fastest; needs grid >= n_heads,
-                                   hidden <= 4096, all workgroups resident,
-                                   else CFPP_EUNSUPPORTED); cfpp_block_decode:
-                                   as mode 1;
-                                3: one wave-specialised streaming kernel for the
-                                   whole stack (experimental; selected shape
-                                   classes, else CFPP_EUNSUPPORTED).
-                                Changing the mode waits for the device and
-                                zeroes the workspace's synchronisation words:
-                                not between capture and replay, not inside a
-                                stream capture.                                */
+                                2: one fused persistent kernel for the whole
+                                   stack (cfpp_block_decode: for the one block),
+                                   every grid-wide hand-over but the layer output
+                                   hidden behind weight streaming (fastest; needs
+                                   grid >= n_heads, hidden <= 4096, hidden and
+                                   ffn multiples of 512, all workgroups resident,
+                                   else CFPP_EUNSUPPORTED).                    */
+#define CFPP_MODE_AUTO  (-1)
 #define CFPP_OPT_GRID     2  /* workgroups; 0 = one per compute unit          */
 #define CFPP_OPT_THREADS  3  /* threads per workgroup: 256 or 512             */
-#define CFPP_OPT_PROFILE_SKIP 100 /* profiling aid only.  Bits 0-3: sub-steps to
-                                skip so that the others can be timed alone
-                                (results are then wrong).  Bit 4 (16): workgroup
-                                ((value >> 8) & 0xfff) records a per-wavefront
-                                timeline (mode 2: of layer ((value >> 20) & 255)
-                                - 1, of the last layer when those bits are 0),
-                                bit 5 (32): every workgroup records a few time
-                                stamps of the last layer (mode 2); both are read
-                                back with cfpp_debug_read(which = 4) and leave
-                                the results intact.                             */
 cfpp_status cfpp_set_option(cfpp_ctx *ctx, int32_t option, int64_t value);
 cfpp_status cfpp_get_option(const cfpp_ctx *ctx, int32_t option, int64_t *value);
 
@@ -215,8 +207,8 @@ cfpp_status cfpp_get_option(const cfpp_ctx *ctx, int32_t option, int64_t *value)
  *                  raise the context's device error flag (cfpp_device_error).
  *   out          : DEVICE fp16 [batch, hidden] block output; must not alias x
  * Asynchronous on `stream`.
- * The sequences are independent and share the weights.  Launch mode 0 with
- * batch > 1 streams the weights once per group of up to 8 sequences (the
+ * The sequences are independent and share the weights.  Launch mode 0 (and
+ * CFPP_MODE_AUTO) with batch > 1 streams the weights once per group of up to 8 sequences (the
  * projections run on the matrix cores; needs 512 threads, hidden and ffn
  * multiples of 256, at most 64 matrix rows per workgroup, else - and in the
  * other launch modes - the sequences run one after the other).  With several
@@ -248,7 +240,7 @@ cfpp_status cfpp_stack_decode(cfpp_ctx *ctx, const void *const *packed_layers,
  *         written in every layer
  *   out : DEVICE [n_tokens][hidden] fp16, the last block's output per token;
  *         must not overlap x
- * Launch mode 0 only (CFPP_EUNSUPPORTED otherwise, or for shapes the batched
+ * Launch mode 0 or CFPP_MODE_AUTO only (CFPP_EUNSUPPORTED otherwise, or for shapes the batched
  * projections do not cover); CFPP_EINVAL for positions outside the cache.
  * Asynchronous on `stream`. */
 cfpp_status cfpp_stack_prefill(cfpp_ctx *ctx, const void *const *packed_layers,
@@ -309,31 +301,16 @@ cfpp_status cfpp_generate_capture(cfpp_ctx *ctx, const void *const *packed_layer
                                   int32_t *pos_dev, void *x_buf, void *hidden_buf,
                                   cfpp_stream stream);
 
+/* The whole-stack kernel marks the words its workgroups exchange with a 32-bit
+ * epoch that every launch advances by n_layers + 1; the library counts the
+ * epochs on the host and, before they could wrap (after about 2^32 / (n_layers + 1)
+ * launches), waits for the device and zeroes the counter and the exchanged
+ * words between two launches - once in days of continuous decoding; that one
+ * call (cfpp_stack_decode, cfpp_block_decode or cfpp_stack_replay) synchronises. */
+
 /* Synchronises `stream` and reports (and clears) the device error flag:
  * CFPP_OK, or CFPP_EDEVICE with the reason in cfpp_last_error(). */
 cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream);
-
-/* Test tap: synchronises `stream`, then copies a workspace intermediate of the
- * most recent block to HOST memory as fp32.  which: 0 = rotated q [batch, h],
- * 1 = GELU(up) [batch, f], 2 = down projection incl. bias [batch, h],
- * 3 = attention output before the output projection [batch, h].
- * (Mode 3 keeps the down projection on chip: tap 2 is then not updated.)
- * count = number of floats to copy (from the start). */
-cfpp_status cfpp_debug_read(cfpp_ctx *ctx, int32_t which, float *dst_host, size_t count,
-                            cfpp_stream stream);
-
-/* ---- bandwidth calibration (measurement aids, not part of the method) -------- */
-
-/* Plain streaming kernels whose HBM traffic is known exactly, used to find the
- * streaming bandwidth this GPU sustains and to scale hardware traffic counters.
- * cfpp_stream_read loads every 16-byte word of src (DEVICE, `bytes` a multiple of
- * 16) once and XORs a checksum into sink (DEVICE, uint32[grid], caller-zeroed);
- * cfpp_stream_copy copies src to dst.  grid <= 65536, threads 256 or 512,
- * unroll = 16-byte loads in flight per thread (2, 4 or 8). */
-cfpp_status cfpp_stream_read(const void *src, size_t bytes, void *sink, int32_t grid,
-                             int32_t threads, int32_t unroll, cfpp_stream stream);
-cfpp_status cfpp_stream_copy(const void *src, void *dst, size_t bytes, int32_t grid,
-                             int32_t threads, cfpp_stream stream);
 
 #ifdef __cplusplus
 }

@@ -7,6 +7,7 @@ There is no fallback: if the library has not been built, loading raises.
 """
 from __future__ import annotations
 
+import contextlib
 import ctypes as C
 import os
 
@@ -41,19 +42,22 @@ class _LayerSrc(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in LAYER_TENSORS]
 
 
-def library_path() -> str:
-    """The in-tree library, or the build named by CFPP_LIBRARY (kernel experiments)."""
-    return os.environ.get("CFPP_LIBRARY") or os.path.join(_PKG, "libcfpp.so")
+OPT_PROFILE_SKIP, OPT_EPOCH_LIMIT = 100, 101          # profiling library only
+MODE_AUTO = -1
+
+_LIBS = {"product": "libcfpp.so", "profile": "libcfpp_profile.so"}
+_loaded = {}
+_active = "product"
 
 
-_lib = None
+def library_path(kind: str = "product") -> str:
+    """Path of the in-tree library: the product, or the profiling build of the same sources."""
+    return os.path.join(_PKG, _LIBS[kind])
 
 
-def lib() -> C.CDLL:
-    """Loads the built library (build it first: python -m paper_2604_23553_amd.build)."""
-    global _lib
-    if _lib is None:
-        path = library_path()
+def _load(kind: str) -> C.CDLL:
+    if kind not in _loaded:
+        path = library_path(kind)
         if not os.path.exists(path):
             raise FileNotFoundError(
                 f"{path} is missing: build the HIP library with "
@@ -66,8 +70,28 @@ def lib() -> C.CDLL:
             getattr(L, n).argtypes = [C.POINTER(Config)]
         L.cfpp_destroy.restype = None
         L.cfpp_destroy.argtypes = [C.c_void_p]
-        _lib = L
-    return _lib
+        _loaded[kind] = L
+    return _loaded[kind]
+
+
+def lib() -> C.CDLL:
+    """The library the calls below go to: the product (libcfpp.so) unless a
+    `with profile_build():` block is active."""
+    return _load(_active)
+
+
+@contextlib.contextmanager
+def profile_build():
+    """Routes the calls made inside the block to libcfpp_profile.so (tracer, skip
+    bits, test taps, calibration kernels: include/cfpp_profile.h).  A context
+    created inside the block must be used and destroyed inside it."""
+    global _active
+    before = _active
+    _active = "profile"
+    try:
+        yield _load("profile")
+    finally:
+        _active = before
 
 
 def _ptr(t) -> C.c_void_p:
@@ -217,6 +241,7 @@ def cfpp_device_error(ctx: int, stream=None):
     _check(lib().cfpp_device_error(C.c_void_p(ctx), _ptr(stream)), "cfpp_device_error")
 
 
+# ---- profiling library only (inside `with profile_build():`) -------------------
 def cfpp_debug_read(ctx: int, which: int, count: int, stream=None):
     import numpy as np
     out = np.empty(count, dtype=np.float32)

@@ -11,6 +11,9 @@
 #include <vector>
 
 #include "cfpp.h"
+#ifdef CFPP_PROFILE
+#include "cfpp_profile.h"
+#endif
 #include "lm_params.h"
 #include "batched_params.h"
 #include "decode_params.h"
@@ -28,6 +31,13 @@ static cfpp_status fail(cfpp_status st, const char *fmt, ...)
     va_end(ap);
     return st;
 }
+
+// keeps the calling thread's error text over a probe whose refusal is not the caller's error
+struct g_err_hold {
+    char saved[sizeof g_err];
+    g_err_hold() { std::memcpy(saved, g_err, sizeof g_err); }
+    ~g_err_hold() { std::memcpy(g_err, saved, sizeof g_err); }
+};
 
 #define HIP_OK(call)                                                                  \
     do {                                                                              \
@@ -180,6 +190,7 @@ extern "C" cfpp_status cfpp_kv_export(const cfpp_config *c, const void *kv_layer
 }
 
 // ---- context -----------------------------------------------------------------------
+static const unsigned long long kEpochLimit = 0xF0000000ull;   // re-zero the epoch counter beyond this many epochs
 struct cfpp_ctx {
     cfpp_config cfg;
     Dims dm;
@@ -188,11 +199,14 @@ struct cfpp_ctx {
     char *ws;
     int n_cu;
     int mode, grid, threads, debug;
-    int events_grid;   // grid size the stream kernel's event counters are consistent with (0: zeroed)
+    unsigned long long epochs_used, epoch_limit;   // tagged-word epochs handed out since the last zeroing; re-zero beyond the limit
     size_t lds_limit;
     bool prepared, lm_prepared;
     hipGraph_t graph;
     hipGraphExec_t exec;
+    unsigned long long graph_epochs;   // tagged-word epochs one replay of the captured graph uses up
+    int fused_grid, fused_threads;     // launch shape the whole-stack kernel was last found to fit
+    bool fused_ok;
     int last_batch;
 };
 
@@ -222,21 +236,24 @@ extern "C" cfpp_status cfpp_create(const cfpp_config *c, void *workspace, size_t
     ctx->wl = wl;
     ctx->ws = static_cast<char *>(workspace);
     ctx->n_cu = prop.multiProcessorCount;
-    ctx->mode = 0;
+    ctx->mode = CFPP_MODE_AUTO;
     ctx->grid = 0;
     ctx->threads = 512;
     ctx->debug = 0;
-    ctx->events_grid = 0;
+    ctx->epochs_used = 0;
+    ctx->epoch_limit = kEpochLimit;
     ctx->lds_limit = prop.sharedMemPerBlock > 0 ? (size_t)prop.sharedMemPerBlock : 65536;
     ctx->prepared = false;
     ctx->lm_prepared = false;
     ctx->graph = nullptr;
     ctx->exec = nullptr;
+    ctx->graph_epochs = 0;
+    ctx->fused_grid = 0; ctx->fused_threads = 0; ctx->fused_ok = false;
     ctx->last_batch = 1;
 
     // barrier words, error flag and per-head arrival counters start at zero
     hipError_t e = hipMemset(ctx->ws + wl.sync, 0, wl.layer_ptrs - wl.sync);
-    if (e == hipSuccess) e = hipMemset(ctx->ws + wl.events, 0, wl.rope - wl.events);
+    if (e == hipSuccess) e = hipMemset(ctx->ws + wl.tagged, 0, wl.rope - wl.tagged);
     // rotary table in double on the host: angle = pos * base^(-2j/r)
     std::vector<float> tab;
     const int half = dm.r / 2;
@@ -269,22 +286,25 @@ extern "C" void cfpp_destroy(cfpp_ctx *ctx)
     delete ctx;
 }
 
+// Barrier words, error flag, arrival counters, the epoch counter and the tagged
+// words back to zero (waits for the device; never inside a stream capture).
+static cfpp_status reset_sync_words(cfpp_ctx *ctx)
+{
+    HIP_OK(hipDeviceSynchronize());
+    HIP_OK(hipMemset(ctx->ws + ctx->wl.sync, 0, ctx->wl.layer_ptrs - ctx->wl.sync));
+    HIP_OK(hipMemset(ctx->ws + ctx->wl.tagged, 0, ctx->wl.rope - ctx->wl.tagged));
+    HIP_OK(hipDeviceSynchronize());
+    ctx->epochs_used = 0;
+    return CFPP_OK;
+}
+
 extern "C" cfpp_status cfpp_set_option(cfpp_ctx *ctx, int32_t option, int64_t value)
 {
     if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
     switch (option) {
     case CFPP_OPT_MODE:
-        if (value < 0 || value > 3) return fail(CFPP_EINVAL, "mode must be 0, 1, 2 or 3");
-        if ((int)value != ctx->mode) {
-            // The modes tag their exchanged words from different counters: start the
-            // new one from zeroed barrier words, counters and tagged words (waits for
-            // the device; not for use inside a stream capture).
-            HIP_OK(hipDeviceSynchronize());
-            HIP_OK(hipMemset(ctx->ws + ctx->wl.sync, 0, ctx->wl.layer_ptrs - ctx->wl.sync));
-            HIP_OK(hipMemset(ctx->ws + ctx->wl.events, 0, ctx->wl.rope - ctx->wl.events));
-            HIP_OK(hipDeviceSynchronize());
-            ctx->events_grid = 0;
-        }
+        if (value == 3) return fail(CFPP_EUNSUPPORTED, "launch mode 3 (the wave-specialised stream kernel) has been retired");
+        if (value < CFPP_MODE_AUTO || value > 2) return fail(CFPP_EINVAL, "mode must be -1 (auto), 0, 1 or 2");
         ctx->mode = (int)value;
         return CFPP_OK;
     case CFPP_OPT_GRID:
@@ -295,9 +315,15 @@ extern "C" cfpp_status cfpp_set_option(cfpp_ctx *ctx, int32_t option, int64_t va
         if (value != 256 && value != 512) return fail(CFPP_EINVAL, "threads must be 256 or 512");
         ctx->threads = (int)value;
         return CFPP_OK;
+#ifdef CFPP_PROFILE
     case CFPP_OPT_PROFILE_SKIP:
         ctx->debug = (int)value;
         return CFPP_OK;
+    case CFPP_OPT_EPOCH_LIMIT:
+        if (value < 1 || value > 0xffffffffll) return fail(CFPP_EINVAL, "epoch limit outside [1, 2^32)");
+        ctx->epoch_limit = (unsigned long long)value;
+        return CFPP_OK;
+#endif
     }
     return fail(CFPP_EINVAL, "unknown option %d", option);
 }
@@ -374,7 +400,6 @@ static cfpp_status prepare(cfpp_ctx *ctx)
 {
     if (ctx->prepared) return CFPP_OK;
     HIP_OK(prepare_kernels(160 * 1024));
-    HIP_OK(prepare_stream_kernels(160 * 1024));
     HIP_OK(prepare_fused_kernels(160 * 1024));
     HIP_OK(prepare_bat_kernels(160 * 1024));
     ctx->prepared = true;
@@ -414,6 +439,8 @@ static StepParams make_params(const cfpp_ctx *ctx, const Shape &sh, int b, const
     P.lds_floats = sh.lds_floats;
     P.debug = ctx->debug;
     P.trace = reinterpret_cast<unsigned long long *>(ctx->ws + wl.trace);
+    P.w_single = nullptr;
+    P.kv_single = nullptr;
     return P;
 }
 
@@ -437,10 +464,13 @@ static hipError_t launch_block_phases(const StepParams &P, const __half *w, __ha
 // Launch mode 0 with several sequences: the projections of a layer run once for
 // groups of up to kBatMax sequences (weights streamed once per group, matrix
 // cores), the attention per sequence in between.
+static bool batched_path_shape(const cfpp_ctx *ctx, const Shape &sh)
+{
+    return !(ctx->dm.flags & kFlagSequentialResidual) && bat_supported(ctx->dm, sh.grid, sh.threads);
+}
 static bool batched_path(const cfpp_ctx *ctx, const Shape &sh, int batch)
 {
-    return ctx->mode == 0 && batch > 1 && !(ctx->dm.flags & kFlagSequentialResidual) &&
-           bat_supported(ctx->dm, sh.grid, sh.threads);
+    return batch > 1 && batched_path_shape(ctx, sh);
 }
 
 // kv_seq < 0: row i of x / pos / out is sequence i with its own cache (a decode step of
@@ -488,13 +518,6 @@ static cfpp_status launch_batched_layer(const cfpp_ctx *ctx, const Shape &sh, co
     return CFPP_OK;
 }
 
-static cfpp_status check_form(const cfpp_ctx *ctx)
-{
-    if ((ctx->dm.flags & kFlagSequentialResidual) && ctx->mode != 0)
-        return fail(CFPP_EUNSUPPORTED, "the sequential residual form runs in launch mode 0 only");
-    return CFPP_OK;
-}
-
 static cfpp_status check_persistent(const cfpp_ctx *ctx, const Shape &sh)
 {
     int per_cu = 0;
@@ -507,8 +530,10 @@ static cfpp_status check_persistent(const cfpp_ctx *ctx, const Shape &sh)
 }
 
 // Mode 2 (whole stack, hand-overs hidden behind streaming): shape limits and residency.
-static cfpp_status check_fused(const cfpp_ctx *ctx, const Shape &sh, const StepParams &P)
+// The answer depends on the launch shape only and is remembered for the last one asked.
+static cfpp_status check_fused(cfpp_ctx *ctx, const Shape &sh, const StepParams &P)
 {
+    if (ctx->fused_grid == sh.grid && ctx->fused_threads == sh.threads && ctx->fused_ok) return CFPP_OK;
     if (!fused_supported(ctx->dm, P, sh.grid, sh.threads))
         return fail(CFPP_EUNSUPPORTED,
                     "mode 2 needs grid >= n_heads, at most 64 rows of the hidden-size matrices per workgroup, "
@@ -521,6 +546,7 @@ static cfpp_status check_fused(const cfpp_ctx *ctx, const Shape &sh, const StepP
     if ((long long)per_cu * ctx->n_cu < sh.grid)
         return fail(CFPP_EUNSUPPORTED, "mode 2 needs all %d workgroups resident, device fits %d x %d", sh.grid,
                     per_cu, ctx->n_cu);
+    ctx->fused_grid = sh.grid; ctx->fused_threads = sh.threads; ctx->fused_ok = true;
     return CFPP_OK;
 }
 
@@ -538,42 +564,62 @@ static cfpp_status check_io(const cfpp_ctx *ctx, const void *x, const int32_t *p
     return CFPP_OK;
 }
 
-// Stream mode (3): shape and residency checks, event counters consistent with the grid.
-static cfpp_status stream_check(cfpp_ctx *ctx, Shape *sh)
+// The launch mode a call runs in.  An explicit mode is checked and refused when
+// the shape has no kernel in it; CFPP_MODE_AUTO takes the fastest mode that
+// supports the call and never refuses: several sequences -> the batched
+// projections (mode 0); the whole-stack kernel where its shape limits and the
+// residency check allow it (a stack step always, a block on its own from hidden
+// 2048 on: below that a block is a handful of dependent hand-overs with nothing to
+// stream behind them and the three phase kernels are quicker); else the phase kernels.
+static cfpp_status resolve_mode(cfpp_ctx *ctx, const Shape &sh, const StepParams &P, int batch, bool stack,
+                                int *mode_out)
 {
-    sh->threads = 512;
-    if (!stream_supported(ctx->dm, sh->grid))
-        return fail(CFPP_EUNSUPPORTED,
-                    "stream mode supports the 2.8B-like (d 80, h 2560), 6.9B-like (d 128, h 4096) and "
-                    "h-512 (d 64) shape classes with grid >= n_heads; use mode 0 for this shape");
+    int mode = ctx->mode;
+    if (mode == CFPP_MODE_AUTO) {
+        mode = 0;
+        const bool one_by_one = batch == 1 || !batched_path_shape(ctx, sh);
+        if (one_by_one && (stack || ctx->dm.h >= 2048)) {
+            g_err_hold hold;                               // a refusal here is not the caller's error
+            if (check_fused(ctx, sh, P) == CFPP_OK) mode = 2;
+        }
+        *mode_out = mode;
+        return CFPP_OK;
+    }
+    *mode_out = mode;
+    if (mode == 2) return check_fused(ctx, sh, P);
+    if (mode == 1) {
+        if (ctx->dm.flags & kFlagSequentialResidual)
+            return fail(CFPP_EUNSUPPORTED, "the sequential residual form runs in launch modes 0 and 2");
+        return check_persistent(ctx, sh);
+    }
     return CFPP_OK;
 }
 
-static cfpp_status stream_residency(const cfpp_ctx *ctx, const Shape &sh, const StepParams &P)
+// Tagged-word epochs: every launch of the whole-stack kernel uses up n_layers + 1
+// values of a 32-bit counter that lives in the workspace.  Long before it could
+// wrap (and a stale word compare equal to a live tag) the counter and the tagged
+// region are zeroed again, between launches, never inside a graph.
+static cfpp_status account_epochs(cfpp_ctx *ctx, unsigned long long need)
 {
-    const size_t lds = stream_lds_bytes(ctx->dm, P, sh.threads, nullptr);
-    if (lds > 160 * 1024) return fail(CFPP_EUNSUPPORTED, "stream mode needs %zu bytes of LDS", lds);
-    int per_cu = 0;
-    HIP_OK(stream_occupancy(ctx->dm, sh.threads, lds, &per_cu));
-    if ((long long)per_cu * ctx->n_cu < sh.grid)
-        return fail(CFPP_EUNSUPPORTED, "stream mode needs all %d workgroups resident, device fits %d x %d",
-                    sh.grid, per_cu, ctx->n_cu);
+    if (ctx->epochs_used + need > ctx->epoch_limit) {
+        cfpp_status st = reset_sync_words(ctx);
+        if (st != CFPP_OK) return st;
+    }
+    ctx->epochs_used += need;
     return CFPP_OK;
 }
 
-// (not capturable: records a memset) zero the event counters when the grid they
-// were counted with changes
-static cfpp_status stream_rearm(cfpp_ctx *ctx, int grid, hipStream_t s)
+static bool capturing(hipStream_t s)
 {
-    if (ctx->events_grid == grid) return CFPP_OK;
-    HIP_OK(hipMemsetAsync(ctx->ws + ctx->wl.events, 0, ctx->wl.rope - ctx->wl.events, s));
-    ctx->events_grid = grid;
-    return CFPP_OK;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cs) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return cs != hipStreamCaptureStatusNone;
 }
 
-extern "C" cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer, void *kv_layer,
-                                         const void *x, const int32_t *pos_dev, int32_t batch, void *out,
-                                         cfpp_stream stream)
+// phases_only: run the phase kernels (launch mode 0) whatever the context's mode says
+static cfpp_status block_decode(cfpp_ctx *ctx, const void *packed_layer, void *kv_layer, const void *x,
+                                const int32_t *pos_dev, int32_t batch, void *out, cfpp_stream stream,
+                                bool phases_only)
 {
     cfpp_status st = check_io(ctx, x, pos_dev, batch, out);
     if (st != CFPP_OK) return st;
@@ -581,53 +627,47 @@ extern "C" cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer
         return fail(CFPP_EINVAL, "packed_layer or kv_layer is NULL or not 16-byte aligned");
     Shape sh;
     if ((st = launch_shape(ctx, &sh)) != CFPP_OK) return st;
-    if ((st = check_form(ctx)) != CFPP_OK) return st;
     if ((st = prepare(ctx)) != CFPP_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int slots = (ctx->dm.flags & kFlagSequentialResidual) ? 2 : 1;   // residual slots per block
-    if (ctx->mode == 3) {
-        if ((st = stream_check(ctx, &sh)) != CFPP_OK) return st;
-        if ((st = stream_residency(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, 1))) != CFPP_OK) return st;
-        if ((st = stream_rearm(ctx, sh.grid, s)) != CFPP_OK) return st;
-        LayerPtrs ptrs;
-        std::memset(&ptrs, 0, sizeof ptrs);
-        ptrs.w[0] = static_cast<const __half *>(packed_layer);
-        ptrs.kv[0] = static_cast<__half *>(kv_layer);
-        LayerPtrs *dev_ptrs = reinterpret_cast<LayerPtrs *>(ctx->ws + ctx->wl.layer_ptrs);
-        HIP_OK(launch_store_layer_ptrs(ptrs, dev_ptrs, 1, s));
-        for (int b = 0; b < batch; ++b) {
-            const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, 1);
-            HIP_OK(launch_stack_stream(P, dev_ptrs, reinterpret_cast<unsigned long long *>(ctx->ws + ctx->wl.events),
-                                       reinterpret_cast<float *>(ctx->ws + ctx->wl.tagged), sh.grid, sh.threads, s));
-        }
-        ctx->last_batch = batch;
-        return CFPP_OK;
-    }
-    if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
-    if (batched_path(ctx, sh, batch)) {
-        ctx->last_batch = batch;
-        return launch_batched_layer(ctx, sh, static_cast<const __half *>(packed_layer), static_cast<__half *>(kv_layer),
-                                    0, 1, x, pos_dev, batch, out, s);
-    }
-    for (int b = 0; b < batch; ++b) {
-        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, ctx->mode == 0 ? slots : 1);
-        if (ctx->mode == 0)
-            HIP_OK(launch_block_phases(P, static_cast<const __half *>(packed_layer), static_cast<__half *>(kv_layer),
-                                       0, sh.grid, sh.threads, s));
-        else
-            HIP_OK(launch_block_persistent(P, static_cast<const __half *>(packed_layer),
-                                           static_cast<__half *>(kv_layer), 0, sh.grid, sh.threads, s));
-    }
+    const bool seq = ctx->dm.flags & kFlagSequentialResidual;
+    int mode = 0;
+    if (!phases_only &&
+        (st = resolve_mode(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, 1), batch, false, &mode)) != CFPP_OK)
+        return st;
+    const __half *w = static_cast<const __half *>(packed_layer);
+    __half *kv = static_cast<__half *>(kv_layer);
     ctx->last_batch = batch;
+    if (mode == 0 && batched_path(ctx, sh, batch)) return launch_batched_layer(ctx, sh, w, kv, 0, 1, x, pos_dev, batch, out, s);
+    if (mode == 2 && !capturing(s) && (st = account_epochs(ctx, 2ull * batch)) != CFPP_OK) return st;
+    for (int b = 0; b < batch; ++b) {
+        StepParams P = make_params(ctx, sh, b, x, pos_dev, out, mode == 0 && seq ? 2 : 1);
+        if (mode == 0) {
+            HIP_OK(launch_block_phases(P, w, kv, 0, sh.grid, sh.threads, s));
+        } else if (mode == 1) {
+            HIP_OK(launch_block_persistent(P, w, kv, 0, sh.grid, sh.threads, s));
+        } else {
+            P.w_single = w;
+            P.kv_single = kv;
+            HIP_OK(launch_stack_fused(P, nullptr, sh.grid, sh.threads, s));
+        }
+    }
     return CFPP_OK;
+}
+
+extern "C" cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer, void *kv_layer,
+                                         const void *x, const int32_t *pos_dev, int32_t batch, void *out,
+                                         cfpp_stream stream)
+{
+    return block_decode(ctx, packed_layer, kv_layer, x, pos_dev, batch, out, stream, false);
 }
 
 // store_table: also enqueue the copy of the pointer table into the workspace
 // (the whole-stack kernel reads it from device memory).  Capture stores it
 // ahead of the captured region, so a replay is the decode kernels alone.
+// epochs: receives the tagged-word epochs the enqueued launches use up.
 static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers, void *const *kv_layers,
                                  const void *x, const int32_t *pos_dev, int32_t batch, void *out,
-                                 hipStream_t s, bool store_table, bool launch)
+                                 hipStream_t s, bool store_table, bool launch, unsigned long long *epochs = nullptr)
 {
     cfpp_status st = check_io(ctx, x, pos_dev, batch, out);
     if (st != CFPP_OK) return st;
@@ -638,15 +678,9 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
             return fail(CFPP_EINVAL, "layer %d: NULL or misaligned pointer", l);
     Shape sh;
     if ((st = launch_shape(ctx, &sh)) != CFPP_OK) return st;
-    if ((st = check_form(ctx)) != CFPP_OK) return st;
-    if (ctx->mode == 3) {
-        if ((st = stream_check(ctx, &sh)) != CFPP_OK) return st;
-        if ((st = stream_residency(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, L))) != CFPP_OK) return st;
-        if (store_table && (st = stream_rearm(ctx, sh.grid, s)) != CFPP_OK) return st;
-        if (!store_table && ctx->events_grid != sh.grid) return fail(CFPP_ESTATE, "event counters not armed for this grid");
-    } else if (ctx->mode == 2) {
-        if ((st = check_fused(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, L))) != CFPP_OK) return st;
-    } else if (ctx->mode != 0 && (st = check_persistent(ctx, sh)) != CFPP_OK) return st;
+    int mode = 0;
+    if ((st = resolve_mode(ctx, sh, make_params(ctx, sh, 0, x, pos_dev, out, L), batch, true, &mode)) != CFPP_OK)
+        return st;
     LayerPtrs ptrs;
     std::memset(&ptrs, 0, sizeof ptrs);
     for (int l = 0; l < L; ++l) {
@@ -654,33 +688,30 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
         ptrs.kv[l] = static_cast<__half *>(kv_layers[l]);
     }
     LayerPtrs *dev_ptrs = reinterpret_cast<LayerPtrs *>(ctx->ws + ctx->wl.layer_ptrs);
-    if (store_table && ctx->mode >= 2) HIP_OK(launch_store_layer_ptrs(ptrs, dev_ptrs, L, s));
+    if (store_table && mode == 2) HIP_OK(launch_store_layer_ptrs(ptrs, dev_ptrs, L, s));
+    if (epochs) *epochs = mode == 2 ? (unsigned long long)(L + 1) * batch : 0;
     if (!launch) return CFPP_OK;
-    if (batched_path(ctx, sh, batch)) {
+    ctx->last_batch = batch;
+    if (mode == 0 && batched_path(ctx, sh, batch)) {
         for (int l = 0; l < L; ++l)
             if ((st = launch_batched_layer(ctx, sh, ptrs.w[l], ptrs.kv[l], l, L, x, pos_dev, batch, out, s)) != CFPP_OK)
                 return st;
-        ctx->last_batch = batch;
         return CFPP_OK;
     }
-    const int slots = (ctx->dm.flags & kFlagSequentialResidual) ? 2 : 1;   // (mode 0 only, checked above)
+    const int slots = (ctx->dm.flags & kFlagSequentialResidual) ? 2 : 1;   // residual slots per block, phase kernels
     for (int b = 0; b < batch; ++b) {
-        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, L * slots);
-        if (ctx->mode == 3) {
-            HIP_OK(launch_stack_stream(P, dev_ptrs, reinterpret_cast<unsigned long long *>(ctx->ws + ctx->wl.events),
-                                       reinterpret_cast<float *>(ctx->ws + ctx->wl.tagged), sh.grid, sh.threads, s));
-        } else if (ctx->mode == 2) {
+        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, mode == 0 ? L * slots : L);
+        if (mode == 2) {
             HIP_OK(launch_stack_fused(P, dev_ptrs, sh.grid, sh.threads, s));
         } else {
             for (int l = 0; l < L; ++l) {
-                if (ctx->mode == 0)
+                if (mode == 0)
                     HIP_OK(launch_block_phases(P, ptrs.w[l], ptrs.kv[l], l, sh.grid, sh.threads, s));
                 else
                     HIP_OK(launch_block_persistent(P, ptrs.w[l], ptrs.kv[l], l, sh.grid, sh.threads, s));
             }
         }
     }
-    ctx->last_batch = batch;
     return CFPP_OK;
 }
 
@@ -691,8 +722,13 @@ extern "C" cfpp_status cfpp_stack_decode(cfpp_ctx *ctx, const void *const *packe
     if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
     cfpp_status st = prepare(ctx);
     if (st != CFPP_OK) return st;
-    return enqueue_stack(ctx, packed_layers, kv_layers, x, pos_dev, batch, out, static_cast<hipStream_t>(stream),
-                         true, true);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!capturing(s)) {
+        // (worst case: every sequence through the whole-stack kernel)
+        if ((st = account_epochs(ctx, (unsigned long long)(ctx->cfg.n_layers + 1) * (batch > 0 ? batch : 1))) != CFPP_OK)
+            return st;
+    }
+    return enqueue_stack(ctx, packed_layers, kv_layers, x, pos_dev, batch, out, s, true, true);
 }
 
 // Prompt processing: groups of up to kBatMax consecutive tokens, each group through every
@@ -722,7 +758,7 @@ extern "C" cfpp_status cfpp_stack_prefill(cfpp_ctx *ctx, const void *const *pack
     }
     Shape sh;
     if ((st = launch_shape(ctx, &sh)) != CFPP_OK) return st;
-    if (ctx->mode != 0 || (ctx->dm.flags & kFlagSequentialResidual))
+    if ((ctx->mode != 0 && ctx->mode != CFPP_MODE_AUTO) || (ctx->dm.flags & kFlagSequentialResidual))
         return fail(CFPP_EUNSUPPORTED, "prompt processing runs in launch mode 0 with the parallel residual form");
     if (!bat_supported(ctx->dm, sh.grid, sh.threads) || sh.grid < kBatMax)
         return fail(CFPP_EUNSUPPORTED, "prompt processing needs the batched projections: 512 threads, grid >= %d, hidden "
@@ -759,7 +795,7 @@ extern "C" cfpp_status cfpp_stack_capture(cfpp_ctx *ctx, const void *const *pack
     if (ctx->exec) { (void)hipGraphExecDestroy(ctx->exec); ctx->exec = nullptr; }
     if (ctx->graph) { (void)hipGraphDestroy(ctx->graph); ctx->graph = nullptr; }
     // validate and store the pointer table first (executes now, not captured)
-    st = enqueue_stack(ctx, packed_layers, kv_layers, x, pos_dev, batch, out, s, true, false);
+    st = enqueue_stack(ctx, packed_layers, kv_layers, x, pos_dev, batch, out, s, true, false, &ctx->graph_epochs);
     if (st != CFPP_OK) return st;
     HIP_OK(hipStreamSynchronize(s));
     HIP_OK(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
@@ -784,6 +820,8 @@ extern "C" cfpp_status cfpp_stack_replay(cfpp_ctx *ctx, cfpp_stream stream)
 {
     if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
     if (!ctx->exec) return fail(CFPP_ESTATE, "cfpp_stack_replay before cfpp_stack_capture");
+    cfpp_status st = account_epochs(ctx, ctx->graph_epochs);
+    if (st != CFPP_OK) return st;
     HIP_OK(hipGraphLaunch(ctx->exec, static_cast<hipStream_t>(stream)));
     return CFPP_OK;
 }
@@ -880,7 +918,7 @@ extern "C" cfpp_status cfpp_generate_capture(cfpp_ctx *ctx, const void *const *p
     if (ctx->exec) { (void)hipGraphExecDestroy(ctx->exec); ctx->exec = nullptr; }
     if (ctx->graph) { (void)hipGraphDestroy(ctx->graph); ctx->graph = nullptr; }
     // validate and store the pointer table first (executes now, not captured)
-    st = enqueue_stack(ctx, packed_layers, kv_layers, x_buf, pos_dev, 1, hidden_buf, s, true, false);
+    st = enqueue_stack(ctx, packed_layers, kv_layers, x_buf, pos_dev, 1, hidden_buf, s, true, false, &ctx->graph_epochs);
     if (st != CFPP_OK) return st;
     HIP_OK(hipStreamSynchronize(s));
     HIP_OK(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
@@ -914,16 +952,18 @@ extern "C" cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream)
     const unsigned err = words[kSyncErr];
     if (err == kErrNone) return CFPP_OK;
     // clear the flag and re-arm the barrier words and arrival counters
-    HIP_OK(hipMemset(ctx->ws + ctx->wl.sync, 0, ctx->wl.layer_ptrs - ctx->wl.sync));
-    HIP_OK(hipMemset(ctx->ws + ctx->wl.events, 0, ctx->wl.rope - ctx->wl.events));
-    ctx->events_grid = 0;
-    HIP_OK(hipDeviceSynchronize());
+    {
+        const cfpp_status st = reset_sync_words(ctx);
+        if (st != CFPP_OK) return st;
+    }
     if (err == kErrBadPos) return fail(CFPP_EDEVICE, "a position in pos_dev was outside [0, max_seq)");
     if (err == kErrBarrierTimeout) return fail(CFPP_EDEVICE, "grid barrier timed out (workgroups not co-resident?)");
     if (err == kErrBadToken) return fail(CFPP_EDEVICE, "a token in tokens_dev was outside [0, vocab)");
     return fail(CFPP_EDEVICE, "device error code %u", err);
 }
 
+#ifdef CFPP_PROFILE
+// ---- profiling library only (declared in cfpp_profile.h) ------------------------------
 extern "C" cfpp_status cfpp_debug_read(cfpp_ctx *ctx, int32_t which, float *dst_host, size_t count,
                                        cfpp_stream stream)
 {
@@ -963,3 +1003,4 @@ extern "C" cfpp_status cfpp_stream_copy(const void *src, void *dst, size_t bytes
     HIP_OK(launch_stream_copy(src, dst, bytes, grid, threads, static_cast<hipStream_t>(stream)));
     return CFPP_OK;
 }
+#endif  // CFPP_PROFILE

@@ -30,10 +30,7 @@ constexpr int kStageM = 16;       // the MLP intermediate is staged with up to 1
 // Loads run two blocks of U units ahead of the arithmetic, and the first two
 // blocks can be issued by the caller long before the activations exist (before a
 // grid barrier, before the attention merges): weights depend on nothing.
-#ifndef CFPP_GEMV_U
-#define CFPP_GEMV_U 4
-#endif
-constexpr int kGemvU = CFPP_GEMV_U;   // (overridable for kernel experiments)
+constexpr int kGemvU = 4;             // units per load block
 // the down projection's first blocks are in flight during the attention arithmetic, which
 // needs most of the register file: smaller blocks there
 constexpr int kGemvUDown = 4;

@@ -219,7 +219,7 @@ __device__ __forceinline__ void attn_share(const StepParams &P, const __half *__
         __syncthreads();
         if (wave == 0) {
             ac.publish(P, s, wp, wm, wl, nw);
-            if (!(P.debug & 8)) {
+            if (!CFPP_SKIPPED(P, 8)) {
                 xwg_wait_stores();
                 tr.mark(15);
                 if (last_seg) tail();

@@ -16,7 +16,7 @@ struct StepParams {
     float *xres;         // [2][h] for this sequence
     float *q, *m, *g, *o;
     float *part;         // [H][part_slots][d+2] for this sequence
-    float *tagged;       // tagged-word region (value, tag pairs): x[2][h], q/k/v[3][h], o[h], part[H][part_slots][d+2]
+    float *tagged;       // tagged-word region (value, tag pairs): x[2][h], (3 h unused), o[h], part[H][part_slots][d+2]
     int part_slots;
     const int *pos;      // device, this sequence's position
     int b;               // sequence index inside the KV cache
@@ -31,9 +31,12 @@ struct StepParams {
     int rows_qkv, rows_up, rows_h;   // matrix rows per workgroup (rows_qkv even)
     int nsl_down, nsl_dense;         // K-slices per row for the two GEMVs with few rows
     unsigned lds_floats;             // dynamic LDS the launch provides, in floats
-    int debug;                       // profiling aid: bit mask of parts to skip (results are then wrong);
-                                     // bit 16: workgroup (debug >> 8) records a timeline into `trace`
+    int debug;                       // profiling library only (0 otherwise): bit mask of parts to skip (results
+                                     // are then wrong); bit 16: workgroup (debug >> 8) records a timeline into `trace`
     unsigned long long *trace;
+    // whole-stack kernel launched for one block on its own (no pointer table): that block's weights and cache
+    const __half *w_single;
+    __half *kv_single;
 };
 
 struct LayerPtrs {
@@ -62,16 +65,6 @@ size_t fused_lds_bytes(const Dims &dm, const StepParams &P, int threads);
 hipError_t launch_stack_fused(const StepParams &P, const LayerPtrs *ptrs, int grid, int threads, hipStream_t s);
 hipError_t fused_occupancy(int head_dim, int threads, size_t lds_bytes, int *blocks_per_cu);
 hipError_t prepare_fused_kernels(size_t lds_bytes);
-
-// implemented in stream_kernel.hip: the wave-specialised whole-stack kernel
-bool stream_supported(const Dims &dm, int grid);
-struct StreamLds;
-size_t stream_lds_bytes(const Dims &dm, const StepParams &P, int threads, StreamLds *out);
-// tagged: the workspace's tagged-word region (see stream_tagged_bytes)
-hipError_t launch_stack_stream(const StepParams &P, const LayerPtrs *ptrs, unsigned long long *events,
-                               float *tagged, int grid, int threads, hipStream_t s);
-hipError_t stream_occupancy(const Dims &dm, int threads, size_t lds_bytes, int *blocks_per_cu);
-hipError_t prepare_stream_kernels(size_t lds_bytes);
 
 // implemented in prep_kernels.hip
 hipError_t launch_pack_layer(const Dims &dm, const PackedLayout &lay, const void *const src[12],

@@ -401,10 +401,13 @@ __device__ __forceinline__ void lds_rendezvous(int *counter, int target, unsigne
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
-// ---- timeline trace (profiling aid) --------------------------------------------
-// Workgroup (debug >> 8) records (tag, 100 MHz wall clock) pairs per wavefront
-// when bit 16 of StepParams::debug is set; `first` lets each kernel of a
-// multi-kernel step use its own part of a wavefront's kTraceLen entries.
+// ---- timeline trace (profiling build only) ---------------------------------------
+// With CFPP_PROFILE defined (the separate profiling library), workgroup
+// (debug >> 8) records (tag, 100 MHz wall clock) pairs per wavefront when bit 16
+// of StepParams::debug is set; `first` lets each kernel of a multi-kernel step use
+// its own part of a wavefront's kTraceLen entries.  In the product build the
+// tracer is an empty object and every mark() compiles to nothing.
+#ifdef CFPP_PROFILE
 struct Tracer {
     unsigned long long *p;
     int n;
@@ -415,6 +418,13 @@ struct Tracer {
         p = on ? P.trace + (size_t)wave * kTraceLen * 2 : nullptr;
         n = first;
     }
+    // the whole-stack kernel records one layer: (debug >> 20) & 255 names it (1-based), 0 = the last
+    template <class Params>
+    __device__ __forceinline__ void select_layer(const Params &P, int layer, int n_layers)
+    {
+        const int want = ((P.debug >> 20) & 255) ? ((P.debug >> 20) & 255) - 1 : n_layers - 1;
+        n = layer == want ? 0 : kTraceLen;
+    }
     __device__ __forceinline__ void mark(int tag)
     {
         if (p && n < kTraceLen && (threadIdx.x & 63) == 0) {
@@ -424,5 +434,23 @@ struct Tracer {
         if (p) ++n;
     }
 };
+// a time stamp of workgroup-level events (bit 32 of debug), slot `slot` of this workgroup
+#define CFPP_STAMP(P, cond, slot)                                                                      \
+    do {                                                                                               \
+        if (((P).debug & 32) && (cond)) (P).trace[blockIdx.x * 8 + (slot)] = wall_clock64();           \
+    } while (0)
+// parts of a phase that the profiling build can leave out (results are then wrong)
+#define CFPP_SKIPPED(P, bit) (((P).debug & (bit)) != 0)
+#else
+struct Tracer {
+    template <class Params>
+    __device__ __forceinline__ void init(const Params &, int, int = 0) {}
+    template <class Params>
+    __device__ __forceinline__ void select_layer(const Params &, int, int) {}
+    __device__ __forceinline__ void mark(int) {}
+};
+#define CFPP_STAMP(P, cond, slot) do { } while (0)
+#define CFPP_SKIPPED(P, bit) false
+#endif
 
 }  // namespace cfpp

@@ -82,7 +82,7 @@ static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qk
 
 struct FusedCtx {
     const StepParams *P;
-    const LayerPtrs *ptrs;
+    const LayerPtrs *ptrs;          // per-layer pointer table in device memory, or null: one block, P->w_single / kv_single
     float *lds;
     FusedLds L;
     int pos, nw;
@@ -90,6 +90,15 @@ struct FusedCtx {
     unsigned E0;                    // epoch base of this launch
     float *xt, *ot, *pt;            // tagged words: layer outputs [2][h], attention output [h], split-KV partials
 };
+
+__device__ __forceinline__ const __half *layer_weights(const FusedCtx &C, int layer)
+{
+    return C.ptrs ? C.ptrs->w[layer] : C.P->w_single;
+}
+__device__ __forceinline__ __half *layer_cache(const FusedCtx &C, int layer)
+{
+    return C.ptrs ? C.ptrs->kv[layer] : C.P->kv_single;
+}
 
 // First part of every layer, all wavefronts: the layer input into LDS - as it is
 // (for the statistics) and multiplied by the weights of the two LayerNorms, in
@@ -196,7 +205,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
     GemvSpan<kGemvU> gsU, gsC;
     {
         const int tid0 = opaque_thread_index();
-        const __half *w0 = C.ptrs->w[0];
+        const __half *w0 = layer_weights(C, 0);
         gsQ.init(GemvSeg{w0 + P.lay.w_qkv + (size_t)C.q_begin * h, y1, h, C.q_n}, GemvSeg{w0 + P.lay.w_qkv, y1, h, 0},
                  w0, tid0, 0);
         gsQ.issue_first();
@@ -210,9 +219,9 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
     for (int layer = 0; layer < L; ++layer) {
         const int tid = opaque_thread_index();
         const int lane = tid & 63, si = gsQ.wave - 1;
-        const __half *w = C.ptrs->w[layer];
-        const __half *kv = C.ptrs->kv[layer];
-        tr.n = layer == (((P.debug >> 20) & 255) ? ((P.debug >> 20) & 255) - 1 : L - 1) ? 0 : kTraceLen;   // the traced layer
+        const __half *w = layer_weights(C, layer);
+        const __half *kv = layer_cache(C, layer);
+        tr.select_layer(P, layer, L);
         // this layer's set of partial-sum slots
         const unsigned set = (unsigned)(layer & 1) * C.L.pset;
         float *pq = lds + C.L.pq + set, *pu = lds + C.L.pu + set, *pd = lds + C.L.pd + set, *pc = lds + C.L.pc + set;
@@ -298,7 +307,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
             // the next layer's first QKV weights stream while the attention output is waited for
             // (nothing for the last layer: the loads re-read one block)
             const bool more = layer + 1 < L;
-            const __half *wn = C.ptrs->w[more ? layer + 1 : layer];
+            const __half *wn = layer_weights(C, more ? layer + 1 : layer);
             gsQ.init(GemvSeg{wn + P.lay.w_qkv + (size_t)C.q_begin * h, y1, h, more ? C.q_n : 0},
                      GemvSeg{wn + P.lay.w_qkv, y1, h, 0}, wn, tid, 0);
             gsQ.issue_first();
@@ -321,7 +330,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
 
 // ---- wavefront 0 : chain ------------------------------------------------------
 template <int D>
-__device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv_layers)
+__device__ __forceinline__ void fused_chain(const FusedCtx &C)
 {
     using AC = AttnCore<D>;
     const StepParams &P = *C.P;
@@ -346,17 +355,17 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
     for (int layer = 0; layer < L; ++layer) {
         const int tid = opaque_thread_index();
         const int lane = tid & 63;
-        const __half *w = C.ptrs->w[layer];
-        __half *kv = kv_layers[layer];
+        const __half *w = layer_weights(C, layer);
+        __half *kv = layer_cache(C, layer);
         const LayerIO io = layer_io(P, layer);
         const bool last_layer = layer == L - 1;
-        tr.n = layer == (((P.debug >> 20) & 255) ? ((P.debug >> 20) & 255) - 1 : L - 1) ? 0 : kTraceLen;   // the traced layer
+        tr.select_layer(P, layer, L);
         const unsigned set = (unsigned)(layer & 1) * C.L.pset;   // this layer's partial-sum slots
         const float *pq = lds + C.L.pq + set, *pu = lds + C.L.pu + set, *pd = lds + C.L.pd + set, *pc = lds + C.L.pc + set;
         tr.mark(1);
         fused_input(C, w, layer, tid);
         tr.mark(2);
-        if ((P.debug & 32) && lane == 0 && layer == L - 1) P.trace[blockIdx.x * 8 + 7] = wall_clock64();
+        CFPP_STAMP(P, lane == 0 && layer == L - 1, 7);
         __syncthreads();                                   // S0: the layer input is in LDS
         tr.mark(3);
 
@@ -477,7 +486,7 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
         tr.mark(12);
         __syncthreads();                                   // S3: attention states in LDS
         tr.mark(14);
-        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 0] = wall_clock64();
+        CFPP_STAMP(P, lane == 0, 0);
         tr.mark(15);
         // attention: this workgroup's partials; the heads it combines; the whole
         // attention output into LDS once every head is combined
@@ -490,7 +499,7 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
 #pragma unroll
         for (int k = 0; k < kFusedSegs; ++k)
             if (k < sg.n && ac.combines(sg.s[k])) ac.combine_tagged(P, C.pt, C.ot, epoch, sg.s[k]);
-        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 1] = wall_clock64();
+        CFPP_STAMP(P, lane == 0, 1);
         tr.mark(16);
         {
             // the attention output, tagged: the whole vector is re-read until every word
@@ -521,17 +530,17 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C, __half *const *kv
                 }
             }
         }
-        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 3] = wall_clock64();
+        CFPP_STAMP(P, lane == 0, 3);
         tr.mark(17);
-        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 4] = wall_clock64();
+        CFPP_STAMP(P, lane == 0, 4);
         __syncthreads();                                   // S4: down rows done
-        if ((P.debug & 32) && lane == 0) P.trace[blockIdx.x * 8 + 5] = wall_clock64();
+        CFPP_STAMP(P, lane == 0, 5);
         tr.mark(20);
         float g_r = 0.f;
         if (lane < r_n) g_r = rt.row_total(pd, lane) + bdn0;
         __syncthreads();                                   // S6: dense rows done
         tr.mark(24);
-        if ((P.debug & 32) && lane == 0 && layer == L - 2) P.trace[blockIdx.x * 8 + 6] = wall_clock64();
+        CFPP_STAMP(P, lane == 0 && layer == L - 2, 6);
         if (lane < r_n) {
             const float a = rt.row_total(pc, lane) + bde0;
             const float res = (x_r + a) + g_r;
@@ -575,7 +584,7 @@ k_stack_fused(StepParams P, const LayerPtrs *__restrict__ ptrs)
     C.pt = P.tagged + 2 * (size_t)6 * dm.h;
     if (threadIdx.x == 0) reinterpret_cast<int *>(lds)[C.L.ctr] = 0;    // (a workgroup barrier follows in both roles)
     clear_partials(lds + C.L.pq, (int)C.L.pset, threadIdx.x);          // layer 0's partial-sum slots
-    if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0) fused_chain<D>(C, ptrs->kv);
+    if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0) fused_chain<D>(C);
     else fused_stream<D>(C);
 }
 
@@ -591,7 +600,7 @@ size_t fused_lds_bytes(const Dims &dm, const StepParams &P, int threads)
 // units (the streaming wavefronts' balanced split)
 bool fused_supported(const Dims &dm, const StepParams &P, int grid, int threads)
 {
-    return grid >= dm.H && P.rows_h <= 64 && dm.h <= 4096 && dm.h % kChunk == 0 && dm.f % kChunk == 0 &&
+    return !(dm.flags & kFlagSequentialResidual) && grid >= dm.H && P.rows_h <= 64 && dm.h <= 4096 && dm.h % kChunk == 0 && dm.f % kChunk == 0 &&
            (size_t)dm.f <= (size_t)2 * kStageMStream * 64 * (threads / 64 - 1) && threads / 64 - 1 <= kFusedSlots && threads >= 128 &&
            (dm.d == 64 || dm.d == 80 || dm.d == 128);
 }

@@ -101,8 +101,7 @@ struct WorkspaceLayout {
     size_t sync;      // uint32[kSyncWords]: grid-barrier words, device error flag
     size_t seg_cnt;   // uint32[max_batch*H]: arrivals per (sequence, head) in the split-KV combine
     size_t layer_ptrs; // device copy of the per-layer pointer table of the stack kernel
-    size_t events;    // uint64 counters of the stream kernel's M event: [1 top + 64 groups], 64 B apart
-    size_t tagged;    // stream kernel's tagged words (value, epoch): xt[2][h] qkv[3][h] ot[h] part[H][slots][d+2]
+    size_t tagged;    // whole-stack kernel's tagged words (value, epoch): xt[2][h] (3 h unused) ot[h] part[H][slots][d+2]
     size_t rope;      // float2[max_seq][r/2]: (cos, sin) of pos * theta_j
     size_t xres;      // float[2][max_batch][h]: fp32 residual stream between blocks (ping-pong)
     size_t q;         // float[max_batch][h]: rotated queries
@@ -112,7 +111,7 @@ struct WorkspaceLayout {
     size_t part;      // float[max_batch*H][part_slots][d+2]: split-KV partials (acc[d], max, sum)
     size_t lm_best;   // float[kMaxGrid][2]: (logit, row) of every workgroup of the LM-head kernel
     size_t pf_pos;    // int32[max_seq]: positions of a prompt's tokens (prompt processing)
-    size_t trace;     // uint64[kTraceWaves][kTraceLen][2]: (tag, 100 MHz clock) pairs, profiling aid
+    size_t trace;     // uint64[kTraceWaves][kTraceLen][2]: (tag, 100 MHz clock) pairs (profiling library only, else empty)
     size_t total;
     int part_slots;
 };
@@ -128,7 +127,6 @@ CFPP_HD WorkspaceLayout workspace_layout(const Dims &m)
     W.sync = take((size_t)kSyncWords * 4);
     W.seg_cnt = take((size_t)m.max_batch * m.H * 4);
     W.layer_ptrs = take(2 * kMaxLayers * sizeof(void *));
-    W.events = take(65 * 64);
     W.tagged = take(8 * ((size_t)6 * m.h + (size_t)m.H * W.part_slots * (m.d + 2)));
     W.rope = take((size_t)m.max_seq * (m.r / 2 > 0 ? m.r / 2 : 1) * 8);
     W.xres = take(2 * (size_t)m.max_batch * m.h * 4);
@@ -139,7 +137,11 @@ CFPP_HD WorkspaceLayout workspace_layout(const Dims &m)
     W.part = take((size_t)m.max_batch * m.H * W.part_slots * (m.d + 2) * 4);
     W.lm_best = take((size_t)kMaxGrid * 8);
     W.pf_pos = take((size_t)m.max_seq * 4);
+#ifdef CFPP_PROFILE
     W.trace = take((size_t)kTraceWaves * kTraceLen * 16);
+#else
+    W.trace = take(0);
+#endif
     W.total = o;
     return W;
 }

@@ -140,7 +140,8 @@ hipError_t launch_fill_positions(int *dst, int first, int n, hipStream_t s)
     return hipGetLastError();
 }
 
-// ---- plain streaming kernels of known traffic (bandwidth calibration) ---------
+#ifdef CFPP_PROFILE
+// ---- plain streaming kernels of known traffic (bandwidth calibration; profiling library only) ---------
 // read: every 16-byte word of src is loaded once and folded into a checksum, one
 // word per workgroup written to sink; copy: dst = src.
 template <int U>
@@ -198,5 +199,6 @@ hipError_t launch_stream_copy(const void *src, void *dst, size_t bytes, int grid
                        static_cast<u32x4 *>(dst), (long long)(bytes / 16));
     return hipGetLastError();
 }
+#endif  // CFPP_PROFILE
 
 }  // namespace cfpp

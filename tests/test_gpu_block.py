@@ -8,12 +8,8 @@ from tests.parity import assert_block_close, assert_fp16_rows_match, errors
 pytestmark = pytest.mark.gpu
 
 
-def run_block(orc, shape, seed, S, cap, mode=0, grid=None, threads=None, taps=False, repeats=1):
+def _device_run(shape, w, K, V, x, S, cap, mode, grid, threads, repeats, taps):
     from paper_2604_23553_amd.harness import DeviceStack
-    w = synth.layer_weights(shape, seed, 0)
-    K, V = synth.kv_cache(shape, seed, 0, S, cap)
-    x = synth.x_input(shape, seed)
-    print(f"[case] shape={shape.name or shape.hidden} seed={seed} S={S} cap={cap} mode={mode} grid={grid} threads={threads}", flush=True)
     ds = DeviceStack(shape, cap, 1, 1)
     try:
         ds.set_options(mode=mode, grid=grid, threads=threads)
@@ -32,9 +28,28 @@ def run_block(orc, shape, seed, S, cap, mode=0, grid=None, threads=None, taps=Fa
                    for i, n in enumerate(("q", "m", "g", "attn"))}
     finally:
         ds.close()
+    return outs, (k_all, v_all), tap
+
+
+def run_block(orc, shape, seed, S, cap, mode=0, grid=None, threads=None, taps=False, repeats=1):
+    """The block on the product library; with taps=True once more on the profiling
+    build of the same sources (the only one with the test taps), whose output must
+    be the product's bit for bit."""
+    import paper_2604_23553_amd as cf
+    w = synth.layer_weights(shape, seed, 0)
+    K, V = synth.kv_cache(shape, seed, 0, S, cap)
+    x = synth.x_input(shape, seed)
+    print(f"[case] shape={shape.name or shape.hidden} seed={seed} S={S} cap={cap} mode={mode} grid={grid} threads={threads}", flush=True)
+    outs, kv_dev, _ = _device_run(shape, w, K, V, x, S, cap, mode, grid, threads, repeats, False)
+    tap = None
+    if taps:
+        with cf.profile_build():
+            outs_p, kv_p, tap = _device_run(shape, w, K, V, x, S, cap, mode, grid, threads, 1, True)
+        assert np.array_equal(outs_p[0].view(np.uint16), outs[0].view(np.uint16)), "profiling build differs from the product"
+        assert np.array_equal(kv_p[0].view(np.uint16), kv_dev[0].view(np.uint16))
     Ko, Vo = K[0].copy(), V[0].copy()
     ref, otaps = orc.block_decode(shape, w, Ko, Vo, S, orc.half_to_real(x[0]), taps=True)
-    return outs, (k_all, v_all), (Ko, Vo), orc.real_to_half(ref), tap, otaps
+    return outs, kv_dev, (Ko, Vo), orc.real_to_half(ref), tap, otaps
 
 
 def check_block(orc, shape, seed, S, cap, **kw):
@@ -49,15 +64,16 @@ def check_block(orc, shape, seed, S, cap, **kw):
     for o in outs[1:]:
         assert np.array_equal(o.view(np.uint16), outs[0].view(np.uint16)), "not bit-identical run to run"
     if tap is not None:
-        for n in ("q", "m", "g", "attn"):
-            if n == "g" and kw.get("mode") == 3:
-                continue        # the stream kernel keeps the down projection in LDS
+        # (the whole-stack kernel keeps the down projection in registers and passes the
+        # attention output on as tagged words: no workspace copy of either)
+        names = ("q", "m") if kw.get("mode") == 2 else ("q", "m", "g", "attn")
+        for n in names:
             e = errors(tap[n], otaps[n])
             assert e[0] < 2e-3 and e[1] < 2e-4, f"intermediate {n}: {e}"
     return ma, rl
 
 
-@pytest.mark.parametrize("mode", [0, 1, 3])
+@pytest.mark.parametrize("mode", [0, 1, 2, -1])
 def test_small_block_config(orc, mode):
     """hidden 512, 8 heads x 64, rotary 16, FFN 2048, 128 cached positions."""
     check_block(orc, synth.SMALL_BLOCK, synth.MASTER_SEED, 128, 129, mode=mode, taps=True, repeats=3)
@@ -73,14 +89,15 @@ def test_launch_shapes(orc, grid, threads):
     check_block(orc, synth.SMALL_BLOCK, 11, 200, 201, mode=0, grid=grid, threads=threads, taps=True)
 
 
-@pytest.mark.parametrize("mode", [0, 1, 3])
+@pytest.mark.parametrize("mode", [0, 1, 2, -1])
 def test_pythia_2_8b_block(orc, mode):
     """hidden 2560, 32 heads x 80, rotary 20, FFN 10240, 1024 cached positions."""
     check_block(orc, synth.PYTHIA_2_8B, synth.MASTER_SEED, 1024, 1025, mode=mode, taps=True, repeats=3)
 
 
-def test_pythia_6_9b_block(orc):
-    check_block(orc, synth.PYTHIA_6_9B, synth.MASTER_SEED, 333, 334, mode=0, taps=True, repeats=2)
+@pytest.mark.parametrize("mode", [0, 2])
+def test_pythia_6_9b_block(orc, mode):
+    check_block(orc, synth.PYTHIA_6_9B, synth.MASTER_SEED, 333, 334, mode=mode, taps=True, repeats=2)
 
 
 @pytest.mark.parametrize("shape", [

@@ -33,7 +33,7 @@ def oracle_stack(orc, shape, ws, kvs, S, x, b=0):
     return out16, per, Ks, Vs
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("mode", [0, 1, 2, -1])
 @pytest.mark.parametrize("graph", [False, True])
 def test_tiny_stack_direct_and_graph(orc, mode, graph):
     S, cap = 70, 75
@@ -352,10 +352,11 @@ def test_fused_kernel_across_launch_shapes(orc, grid, threads):
         ds.close()
 
 
-@pytest.mark.parametrize("flags,mode", [(1, 0), (1, 1), (1, 2), (1, 3), (2, 0), (3, 0)])
+@pytest.mark.parametrize("flags,mode", [(1, 0), (1, 1), (1, 2), (1, -1), (2, 0), (3, 0), (2, -1)])
 def test_other_readings_of_the_block(orc, flags, mode):
     """tanh GELU (every launch mode) and the sequential residual form (launch
-    mode 0, two passes per block) against the oracle's variants."""
+    mode 0, two passes per block; the automatic mode falls back to it) against the
+    oracle's variants."""
     import dataclasses
     shape = dataclasses.replace(TINY_STACK, flags=flags)
     S, cap = 90, 96
@@ -397,10 +398,13 @@ def test_sequential_form_is_refused_by_the_overlapping_modes():
     ds, ws, kvs = build_stack(shape, 42, 10, 12)
     try:
         ds.set_inputs(synth.x_input(shape, 1), 10)
-        for mode in (1, 2, 3):
+        for mode in (1, 2):
             ds.set_options(mode=mode)
-            with pytest.raises(CfppError):
+            with pytest.raises(CfppError) as e:
                 ds.stack_decode()
+            assert e.value.status == -2
+            with pytest.raises(CfppError):
+                ds.block_decode(0)
     finally:
         ds.close()
 
@@ -436,7 +440,7 @@ def test_whole_stack_kernel_at_other_shapes(orc, shape, S):
         ds.close()
 
 
-def test_whole_stack_kernel_refuses_rows_of_partial_units():
+def test_whole_stack_kernel_refuses_rows_of_partial_units(orc):
     """Launch mode 2 splits rows over its streaming wavefronts in whole 512-weight
     units: a hidden size that is not a multiple of 512 is refused (mode 0 runs it)."""
     from paper_2604_23553_amd import CfppError
@@ -450,9 +454,64 @@ def test_whole_stack_kernel_refuses_rows_of_partial_units():
         with pytest.raises(CfppError) as e:
             ds.stack_decode()
         assert e.value.status == -2
-        ds.set_options(mode=0)
-        ds.stack_decode()
-        ds.check()
+        for mode in (0, -1):                               # the automatic mode falls back instead
+            ds.set_options(mode=mode)
+            ds.stack_decode()
+            ds.check()
+            ref16, _, _, _ = oracle_stack(orc, shape, ws, kvs, S, x[0])
+            assert_block_close(ds.result()[0], ref16, f"h 640 in mode {mode}")
+    finally:
+        ds.close()
+
+
+def test_epoch_counter_is_rearmed_before_it_wraps(orc):
+    """The whole-stack kernel tags exchanged words with a 32-bit epoch that every
+    launch advances; the host re-zeroes counter and words long before a wrap.  The
+    profiling build lets the limit be set to a few launches' worth: results stay
+    the same bits across many re-armings, direct launches and graph replays."""
+    import paper_2604_23553_amd as cf
+    S, cap = 70, 75
+    print("[case] epoch re-arming", flush=True)
+    with cf.profile_build():
+        ds, ws, kvs = build_stack(TINY_STACK, 21, S, cap)
+        try:
+            ds.set_options(mode=2)
+            cf.cfpp_set_option(ds.ctx, cf.OPT_EPOCH_LIMIT, 3 * (TINY_STACK.n_layers + 1) + 1)
+            x = synth.x_input(TINY_STACK, 100)
+            ds.set_inputs(x, S)
+            outs = []
+            for _ in range(8):
+                ds.stack_decode()
+                ds.check()
+                outs.append(ds.result()[0].copy())
+            ds.capture()
+            for _ in range(8):
+                ds.replay()
+                ds.check()
+                outs.append(ds.result()[0].copy())
+            for _ in range(3):
+                ds.block_decode(0)                        # (one block: two epochs per launch)
+                ds.check()
+            ds.stack_decode()
+            ds.check()
+            outs.append(ds.result()[0].copy())
+            ref16, _, _, _ = oracle_stack(orc, TINY_STACK, ws, kvs, S, x[0])
+            assert_block_close(outs[0], ref16, "stack output")
+            for o in outs[1:]:
+                assert np.array_equal(o.view(np.uint16), outs[0].view(np.uint16)), "changed across a re-arming"
+        finally:
+            ds.close()
+
+
+def test_retired_launch_mode_is_refused():
+    import paper_2604_23553_amd as cf
+    from paper_2604_23553_amd.harness import DeviceStack
+    ds = DeviceStack(TINY_STACK, 16, 1, 1)
+    try:
+        with pytest.raises(cf.CfppError) as e:
+            ds.set_options(mode=3)
+        assert e.value.status == -2
+        assert cf.cfpp_get_option(ds.ctx, cf.OPT_MODE) == cf.MODE_AUTO      # the default, unchanged
     finally:
         ds.close()
 

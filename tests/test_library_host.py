@@ -13,8 +13,8 @@ import paper_2604_23553_amd as cf
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "cfpp.h")).read()
+def declared_functions(header="cfpp.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(cfpp_[a-z0-9_]+)\s*\(", text)))
 
@@ -25,6 +25,23 @@ def test_library_exports_every_declared_symbol():
     L = cf.lib()
     for n in names:
         assert hasattr(L, n), f"{n} is declared in cfpp.h but not exported"
+
+
+def test_product_library_has_no_profiling_entry_points():
+    """Tracer switches, test taps and calibration kernels live in the profiling
+    build only (include/cfpp_profile.h); that build exports them beside the ABI."""
+    extra = sorted(set(declared_functions("cfpp_profile.h")) - set(declared_functions()))
+    assert "cfpp_debug_read" in extra and "cfpp_stream_copy" in extra
+    L = cf.lib()
+    for n in extra:
+        assert not hasattr(L, n), f"{n} is exported by the product library"
+    with cf.profile_build() as P:
+        for n in extra + declared_functions():
+            assert hasattr(P, n), f"{n} is missing from the profiling library"
+        assert cf.lib() is P
+    assert cf.lib() is L
+    text = open(os.path.join(ROOT, "include", "cfpp.h")).read()
+    assert "PROFILE_SKIP" not in text and "debug_read" not in text
 
 
 def test_binding_has_the_same_names():
