@@ -76,6 +76,7 @@ typedef struct {
     real *a;           /* [h] output projection                   */
     real *m;           /* [f] GELU(up)                            */
     real *g;           /* [h] down projection                     */
+    real *k_new, *v_new; /* [h] the new token's K (rotated) and V rows before they are rounded to fp16 */
 } orc_taps;
 
 int orc_sizeof_real(void) { return (int)sizeof(real); }
@@ -273,6 +274,8 @@ int orc_block_decode_flags(const orc_shape *sh, const orc_layer *w,
         orc_rope(kn, r, pos, sh->rope_base);
         uint16_t *Kn = K + (int64_t)n * capacity * d;
         uint16_t *Vn = V + (int64_t)n * capacity * d;
+        if (taps && taps->k_new) memcpy(taps->k_new + (int64_t)n * d, kn, sizeof(real) * d);
+        if (taps && taps->v_new) memcpy(taps->v_new + (int64_t)n * d, vn, sizeof(real) * d);
         for (int i = 0; i < d; ++i) {
             Kn[(int64_t)pos * d + i] = orc_real_to_half(kn[i]);
             Vn[(int64_t)pos * d + i] = orc_real_to_half(vn[i]);

@@ -31,7 +31,7 @@ class _Layer(C.Structure):
     _fields_ = [(n, _U16P) for n in _LAYER_FIELDS]
 
 
-_TAP_FIELDS = ("y1", "y2", "q", "attn", "a", "m", "g")
+_TAP_FIELDS = ("y1", "y2", "q", "attn", "a", "m", "g", "k_new", "v_new")
 
 
 class _Taps(C.Structure):
@@ -164,13 +164,18 @@ class Oracle:
         """The block at its fp16 boundary: fp16 x in, fp16-rounded output."""
         return self.real_to_half(self.block_decode(shape, w, K, V, pos, self.half_to_real(x_f16)))
 
-    def stack_decode(self, shape, layers, Ks, Vs, pos: int, x_f16, per_layer=None):
+    def stack_decode(self, shape, layers, Ks, Vs, pos: int, x_f16, per_layer=None, taps_per_layer=None):
         """L blocks in sequence for one sequence.  The residual stream between
         blocks stays unrounded (`real`); fp16 only at entry and exit.
-        per_layer (optional list) receives every layer's unrounded output."""
+        per_layer (optional list) receives every layer's unrounded output,
+        taps_per_layer (optional list) every layer's dict of intermediates."""
         x = self.half_to_real(np.asarray(x_f16).reshape(-1))
         for l, w in enumerate(layers):
-            x = self.block_decode(shape, w, Ks[l], Vs[l], pos, x)
+            if taps_per_layer is not None:
+                x, t = self.block_decode(shape, w, Ks[l], Vs[l], pos, x, taps=True)
+                taps_per_layer.append(t)
+            else:
+                x = self.block_decode(shape, w, Ks[l], Vs[l], pos, x)
             if per_layer is not None:
                 per_layer.append(x.copy())
         return self.real_to_half(x), x

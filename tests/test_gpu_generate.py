@@ -58,22 +58,37 @@ def test_generation_graph_matches_oracle_over_64_steps(orc, mode):
     try:
         ds.set_tokens(tokens, S)
         ds.generate_capture()
+        hidden = []
         for _ in range(steps):
             ds.replay()
+            ds.stream.synchronize()
+            hidden.append(ds.out[0].cpu().numpy().copy())      # the stack's output of this step
         ds.check()
         got = ds.tokens.cpu().numpy()
         assert int(ds.pos[0].item()) == S + steps
         assert list(got[: S + 1]) == tokens and np.all(got[S + steps + 1:] == 0)
         ref, Ks, Vs = _follow(orc, layers, kv, head, embed, got, S, steps)
-        exact = 0
+        # Greedy choice per step: where the oracle's two best logits are further apart than ten
+        # times the logit error of this step (oracle's LM head on the GPU's hidden state against
+        # the oracle's own logits), the token must be the oracle's; in a near-tie both leaders are
+        # correct greedy choices and the GPU's must be one of them.  (The oracle follows the GPU's
+        # tokens, so a near-tie does not derail the comparison of the later steps.)
+        exact, ties = 0, []
         for i, (h16, lg, tok) in enumerate(ref):
             g = int(got[S + 1 + i])
             assert 0 <= g < VOCAB
-            # the GPU's choice is the oracle's, or within the logit error of its maximum
-            assert lg[g] >= lg.max() - 2e-2, f"step {i}: token {g} logit {lg[g]} vs max {lg.max()}"
+            assert_block_close(hidden[i], h16, f"hidden state of step {i}")
+            err = float(np.abs(orc.lm_head_logits(SHAPE, head, orc.half_to_real(hidden[i])) - lg).max())
+            top = np.argsort(lg)[-2:]
+            margin = float(lg[top[1]] - lg[top[0]])
+            if margin > 10 * err:
+                assert g == tok, f"step {i}: token {g}, oracle {tok} (margin {margin:.3e}, logit error {err:.3e})"
+            else:
+                ties.append((i, margin, err))
+                assert g in top, f"step {i}: token {g} is neither leader of a near-tie"
             exact += g == tok
-        print(f"[result] mode {mode}: {exact}/{steps} tokens identical to the oracle's choice", flush=True)
-        assert exact >= steps - 2
+        print(f"[result] mode {mode}: {exact}/{steps} tokens identical to the oracle's choice; near-ties {ties}", flush=True)
+        assert len(ties) <= 2
         # the K/V rows appended on the way are the oracle's (fp16: equal up to one rounding step)
         for l in range(SHAPE.n_layers):
             k, v = ds.export_kv(l, 0, S, steps)

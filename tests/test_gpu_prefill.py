@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 import synth
-from tests.parity import assert_block_close, assert_fp16_rows_match, errors
+from tests.parity import assert_appended_rows, assert_block_close, errors
 
 pytestmark = pytest.mark.gpu
 
@@ -42,8 +42,13 @@ def _check_prompt(orc, shape, seed, pos0, T, max_batch, b=0, then_decode=True):
         for l in range(shape.n_layers):
             kg, vg = ds.export_kv(l, b, 0, cap)
             if l == 0:
-                assert_fp16_rows_match(kg[:, pos0:pos0 + T], Ks[l][:, pos0:pos0 + T], "appended K, layer 0")
-                assert_fp16_rows_match(vg[:, pos0:pos0 + T], Vs[l][:, pos0:pos0 + T], "appended V, layer 0")
+                # the first layer reads each token's own input row, the same bits on both sides: its
+                # rows must be correct roundings of the oracle's unrounded values
+                for t in range(T):
+                    _, taps = orc.block_decode(shape, ws[0], kvs[0][0][b].copy(), kvs[0][1][b].copy(), pos0 + t,
+                                               orc.half_to_real(X[t]), taps=True)
+                    assert_appended_rows(kg[:, pos0 + t], vg[:, pos0 + t], shape, ws[0], orc.half_to_real(X[t]), taps,
+                                         f"token {t} layer 0")
             else:   # deeper layers see an input that already carries the earlier layers' rounding
                 for g_, w_ in ((kg, Ks[l]), (vg, Vs[l])):
                     e = errors(g_[:, pos0:pos0 + T], w_[:, pos0:pos0 + T])

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import synth
-from tests.parity import assert_block_close, assert_fp16_rows_match, errors
+from tests.parity import assert_appended_rows, assert_block_close, assert_drifted_rows_close, errors
 
 pytestmark = pytest.mark.gpu
 
@@ -23,14 +23,31 @@ def build_stack(shape, seed, S, cap, batch=1, layers=None):
     return ds, ws, kvs
 
 
-def oracle_stack(orc, shape, ws, kvs, S, x, b=0):
+def oracle_stack(orc, shape, ws, kvs, S, x, b=0, taps=None):
     """Oracle over the same tensors; returns fp16 output, per-layer unrounded outputs
-    and the oracle's updated caches."""
+    and the oracle's updated caches (taps: optional list that receives every layer's
+    intermediates)."""
     Ks = [kv[0][b].copy() for kv in kvs]
     Vs = [kv[1][b].copy() for kv in kvs]
     per = []
-    out16, _ = orc.stack_decode(shape, ws, Ks, Vs, int(S), x, per_layer=per)
+    out16, _ = orc.stack_decode(shape, ws, Ks, Vs, int(S), x, per_layer=per, taps_per_layer=taps)
     return out16, per, Ks, Vs
+
+
+def check_appended_rows(orc, ds, shape, ws, kvs, S, x16, b=0, what=""):
+    """Rows appended at position S of sequence b in every layer.  Layer 0 reads the same
+    input bits as the oracle: its rows must be correct roundings of the oracle's unrounded
+    values.  Later layers inherit the drift of the residual stream and are held to the
+    block tolerance."""
+    taps = []
+    _, _, Ks, Vs = oracle_stack(orc, shape, ws, kvs, S, x16, b, taps=taps)
+    for l in range(len(ws)):
+        kg, vg = ds.export_kv(l, b, int(S), 1)
+        if l == 0:
+            assert_appended_rows(kg[:, 0], vg[:, 0], shape, ws[0], orc.half_to_real(x16), taps[0], f"{what} layer 0")
+        else:
+            assert_drifted_rows_close(kg[:, 0], Ks[l][:, S], f"{what} layer {l} appended K")
+            assert_drifted_rows_close(vg[:, 0], Vs[l][:, S], f"{what} layer {l} appended V")
 
 
 @pytest.mark.parametrize("mode", [0, 1, 2, -1])
@@ -58,11 +75,7 @@ def test_tiny_stack_direct_and_graph(orc, mode, graph):
             assert_block_close(outs[i], ref16, f"stack out (input {i})")
             assert np.array_equal(outs[i].view(np.uint16), outs[i + 3].view(np.uint16)), "not bit-identical"
         # the caches hold the rows appended by the last run (input 2)
-        ref16, _, Ks, Vs = oracle_stack(orc, TINY_STACK, ws, kvs, S, xs[2][0])
-        for l in range(TINY_STACK.n_layers):
-            kg, vg = ds.export_kv(l, 0, S, 1)
-            assert_fp16_rows_match(kg[:, 0], Ks[l][:, S], f"layer {l} appended K")
-            assert_fp16_rows_match(vg[:, 0], Vs[l][:, S], f"layer {l} appended V")
+        check_appended_rows(orc, ds, TINY_STACK, ws, kvs, S, xs[2][0])
     finally:
         ds.close()
 
@@ -125,8 +138,12 @@ def test_teacher_forced_layers(orc):
             ds.block_decode(l)
             ds.check()
             got = ds.result().copy()
-            ref = orc.block_decode_f16(shape, ws[l], kvs[l][0][0].copy(), kvs[l][1][0].copy(), S, cur[0])
-            assert_block_close(got[0], ref, f"layer {l}")
+            Ko, Vo = kvs[l][0][0].copy(), kvs[l][1][0].copy()
+            ref, taps = orc.block_decode(shape, ws[l], Ko, Vo, S, orc.half_to_real(cur[0]), taps=True)
+            assert_block_close(got[0], orc.real_to_half(ref), f"layer {l}")
+            # (the layer's input is the same bits on both sides: the sharp bound holds at every depth)
+            kg, vg = ds.export_kv(l, 0, S, 1)
+            assert_appended_rows(kg[:, 0], vg[:, 0], shape, ws[l], orc.half_to_real(cur[0]), taps, f"layer {l}")
             cur = got
     finally:
         ds.close()
@@ -198,16 +215,21 @@ def test_full_pythia_2_8b_stack_graph_and_argmax(orc):
             ma, rl = assert_block_close(out, ref16, f"32-layer output, mode {mode}")
             print(f"[result] mode {mode}: max-abs {ma:.4e} rel-L2 {rl:.4e}", flush=True)
         outs = [results[2]]
-        head = synth.lm_head(shape, synth.MASTER_SEED)
-        lg_ref = orc.lm_head_logits(shape, head, orc.half_to_real(ref16))
-        lg_gpu = orc.lm_head_logits(shape, head, orc.half_to_real(outs[0]))
-        top2 = np.sort(lg_ref)[-2:]
-        margin, err = float(top2[1] - top2[0]), float(np.abs(lg_ref - lg_gpu).max())
-        print(f"[result] logit margin {margin:.4f}, max logit error {err:.4f}", flush=True)
-        if margin > 2 * err:
-            assert int(np.argmax(lg_gpu)) == int(np.argmax(lg_ref))
-        else:   # a near-tie: either of the two leaders is a correct greedy choice
-            assert int(np.argmax(lg_gpu)) in np.argsort(lg_ref)[-2:]
+        # Greedy argmax through a random LM head: equality is demanded when the oracle's two best
+        # logits are further apart than ten times the observed logit error; a head whose leaders
+        # are closer than that says nothing either way and another one is drawn.
+        for draw in range(8):
+            head = synth.lm_head(shape, synth.MASTER_SEED + draw)
+            lg_ref = orc.lm_head_logits(shape, head, orc.half_to_real(ref16))
+            lg_gpu = orc.lm_head_logits(shape, head, orc.half_to_real(outs[0]))
+            top2 = np.sort(lg_ref)[-2:]
+            margin, err = float(top2[1] - top2[0]), float(np.abs(lg_ref - lg_gpu).max())
+            print(f"[result] LM head draw {draw}: logit margin {margin:.4f}, max logit error {err:.4f}", flush=True)
+            if margin > 10 * err:
+                assert int(np.argmax(lg_gpu)) == int(np.argmax(lg_ref))
+                break
+        else:
+            raise AssertionError("no LM head in 8 draws separated its two best logits by 10x the logit error")
         # the library's own LM head at the full vocabulary (50304 rows) on that output:
         # every logit against the oracle's, and its pick against its own logits
         print("[case] full 2.8B stack: LM head on the GPU", flush=True)
@@ -219,26 +241,69 @@ def test_full_pythia_2_8b_stack_graph_and_argmax(orc):
         lg_dev = ds.logits.cpu().numpy()
         assert np.abs(lg_dev.astype(np.float64) - lg_gpu).max() <= 2e-4
         assert int(ds.tokens[S].item()) == int(np.argmax(lg_dev)) and int(ds.pos[0].item()) == S
+        # The same resident stack at the shorter contexts of the paper's latency tables (Sec. 3 and
+        # its appendix sweep 16 to 2048 decode positions), whole-stack kernel: the new token goes to
+        # row S2 and rows below it are read.  Longest first, so that no run reads a row an earlier
+        # one appended.
+        ds.set_options(mode=2)
+        for S2 in (2048, 128, 16):
+            print(f"[case] full 2.8B stack: {S2} cached positions", flush=True)
+            ds.set_inputs(x, S2)
+            outs = []
+            for _ in range(3):
+                ds.stack_decode()
+                ds.check()
+                outs.append(ds.result()[0].copy())
+            assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16)) and \
+                np.array_equal(outs[0].view(np.uint16), outs[2].view(np.uint16)), f"S {S2}: not bit-identical"
+            ref16, _, _, _ = oracle_stack(orc, shape, ws, kvs, S2, x[0])
+            ma, rl = assert_block_close(outs[0], ref16, f"32-layer output at {S2} cached positions")
+            print(f"[result] S {S2}: max-abs {ma:.4e} rel-L2 {rl:.4e}", flush=True)
     finally:
         ds.close()
 
 
-def test_pythia_6_9b_stack_shape(orc):
-    """6.9B-shaped layers (head_dim 128, hidden 4096, FFN 16384), 4 of them, 2048
-    cached positions, whole-stack kernel."""
-    shape = synth.ModelShape(4096, 32, 128, 32, 16384, n_layers=4, name="pythia-6.9b-x4")
+def test_full_pythia_6_9b_stack(orc):
+    """The 6.9B-shaped stack at its full depth: 32 layers (head_dim 128, hidden 4096,
+    FFN 16384), 2048 cached positions per layer, batch 1; phase kernels and whole-stack
+    kernel, every output element against the oracle, bit-identical reruns, the rows
+    appended in the first and the last layer."""
+    shape = synth.PYTHIA_6_9B
     S, cap = 2048, 2049
-    ds, ws, kvs = build_stack(shape, synth.MASTER_SEED, S, cap)
+    print("[case] full 6.9B stack: generating inputs", flush=True)
+    from paper_2604_23553_amd.harness import DeviceStack
+    ds = DeviceStack(shape, cap, 1)
     try:
+        ws = synth.stack_weights(shape, synth.MASTER_SEED, workers=16)
+        kvs = []
+        for l in range(shape.n_layers):
+            ds.load_layer(l, ws[l])
+            kv = synth.kv_cache(shape, synth.MASTER_SEED, l, S, cap)
+            ds.load_kv(l, kv[0], kv[1], S)
+            kvs.append(kv)
         x = synth.x_input(shape, synth.MASTER_SEED)
+        print("[case] full 6.9B stack: oracle", flush=True)
+        taps = []
+        ref16, _, Ks, Vs = oracle_stack(orc, shape, ws, kvs, S, x[0], taps=taps)
         for mode in (0, 2):
+            print(f"[case] full 6.9B stack: mode {mode}", flush=True)
             ds.set_options(mode=mode)
             ds.set_inputs(x, S)
-            ds.stack_decode()
-            ds.check()
-            got = ds.result()[0].copy()
-            ref16, _, _, _ = oracle_stack(orc, shape, ws, kvs, S, x[0])
-            assert_block_close(got, ref16, f"6.9B-shape stack mode {mode}")
+            outs = []
+            for _ in range(3):
+                ds.stack_decode()
+                ds.check()
+                outs.append(ds.result()[0].copy())
+            assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16)) and \
+                np.array_equal(outs[0].view(np.uint16), outs[2].view(np.uint16)), f"mode {mode}: not bit-identical"
+            ma, rl = assert_block_close(outs[0], ref16, f"32-layer 6.9B output, mode {mode}")
+            print(f"[result] mode {mode}: max-abs {ma:.4e} rel-L2 {rl:.4e}", flush=True)
+            kg, vg = ds.export_kv(0, 0, S, 1)
+            assert_appended_rows(kg[:, 0], vg[:, 0], shape, ws[0], orc.half_to_real(x[0]), taps[0], "layer 0")
+            last = shape.n_layers - 1
+            kg, vg = ds.export_kv(last, 0, S, 1)
+            assert_drifted_rows_close(kg[:, 0], Ks[last][:, S], "last layer appended K")
+            assert_drifted_rows_close(vg[:, 0], Vs[last][:, S], "last layer appended V")
     finally:
         ds.close()
 
@@ -377,10 +442,7 @@ def test_other_readings_of_the_block(orc, flags, mode):
         # the variant is really in effect: the default reading gives another result
         ref_default, _, _, _ = oracle_stack(orc, TINY_STACK, ws, kvs, S, x[0])
         assert np.abs(ref16.astype(np.float64) - ref_default.astype(np.float64)).max() > 1e-3
-        for l in range(shape.n_layers):
-            kg, vg = ds.export_kv(l, 0, S, 1)
-            assert_fp16_rows_match(kg[:, 0], Ks[l][:, S], f"layer {l} appended K")
-            assert_fp16_rows_match(vg[:, 0], Vs[l][:, S], f"layer {l} appended V")
+        check_appended_rows(orc, ds, shape, ws, kvs, S, x[0])
         # one block on its own
         ds.set_inputs(x, S)
         ds.block_decode(0)
@@ -433,9 +495,7 @@ def test_whole_stack_kernel_at_other_shapes(orc, shape, S):
         assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
         ref16, _, Ks, Vs = oracle_stack(orc, shape, ws, kvs, S, x[0])
         assert_block_close(outs[0], ref16, shape.name)
-        kg, vg = ds.export_kv(0, 0, 0, cap)
-        assert_fp16_rows_match(kg[:, S], Ks[0][:, S], "appended K, layer 0")
-        assert_fp16_rows_match(vg[:, S], Vs[0][:, S], "appended V, layer 0")
+        check_appended_rows(orc, ds, shape, ws, kvs, S, x[0])
     finally:
         ds.close()
 
@@ -530,13 +590,15 @@ def test_batched_attention_split_with_extreme_lengths(orc):
     """Sequences from an empty cache to thousands of positions in one group: the
     attention launch gives every sequence at least one workgroup and the long
     ones nearly all."""
-    # (single rows of 512 values: the share that lands on the other side of an fp16
-    # rounding boundary fluctuates more than in the long rows of the other cases -
-    # 4.3 % in one row here, the same row in every launch mode)
-    _batched_case(orc, TINY_STACK, 6, 2, np.array([0, 1, 3000, 17, 0, 1500], dtype=np.int32), max_fraction=0.06)
+    # (with an empty cache the attention output IS the new token's fp16 V row: where the two
+    # sides round that row to neighbouring fp16 values - both correct roundings - the step
+    # enters the output projection with weight 1, and the second layer's rows of such a
+    # sequence differ from the oracle's far more often than anywhere else.  That is drift,
+    # not rounding: the rows of layers behind the first are held to the block tolerance.)
+    _batched_case(orc, TINY_STACK, 6, 2, np.array([0, 1, 3000, 17, 0, 1500], dtype=np.int32))
 
 
-def _batched_case(orc, shape, B, layers, lens, max_fraction=0.02):
+def _batched_case(orc, shape, B, layers, lens):
     """Launch mode 0 with several sequences: the projections run once per group
     of up to 8 sequences (MFMA, activations split into fp16 head + remainder),
     the attention per sequence.  Every sequence against the oracle; the appended
@@ -563,10 +625,7 @@ def _batched_case(orc, shape, B, layers, lens, max_fraction=0.02):
         for b in range(B):
             ref16, _, Ks, Vs = oracle_stack(orc, shape, ws, kvs, lens[b], x[b], b)
             assert_block_close(outs[0][b], ref16, f"sequence {b}")
-            for l in range(layers):
-                kg, vg = ds.export_kv(l, b, int(lens[b]), 1)
-                assert_fp16_rows_match(kg[:, 0], Ks[l][:, lens[b]], f"sequence {b} layer {l} appended K", max_fraction)
-                assert_fp16_rows_match(vg[:, 0], Vs[l][:, lens[b]], f"sequence {b} layer {l} appended V", max_fraction)
+            check_appended_rows(orc, ds, shape, ws[:layers], kvs[:layers], int(lens[b]), x[b], b, f"sequence {b}")
     finally:
         ds.close()
 
