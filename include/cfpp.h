@@ -217,6 +217,29 @@ cfpp_status cfpp_block_decode(cfpp_ctx *ctx, const void *packed_layer, void *kv_
                               const void *x, const int32_t *pos_dev, int32_t batch,
                               void *out, cfpp_stream stream);
 
+/* cfpp_block_decode for callers that cannot allocate device memory or keep a
+ * context: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid allocation.  It takes the configuration instead of a context and runs
+ * the same step with the phase kernels (launch mode 0; several sequences: the
+ * batched projections) on a workspace that is a fixed 16 MiB array in the
+ * library's device image - no hipMalloc/hipFree, no workspace argument, nothing
+ * to create or destroy.  Inputs and outputs are the caller's, as above.
+ *   - CFPP_ENOMEM when cfpp_workspace_bytes(cfg) exceeds the 16 MiB (it grows
+ *     with max_seq, max_batch, hidden and ffn: the Pythia-6.9B shape with 8
+ *     sequences of 8192 positions needs about 8 MiB).
+ *   - The first call on a GPU, and every call whose cfg differs from the
+ *     previous call's on that GPU, first enqueues one small set-up kernel on
+ *     `stream` (zeroes the array's counters, writes the rotary table for cfg).
+ *   - Every call on a GPU shares that GPU's array: calls that overlap in time on
+ *     one GPU (two streams, two threads) race; serialise them.  Each GPU has its
+ *     own copy, held until the process ends.
+ *   - An out-of-range position skips the step as in cfpp_block_decode; with no
+ *     context there is no cfpp_device_error to report it: validate positions first.
+ * Asynchronous on `stream`; host-side state is guarded by a mutex. */
+cfpp_status cfpp_block_decode_static(const cfpp_config *cfg, const void *packed_layer, void *kv_layer,
+                                     const void *x, const int32_t *pos_dev, int32_t batch,
+                                     void *out, cfpp_stream stream);
+
 /* One decode step through cfg.n_layers blocks.  packed_layers, kv_layers: HOST
  * arrays of n_layers DEVICE pointers.  The residual stream between blocks is
  * kept in fp32 in the workspace; fp16 only at x and out. */

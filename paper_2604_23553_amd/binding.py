@@ -241,6 +241,12 @@ def cfpp_device_error(ctx: int, stream=None):
     _check(lib().cfpp_device_error(C.c_void_p(ctx), _ptr(stream)), "cfpp_device_error")
 
 
+def cfpp_block_decode_static(cfg: Config, packed_layer, kv_layer, x, pos_dev, batch: int, out, stream=None):
+    _check(lib().cfpp_block_decode_static(C.byref(cfg), _ptr(packed_layer), _ptr(kv_layer), _ptr(x),
+                                          _ptr(pos_dev), C.c_int32(batch), _ptr(out), _ptr(stream)),
+           "cfpp_block_decode_static")
+
+
 # ---- profiling library only (inside `with profile_build():`) -------------------
 def cfpp_debug_read(ctx: int, which: int, count: int, stream=None):
     import numpy as np

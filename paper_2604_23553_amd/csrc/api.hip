@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -960,6 +961,99 @@ extern "C" cfpp_status cfpp_device_error(cfpp_ctx *ctx, cfpp_stream stream)
     if (err == kErrBarrierTimeout) return fail(CFPP_EDEVICE, "grid barrier timed out (workgroups not co-resident?)");
     if (err == kErrBadToken) return fail(CFPP_EDEVICE, "a token in tokens_dev was outside [0, vocab)");
     return fail(CFPP_EDEVICE, "device error code %u", err);
+}
+
+// ---- block decode for callers that cannot allocate --------------------------------------
+// The same step as cfpp_block_decode with the phase kernels, on a workspace that
+// is a fixed array in device memory instead of a caller's buffer: nothing is
+// allocated, no context is created.  Each GPU holds its own copy of the array at
+// its own address; that address is looked up once per device.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kStaticMaxDevices = 16;
+struct StaticSlot {
+    char *ptr;              // device address of this GPU's copy of `scratch` (null: not looked up yet)
+    bool configured;        // ctx below is set up for `cfg` and the array's sync words and rotary table match it
+    cfpp_config cfg;
+    cfpp_ctx ctx;
+};
+static StaticSlot g_static[kStaticMaxDevices];
+static std::mutex g_static_mutex;
+
+// words [0, n_zero) of `zero` cleared; the rotary table in double, as cfpp_create
+// builds it on the host: angle = pos * base^(-2j/r)
+__global__ void k_static_setup(unsigned *zero, int n_zero, float2 *rope, int max_seq, int half, int r, double base)
+{
+    const int stride = gridDim.x * blockDim.x;
+    const int t0 = blockIdx.x * blockDim.x + threadIdx.x;
+    for (int i = t0; i < n_zero; i += stride) zero[i] = 0u;
+    for (long long i = t0; i < (long long)max_seq * half; i += stride) {
+        const int t = (int)(i / half), j = (int)(i - (long long)t * half);
+        const double a = (double)t * pow(base, -2.0 * j / (double)r);
+        rope[i] = float2{(float)cos(a), (float)sin(a)};
+    }
+}
+
+extern "C" cfpp_status cfpp_block_decode_static(const cfpp_config *c, const void *packed_layer, void *kv_layer,
+                                                const void *x, const int32_t *pos_dev, int32_t batch, void *out,
+                                                cfpp_stream stream)
+{
+    cfpp_status st = cfpp_validate_config(c);
+    if (st != CFPP_OK) return st;
+    const Dims dm = dims_of(*c);
+    const WorkspaceLayout wl = workspace_layout(dm);
+    if (wl.total > kStaticScratchBytes)
+        return fail(CFPP_ENOMEM, "this configuration needs %zu bytes of workspace; the built-in array holds %zu "
+                    "(lower max_seq or max_batch, or use cfpp_block_decode with a workspace of your own)",
+                    wl.total, kStaticScratchBytes);
+    int dev = 0;
+    HIP_OK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStaticMaxDevices) return fail(CFPP_EUNSUPPORTED, "device %d: only devices 0..%d", dev, kStaticMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticSlot &S = g_static[dev];
+    if (!S.ptr) {
+        // (the array's name is a host-side stand-in; this is its address on the current device)
+        char *ptr = nullptr;
+        HIP_OK(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(CFPP_EHIP, "hipGetSymbolAddress returned a null address");
+        S.ptr = ptr;
+        S.configured = false;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!S.configured || std::memcmp(&S.cfg, c, sizeof *c) != 0) {
+        int n_cu = 0;
+        HIP_OK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+        int lds_limit = 0;
+        HIP_OK(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+        cfpp_ctx &ctx = S.ctx;
+        const bool prepared = ctx.prepared, lm_prepared = ctx.lm_prepared;   // (kernel attributes: set once per process)
+        ctx = cfpp_ctx();
+        ctx.cfg = *c;
+        ctx.dm = dm;
+        ctx.lay = packed_layout(dm.h, dm.f);
+        ctx.wl = wl;
+        ctx.ws = S.ptr;
+        ctx.n_cu = n_cu;
+        ctx.mode = 0;
+        ctx.grid = 0;
+        ctx.threads = 512;
+        ctx.epoch_limit = kEpochLimit;
+        ctx.lds_limit = lds_limit > 0 ? (size_t)lds_limit : 65536;
+        ctx.prepared = prepared;
+        ctx.lm_prepared = lm_prepared;
+        ctx.last_batch = 1;
+        // the array keeps whatever the last configuration left: this one's sync words and
+        // arrival counters start at zero, its rotary table is written (on `stream`, ahead of the step)
+        const int half = dm.r / 2;
+        hipLaunchKernelGGL(k_static_setup, dim3(256), dim3(256), 0, s, reinterpret_cast<unsigned *>(S.ptr + wl.sync),
+                           (int)((wl.layer_ptrs - wl.sync) / 4), reinterpret_cast<float2 *>(S.ptr + wl.rope), dm.max_seq,
+                           half, dm.r, (double)c->rope_base);
+        HIP_OK(hipGetLastError());
+        S.cfg = *c;
+        S.configured = true;
+    }
+    return block_decode(&S.ctx, packed_layer, kv_layer, x, pos_dev, batch, out, stream, true);
 }
 
 #ifdef CFPP_PROFILE

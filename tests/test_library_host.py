@@ -125,6 +125,13 @@ def test_argument_errors_without_a_gpu():
     assert e.value.status == -3
     assert L.cfpp_stack_replay(None, None) == -1
     assert L.cfpp_block_decode(None, None, None, None, None, 1, None, None) == -1
+    assert L.cfpp_block_decode_static(None, None, None, None, None, 1, None, None) == -1
+    # the built-in workspace of the allocation-free entry point has a stated maximum
+    big = cf.Config.from_shape(synth.PYTHIA_6_9B, 1 << 20, max_batch=8)
+    assert cf.cfpp_workspace_bytes(big) > (16 << 20)
+    with pytest.raises(cf.CfppError) as e:
+        cf.cfpp_block_decode_static(big, 4096, 4096, 4096, 4096, 1, 8192)
+    assert e.value.status == -3
     assert b"ok" == L.cfpp_status_string(0)
 
 
