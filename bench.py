@@ -3,13 +3,17 @@
 (4096 cached positions, batch 1, fp16 weights/KV, fp32 accumulate) replayed
 from one HIP graph on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode M] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode M] [--no-cpu] [--no-configs]
 
 Prints ONE JSON line.  A "step" is one replay of the whole stack.  Inputs are
 the seeded synthetic tensors of synth/ (resident in HBM before timing starts).
 The roofline entry divides the algorithmic bytes of one replay by its average
 duration measured with HIP events on the launch stream; cpu_baseline times the
-CPU oracle on a few layers of the same workload on the host cores.
+CPU oracle on a few layers of the same workload on the host cores.  Beside the
+headline the line carries, under "configs", the other workloads of the
+measurement table (single blocks warm and cold, the 6.9B-shaped stack, the
+batch of 8 sequences, the context sweep), each with its microseconds, GB/s of
+algorithmic bytes and roofline fraction.
 """
 import argparse
 import json
@@ -26,18 +30,169 @@ PAPER_CONTEXT = {"paper_speedup_vs_hf": 1.34,
                  "paper_hw": "RTX 5090-class, Pythia-2.8B, 2048 decode tokens (context only)"}
 
 
+KERNEL_SOURCES = ("fused_kernel.hip", "decode_blocks.h", "attention_blocks.h", "attention_common.h", "device_utils.h",
+                  "layout.h", "decode_params.h")
+
+
+def kernel_sources_digest():
+    """Digest of the sources the dominant kernel is compiled from: the committed counter summary
+    names the digest it was measured with, so a summary older than the kernel is not passed on."""
+    import hashlib
+    m = hashlib.sha256()
+    for n in KERNEL_SOURCES:
+        m.update(open(os.path.join(ROOT, "paper_2604_23553_amd", "csrc", n), "rb").read())
+    return m.hexdigest()[:16]
+
+
 def read_traffic_note():
-    """HBM traffic per replay from the committed rocprofv3 --pmc summary, if any."""
+    """HBM traffic per replay from the committed rocprofv3 --pmc summary (counters cannot be read
+    from inside this run): (bytes, note).  None when the summary was measured on other kernel sources."""
     path = os.path.join(ROOT, "profiles", "stack_decode_pythia2.8b_s4096_hbm_traffic.txt")
     try:
         vals = {}
         for line in open(path):
             if "=" in line and not line.lstrip().startswith("#"):
                 k, v = line.split("=", 1)
-                vals[k.strip()] = float(v.split()[0])
-        return vals["fetch_bytes_per_replay"] + vals["write_bytes_per_replay"]
+                vals[k.strip()] = v.split()[0]
+        if vals.get("kernel_sources_digest") != kernel_sources_digest():
+            return None, "profiles/ summary is older than the kernel sources: not reported"
+        return (float(vals["fetch_bytes_per_replay"]) + float(vals["write_bytes_per_replay"]),
+                "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, " + os.path.relpath(path, ROOT))
     except Exception:
-        return None
+        return None, "no counter summary under profiles/"
+
+
+def time_replays(ctxs, stream, steps, warmup):
+    """Mean microseconds per graph replay: `ctxs` (captured contexts) replayed in rotation on one
+    torch stream, HIP events around the whole timed batch."""
+    import torch
+    import paper_2604_23553_amd as cf
+    n = len(ctxs)
+    for i in range(warmup):
+        cf.cfpp_stack_replay(ctxs[i % n], stream.cuda_stream)
+    stream.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for i in range(steps):
+        cf.cfpp_stack_replay(ctxs[i % n], stream.cuda_stream)
+    b.record(stream)
+    stream.synchronize()
+    return a.elapsed_time(b) * 1e3 / steps
+
+
+def entry(us, alg_bytes, **kw):
+    gbs = alg_bytes / (us * 1e-6) / 1e9
+    d = {"us": round(us, 2), "GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": alg_bytes}
+    d.update(kw)
+    return d
+
+
+def secondary_configs(ds, layers, x, args):
+    """The other workloads of the measurement table, beside the headline: µs per step, GB/s of
+    algorithmic bytes and the roofline fraction each (HIP events on the launch stream).
+    ds: the resident 2.8B stack of the headline; layers: its numpy weights."""
+    import numpy as np
+    import torch
+    import synth
+    import synth.device as sdev
+    import paper_2604_23553_amd as cf
+    from paper_2604_23553_amd.harness import DeviceStack
+    seed = synth.MASTER_SEED
+    out = {}
+    MODE_NAMES = {-1: "auto", 0: "0 (phase kernels)", 1: "1", 2: "2 (whole-stack kernel)"}
+
+    # context sweep of the 32-layer 2.8B stack (the paper's latency tables sweep 16 -> 2048
+    # positions, Sec. 3 and appendix), default launch mode
+    shape = ds.shape
+    sweep = {}
+    for S in (16, 128, 512, 1024, 2048, 4096):
+        if S + 1 > ds.max_seq:
+            continue
+        ds.set_inputs(x, S)
+        ds.capture()
+        us = time_replays([ds.ctx], ds.stream, 40, 8)
+        ds.check()
+        sweep[str(S)] = entry(us, cf.cfpp_algorithmic_bytes(ds.cfg, [S], shape.n_layers))
+    big = DeviceStack(shape, 8193, 1, share_weights_of=ds)         # same weights, a cache of 8192 positions
+    for l in range(shape.n_layers):
+        sdev.fill_kv(big.kv[l], seed, l)
+    big.set_options(mode=args.mode, grid=args.grid, threads=args.threads)
+    big.set_inputs(x, 8192)
+    big.capture()
+    us = time_replays([big.ctx], big.stream, 40, 8)
+    big.check()
+    sweep["8192"] = entry(us, cf.cfpp_algorithmic_bytes(big.cfg, [8192], shape.n_layers),
+                          note="cache filled by the device generator (synth/device.py)")
+    big.close()
+    out["context_sweep_pythia2.8b_32L"] = {"unit": "us per token", "launch_mode": MODE_NAMES[args.mode], "by_cached_positions": sweep}
+
+    def block_copies(shape_, lens, cap, batch, n_copies, w_np=None):
+        cs = []
+        for i in range(n_copies):
+            c = DeviceStack(shape_, cap, batch, 1)
+            if w_np is not None:
+                c.load_layer(0, w_np)
+            else:
+                c.load_layer_device(0, sdev.layer_tensors(shape_, seed, 0, c.dev))
+            sdev.fill_kv(c.kv[0], seed, i)
+            c.set_inputs(synth.x_input(shape_, seed, batch), lens)
+            cs.append(c)
+        return cs
+
+    def block_times(cs, lens, shape_, modes, steps):
+        r = {}
+        alg = cf.cfpp_algorithmic_bytes(cs[0].cfg, [int(v) for v in np.atleast_1d(lens)], 1)
+        for mode in modes:
+            try:
+                for c in cs:
+                    c.set_options(mode=mode)
+                    c.capture()
+                warm = time_replays([cs[0].ctx], cs[0].stream, steps, 20)
+                cold = time_replays([c.ctx for c in cs], cs[0].stream, steps, 20) if len(cs) > 1 else None
+                for c in cs:
+                    c.check()
+                r[MODE_NAMES[mode]] = {"warm": entry(warm, alg), "cold": entry(cold, alg) if cold else None}
+            except cf.CfppError as e:
+                r[MODE_NAMES[mode]] = {"error": str(e)}
+        return r
+
+    # config 1: the h-512 block, 128 cached positions; cold = 100 copies in rotation (> 600 MB)
+    cs = block_copies(synth.SMALL_BLOCK, 128, 129, 1, 100, synth.layer_weights(synth.SMALL_BLOCK, seed, 0))
+    out["cfg1_block_h512_s128"] = {"workload": "one h-512 block, 128 cached positions, batch 1 (6.6 MB: latency-bound; cold = 100 copies "
+                                               "replayed in rotation)", "by_launch_mode": block_times(cs, 128, synth.SMALL_BLOCK, (-1, 0, 2), 300)}
+    for c in cs:
+        c.close()
+    # config 2: one 2.8B-shaped block, 1024 cached positions; cold = 4 copies in rotation (672 MB > the 256 MB Infinity Cache)
+    cs = block_copies(shape, 1024, 1025, 1, 4, layers[0])
+    out["cfg2_block_pythia2.8b_s1024"] = {"workload": "one Pythia-2.8B-shaped block, 1024 cached positions, batch 1 (168 MB; cold = 4 copies "
+                                                      "replayed in rotation, 70 % of the roofline = 29.97 us)",
+                                          "by_launch_mode": block_times(cs, 1024, shape, (-1, 0, 2), 200)}
+    for c in cs:
+        c.close()
+    # config 4: the 32-layer 6.9B-shaped stack, 2048 cached positions (weights from the device generator)
+    s69 = synth.PYTHIA_6_9B
+    d4 = DeviceStack(s69, 2049, 1)
+    for l in range(s69.n_layers):
+        d4.load_layer_device(l, sdev.layer_tensors(s69, seed, l, d4.dev))
+        sdev.fill_kv(d4.kv[l], seed, l)
+    d4.set_options(mode=args.mode, grid=args.grid, threads=args.threads)
+    d4.set_inputs(synth.x_input(s69, seed), 2048)
+    d4.capture()
+    us = time_replays([d4.ctx], d4.stream, 30, 6)
+    d4.check()
+    out["cfg4_stack_pythia6.9b_32L_s2048"] = entry(us, cf.cfpp_algorithmic_bytes(d4.cfg, [2048], s69.n_layers),
+                                                   workload="32-layer Pythia-6.9B-shaped decode step, 2048 cached positions, batch 1, one graph replay",
+                                                   launch_mode=MODE_NAMES[args.mode], tokens_per_s=round(1e6 / us, 1))
+    d4.close()
+    # config 5: one 6.9B-shaped block, 8 sequences with cached lengths drawn from [1024, 8192]
+    lens = synth.seq_lens(seed, 8, 1024, 8192)
+    cs = block_copies(s69, lens, int(lens.max()) + 1, 8, 1)
+    r = block_times(cs, lens, s69, (-1,), 100)
+    out["cfg5_block_pythia6.9b_batch8"] = {"workload": f"one Pythia-6.9B-shaped block, batch 8, cached positions {[int(v) for v in lens]} "
+                                                       "(1.1 GB per step: cold by construction; 70 % of the roofline = 180 us)",
+                                           "by_launch_mode": {k: v["warm"] if "warm" in v else v for k, v in r.items()}}
+    cs[0].close()
+    return out
 
 
 def cpu_baseline(shape, layers, kvs, x, S, n_layers_sample):
@@ -211,10 +366,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--mode", type=int, default=int(os.environ.get("CFPP_MODE", "2")),
-                    help="0: kernel per phase, 1: persistent per block, 2: persistent stack")
-    ap.add_argument("--grid", type=int, default=int(os.environ.get("CFPP_GRID", "0")))
-    ap.add_argument("--threads", type=int, default=int(os.environ.get("CFPP_THREADS", "512")))
+    ap.add_argument("--mode", type=int, default=-1,
+                    help="-1: automatic (the library's default), 0: kernel per phase, 1: persistent per block, "
+                         "2: whole-stack kernel")
+    ap.add_argument("--grid", type=int, default=0)
+    ap.add_argument("--threads", type=int, default=512)
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the other workloads of the measurement table (reported under \"configs\")")
     ap.add_argument("--ctx", type=int, default=4096, help="cached positions per layer")
     ap.add_argument("--workload", choices=["stack", "block", "prefill"], default="stack",
                     help="stack: the headline (32 layers, batch 1); block: one block, see --copies / --batch; "
@@ -310,6 +468,8 @@ def main():
     us_launch = float(per.mean())
 
     alg_bytes = cf.cfpp_algorithmic_bytes(ds.cfg, [S], shape.n_layers)
+    fused = args.mode in (-1, 2)             # (the automatic mode runs a stack step in the whole-stack kernel)
+    traffic, traffic_note = read_traffic_note() if headline and fused and args.grid == 0 and args.threads == 512 else (None, "not the profiled launch")
     achieved = alg_bytes / (us_launch * 1e-6) / 1e9
     grid = cf.cfpp_get_option(ds.ctx, cf.OPT_GRID)
     out = {
@@ -326,16 +486,16 @@ def main():
         "config": {"workload": f"32-layer Pythia-{args.shape.upper()}-shaped decode step, ctx {S}, batch 1, one HIP graph replay",
                    "hidden": shape.hidden, "n_heads": shape.n_heads, "head_dim": shape.head_dim,
                    "ffn": shape.ffn, "n_layers": shape.n_layers, "ctx": S, "batch": 1,
-                   "launch_mode": args.mode, "grid": grid, "threads": args.threads},
+                   "launch_mode": "auto (whole-stack kernel)" if args.mode == -1 else args.mode, "grid": grid, "threads": args.threads},
         "tokens_per_s": 1e6 / us_wall,
         "us_per_block": us_wall / shape.n_layers,
         "us_per_replay_events": {"mean": us_launch, "median": float(np.median(per)),
                                  "min": float(per.min()), "p95": float(np.percentile(per, 95))},
         "achieved_hbm_GBps": achieved,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic_note() if headline and args.mode == 2 else None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_note,
                      "algorithmic_bytes_per_launch": alg_bytes,
-                     "kernel": f"k_stack_fused<{shape.head_dim}> (the whole 32-layer step is one launch)" if args.mode == 2
+                     "kernel": f"k_stack_fused<{shape.head_dim}> (the whole 32-layer step is one launch)" if fused
                      else "all kernels of one graph replay",
                      "launch": "one graph replay of the 32-layer step"},
         "context": PAPER_CONTEXT,
@@ -366,6 +526,8 @@ def main():
                              "achieved_hbm_GBps": (alg_bytes + lm_bytes) / (gen_us * 1e-6) / 1e9,
                              "what": "one graph replay per token: embedding row, the stack step, final LayerNorm, "
                                      "LM head and argmax; position advanced on the device"}
+    if headline and not args.no_configs:
+        out["configs"] = secondary_configs(ds, layers, x, args)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(shape, layers, kvs, x, S, 4)
     ds.close()

@@ -569,9 +569,10 @@ static cfpp_status check_io(const cfpp_ctx *ctx, const void *x, const int32_t *p
 // the shape has no kernel in it; CFPP_MODE_AUTO takes the fastest mode that
 // supports the call and never refuses: several sequences -> the batched
 // projections (mode 0); the whole-stack kernel where its shape limits and the
-// residency check allow it (a stack step always, a block on its own from hidden
-// 2048 on: below that a block is a handful of dependent hand-overs with nothing to
-// stream behind them and the three phase kernels are quicker); else the phase kernels.
+// residency check allow it (a step of several layers always, a block on its own - or
+// a one-layer stack - from hidden 2048 on: below that a block is a handful of
+// dependent hand-overs with nothing to stream behind them and the three phase
+// kernels are quicker); else the phase kernels.
 static cfpp_status resolve_mode(cfpp_ctx *ctx, const Shape &sh, const StepParams &P, int batch, bool stack,
                                 int *mode_out)
 {
@@ -579,7 +580,7 @@ static cfpp_status resolve_mode(cfpp_ctx *ctx, const Shape &sh, const StepParams
     if (mode == CFPP_MODE_AUTO) {
         mode = 0;
         const bool one_by_one = batch == 1 || !batched_path_shape(ctx, sh);
-        if (one_by_one && (stack || ctx->dm.h >= 2048)) {
+        if (one_by_one && ((stack && ctx->cfg.n_layers > 1) || ctx->dm.h >= 2048)) {
             g_err_hold hold;                               // a refusal here is not the caller's error
             if (check_fused(ctx, sh, P) == CFPP_OK) mode = 2;
         }

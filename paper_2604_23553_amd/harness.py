@@ -13,7 +13,7 @@ class DeviceStack:
     """An L-layer stack resident on one GPU (L = 1 for a single block)."""
 
     def __init__(self, shape, max_seq: int, max_batch: int = 1, n_layers: int | None = None,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", share_weights_of: "DeviceStack | None" = None):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the HIP path has no CPU fallback")
         self.shape = shape
@@ -26,7 +26,9 @@ class DeviceStack:
             raise B.CfppError(st, "cfpp_validate_config", B.lib().cfpp_last_error().decode())
         self.max_seq, self.max_batch = max_seq, max_batch
         u8 = dict(dtype=torch.uint8, device=self.dev)
-        self.packed = [torch.empty(B.cfpp_packed_layer_bytes(self.cfg), **u8) for _ in range(self.L)]
+        # (packed layers do not depend on max_seq or max_batch: another stack's can be borrowed)
+        self.packed = (share_weights_of.packed[: self.L] if share_weights_of is not None else
+                       [torch.empty(B.cfpp_packed_layer_bytes(self.cfg), **u8) for _ in range(self.L)])
         # 0xFF bytes = fp16 NaN everywhere: any read of a never-written slot shows up
         self.kv = [torch.full((B.cfpp_kv_layer_bytes(self.cfg),), 0xFF, **u8) for _ in range(self.L)]
         self.ws_bytes = B.cfpp_workspace_bytes(self.cfg)
@@ -69,6 +71,12 @@ class DeviceStack:
         dev = {n: torch.from_numpy(np.ascontiguousarray(w[n])).to(self.dev) for n in B.LAYER_TENSORS}
         torch.cuda.synchronize()
         B.cfpp_pack_layer(self.cfg, dev, self.packed[l], self.s)
+        self.stream.synchronize()
+
+    def load_layer_device(self, l: int, dev_tensors: dict):
+        """dev_tensors: canonical fp16 torch tensors of one block, already on this GPU."""
+        torch.cuda.synchronize()
+        B.cfpp_pack_layer(self.cfg, dev_tensors, self.packed[l], self.s)
         self.stream.synchronize()
 
     def load_kv(self, l: int, K: np.ndarray, V: np.ndarray, n_cached):
