@@ -363,6 +363,7 @@ static int pick_slices(int nrows, int nchunk, int nw)
 struct Shape {
     int grid, threads;
     int rows_qkv, rows_up, rows_h, nsl_down, nsl_dense;
+    int f_a, rows_up_a, rows_up_b;   // whole-stack kernel: the MLP intermediate in two halves
     unsigned lds_floats;
 };
 
@@ -375,6 +376,10 @@ static cfpp_status launch_shape(const cfpp_ctx *ctx, Shape *sh)
     sh->rows_qkv = (ceil_div(3 * dm.h, G) + 1) & ~1;
     sh->rows_up = ceil_div(dm.f, G);
     sh->rows_h = ceil_div(dm.h, G);
+    sh->f_a = ceil_div(ceil_div(dm.f, kChunk), 2) * kChunk;       // the first half, in whole 512-column units
+    if (sh->f_a > dm.f) sh->f_a = dm.f;
+    sh->rows_up_a = ceil_div(sh->f_a, G);
+    sh->rows_up_b = ceil_div(dm.f - sh->f_a, G);
     const int nch_h = ceil_div(dm.h, kChunk), nch_f = ceil_div(dm.f, kChunk);
     sh->nsl_down = pick_slices(sh->rows_h, nch_f, nw);
     sh->nsl_dense = pick_slices(sh->rows_h, nch_h, nw);
@@ -436,6 +441,7 @@ static StepParams make_params(const cfpp_ctx *ctx, const Shape &sh, int b, const
     P.attn_G = 0;
     P.attn_bstep = 1;
     P.rows_qkv = sh.rows_qkv; P.rows_up = sh.rows_up; P.rows_h = sh.rows_h;
+    P.f_a = sh.f_a; P.rows_up_a = sh.rows_up_a; P.rows_up_b = sh.rows_up_b;
     P.nsl_down = sh.nsl_down; P.nsl_dense = sh.nsl_dense;
     P.lds_floats = sh.lds_floats;
     P.debug = ctx->debug;

@@ -57,7 +57,10 @@ struct GemvSeg {
 // GEMV whose first blocks are requested long before its activations exist (ahead of a
 // hand-over with nothing else to stream): the stretch then starts with 2 + XB blocks in
 // registers and the queue is full again by the time they are consumed.
-template <int U_, int XB = 0>
+// STRIDED: the block is a column range of a wider row-major matrix (one segment only):
+// a row's units are contiguous, consecutive rows lie `row_stride` elements apart.  Units
+// are then addressed through a cursor that the load blocks advance in order.
+template <int U_, int XB = 0, bool STRIDED = false>
 struct GemvSpan {
     static constexpr int U = U_;
     u32x4 a[U], b[U];
@@ -70,6 +73,10 @@ struct GemvSpan {
     int n0, N, lo, hi, last, nw, wave, lane;
     const __half *safe;             // any readable 1 KiB: target of loads that are issued but not used
     bool regular;
+    // STRIDED: the next unit to request, its index inside its row, its offset from p0 in units, and the
+    // units to skip at the end of a row
+    int is_u, is_c, is_skip;
+    unsigned is_off;
     // walking state of consume()
     const float *yc;
     int c, nchc, rowg;
@@ -79,7 +86,7 @@ struct GemvSpan {
     // share (4 = equal split); callers lower it when that wavefront has other
     // work to finish first.
     __device__ __forceinline__ void init(const GemvSeg &s0, const GemvSeg &s1, const __half *safe_, int tid,
-                                         int share0 = 4)
+                                         int share0 = 4, int row_stride = 0)
     {
         safe = safe_;
         lane = tid & 63; wave = __builtin_amdgcn_readfirstlane(tid >> 6); nw = blockDim.x >> 6;
@@ -109,6 +116,13 @@ struct GemvSpan {
         rowg = in1 ? rows0 + row : row;
         yc = in1 ? y1 : y0;
         acc0 = 0.f; acc1 = 0.f;
+        if constexpr (STRIDED) {
+            // (single segment, whole units: the caller guarantees rows1 == 0 and K0 % kChunk == 0)
+            is_u = hi > lo ? lo : last;                     // (nothing to stream: the cursor stays on one readable unit)
+            is_c = hi > lo ? c : 0;
+            is_skip = row_stride / kChunk - nch0;
+            is_off = hi > lo ? (unsigned)(row * (row_stride / kChunk) + c) : 0u;
+        }
     }
 
     // Always exactly U load instructions on a single code path, so that the
@@ -122,12 +136,32 @@ struct GemvSpan {
         const bool in0 = uc < n0;
         return (in0 ? p0 : p1) + (size_t)(in0 ? uc : uc - n0) * kChunk;
     }
-    __device__ __forceinline__ void issue(u32x4 (&r)[U], int i) const
+    __device__ __forceinline__ void issue(u32x4 (&r)[U], int i)
     {
+        if constexpr (STRIDED) {
+            // (i only documents the order: every call continues where the previous one ended)
 #pragma unroll
-        for (int j = 0; j < U; ++j) r[j] = load16_stream_at(unit_ptr(i + j), lane_off);
+            for (int j = 0; j < U; ++j) {
+                r[j] = load16_stream_at(p0 + (size_t)is_off * kChunk, lane_off);
+                advance_cursor();
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < U; ++j) r[j] = load16_stream_at(unit_ptr(i + j), lane_off);
+        }
         // keep the instruction scheduler from sinking these loads towards their use
         __builtin_amdgcn_sched_barrier(0);
+    }
+    // STRIDED: the cursor moves to the next unit of this wavefront's range; at its last unit it
+    // stays.  Plain arithmetic on purpose: a branch here would make the loads conditional.
+    __device__ __forceinline__ void advance_cursor()
+    {
+        const int adv = (int)(is_u < last);
+        const int c1 = is_c + adv;
+        const int wrap = (int)(c1 == nch0);               // (only ever with adv = 1: is_c < nch0)
+        is_u += adv;
+        is_c = c1 - wrap * nch0;
+        is_off += (unsigned)(adv + wrap * is_skip);
     }
     __device__ __forceinline__ void issue_first() { issue(a, lo); }
     __device__ __forceinline__ void issue_second() { issue(b, lo + U); }
@@ -138,7 +172,14 @@ struct GemvSpan {
 #pragma unroll
         for (int x = 0; x < XB; ++x)
 #pragma unroll
-            for (int j = 0; j < U; ++j) ex[x][j] = load16_stream_at(unit_ptr(lo + (2 + x) * U + j), lane_off);
+            for (int j = 0; j < U; ++j) {
+                if constexpr (STRIDED) {
+                    ex[x][j] = load16_stream_at(p0 + (size_t)is_off * kChunk, lane_off);
+                    advance_cursor();
+                } else {
+                    ex[x][j] = load16_stream_at(unit_ptr(lo + (2 + x) * U + j), lane_off);
+                }
+            }
         __builtin_amdgcn_sched_barrier(0);
     }
 
@@ -198,13 +239,22 @@ struct GemvSpan {
     template <class Hook>
     __device__ __forceinline__ void run(float *part, Hook &&before_drain)
     {
-        if (!regular) { before_drain(); run_general(part); return; }
+        run(part, [] {}, before_drain);
+    }
+    // after_start(): called once, a few blocks into the stretch (XB > 0: behind the first two
+    // refills; else at once) - straight-line code, the place for loads that should join the stream late
+    template <class Start, class Hook>
+    __device__ __forceinline__ void run(float *part, Start &&after_start, Hook &&before_drain)
+    {
+        if (!regular) { after_start(); before_drain(); run_general(part); return; }
         int i = lo;
+        if constexpr (XB == 0) after_start();
         if constexpr (XB > 0) {
             // 2 + XB blocks are in registers: the first two are replaced as they are consumed,
             // the others just drain
             consume(a, i, part); issue(a, i + (2 + XB) * U);
             consume(b, i + U, part); issue(b, i + (3 + XB) * U);
+            after_start();
 #pragma unroll
             for (int x = 0; x < XB; ++x) consume(ex[x], i + (2 + x) * U, part);
             i += (2 + XB) * U;

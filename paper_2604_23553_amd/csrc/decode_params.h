@@ -29,6 +29,8 @@ struct StepParams {
     int parts;           // kPart* bits: what a phase launch performs (kPartAll unless the block runs in two halves)
     // work split (chosen on the host from the grid and the workgroup size)
     int rows_qkv, rows_up, rows_h;   // matrix rows per workgroup (rows_qkv even)
+    // whole-stack kernel: the MLP in two halves - up rows [0, f_a) and [f_a, f), rows of each per workgroup
+    int f_a, rows_up_a, rows_up_b;
     int nsl_down, nsl_dense;         // K-slices per row for the two GEMVs with few rows
     unsigned lds_floats;             // dynamic LDS the launch provides, in floats
     int debug;                       // profiling library only (0 otherwise): bit mask of parts to skip (results

@@ -221,7 +221,7 @@ struct GridBarrier {
     unsigned nbar;       // barriers completed by this launch
     unsigned nleaf, members;
     unsigned *leaf;
-    bool pending, last;
+    bool pending, last, propagated, released;
 
     // s: the workspace's sync words; which: one of the kSyncBarriers independent barriers
     __device__ __forceinline__ void init(unsigned *s, unsigned nwg, int which = 0)
@@ -232,6 +232,8 @@ struct GridBarrier {
         nbar = 0;
         pending = false;
         last = false;
+        propagated = false;
+        released = false;
         nleaf = nwg < (unsigned)kSyncLeaves ? nwg : (unsigned)kSyncLeaves;
         const unsigned l = blockIdx.x % nleaf;
         members = (nwg - l + nleaf - 1) / nleaf;
@@ -280,15 +282,28 @@ struct GridBarrier {
         wait_leader();
     }
 
+    // Second half of an arrival: the workgroup that was last at its leaf arrives at the root,
+    // and the last one there publishes the next generation.  It needs the value the leaf
+    // arrival returned, so it runs a little after arrive(); a caller that puts other work
+    // between arrive and wait calls it in between (once the arrival has had time to return),
+    // or the whole grid's release would wait for that work.  wait() runs it if nobody has.
+    __device__ __forceinline__ void propagate()
+    {
+        if (!pending || propagated) return;
+        propagated = true;
+        released = false;
+        if (threadIdx.x == 0 && last && count(sync + kSyncRoot, nleaf)) {
+            __hip_atomic_store(as_global(&sync[kSyncGen]), gen + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            released = true;
+        }
+    }
+
     __device__ __forceinline__ void wait_leader()
     {
+        propagate();
         pending = false;
+        propagated = false;
         if (threadIdx.x == 0) {
-            bool released = false;
-            if (last && count(sync + kSyncRoot, nleaf)) {
-                __hip_atomic_store(as_global(&sync[kSyncGen]), gen + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                released = true;
-            }
             if (!released) {
                 const unsigned long long t0 = wall_clock64();
                 unsigned spins = 0;
@@ -395,6 +410,35 @@ __device__ __forceinline__ void lds_rendezvous(int *counter, int target, unsigne
     PollGuard pg;
     pg.start(sync_words);
     while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target) {
+        __builtin_amdgcn_s_sleep(1);
+        if (pg.give_up()) break;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// One-sided signals through LDS words that only grow.  lds_signal: a wavefront adds one to a
+// counter after its LDS writes; lds_post: a wavefront stores a value; lds_await: spins until the
+// word has reached `target` (bounded like every other wait) and orders later LDS reads behind
+// it; lds_peek: one look, no waiting.
+__device__ __forceinline__ void lds_signal(int *counter, int lane)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0) __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void lds_post(int *word, int value, int lane)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0) __hip_atomic_store(word, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ bool lds_peek(const int *word, int target)
+{
+    return __hip_atomic_load(word, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= target;
+}
+__device__ __forceinline__ void lds_await(const int *word, int target, unsigned *sync_words)
+{
+    PollGuard pg;
+    pg.start(sync_words);
+    while (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target) {
         __builtin_amdgcn_s_sleep(1);
         if (pg.give_up()) break;
     }

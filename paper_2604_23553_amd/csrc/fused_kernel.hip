@@ -6,11 +6,23 @@
 // grid-wide hand-over of one chain can be waited for while the other chain's
 // weights stream:
 //
-//   QKV rows   -> q,k,v published      ... waited for behind the MLP-up rows
-//   up rows    -> GELU(up) published   ... waited for behind the attention
-//   attention  -> o published          ... waited for behind the MLP-down rows
-//   down rows  (stay inside the workgroup)
-//   dense rows -> next layer's input   ... the one exposed hand-over per layer
+//   QKV rows      -> q,k,v published          ... waited for behind the MLP-up rows
+//   up rows, A    -> first half of GELU(up)   ... waited for behind the B rows and the attention
+//   up rows, B    -> second half of GELU(up)  ... waited for behind the attention and the down columns A
+//   attention     -> o published              ... waited for behind the MLP-down columns
+//   down, columns A then B (stay inside the workgroup)
+//   dense rows    -> next layer's input       ... the one exposed hand-over per layer
+//
+// The MLP is cut in two so that its intermediate never has to be waited for: the
+// up-projection rows [0, f_a) of all workgroups finish first, and the down
+// projection starts with the matching columns [0, f_a) of its rows while the
+// second half is still on its way (a workgroup's down rows are streamed as two
+// column ranges of the row-major matrix).  Each half is copied to LDS
+// optimistically: the loads are issued at a point where the half is normally
+// complete (a flag in LDS, set by the chain wavefront once the half's grid
+// barrier has been passed, says whether it was) and only written to LDS behind
+// the stretch that streams meanwhile; when the flag was not yet set the copy is
+// repeated there.
 //
 // Nothing but that hand-over stands between two layers: the QKV and MLP-up rows
 // run on gamma * x, which needs no statistics, and the LayerNorm itself (paper
@@ -50,14 +62,18 @@ constexpr int kFusedSlots = 8;      // LDS slots for the streaming wavefronts' a
 // head_dim-128 instance keeps 4: at the 6.9B shape the stretch is 2.5 times longer and the
 // hand-overs end well inside it.
 constexpr int kFusedUDown = 3;
-constexpr int kStageMStream = 22;   // float2 per streaming thread when staging GELU(up): ffn <= 44 * 64 * (nw - 1)
+constexpr int kStageHalf = 12;      // float2 per streaming thread when staging one half of GELU(up): f_a <= 24 * 64 * (nw - 1)
+// words of FusedLds::ctr: rendezvous of the streaming wavefronts; A rows of the up projection done;
+// first / second half of GELU(up) complete everywhere (layer + 1)
+enum { kCtrRendezvous = 0, kCtrRowsA = 1, kCtrHalfA = 2, kCtrHalfB = 3 };
 
 // LDS of the fused kernel, in floats
 struct FusedLds {
-    unsigned y1, y2, ml, ol, xs, pq, pu, pd, pc, pset, qs, kn, vn, wp, wm, wl, ctr, total;
+    unsigned y1, y2, ml, ol, xs, pq, pua, pub, pda, pdb, pc, pset, qs, kn, vn, wp, wm, wl, ctr, total;
 };
 
-static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qkv, int rows_up, int rows_h, int nw)
+static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qkv, int rows_up_a, int rows_up_b, int rows_h,
+                                                     int nw)
 {
     FusedLds L;
     const unsigned Kph = (unsigned)((dm.h + kChunk - 1) / kChunk * kChunk);
@@ -65,8 +81,9 @@ static __host__ __device__ inline FusedLds fused_lds(const Dims &dm, int rows_qk
     unsigned o = 0;
     auto take = [&](unsigned n) { unsigned at = o; o += (n + 3u) & ~3u; return at; };
     L.y1 = take(Kph); L.y2 = take(Kph); L.ml = take(Kpf); L.ol = take(Kph); L.xs = take(Kph);
-    L.pq = take((unsigned)(rows_qkv * nw)); L.pu = take((unsigned)(rows_up * nw));
-    L.pd = take((unsigned)(rows_h * nw)); L.pc = take((unsigned)(rows_h * nw));
+    L.pq = take((unsigned)(rows_qkv * nw));
+    L.pua = take((unsigned)(rows_up_a * nw)); L.pub = take((unsigned)(rows_up_b * nw));
+    L.pda = take((unsigned)(rows_h * nw)); L.pdb = take((unsigned)(rows_h * nw)); L.pc = take((unsigned)(rows_h * nw));
     // one set of partial-sum slots; a second set follows (layers alternate, so that the
     // next layer's slots can be cleared while this layer's are still being read)
     L.pset = o - L.pq;
@@ -86,7 +103,9 @@ struct FusedCtx {
     float *lds;
     FusedLds L;
     int pos, nw;
-    int q_begin, q_n, u_begin, u_n, r_begin, r_n;
+    int q_begin, q_n, r_begin, r_n;
+    int ua_begin, ua_n, ub_begin, ub_n;   // this workgroup's up-projection rows of the first half [0, f_a) and of the second
+    int f_a;                              // columns of the first half of GELU(up)
     unsigned E0;                    // epoch base of this launch
     float *xt, *ot, *pt;            // tagged words: layer outputs [2][h], attention output [h], split-KV partials
 };
@@ -182,27 +201,58 @@ struct FusedSegs {
     }
 };
 
+// One half of GELU(up), workspace -> registers -> LDS (GEMV order), shared by the streaming
+// threads.  Always exactly UN load instructions per thread on one code path (threads past the
+// end re-read the first words), so that the loads can sit in the middle of a stream of weight
+// loads without upsetting the in-order load counter.  n: a multiple of 512.
+template <int UN>
+struct StagedPart {
+    float2 v[UN];
+    __device__ __forceinline__ void issue(const float *__restrict__ src, int n, int tid, int nt)
+    {
+        const int n2 = n >> 1;
+#pragma unroll
+        for (int j = 0; j < UN; ++j) {
+            const int i2 = tid + j * nt;
+            v[j] = xwg_load2(src + 2 * (i2 < n2 ? i2 : 0));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __device__ __forceinline__ void commit(int n, float *dst, int tid, int nt) const
+    {
+        const int n2 = n >> 1;
+#pragma unroll
+        for (int j = 0; j < UN; ++j) {
+            const int i2 = tid + j * nt;
+            if (i2 < n2) *reinterpret_cast<float2 *>(dst + lds_perm(i2 * 2)) = v[j];
+        }
+    }
+};
+
 // ---- wavefronts 1.. : stream --------------------------------------------------
 template <int D>
 __device__ __forceinline__ void fused_stream(const FusedCtx &C)
 {
     using AC = AttnCore<D>;
     constexpr int NP = AC::NP;
+    constexpr int UD = D == 128 ? kGemvU : kFusedUDown;
     const StepParams &P = *C.P;
     const Dims &dm = P.dm;
-    const int h = dm.h, f = dm.f, L = P.n_layers, nw = C.nw, NS = nw - 1;
+    const int h = dm.h, f = dm.f, fa = C.f_a, fb = f - C.f_a, L = P.n_layers, nw = C.nw, NS = nw - 1;
     float *lds = C.lds;
     float *y1 = lds + C.L.y1, *y2 = lds + C.L.y2, *ml = lds + C.L.ml, *ol = lds + C.L.ol;
+    int *ctr = reinterpret_cast<int *>(lds) + C.L.ctr;
     const int n_tok = C.pos + 1;
 
     // The two stretches that follow a gap with nothing to stream start with more blocks in
     // registers than the usual two: the QKV rows behind the layer-input hand-over (two more,
-    // requested when that hand-over begins), the down rows behind the staging of GELU(up)
-    // (one more, requested behind the staging loads).  Measured: more, or earlier, only
-    // lengthens the queue the hand-over's own loads wait in.
+    // requested when that hand-over begins), the first down columns behind the attention merges
+    // (one more).  Measured: more, or earlier, only lengthens the queue the hand-over's own
+    // loads wait in.
     GemvSpan<kGemvU, 2> gsQ;
-    GemvSpan<(D == 128 ? kGemvU : kFusedUDown), 1> gsD;
-    GemvSpan<kGemvU> gsU, gsC;
+    GemvSpan<UD, 1, true> gsDA;                           // down rows, columns [0, f_a)
+    GemvSpan<UD, 0, true> gsDB;                           // down rows, columns [f_a, f)
+    GemvSpan<kGemvU> gsUA, gsUB, gsC;
     {
         const int tid0 = opaque_thread_index();
         const __half *w0 = layer_weights(C, 0);
@@ -224,18 +274,26 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
         tr.select_layer(P, layer, L);
         // this layer's set of partial-sum slots
         const unsigned set = (unsigned)(layer & 1) * C.L.pset;
-        float *pq = lds + C.L.pq + set, *pu = lds + C.L.pu + set, *pd = lds + C.L.pd + set, *pc = lds + C.L.pc + set;
+        float *pq = lds + C.L.pq + set, *pua = lds + C.L.pua + set, *pub = lds + C.L.pub + set;
+        float *pda = lds + C.L.pda + set, *pdb = lds + C.L.pdb + set, *pc = lds + C.L.pc + set;
         tr.mark(1);
         fused_input(C, w, layer, tid);
         __syncthreads();                                   // S0: the layer input is in LDS
         tr.mark(3);
 
-        gsU.init(GemvSeg{w + P.lay.w_up + (size_t)C.u_begin * h, y2, h, C.u_n}, GemvSeg{w + P.lay.w_up, y2, h, 0},
-                 w, tid, 0);
-        gsQ.run(pq, [&] { gsU.issue_first(); gsU.issue_second(); });
+        gsUA.init(GemvSeg{w + P.lay.w_up + (size_t)C.ua_begin * h, y2, h, C.ua_n}, GemvSeg{w + P.lay.w_up, y2, h, 0},
+                  w, tid, 0);
+        gsQ.run(pq, [&] { gsUA.issue_first(); gsUA.issue_second(); });
         tr.mark(4);
         __syncthreads();                                   // S1: QKV rows done
         tr.mark(5);
+
+        gsUB.init(GemvSeg{w + P.lay.w_up + (size_t)C.ub_begin * h, y2, h, C.ub_n}, GemvSeg{w + P.lay.w_up, y2, h, 0},
+                  w, tid, 0);
+        gsUA.run(pua, [&] { gsUB.issue_first(); gsUB.issue_second(); });
+        // the A rows' partial sums are in LDS: the chain wavefront finishes them (nobody waits here)
+        lds_signal(ctr + kCtrRowsA, lane);
+        tr.mark(6);
 
         // attention share: the first K/V row is requested behind the last up-projection weights, the
         // second behind the barrier (both ahead of it and the chain wavefront's GELU(up) stores
@@ -246,14 +304,14 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
         sg.init(ac);
         u32x4 kA[NP], vA[NP], kB[NP], vB[NP];
         const int row0 = sg.row_lo[0] + si;
-        gsU.run(pu, [&] { ac.issue(kA, vA, sg.s[0], sg.n > 0 && row0 < sg.row_hi[0] ? row0 : -1); });
-        tr.mark(6);
+        gsUB.run(pub, [&] { ac.issue(kA, vA, sg.s[0], sg.n > 0 && row0 < sg.row_hi[0] ? row0 : -1); });
+        tr.mark(7);
         __syncthreads();                                   // S2: up rows done; q and the new K/V rows staged
         tr.mark(10);
         ac.issue(kB, vB, sg.s[0], sg.n > 0 && row0 + NS < sg.row_hi[0] ? row0 + NS : -1);
 
-        gsD.init(GemvSeg{w + P.lay.w_down + (size_t)C.r_begin * f, ml, f, C.r_n}, GemvSeg{w + P.lay.w_down, ml, f, 0},
-                 w, tid, 0);
+        gsDA.init(GemvSeg{w + P.lay.w_down + (size_t)C.r_begin * f, ml, fa, C.r_n}, GemvSeg{w + P.lay.w_down, ml, fa, 0},
+                  w, tid, 0, f);
 #pragma unroll
         for (int k = 0; k < kFusedSegs; ++k) {
             if (k < sg.n) {
@@ -280,29 +338,52 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
                               lds + C.L.wl + k * kFusedSlots, si);
             }
         }
-        // the first down-projection weights stream while the attention states are
-        // merged and GELU(up) is staged (requested any earlier they only lengthen the
-        // queue the hand-overs wait in)
-        gsD.issue_first();
-        gsD.issue_second();
+        // The first half of GELU(up) is normally complete by now (its grid barrier was passed
+        // behind the B rows and the attention): its copy is requested here, ahead of the first
+        // down-projection weights, and written to LDS behind the workgroup barrier.
+        StagedPart<kStageHalf> sm;
+        const bool a_ready = lds_peek(ctr + kCtrHalfA, layer + 1);
+        sm.issue(P.m, fa, tid - 64, NS * 64);
+        gsDA.issue_first();
+        gsDA.issue_second();
         tr.mark(13);
-        __syncthreads();                                   // S3: attention states in LDS; GELU(up) complete everywhere
+        __syncthreads();                                   // S3: attention states in LDS
         tr.mark(14);
-        {
-            StagedVector<kStageMStream> sm;                // (the chain wavefront is busy with the partials)
-            sm.issue(P.m, f, tid - 64, NS * 64);
-            gsD.issue_more();
-            sm.commit(f, ml, tid - 64, NS * 64);
+        if (!a_ready) {                                    // (uniform) not yet complete when it was read: again
+            lds_await(ctr + kCtrHalfA, layer + 1, P.sync);
+            sm.issue(P.m, fa, tid - 64, NS * 64);
         }
-        // GELU(up) staged: a rendezvous of the streaming wavefronts only (the chain
-        // wavefront is already publishing the attention partials)
-        lds_rendezvous(reinterpret_cast<int *>(lds) + C.L.ctr, NS * (layer + 1), P.sync, lane);
+        gsDA.issue_more();
+        sm.commit(fa, ml, tid - 64, NS * 64);
+        // staged: a rendezvous of the streaming wavefronts only (the chain wavefront is
+        // already publishing the attention partials)
+        lds_rendezvous(ctr + kCtrRendezvous, NS * (2 * layer + 1), P.sync, lane);
         tr.mark(17);
+
+        // down projection, columns A; the second half of GELU(up) is copied meanwhile, the same way
+        // (requested a few blocks into the stretch: its flag is posted just behind the attention)
+        gsDB.init(GemvSeg{w + P.lay.w_down + (size_t)C.r_begin * f + fa, ml + fa, fb, C.r_n},
+                  GemvSeg{w + P.lay.w_down, ml, fb, 0}, w, tid, 0, f);
+        bool b_ready = false;
+        gsDA.run(pda,
+                 [&] {
+                     b_ready = lds_peek(ctr + kCtrHalfB, layer + 1);
+                     sm.issue(P.m + fa, fb, tid - 64, NS * 64);
+                 },
+                 [&] { gsDB.issue_first(); gsDB.issue_second(); });
+        tr.mark(18);
+        if (!b_ready) {
+            lds_await(ctr + kCtrHalfB, layer + 1, P.sync);
+            sm.issue(P.m + fa, fb, tid - 64, NS * 64);
+        }
+        sm.commit(fb, ml + fa, tid - 64, NS * 64);
+        lds_rendezvous(ctr + kCtrRendezvous, NS * (2 * layer + 2), P.sync, lane);
+        tr.mark(19);
 
         gsC.init(GemvSeg{w + P.lay.w_dense + (size_t)C.r_begin * h, ol, h, C.r_n}, GemvSeg{w + P.lay.w_dense, ol, h, 0},
                  w, tid, 0);
-        gsD.run(pd, [&] { gsC.issue_first(); gsC.issue_second(); });
-        tr.mark(18);
+        gsDB.run(pdb, [&] { gsC.issue_first(); gsC.issue_second(); });
+        tr.mark(20);
         {
             // the next layer's first QKV weights stream while the attention output is waited for
             // (nothing for the last layer: the loads re-read one block)
@@ -314,7 +395,7 @@ __device__ __forceinline__ void fused_stream(const FusedCtx &C)
             gsQ.issue_second();
         }
         __syncthreads();                                   // S4: down rows done; attention output staged
-        tr.mark(20);
+        tr.mark(21);
         gsC.run(pc);
         tr.mark(23);
         __syncthreads();                                   // S6: dense rows done
@@ -339,11 +420,15 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C)
     float *lds = C.lds;
     float *ol = lds + C.L.ol;
     const int pos = C.pos, n_tok = pos + 1;
-    const int q_begin = C.q_begin, q_n = C.q_n, u_begin = C.u_begin, u_n = C.u_n, r_begin = C.r_begin, r_n = C.r_n;
+    const int q_begin = C.q_begin, q_n = C.q_n, r_begin = C.r_begin, r_n = C.r_n;
+    const int ua_begin = C.ua_begin, ua_n = C.ua_n, ub_begin = C.ub_begin, ub_n = C.ub_n;
+    int *ctr = reinterpret_cast<int *>(lds) + C.L.ctr;
 
-    GridBarrier b1, b2;
+    // one grid barrier per hand-over that is not self-describing: q/k/v, and the two halves of GELU(up)
+    GridBarrier b1, b2, b3;
     b1.init(P.sync, gridDim.x, 0);
     b2.init(P.sync, gridDim.x, 1);
+    b3.init(P.sync, gridDim.x, 2);
     // the partial sums of a row sit in wavefront slots; only the streaming wavefronts fill them
     GemvSpan<kGemvU> rt;                                  // (row_total() only)
     rt.nw = nw;
@@ -361,7 +446,8 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C)
         const bool last_layer = layer == L - 1;
         tr.select_layer(P, layer, L);
         const unsigned set = (unsigned)(layer & 1) * C.L.pset;   // this layer's partial-sum slots
-        const float *pq = lds + C.L.pq + set, *pu = lds + C.L.pu + set, *pd = lds + C.L.pd + set, *pc = lds + C.L.pc + set;
+        const float *pq = lds + C.L.pq + set, *pua = lds + C.L.pua + set, *pub = lds + C.L.pub + set;
+        const float *pda = lds + C.L.pda + set, *pdb = lds + C.L.pdb + set, *pc = lds + C.L.pc + set;
         tr.mark(1);
         fused_input(C, w, layer, tid);
         tr.mark(2);
@@ -372,10 +458,11 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C)
         // what the epilogues need for this lane's first rows: requested now, used behind the GEMVs
         // (rcq: the constants (s, c) of two adjacent packed QKV rows; rcu: of one MLP-up row)
         const float4 *rcq = reinterpret_cast<const float4 *>(w + P.lay.rc_qkv) + (q_begin >> 1);
-        const float2 *rcu = reinterpret_cast<const float2 *>(w + P.lay.rc_up) + u_begin;
+        const float2 *rcua = reinterpret_cast<const float2 *>(w + P.lay.rc_up) + ua_begin;
+        const float2 *rcub = reinterpret_cast<const float2 *>(w + P.lay.rc_up) + ub_begin;
         const __half *bdn = w + P.lay.b_down, *bde = w + P.lay.b_dense;
         float4 rq0 = {0.f, 0.f, 0.f, 0.f};
-        float2 ru0 = {0.f, 0.f};
+        float2 rua0 = {0.f, 0.f}, rub0 = {0.f, 0.f};
         float bdn0 = 0.f, bde0 = 0.f;
         float2 cs0 = {1.f, 0.f};
         if (lane < q_n / 2) {
@@ -384,7 +471,8 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C)
             rq0 = rcq[lane];
             if (c < 2 && i < r) cs0 = P.rope[(size_t)pos * (r >> 1) + (i >> 1)];
         }
-        if (lane < u_n) ru0 = rcu[lane];
+        if (lane < ua_n) rua0 = rcua[lane];
+        if (lane < ub_n) rub0 = rcub[lane];
         if (lane < r_n) {
             bdn0 = __half2float(bdn[r_begin + lane]);
             bde0 = __half2float(bde[r_begin + lane]);
@@ -446,6 +534,16 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C)
             }
         }
         b1.arrive_wave();
+        b1.propagate();                                    // (waits for the arrival to return: this wavefront is idle until the A rows are done anyway)
+        // first half of GELU(up): its rows' partial sums are in LDS once every streaming wavefront
+        // has passed them (this wavefront alone waits); its grid barrier runs behind the B rows
+        lds_await(ctr + kCtrRowsA, NS * (layer + 1), P.sync);
+        tr.mark(6);
+        for (int t = lane; t < ua_n; t += 64) {
+            const float2 ru = t == lane ? rua0 : rcua[t];
+            xwg_store(P.m + ua_begin + t, gelu_act(inv * (rt.row_total(pua, t) - mean * ru.x) + ru.y, dm.flags));
+        }
+        b2.arrive_wave();
         b1.wait_wave();                                    // q and the new K/V rows are complete everywhere
         tr.mark(7);
         {
@@ -462,6 +560,7 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C)
                     knv[k][e] = xwg_load_half(kv + kv_offset(dm, 0, P.b, s, ii, n_tok - 1));
                     vnv[k][e] = xwg_load_half(kv + kv_offset(dm, 1, P.b, s, ii, n_tok - 1));
                 }
+            b2.propagate();                                // (behind the loads just requested: its arrival is older)
 #pragma unroll
             for (int k = 0; k < kFusedSegs; ++k)
 #pragma unroll
@@ -477,12 +576,14 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C)
         tr.mark(8);
         __syncthreads();                                   // S2: up rows done
         tr.mark(10);
-        for (int t = lane; t < u_n; t += 64) {
-            const float2 ru = t == lane ? ru0 : rcu[t];
-            xwg_store(P.m + u_begin + t, gelu_act(inv * (rt.row_total(pu, t) - mean * ru.x) + ru.y, dm.flags));
+        for (int t = lane; t < ub_n; t += 64) {
+            const float2 ru = t == lane ? rub0 : rcub[t];
+            xwg_store(P.m + ub_begin + t, gelu_act(inv * (rt.row_total(pub, t) - mean * ru.x) + ru.y, dm.flags));
         }
-        b2.arrive_wave();
-        b2.wait_wave();                                    // GELU(up) is complete everywhere
+        b3.arrive_wave();
+        b2.wait_wave();                                    // the first half of GELU(up) is complete everywhere
+        lds_post(ctr + kCtrHalfA, layer + 1, lane);
+        b3.propagate();
         tr.mark(12);
         __syncthreads();                                   // S3: attention states in LDS
         tr.mark(14);
@@ -496,6 +597,8 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C)
             if (k < sg.n)
                 ac.publish_tagged(P, C.pt, epoch, sg.s[k], lds + C.L.wp + k * kFusedSlots * D,
                                   lds + C.L.wm + k * kFusedSlots, lds + C.L.wl + k * kFusedSlots, NS);
+        b3.wait_wave();                                    // the second half of GELU(up) is complete everywhere
+        lds_post(ctr + kCtrHalfB, layer + 1, lane);
 #pragma unroll
         for (int k = 0; k < kFusedSegs; ++k)
             if (k < sg.n && ac.combines(sg.s[k])) ac.combine_tagged(P, C.pt, C.ot, epoch, sg.s[k]);
@@ -537,7 +640,7 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C)
         CFPP_STAMP(P, lane == 0, 5);
         tr.mark(20);
         float g_r = 0.f;
-        if (lane < r_n) g_r = rt.row_total(pd, lane) + bdn0;
+        if (lane < r_n) g_r = (rt.row_total(pda, lane) + rt.row_total(pdb, lane)) + bdn0;
         __syncthreads();                                   // S6: dense rows done
         tr.mark(24);
         CFPP_STAMP(P, lane == 0 && layer == L - 2, 6);
@@ -552,6 +655,7 @@ __device__ __forceinline__ void fused_chain(const FusedCtx &C)
     }
     b1.finish_wave();
     b2.finish_wave();
+    b3.finish_wave();
     // every workgroup has read E0 and finished its layers: the next launch gets fresh epochs
     if (blockIdx.x == 0 && threadIdx.x == 0)
         __hip_atomic_store(as_global(P.sync + kSyncEpoch), C.E0 + (unsigned)L + 1u, __ATOMIC_RELAXED,
@@ -571,18 +675,20 @@ k_stack_fused(StepParams P, const LayerPtrs *__restrict__ ptrs)
     C.ptrs = ptrs;
     C.lds = lds;
     C.nw = blockDim.x >> 6;
-    C.L = fused_lds(dm, P.rows_qkv, P.rows_up, P.rows_h, C.nw);
+    C.L = fused_lds(dm, P.rows_qkv, P.rows_up_a, P.rows_up_b, P.rows_h, C.nw);
     C.pos = pos;
     const int g = blockIdx.x;
     C.q_begin = g * P.rows_qkv; C.q_n = max(0, min(P.rows_qkv, 3 * dm.h - C.q_begin));
-    C.u_begin = g * P.rows_up;  C.u_n = max(0, min(P.rows_up, dm.f - C.u_begin));
+    C.f_a = P.f_a;
+    C.ua_begin = g * P.rows_up_a;          C.ua_n = max(0, min(P.rows_up_a, P.f_a - C.ua_begin));
+    C.ub_begin = P.f_a + g * P.rows_up_b;  C.ub_n = max(0, min(P.rows_up_b, dm.f - C.ub_begin));
     C.r_begin = g * P.rows_h;   C.r_n = max(0, min(P.rows_h, dm.h - C.r_begin));
     // (only changed at the very end of a launch, behind the last barriers)
     C.E0 = __hip_atomic_load(as_global(P.sync + kSyncEpoch), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     C.xt = P.tagged;
     C.ot = P.tagged + 2 * (size_t)5 * dm.h;
     C.pt = P.tagged + 2 * (size_t)6 * dm.h;
-    if (threadIdx.x == 0) reinterpret_cast<int *>(lds)[C.L.ctr] = 0;    // (a workgroup barrier follows in both roles)
+    if (threadIdx.x < 4) reinterpret_cast<int *>(lds)[C.L.ctr + threadIdx.x] = 0;    // (a workgroup barrier follows in both roles)
     clear_partials(lds + C.L.pq, (int)C.L.pset, threadIdx.x);          // layer 0's partial-sum slots
     if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0) fused_chain<D>(C);
     else fused_stream<D>(C);
@@ -591,7 +697,7 @@ k_stack_fused(StepParams P, const LayerPtrs *__restrict__ ptrs)
 // ---- host side -----------------------------------------------------------------
 size_t fused_lds_bytes(const Dims &dm, const StepParams &P, int threads)
 {
-    return (size_t)fused_lds(dm, P.rows_qkv, P.rows_up, P.rows_h, threads / 64).total * 4;
+    return (size_t)fused_lds(dm, P.rows_qkv, P.rows_up_a, P.rows_up_b, P.rows_h, threads / 64).total * 4;
 }
 
 // grid >= heads (a workgroup's attention share then covers at most two heads),
@@ -601,7 +707,8 @@ size_t fused_lds_bytes(const Dims &dm, const StepParams &P, int threads)
 bool fused_supported(const Dims &dm, const StepParams &P, int grid, int threads)
 {
     return !(dm.flags & kFlagSequentialResidual) && grid >= dm.H && P.rows_h <= 64 && dm.h <= 4096 && dm.h % kChunk == 0 && dm.f % kChunk == 0 &&
-           (size_t)dm.f <= (size_t)2 * kStageMStream * 64 * (threads / 64 - 1) && threads / 64 - 1 <= kFusedSlots && threads >= 128 &&
+           dm.f >= 2 * kChunk && P.f_a % kChunk == 0 && P.f_a > 0 && P.f_a < dm.f &&
+           (size_t)P.f_a <= (size_t)2 * kStageHalf * 64 * (threads / 64 - 1) && threads / 64 - 1 <= kFusedSlots && threads >= 128 &&
            (dm.d == 64 || dm.d == 80 || dm.d == 128);
 }
 
