@@ -72,10 +72,10 @@ typedef struct cfpp_config {
  *   CFPP_FLAG_TANH_GELU            gelu(z) = z/2 (1 + tanh(sqrt(2/pi)(z + 0.044715 z^3)))
  *                                  instead of the exact erf form (all launch modes)
  *   CFPP_FLAG_SEQUENTIAL_RESIDUAL  x1 = x + Dense(Attn(LN1(x))); out = x1 + Down(GELU(Up(LN2(x1))))
- *                                  instead of the parallel form (launch mode 0 only: the
- *                                  other modes overlap the two branches, which this form
- *                                  forbids; they return CFPP_EUNSUPPORTED, and
- *                                  CFPP_MODE_AUTO takes mode 0)                        */
+ *                                  instead of the parallel form (launch modes 0 and 1: two
+ *                                  passes per block; mode 2 overlaps the two branches,
+ *                                  which this form forbids, and returns
+ *                                  CFPP_EUNSUPPORTED; CFPP_MODE_AUTO takes mode 0)      */
 #define CFPP_FLAG_TANH_GELU 1
 #define CFPP_FLAG_SEQUENTIAL_RESIDUAL 2
 

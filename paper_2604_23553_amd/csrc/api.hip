@@ -451,21 +451,23 @@ static StepParams make_params(const cfpp_ctx *ctx, const Shape &sh, int b, const
     return P;
 }
 
-// One block with the phase kernels.  Parallel residual: one pass.  Sequential
+// One block with the phase kernels (or, persistent = true, with the persistent kernel that runs
+// the same phases behind grid barriers).  Parallel residual: one pass.  Sequential
 // residual: two passes over the same kernels - the attention half (LayerNorm,
 // QKV, attention, output projection, x1 = x + a) and the MLP half (LayerNorm of
 // x1, up, down, out = x1 + g) - as two consecutive slots of the fp32 residual
 // ping-pong; P.n_layers counts slots.
 static hipError_t launch_block_phases(const StepParams &P, const __half *w, __half *kv, int l, int grid,
-                                      int threads, hipStream_t s)
+                                      int threads, hipStream_t s, bool persistent = false)
 {
-    if (!(P.dm.flags & kFlagSequentialResidual)) return launch_phases(P, w, kv, l, grid, threads, s);
+    auto launch = persistent ? launch_block_persistent : launch_phases;
+    if (!(P.dm.flags & kFlagSequentialResidual)) return launch(P, w, kv, l, grid, threads, s);
     StepParams Q = P;
     Q.parts = kPartQkv | kPartAttention | kPartDense;
-    hipError_t e = launch_phases(Q, w, kv, 2 * l, grid, threads, s);
+    hipError_t e = launch(Q, w, kv, 2 * l, grid, threads, s);
     if (e != hipSuccess) return e;
     Q.parts = kPartUp | kPartDown;
-    return launch_phases(Q, w, kv, 2 * l + 1, grid, threads, s);
+    return launch(Q, w, kv, 2 * l + 1, grid, threads, s);
 }
 
 // Launch mode 0 with several sequences: the projections of a layer run once for
@@ -595,11 +597,7 @@ static cfpp_status resolve_mode(cfpp_ctx *ctx, const Shape &sh, const StepParams
     }
     *mode_out = mode;
     if (mode == 2) return check_fused(ctx, sh, P);
-    if (mode == 1) {
-        if (ctx->dm.flags & kFlagSequentialResidual)
-            return fail(CFPP_EUNSUPPORTED, "the sequential residual form runs in launch modes 0 and 2");
-        return check_persistent(ctx, sh);
-    }
+    if (mode == 1) return check_persistent(ctx, sh);
     return CFPP_OK;
 }
 
@@ -648,11 +646,9 @@ static cfpp_status block_decode(cfpp_ctx *ctx, const void *packed_layer, void *k
     if (mode == 0 && batched_path(ctx, sh, batch)) return launch_batched_layer(ctx, sh, w, kv, 0, 1, x, pos_dev, batch, out, s);
     if (mode == 2 && !capturing(s) && (st = account_epochs(ctx, 2ull * batch)) != CFPP_OK) return st;
     for (int b = 0; b < batch; ++b) {
-        StepParams P = make_params(ctx, sh, b, x, pos_dev, out, mode == 0 && seq ? 2 : 1);
-        if (mode == 0) {
-            HIP_OK(launch_block_phases(P, w, kv, 0, sh.grid, sh.threads, s));
-        } else if (mode == 1) {
-            HIP_OK(launch_block_persistent(P, w, kv, 0, sh.grid, sh.threads, s));
+        StepParams P = make_params(ctx, sh, b, x, pos_dev, out, mode != 2 && seq ? 2 : 1);
+        if (mode == 0 || mode == 1) {
+            HIP_OK(launch_block_phases(P, w, kv, 0, sh.grid, sh.threads, s, mode == 1));
         } else {
             P.w_single = w;
             P.kv_single = kv;
@@ -708,16 +704,12 @@ static cfpp_status enqueue_stack(cfpp_ctx *ctx, const void *const *packed_layers
     }
     const int slots = (ctx->dm.flags & kFlagSequentialResidual) ? 2 : 1;   // residual slots per block, phase kernels
     for (int b = 0; b < batch; ++b) {
-        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, mode == 0 ? L * slots : L);
+        const StepParams P = make_params(ctx, sh, b, x, pos_dev, out, mode != 2 ? L * slots : L);
         if (mode == 2) {
             HIP_OK(launch_stack_fused(P, dev_ptrs, sh.grid, sh.threads, s));
         } else {
-            for (int l = 0; l < L; ++l) {
-                if (mode == 0)
-                    HIP_OK(launch_block_phases(P, ptrs.w[l], ptrs.kv[l], l, sh.grid, sh.threads, s));
-                else
-                    HIP_OK(launch_block_persistent(P, ptrs.w[l], ptrs.kv[l], l, sh.grid, sh.threads, s));
-            }
+            for (int l = 0; l < L; ++l)
+                HIP_OK(launch_block_phases(P, ptrs.w[l], ptrs.kv[l], l, sh.grid, sh.threads, s, mode == 1));
         }
     }
     return CFPP_OK;

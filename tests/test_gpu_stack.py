@@ -417,11 +417,11 @@ def test_fused_kernel_across_launch_shapes(orc, grid, threads):
         ds.close()
 
 
-@pytest.mark.parametrize("flags,mode", [(1, 0), (1, 1), (1, 2), (1, -1), (2, 0), (3, 0), (2, -1)])
+@pytest.mark.parametrize("flags,mode", [(1, 0), (1, 1), (1, 2), (1, -1), (2, 0), (3, 0), (2, -1), (2, 1), (3, 1)])
 def test_other_readings_of_the_block(orc, flags, mode):
     """tanh GELU (every launch mode) and the sequential residual form (launch
-    mode 0, two passes per block; the automatic mode falls back to it) against the
-    oracle's variants."""
+    modes 0 and 1, two passes per block; the automatic mode falls back to mode 0)
+    against the oracle's variants."""
     import dataclasses
     shape = dataclasses.replace(TINY_STACK, flags=flags)
     S, cap = 90, 96
@@ -453,20 +453,19 @@ def test_other_readings_of_the_block(orc, flags, mode):
         ds.close()
 
 
-def test_sequential_form_is_refused_by_the_overlapping_modes():
+def test_sequential_form_is_refused_by_the_overlapping_mode():
     import dataclasses
     from paper_2604_23553_amd import CfppError
     shape = dataclasses.replace(TINY_STACK, flags=synth.FLAG_SEQUENTIAL_RESIDUAL)
     ds, ws, kvs = build_stack(shape, 42, 10, 12)
     try:
         ds.set_inputs(synth.x_input(shape, 1), 10)
-        for mode in (1, 2):
-            ds.set_options(mode=mode)
-            with pytest.raises(CfppError) as e:
-                ds.stack_decode()
-            assert e.value.status == -2
-            with pytest.raises(CfppError):
-                ds.block_decode(0)
+        ds.set_options(mode=2)                            # (the whole-stack kernel overlaps the two branches)
+        with pytest.raises(CfppError) as e:
+            ds.stack_decode()
+        assert e.value.status == -2
+        with pytest.raises(CfppError):
+            ds.block_decode(0)
     finally:
         ds.close()
 
