@@ -762,7 +762,7 @@ extern "C" cfpp_status cfpp_stack_prefill(cfpp_ctx *ctx, const void *const *pack
         return fail(CFPP_EUNSUPPORTED, "prompt processing runs in launch mode 0 with the parallel residual form");
     if (!bat_supported(ctx->dm, sh.grid, sh.threads) || sh.grid < kBatMax)
         return fail(CFPP_EUNSUPPORTED, "prompt processing needs the batched projections: 512 threads, grid >= %d, hidden "
-                    "and ffn multiples of 256, at most 64 matrix rows per workgroup", kBatMax);
+                    "and ffn multiples of 128, at most 64 matrix rows per workgroup", kBatMax);
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t *pos_dev = reinterpret_cast<int32_t *>(ctx->ws + ctx->wl.pf_pos);
     HIP_OK(launch_fill_positions(pos_dev, pos0, n_tokens, s));

@@ -6,7 +6,7 @@
 
 namespace cfpp {
 
-constexpr int kBatMax = 8;             // sequences per launch (columns of the MFMA B operand in use)
+constexpr int kBatMax = 8;             // sequences per launch (two 4-column blocks of the MFMA B operand)
 constexpr int kBatLnPerLane = 64;      // hidden values a lane normalises at most (hidden <= 4096)
 
 // All per-sequence pointers are already offset to the first sequence of the
@@ -35,7 +35,7 @@ struct BatParams {
 };
 
 bool bat_supported(const Dims &dm, int grid, int threads);
-size_t bat_lds_bytes(const Dims &dm);
+size_t bat_lds_bytes(const Dims &dm, int grid);
 hipError_t launch_bat_qkv_up(BatParams P, int grid, hipStream_t s);
 hipError_t launch_bat_out(BatParams P, int grid, hipStream_t s);
 hipError_t prepare_bat_kernels(size_t lds_bytes);

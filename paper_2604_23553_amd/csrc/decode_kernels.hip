@@ -426,8 +426,11 @@ k_attention_batched(StepParams P, int nb, const __half *w, const __half *kv)
     Q.attn_g0 = g0;
     Q.attn_G = g1 - g0;
     Q.parts = kPartAttention;
-    NoSync sync;
-    phase_b<D>(Q, w, kv, *Q.pos, lds, sync);
+    // the attention alone: nothing of the MLP-down stretch that shares phase B with it
+    // (no GELU(up) staged into LDS, no weights requested)
+    Tracer tr;
+    tr.init(Q, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), 16);
+    attn_share<D>(Q, kv, *Q.pos + 1, lds, opaque_thread_index(), [] {}, [] {}, [] {}, [] {}, tr);
 }
 
 template <int D>
