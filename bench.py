@@ -309,8 +309,9 @@ def bench_block(args):
 
 
 def bench_prefill(args):
-    """Prompt processing (cfpp_stack_prefill): a prompt of --tokens tokens through the whole stack from an
-    empty cache, groups of 8 tokens per pass over the weights."""
+    """Prompt processing: a prompt of --tokens tokens through the whole stack from an empty cache.
+    --gemm-rows 0: cfpp_stack_prefill (groups of 8 tokens per pass over the weights, batched projections);
+    --gemm-rows N: cfpp_stack_prefill_gemm (N tokens per pass, GEMMs on the matrix cores)."""
     import numpy as np
     import torch
     import synth
@@ -318,47 +319,63 @@ def bench_prefill(args):
     from paper_2604_23553_amd.harness import DeviceStack
 
     shape = {"2.8b": synth.PYTHIA_2_8B, "6.9b": synth.PYTHIA_6_9B}[args.shape]
-    seed, T, G = synth.MASTER_SEED, args.tokens, 8
+    seed, T = synth.MASTER_SEED, args.tokens
+    rows = args.gemm_rows
+    G = rows if rows else 8
     L = shape.n_layers
-    ds = DeviceStack(shape, T + 1, G, L)
+    ds = DeviceStack(shape, T + 1, 1 if rows else 8, L)
     for l in range(L):
         ds.load_layer(l, synth.layer_weights(shape, seed, l))
-        kv = synth.kv_cache(shape, seed, l, 0, T + 1, G, poison=False)
+        kv = synth.kv_cache(shape, seed, l, 0, T + 1, 1 if rows else 8, poison=False)
         ds.load_kv(l, kv[0], kv[1], 0)
     ds.set_options(mode=0, grid=args.grid, threads=args.threads)
     xd = torch.from_numpy(synth.x_input(shape, seed, T)).to(ds.dev)
     od = torch.zeros_like(xd)
+    if rows:
+        nbytes = cf.cfpp_prefill_scratch_bytes(ds.cfg, rows)
+        if nbytes == 0:
+            raise SystemExit(f"--gemm-rows {rows}: a multiple of 128 up to 4096 is needed")
+        scratch = torch.empty(nbytes, dtype=torch.uint8, device=ds.dev)
+        run = lambda: cf.cfpp_stack_prefill_gemm(ds.ctx, ds.packed, ds.kv, xd, 0, T, 0, od, scratch, nbytes, rows, ds.s)
+    else:
+        run = lambda: cf.cfpp_stack_prefill(ds.ctx, ds.packed, ds.kv, xd, 0, T, 0, od, ds.s)
     torch.cuda.synchronize()
-    run = lambda: cf.cfpp_stack_prefill(ds.ctx, ds.packed, ds.kv, xd, 0, T, 0, od, ds.s)
     for _ in range(args.warmup):
         run()
     ds.stream.synchronize()
     ds.check()
-    t0 = time.perf_counter()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(ds.stream)
     for _ in range(args.steps):
         run()
+    b.record(ds.stream)
     ds.stream.synchronize()
-    us = (time.perf_counter() - t0) / args.steps * 1e6
+    us = a.elapsed_time(b) * 1e3 / args.steps
     ds.check()
-    # what this path streams: per group of 8 tokens the weights once and every token's K/V rows
-    streamed = sum(cf.cfpp_algorithmic_bytes(ds.cfg, list(range(t0_, min(t0_ + G, T))), L) for t0_ in range(0, T, G))
+    # what the path streams: per pass of G tokens the weights once and every token's K/V rows
+    streamed = sum(cf.cfpp_algorithmic_bytes(ds.cfg, [t0_], L) for t0_ in range(0, T, G))
     h, f = shape.hidden, shape.ffn
     flops = 2.0 * (4 * h * h + 2 * h * f) * T * L + 4.0 * h * L * (T * (T + 1) / 2)
     ds.close()
     achieved = streamed / (us * 1e-6) / 1e9
-    print(json.dumps({
+    tf = flops / (us * 1e-6) / 1e12
+    line = {
         "metric": f"us_per_prompt_prefill_{L}L_{args.shape}_T{T}", "value": us, "unit": "us/prompt", "n_gpus": 1,
         "tokens_per_s": T * 1e6 / us, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False,
         "data": "synthetic", "dtype": "f16 weights/KV, f32 accumulate",
         "config": {"workload": f"prompt of {T} tokens through {L} {shape.name} blocks from an empty cache, "
-                               f"groups of {G} tokens (launch mode 0, batched projections)", "launch_mode": 0},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "streamed_bytes_per_prompt": streamed,
-                     "note": "bytes this path streams: the weights once per group of 8 tokens; a prompt-sized "
-                             "GEMM would read them once per prompt and be bound by the matrix cores instead"},
-        "mfma": {"flops_per_prompt": flops, "achieved_TFLOPs": flops / (us * 1e-6) / 1e12,
-                 "frac_of_f16_peak": flops / (us * 1e-6) / 2.5e15},
-    }))
+                               + (f"{rows} tokens per pass (GEMMs on the matrix cores, activations as fp16 head + remainder)" if rows
+                                  else "groups of 8 tokens (batched projections)"), "tokens_per_pass": G},
+        "mfma": {"flops_per_prompt": flops, "achieved_TFLOPs": tf, "frac_of_f16_peak": tf / 2500.0,
+                 "note": "useful flops (2 per weight and token, 4 per attention pair and dimension); the GEMM path "
+                         "issues twice as many in the projections (head and remainder of every activation)"},
+        "hbm": {"streamed_bytes_per_prompt": streamed, "GBps": achieved, "frac": achieved / HBM_PEAK_GBS},
+    }
+    line["roofline"] = ({"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}
+                        if rows else
+                        {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": achieved / HBM_PEAK_GBS, "traffic": None})
+    print(json.dumps(line))
 
 
 def main():
@@ -378,6 +395,9 @@ def main():
                     help="stack: the headline (32 layers, batch 1); block: one block, see --copies / --batch; "
                          "prefill: a prompt of --tokens tokens through the stack")
     ap.add_argument("--tokens", type=int, default=512, help="prefill workload: prompt length")
+    ap.add_argument("--gemm-rows", type=int, default=512,
+                    help="prefill workload: tokens per pass of the prompt-sized kernels (a multiple of 128); 0 = the "
+                         "batched path, 8 tokens per pass")
     ap.add_argument("--copies", type=int, default=1, help="block workload: copies replayed in rotation (cold when large)")
     ap.add_argument("--batch", type=int, default=1, help="block workload: sequences (ragged lengths 1024..8192 when > 1)")
     ap.add_argument("--layers", type=int, default=1, help="block workload: blocks in a row (a stack of that many layers)")

@@ -270,6 +270,29 @@ cfpp_status cfpp_stack_prefill(cfpp_ctx *ctx, const void *const *packed_layers,
                                void *const *kv_layers, const void *x, int32_t pos0,
                                int32_t n_tokens, int32_t b, void *out, cfpp_stream stream);
 
+/* The same computation for long prompts, with each layer's weights read once
+ * per pass of up to `rows` tokens instead of once per 8: per layer a LayerNorm
+ * launch, the four projections as LDS-tiled GEMMs on the matrix cores
+ * (tokens x K activations times K x rows weights: here the paper's memory-bound
+ * GEMVs, Sec. 2.2, are dense contractions), and one causal-attention launch over
+ * the cache rows the pass has just appended.  Activations enter the fp16 matrix
+ * instruction as head + remainder, so the products match the fp32 path to
+ * rounding.  Arguments as for cfpp_stack_prefill, plus
+ *   scratch      : DEVICE, 256-byte aligned, at least
+ *                  cfpp_prefill_scratch_bytes(cfg, rows) bytes; the caller's,
+ *                  contents undefined afterwards
+ *   rows         : tokens per pass, a multiple of 128 up to 4096
+ * Any launch mode (the kernels are its own).  CFPP_EUNSUPPORTED unless hidden and
+ * ffn are multiples of 128, hidden <= 4096 and the residual form is the parallel
+ * one; CFPP_ENOMEM for a scratch that is too small; CFPP_EINVAL as above.
+ * cfpp_prefill_scratch_bytes returns 0 for an invalid configuration or rows.
+ * Asynchronous on `stream`. */
+size_t cfpp_prefill_scratch_bytes(const cfpp_config *cfg, int32_t rows);
+cfpp_status cfpp_stack_prefill_gemm(cfpp_ctx *ctx, const void *const *packed_layers,
+                                    void *const *kv_layers, const void *x, int32_t pos0,
+                                    int32_t n_tokens, int32_t b, void *out, void *scratch,
+                                    size_t scratch_bytes, int32_t rows, cfpp_stream stream);
+
 /* Graph mode with static buffers (paper Sec. 2.3): capture records the whole
  * stack step for these exact pointers into one HIP graph (nothing executes);
  * each replay is one graph launch.  Between replays the caller updates the

@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     cfpp_validate_config, cfpp_packed_layer_bytes, cfpp_kv_layer_bytes, cfpp_workspace_bytes,
     cfpp_algorithmic_bytes, cfpp_pack_layer, cfpp_kv_import, cfpp_kv_export,
     cfpp_create, cfpp_destroy, cfpp_set_option, cfpp_get_option,
-    cfpp_block_decode, cfpp_stack_decode, cfpp_stack_prefill, cfpp_stack_capture, cfpp_stack_replay,
+    cfpp_block_decode, cfpp_stack_decode, cfpp_stack_prefill, cfpp_prefill_scratch_bytes, cfpp_stack_prefill_gemm, cfpp_stack_capture, cfpp_stack_replay,
     cfpp_block_decode_static, cfpp_device_error, cfpp_debug_read, cfpp_stream_read, cfpp_stream_copy,
     Lm, cfpp_lm_embed, cfpp_lm_next, cfpp_generate_capture,
     OPT_MODE, OPT_GRID, OPT_THREADS, OPT_PROFILE_SKIP, OPT_EPOCH_LIMIT, MODE_AUTO,

@@ -68,6 +68,8 @@ def _load(kind: str) -> C.CDLL:
         for n in ("cfpp_packed_layer_bytes", "cfpp_kv_layer_bytes", "cfpp_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
             getattr(L, n).argtypes = [C.POINTER(Config)]
+        L.cfpp_prefill_scratch_bytes.restype = C.c_size_t
+        L.cfpp_prefill_scratch_bytes.argtypes = [C.POINTER(Config), C.c_int32]
         L.cfpp_destroy.restype = None
         L.cfpp_destroy.argtypes = [C.c_void_p]
         _loaded[kind] = L
@@ -197,6 +199,18 @@ def cfpp_stack_prefill(ctx: int, packed_layers, kv_layers, x, pos0: int, n_token
                                     _ptr(x), C.c_int32(pos0), C.c_int32(n_tokens), C.c_int32(b), _ptr(out),
                                     _ptr(stream)),
            "cfpp_stack_prefill")
+
+
+def cfpp_prefill_scratch_bytes(cfg: Config, rows: int) -> int:
+    return int(lib().cfpp_prefill_scratch_bytes(C.byref(cfg), C.c_int32(rows)))
+
+
+def cfpp_stack_prefill_gemm(ctx: int, packed_layers, kv_layers, x, pos0: int, n_tokens: int, b: int, out, scratch,
+                            scratch_bytes: int, rows: int, stream=None):
+    _check(lib().cfpp_stack_prefill_gemm(C.c_void_p(ctx), _ptr_array(packed_layers), _ptr_array(kv_layers),
+                                         _ptr(x), C.c_int32(pos0), C.c_int32(n_tokens), C.c_int32(b), _ptr(out),
+                                         _ptr(scratch), C.c_size_t(scratch_bytes), C.c_int32(rows), _ptr(stream)),
+           "cfpp_stack_prefill_gemm")
 
 
 def cfpp_stack_capture(ctx: int, packed_layers, kv_layers, x, pos_dev, batch: int, out, stream):

@@ -16,9 +16,9 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcfpp.so")
 LIB_PROFILE = os.path.join(PKG, "libcfpp_profile.so")
 SOURCES = ["api.hip", "decode_kernels.hip", "fused_kernel.hip", "lm_kernels.hip", "batched_kernels.hip",
-           "prep_kernels.hip"]
+           "prep_kernels.hip", "prefill_kernels.hip"]
 HEADERS = ["layout.h", "device_utils.h", "decode_params.h", "attention_common.h", "decode_blocks.h",
-           "attention_blocks.h", "lm_params.h", "batched_params.h"]
+           "attention_blocks.h", "lm_params.h", "batched_params.h", "prefill_params.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -17,6 +17,7 @@
 #endif
 #include "lm_params.h"
 #include "batched_params.h"
+#include "prefill_params.h"
 #include "decode_params.h"
 
 using namespace cfpp;
@@ -118,6 +119,12 @@ extern "C" size_t cfpp_workspace_bytes(const cfpp_config *c)
 {
     if (cfpp_validate_config(c) != CFPP_OK) return 0;
     return workspace_layout(dims_of(*c)).total;
+}
+
+extern "C" size_t cfpp_prefill_scratch_bytes(const cfpp_config *c, int32_t rows)
+{
+    if (cfpp_validate_config(c) != CFPP_OK || rows <= 0 || rows > kPfMaxRows || rows % kPfTile != 0) return 0;
+    return pf_layout(dims_of(*c), rows).total;
 }
 
 extern "C" cfpp_status cfpp_algorithmic_bytes(const cfpp_config *c, const int32_t *pos_host,
@@ -778,6 +785,75 @@ extern "C" cfpp_status cfpp_stack_prefill(cfpp_ctx *ctx, const void *const *pack
                                            static_cast<__half *>(kv_layers[l]), l, L, xg, pos_dev + t0, nb, og, s,
                                            b)) != CFPP_OK)
                 return st;
+    }
+    ctx->last_batch = 1;
+    return CFPP_OK;
+}
+
+// Prompt processing with the weights read once per pass of up to `rows` tokens: every pass
+// goes through all layers (LayerNorm inputs, four GEMMs and the causal attention per layer)
+// before the next pass starts, which attends over this pass's rows in every layer's cache.
+extern "C" cfpp_status cfpp_stack_prefill_gemm(cfpp_ctx *ctx, const void *const *packed_layers, void *const *kv_layers,
+                                               const void *x, int32_t pos0, int32_t n_tokens, int32_t b, void *out,
+                                               void *scratch, size_t scratch_bytes, int32_t rows, cfpp_stream stream)
+{
+    if (!ctx) return fail(CFPP_EINVAL, "ctx is NULL");
+    cfpp_status st = prepare(ctx);
+    if (st != CFPP_OK) return st;
+    if (!aligned16(x) || !aligned16(out)) return fail(CFPP_EINVAL, "x or out is NULL or not 16-byte aligned");
+    if (!packed_layers || !kv_layers) return fail(CFPP_EINVAL, "layer pointer arrays are NULL");
+    const int L = ctx->cfg.n_layers;
+    for (int l = 0; l < L; ++l)
+        if (!aligned16(packed_layers[l]) || !aligned16(kv_layers[l]))
+            return fail(CFPP_EINVAL, "layer %d: NULL or misaligned pointer", l);
+    if (b < 0 || b >= ctx->cfg.max_batch) return fail(CFPP_EINVAL, "sequence %d outside [0, max_batch = %d)", b, ctx->cfg.max_batch);
+    if (n_tokens <= 0 || pos0 < 0 || (long long)pos0 + n_tokens > ctx->cfg.max_seq)
+        return fail(CFPP_EINVAL, "positions [%d, %d + %d) outside the cache of %d positions", pos0, pos0, n_tokens,
+                    ctx->cfg.max_seq);
+    {
+        const char *xb = static_cast<const char *>(x), *ob = static_cast<const char *>(out);
+        const size_t n = (size_t)n_tokens * ctx->dm.h * 2;
+        if (xb < ob + n && ob < xb + n) return fail(CFPP_EINVAL, "out overlaps x");
+    }
+    if (rows <= 0 || rows > kPfMaxRows || rows % kPfTile != 0)
+        return fail(CFPP_EINVAL, "rows %d: a multiple of %d up to %d is needed", rows, kPfTile, kPfMaxRows);
+    if (!pf_supported(ctx->dm))
+        return fail(CFPP_EUNSUPPORTED, "the prompt-sized kernels need hidden and ffn multiples of %d, hidden <= 4096 and "
+                    "the parallel residual form", kPfTile);
+    const PfLayout pl = pf_layout(ctx->dm, rows);
+    if (!scratch || (reinterpret_cast<uintptr_t>(scratch) & 255u))
+        return fail(CFPP_EINVAL, "scratch is NULL or not 256-byte aligned");
+    if (scratch_bytes < pl.total) return fail(CFPP_ENOMEM, "scratch of %zu bytes, %zu needed for %d rows", scratch_bytes, pl.total, rows);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *sc = static_cast<char *>(scratch);
+    const size_t h = (size_t)ctx->dm.h;
+    for (int t0 = 0; t0 < n_tokens; t0 += rows) {
+        PfParams P;
+        std::memset(&P, 0, sizeof P);
+        P.dm = ctx->dm; P.lay = ctx->lay;
+        P.b = b; P.pos0 = pos0 + t0;
+        P.n_rows = n_tokens - t0 < rows ? n_tokens - t0 : rows;
+        P.rows = rows; P.n_layers = L;
+        P.x_in = static_cast<const __half *>(x) + (size_t)t0 * h;
+        P.out = static_cast<__half *>(out) + (size_t)t0 * h;
+        P.y1h = reinterpret_cast<__half *>(sc + pl.y1h); P.y1l = reinterpret_cast<__half *>(sc + pl.y1l);
+        P.y2h = reinterpret_cast<__half *>(sc + pl.y2h); P.y2l = reinterpret_cast<__half *>(sc + pl.y2l);
+        P.stats = reinterpret_cast<float2 *>(sc + pl.stats);
+        P.q = reinterpret_cast<float *>(sc + pl.q);
+        P.oh = reinterpret_cast<__half *>(sc + pl.oh); P.ol = reinterpret_cast<__half *>(sc + pl.ol);
+        P.mh = reinterpret_cast<__half *>(sc + pl.mh); P.ml = reinterpret_cast<__half *>(sc + pl.ml);
+        P.part = reinterpret_cast<float *>(sc + pl.part);
+        P.rope = reinterpret_cast<const float2 *>(ctx->ws + ctx->wl.rope);
+        P.sync = reinterpret_cast<unsigned *>(ctx->ws + ctx->wl.sync);
+        float *xa = reinterpret_cast<float *>(sc + pl.xres), *xb2 = reinterpret_cast<float *>(sc + pl.xnext);
+        for (int l = 0; l < L; ++l) {
+            P.layer = l;
+            P.w = static_cast<const __half *>(packed_layers[l]);
+            P.kv = static_cast<__half *>(kv_layers[l]);
+            P.xres = (l & 1) ? xb2 : xa;                   // the block's output is the next block's input
+            P.xnext = (l & 1) ? xa : xb2;
+            HIP_OK(launch_pf_layer(P, s));
+        }
     }
     ctx->last_batch = 1;
     return CFPP_OK;

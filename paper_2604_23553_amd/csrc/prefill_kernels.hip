@@ -1,0 +1,422 @@
+// Prompt processing with the weights read once per pass over up to kPfMaxRows
+// tokens (the paper names a prefill phase beside its fused decode kernel, Sec. 4.2;
+// what is computed is the block of Sec. 2.2 applied to every prompt token with
+// causal attention).  With hundreds of tokens the four projections are dense
+// contractions - tokens x K activations times K x rows weights - and run as
+// LDS-tiled GEMMs on the matrix cores (v_mfma_f32_32x32x16_f16); the attention of
+// a pass reads the cache rows its own QKV launch appended.
+//
+//   k_pf_ln     : per token: mean, 1/sigma, and gamma_1 * x, gamma_2 * x as two fp16
+//                 planes each (head + remainder: y = hi + lo to ~2^-22, so that the
+//                 fp16 matrix instruction reproduces the fp32 product to rounding)
+//   k_pf_gemm<> : C[tokens][n] = A[tokens][K] . W[n][K]^T, both operands K-major,
+//                 fp32 accumulation, two instructions per tile (head, remainder);
+//                 the epilogue completes the LayerNorm from the packing's row
+//                 constants (QKV, MLP-up) and does what follows the product:
+//                 rotary + cache append + q | GELU -> planes | residual sums
+//   k_pf_attn<> : causal attention of a block of queries of one head over the
+//                 cache, keys in LDS tiles of 64 positions, online softmax
+//
+// Every sum has a fixed order: one bit pattern per build and pass size.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include "device_utils.h"
+#include "prefill_params.h"
+
+namespace cfpp {
+
+typedef _Float16 pf_f16x8 __attribute__((ext_vector_type(8)));
+typedef float pf_f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ void pf_split(float v, __half &hi, __half &lo)
+{
+    hi = __float2half_rn(v);
+    lo = __float2half_rn(v - __half2float(hi));
+}
+
+// ---------------------------------------------------------------------------
+// One workgroup of 256 threads per scratch row.  Rows past the pass's tokens get
+// zero planes (their products are never stored).
+constexpr int kPfLnPerThread = 16;     // hidden <= 4096
+__global__ void __launch_bounds__(256) k_pf_ln(PfParams P)
+{
+    __shared__ float red[8];
+    const Dims &dm = P.dm;
+    const int h = dm.h, row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __half *y1h = P.y1h + (size_t)row * h, *y1l = P.y1l + (size_t)row * h;
+    __half *y2h = P.y2h + (size_t)row * h, *y2l = P.y2l + (size_t)row * h;
+    if (row >= P.n_rows) {
+        const __half z = __float2half_rn(0.f);
+        for (int i = tid; i < h; i += 256) { y1h[i] = z; y1l[i] = z; y2h[i] = z; y2l[i] = z; }
+        return;
+    }
+    float x[kPfLnPerThread];
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPfLnPerThread; ++k) {
+        const int i = tid + 256 * k;
+        x[k] = 0.f;
+        if (i < h) x[k] = P.layer == 0 ? __half2float(P.x_in[(size_t)row * h + i]) : P.xres[(size_t)row * h + i];
+        s += x[k];
+    }
+    s = wave_sum(s);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    const float mean = ((red[0] + red[1]) + (red[2] + red[3])) / (float)h;
+    float q = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPfLnPerThread; ++k) {
+        const float dlt = tid + 256 * k < h ? x[k] - mean : 0.f;
+        q += dlt * dlt;
+    }
+    q = wave_sum(q);
+    if (lane == 0) red[4 + wave] = q;
+    __syncthreads();
+    const float inv = 1.0f / sqrtf(((red[4] + red[5]) + (red[6] + red[7])) / (float)h + dm.ln_eps);
+    if (tid == 0) P.stats[row] = float2{mean, inv};
+    const __half *g1 = P.w + P.lay.ln1_g, *g2 = P.w + P.lay.ln2_g;
+#pragma unroll
+    for (int k = 0; k < kPfLnPerThread; ++k) {
+        const int i = tid + 256 * k;
+        if (i < h) {
+            if (P.layer == 0) P.xres[(size_t)row * h + i] = x[k];
+            pf_split(x[k] * __half2float(g1[i]), y1h[i], y1l[i]);
+            pf_split(x[k] * __half2float(g2[i]), y2h[i], y2l[i]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// What follows a product, for the element (row = token, col = output feature) with the
+// K-sum `val`, in two steps because a rotation pair of the packed QKV order sits in two
+// adjacent columns (the first one even) and each needs the other's completed value.
+enum { kPfQkv = 0, kPfUp = 1, kPfDense = 2, kPfDown = 3 };
+
+// the LayerNorm, completed: inv (W (gamma x) - mu s) + c, with c = W beta + b from the packing
+template <int EPI>
+__device__ __forceinline__ float pf_complete(const PfParams &P, int row, int col, float val)
+{
+    if (EPI == kPfQkv || EPI == kPfUp) {
+        const float2 rc = reinterpret_cast<const float2 *>(P.w + (EPI == kPfQkv ? P.lay.rc_qkv : P.lay.rc_up))[col];
+        const float2 st = P.stats[row];
+        val = (val - st.x * rc.x) * st.y + rc.y;
+    }
+    return val;
+}
+
+// other: the completed value of the neighbouring column (col ^ 1) of the same row (QKV only)
+template <int EPI>
+__device__ __forceinline__ void pf_store(const PfParams &P, int row, int col, float val, float other)
+{
+    const Dims &dm = P.dm;
+    const int h = dm.h;
+    if (EPI == kPfQkv) {
+        const int pd = col / dm.d, i = col - pd * dm.d, nh = pd / 3, c = pd - 3 * nh;
+        int dim = i;
+        if (c < 2 && i < dm.r) {
+            const float2 cs = P.rope[(size_t)(P.pos0 + row) * (dm.r >> 1) + (i >> 1)];
+            if (i & 1) { val = val * cs.x + other * cs.y; dim = (i >> 1) + (dm.r >> 1); }
+            else { val = val * cs.x - other * cs.y; dim = i >> 1; }
+        }
+        if (c == 0) P.q[(size_t)row * h + nh * dm.d + dim] = val;
+        else P.kv[kv_offset(dm, c - 1, P.b, nh, dim, P.pos0 + row)] = __float2half_rn(val);
+    } else if (EPI == kPfUp) {
+        __half hi, lo;
+        pf_split(gelu_act(val, dm.flags), hi, lo);
+        P.mh[(size_t)row * dm.f + col] = hi;
+        P.ml[(size_t)row * dm.f + col] = lo;
+    } else if (EPI == kPfDense) {
+        P.xnext[(size_t)row * h + col] = P.xres[(size_t)row * h + col] + (val + __half2float(P.w[P.lay.b_dense + col]));
+    } else {
+        const float res = P.xnext[(size_t)row * h + col] + (val + __half2float(P.w[P.lay.b_down + col]));
+        if (P.layer == P.n_layers - 1) P.out[(size_t)row * h + col] = __float2half_rn(res);
+        else P.xnext[(size_t)row * h + col] = res;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// GEMM.  Workgroup: 256 threads = 2 x 2 wavefronts, tile 128 tokens x 128 output
+// features, K in steps of 32 through double-buffered LDS (rows 40 halves apart:
+// the 16-byte fragment reads of 16 consecutive rows hit 16 different groups of four
+// banks).  A wavefront owns 64 x 64 of the tile: 2 x 2 instruction tiles of 32 x 32
+// (v_mfma_f32_32x32x16_f16: a lane supplies 8 consecutive K values of its row),
+// each fed the head and the remainder plane of the activations; consecutive
+// instructions go to different accumulators.
+// Tiles are numbered with the token tiles fastest and dealt so that consecutive
+// numbers run on the same XCD (workgroup i runs on XCD i % 8): the token tiles
+// that share a tile of the weight matrix read it through one L2.
+// splits > 1: workgroup z of a tile takes the z-th part of K and leaves its sums in
+// part[z][row][col] (rows of whole token tiles); k_pf_reduce adds the parts in order and finishes.
+constexpr int kPfBK = 32, kPfStride = 40;
+
+template <int EPI>
+__global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__restrict__ Ah, const __half *__restrict__ Al,
+                                                  const __half *__restrict__ W, int K, int N, int splits, float *part)
+{
+    __shared__ __align__(16) __half sA[2][2][kPfTile * kPfStride];
+    __shared__ __align__(16) __half sW[2][kPfTile * kPfStride];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int mt = (P.n_rows + kPfTile - 1) / kPfTile, total = (N / kPfTile) * mt * splits;
+    const int per_xcd = (total + 7) >> 3;
+    const int v = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (v >= total) return;                               // (whole workgroup)
+    const int z = v % splits, tile = v / splits;
+    const int m0 = (tile % mt) * kPfTile, n0 = (tile / mt) * kPfTile;
+    const int kb = (K / splits) * z, nk = K / splits / kPfBK;
+    // global -> LDS: a tile plane is 128 rows x 32 halves = 512 pieces of 16 bytes, two per thread
+    const int lrow0 = tid >> 2, lrow1 = lrow0 + 64, lk = (tid & 3) * 8 + kb;
+    const __half *pa_h0 = Ah + (size_t)(m0 + lrow0) * K + lk, *pa_h1 = Ah + (size_t)(m0 + lrow1) * K + lk;
+    const __half *pa_l0 = Al + (size_t)(m0 + lrow0) * K + lk, *pa_l1 = Al + (size_t)(m0 + lrow1) * K + lk;
+    const __half *pw0 = W + (size_t)(n0 + lrow0) * K + lk, *pw1 = W + (size_t)(n0 + lrow1) * K + lk;
+    const int st0 = lrow0 * kPfStride + (tid & 3) * 8, st1 = lrow1 * kPfStride + (tid & 3) * 8;
+    // Three register sets hold the tiles of the next three steps while the current one is
+    // multiplied out of LDS: a global load has three steps to arrive.  Every step requests,
+    // multiplies, writes LDS and meets the others once, without conditions around the loads
+    // (steps past the end re-read the last tile and are not multiplied).
+    struct Regs { u32x4 ah0, ah1, al0, al1, w0, w1; } g0, g1, g2;
+    const int nk1 = nk - 1;
+    auto fetch = [&](Regs &g, int kt) {
+        const int k0 = (kt < nk1 ? kt : nk1) * kPfBK;
+        g.ah0 = load16(pa_h0 + k0); g.ah1 = load16(pa_h1 + k0);
+        g.al0 = load16(pa_l0 + k0); g.al1 = load16(pa_l1 + k0);
+        g.w0 = load16(pw0 + k0); g.w1 = load16(pw1 + k0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto put = [&](__half *dst, u32x4 v4) { *reinterpret_cast<u32x4 *>(dst) = v4; };
+    auto stash = [&](const Regs &g, int buf) {
+        put(&sA[buf][0][st0], g.ah0); put(&sA[buf][0][st1], g.ah1);
+        put(&sA[buf][1][st0], g.al0); put(&sA[buf][1][st1], g.al1);
+        put(&sW[buf][st0], g.w0); put(&sW[buf][st1], g.w1);
+    };
+    pf_f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+    // fragment of this lane: row lane % 32 of an instruction tile, halves 8 * (lane / 32) .. + 7 of a step of 16
+    const int fr = lane & 31, fk = (lane >> 5) * 8;
+    const int a_off = (wm * 64 + fr) * kPfStride + fk, w_off = (wn * 64 + fr) * kPfStride + fk;
+    auto multiply = [&](int buf) {
+#pragma unroll
+        for (int ks = 0; ks < kPfBK / 16; ++ks) {
+            pf_f16x8 ah[2], al[2], wf[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                ah[t] = *reinterpret_cast<const pf_f16x8 *>(&sA[buf][0][a_off + t * 32 * kPfStride + ks * 16]);
+                al[t] = *reinterpret_cast<const pf_f16x8 *>(&sA[buf][1][a_off + t * 32 * kPfStride + ks * 16]);
+                wf[t] = *reinterpret_cast<const pf_f16x8 *>(&sW[buf][w_off + t * 32 * kPfStride + ks * 16]);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[a], wf[b], acc[a][b], 0, 0, 0);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[a], wf[b], acc[a][b], 0, 0, 0);
+        }
+    };
+    fetch(g0, 0);
+    fetch(g1, 1);
+    fetch(g2, 2);
+    stash(g0, 0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; kt += 3) {                  // tile t sits in LDS buffer t % 2
+        const int b0 = kt & 1, b1 = b0 ^ 1;
+        fetch(g0, kt + 3); multiply(b0); stash(g1, b1); __syncthreads();
+        fetch(g1, kt + 4); if (kt + 1 < nk) multiply(b1); stash(g2, b0); __syncthreads();
+        fetch(g2, kt + 5); if (kt + 2 < nk) multiply(b0); stash(g0, b1); __syncthreads();
+    }
+    // this lane holds, per instruction tile, column lane % 32 and rows 8 (e / 4) + 4 (lane / 32) + e % 4
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int col = n0 + wn * 64 + b * 32 + (lane & 31);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = m0 + wm * 64 + a * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                if (splits > 1) {
+                    part[((size_t)z * mt * kPfTile + row) * N + col] = acc[a][b][e];
+                } else {
+                    const bool live = row < P.n_rows;
+                    const float val = pf_complete<EPI>(P, live ? row : 0, col, acc[a][b][e]);
+                    const float other = EPI == kPfQkv ? dpp_mov<kDppXor1>(val) : 0.f;   // (all lanes: the neighbouring lane holds col ^ 1)
+                    if (live) pf_store<EPI>(P, row, col, val, other);
+                }
+            }
+    }
+}
+
+// the parts of a split-K product, added in order, then what follows the product; a thread
+// takes four consecutive columns of a row (two rotation pairs)
+template <int EPI>
+__global__ void __launch_bounds__(256) k_pf_reduce(PfParams P, const float *__restrict__ part, int N, int splits)
+{
+    const int mt = (P.n_rows + kPfTile - 1) / kPfTile, n4 = N >> 2;
+    const unsigned n_el = (unsigned)P.n_rows * (unsigned)n4;
+    const size_t zstride = (size_t)mt * kPfTile * N;
+    for (unsigned e = blockIdx.x * 256u + threadIdx.x; e < n_el; e += gridDim.x * 256u) {
+        const int row = (int)(e / (unsigned)n4), col = (int)(e - (unsigned)row * (unsigned)n4) * 4;
+        const float *p = part + (size_t)row * N + col;
+        f32x4 s = *as_global(reinterpret_cast<const f32x4 *>(p));
+        for (int z = 1; z < splits; ++z) s += *as_global(reinterpret_cast<const f32x4 *>(p + z * zstride));
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = pf_complete<EPI>(P, row, col + j, s[j]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pf_store<EPI>(P, row, col + j, v[j], v[j ^ 1]);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Causal attention of kPfQB consecutive queries of one head: grid (H, blocks of
+// queries).  Keys and values of 64 positions at a time in LDS (rows D + 2 halves
+// apart: an odd number of words, so the lanes' row reads spread over the banks);
+// a wavefront takes its queries one after the other: lane = key for the scores,
+// lane = dimension (lane, lane + 64) for the weighted sum; online softmax in fp32.
+constexpr int kPfQB = 16;
+
+template <int D>
+__global__ void __launch_bounds__(256) k_pf_attn(PfParams P)
+{
+    constexpr int RS = D + 2;                              // halves per LDS row
+    __shared__ __align__(16) __half sK[64 * RS];
+    __shared__ __align__(16) __half sV[64 * RS];
+    __shared__ float sQ[kPfQB][D];
+    __shared__ float sP[4][64];
+    const Dims &dm = P.dm;
+    const int head = blockIdx.x, q0 = blockIdx.y * kPfQB, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (q0 >= P.n_rows) return;
+    const int nq = min(kPfQB, P.n_rows - q0);
+    const float scale = 1.0f / sqrtf((float)D);
+    for (int e = tid; e < nq * D; e += 256) {
+        const int qi = e / D, dmi = e - qi * D;
+        sQ[qi][dmi] = P.q[(size_t)(q0 + qi) * dm.h + head * D + dmi] * scale;
+    }
+    // this wavefront's queries: wave, wave + 4, ..
+    constexpr int QW = kPfQB / 4;
+    float m_run[QW], l_run[QW], o0[QW], o1[QW];
+#pragma unroll
+    for (int k = 0; k < QW; ++k) { m_run[k] = -INFINITY; l_run[k] = 0.f; o0[k] = 0.f; o1[k] = 0.f; }
+    const int last_pos = P.pos0 + q0 + nq - 1;             // the block's last query attends up to here
+    const __half *Kc = P.kv + kv_offset(dm, 0, P.b, head, 0, 0), *Vc = P.kv + kv_offset(dm, 1, P.b, head, 0, 0);
+    for (int t0 = 0; t0 <= last_pos; t0 += 64) {
+        __syncthreads();                                   // the previous tile is no longer read (first: sQ is written)
+        // 64 positions x D dims of K and V: pieces of 8 halves (one 16-byte load), slab by slab
+        for (int e = tid; e < 64 * (D / 8); e += 256) {
+            const int pc = e / 64, t = e - pc * 64;        // piece pc = dims 8 pc .. 8 pc + 7 of position t0 + t
+            const int tp = min(t0 + t, last_pos);          // (positions past the block's last are never weighted)
+            const size_t off = ((size_t)(pc >> 1) * dm.max_seq + tp) * 16 + (pc & 1) * 8;
+            const u32x4 kk = load16(Kc + off), vv = load16(Vc + off);
+            unsigned *dk = reinterpret_cast<unsigned *>(&sK[t * RS + 8 * pc]);
+            unsigned *dv = reinterpret_cast<unsigned *>(&sV[t * RS + 8 * pc]);
+            dk[0] = kk.x; dk[1] = kk.y; dk[2] = kk.z; dk[3] = kk.w;
+            dv[0] = vv.x; dv[1] = vv.y; dv[2] = vv.z; dv[3] = vv.w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < QW; ++k) {
+            const int qi = wave + 4 * k;
+            const int qpos = P.pos0 + q0 + qi;
+            if (qi < nq && t0 <= qpos) {                   // (uniform)
+                // score of key t0 + lane
+                float sc = 0.f;
+                const unsigned *kr = reinterpret_cast<const unsigned *>(&sK[lane * RS]);
+#pragma unroll 8
+                for (int j = 0; j < D / 2; ++j) {
+                    const float2 kf = unpack_h2(kr[j]);
+                    sc = fmaf(sQ[qi][2 * j], kf.x, sc);
+                    sc = fmaf(sQ[qi][2 * j + 1], kf.y, sc);
+                }
+                const bool valid = t0 + lane <= qpos;
+                sc = valid ? sc : -INFINITY;
+                const float mt = wave_max(sc);             // finite: key t0 itself is valid
+                const float mn = fmaxf(m_run[k], mt);
+                const float corr = m_run[k] == -INFINITY ? 0.f : expf(m_run[k] - mn);
+                const float p = valid ? expf(sc - mn) : 0.f;
+                l_run[k] = l_run[k] * corr + wave_sum(p);
+                sP[wave][lane] = p;
+                float a0 = o0[k] * corr, a1 = o1[k] * corr;
+                const int nkeys = min(64, qpos - t0 + 1);
+                for (int j = 0; j < nkeys; ++j) {
+                    const float pj = sP[wave][j];
+                    a0 = fmaf(pj, __half2float(sV[j * RS + lane]), a0);
+                    if (D > 64) a1 = fmaf(pj, __half2float(sV[j * RS + (lane + 64 < D ? lane + 64 : 0)]), a1);
+                }
+                o0[k] = a0; o1[k] = a1;
+                m_run[k] = mn;
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < QW; ++k) {
+        const int qi = wave + 4 * k;
+        if (qi < nq) {
+            const size_t at = (size_t)(q0 + qi) * dm.h + head * D;
+            __half hi, lo;
+            pf_split(o0[k] / l_run[k], hi, lo);
+            P.oh[at + lane] = hi; P.ol[at + lane] = lo;
+            if (D > 64 && lane + 64 < D) {
+                pf_split(o1[k] / l_run[k], hi, lo);
+                P.oh[at + lane + 64] = hi; P.ol[at + lane + 64] = lo;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+bool pf_supported(const Dims &dm)
+{
+    return dm.h % kPfTile == 0 && dm.f % kPfTile == 0 && dm.h <= 256 * kPfLnPerThread && (dm.d == 64 || dm.d == 80 || dm.d == 128) &&
+           !(dm.flags & kFlagSequentialResidual) && dm.r % 2 == 0;
+}
+
+// splits of K for a product with few tiles: doubled while the parts stay within what the scratch
+// holds (kPfSplitTiles) and whole steps of 32
+static int pf_splits(int tiles, int K)
+{
+    int s = 1;
+    while (s < 8 && tiles * s <= kPfSplitTiles / 2 && K % (2 * s * kPfBK) == 0) s *= 2;   // (tiles * s <= kPfSplitTiles: what the scratch holds)
+    return s;
+}
+
+template <int EPI>
+static void pf_gemm(const PfParams &P, const __half *Ah, const __half *Al, const __half *W, int K, int N, float *part,
+                    hipStream_t s)
+{
+    const int mt = (P.n_rows + kPfTile - 1) / kPfTile, tiles = (N / kPfTile) * mt;
+    const int splits = pf_splits(tiles, K);
+    const int grid = (tiles * splits + 7) / 8 * 8;
+    hipLaunchKernelGGL(k_pf_gemm<EPI>, dim3(grid), dim3(256), 0, s, P, Ah, Al, W, K, N, splits, part);
+    if (splits > 1) {
+        const size_t n_el = (size_t)P.n_rows * (N / 4);
+        hipLaunchKernelGGL(k_pf_reduce<EPI>, dim3((unsigned)((n_el + 255) / 256)), dim3(256), 0, s, P, (const float *)part, N,
+                           splits);
+    }
+}
+
+hipError_t launch_pf_layer(const PfParams &P, hipStream_t s)
+{
+    const Dims &dm = P.dm;
+    const int mt = (P.n_rows + kPfTile - 1) / kPfTile;
+    const __half *w = P.w;
+    hipLaunchKernelGGL(k_pf_ln, dim3(mt * kPfTile), dim3(256), 0, s, P);
+    pf_gemm<kPfQkv>(P, P.y1h, P.y1l, w + P.lay.w_qkv, dm.h, 3 * dm.h, P.part, s);
+    pf_gemm<kPfUp>(P, P.y2h, P.y2l, w + P.lay.w_up, dm.h, dm.f, P.part, s);
+    const dim3 ag(dm.H, (P.n_rows + kPfQB - 1) / kPfQB);
+    switch (dm.d) {
+    case 64: hipLaunchKernelGGL(k_pf_attn<64>, ag, dim3(256), 0, s, P); break;
+    case 80: hipLaunchKernelGGL(k_pf_attn<80>, ag, dim3(256), 0, s, P); break;
+    case 128: hipLaunchKernelGGL(k_pf_attn<128>, ag, dim3(256), 0, s, P); break;
+    default: return hipErrorInvalidValue;
+    }
+    pf_gemm<kPfDense>(P, P.oh, P.ol, w + P.lay.w_dense, dm.h, dm.h, P.part, s);
+    pf_gemm<kPfDown>(P, P.mh, P.ml, w + P.lay.w_down, dm.f, dm.h, P.part, s);
+    return hipGetLastError();
+}
+
+}  // namespace cfpp

@@ -129,6 +129,19 @@ class DeviceStack:
         self.stream.synchronize()
         return od.cpu().numpy()
 
+    def prefill_gemm(self, x: np.ndarray, pos0: int, b: int = 0, rows: int = 128) -> np.ndarray:
+        """As prefill(), through the prompt-sized kernels, `rows` tokens per pass."""
+        xd = torch.from_numpy(np.ascontiguousarray(x)).to(self.dev)
+        od = torch.zeros_like(xd)
+        nbytes = B.cfpp_prefill_scratch_bytes(self.cfg, rows)
+        if nbytes == 0:
+            raise B.CfppError(-1, "cfpp_prefill_scratch_bytes", "invalid configuration or rows")
+        scratch = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+        torch.cuda.synchronize()
+        B.cfpp_stack_prefill_gemm(self.ctx, self.packed, self.kv, xd, pos0, x.shape[0], b, od, scratch, nbytes, rows, self.s)
+        self.stream.synchronize()
+        return od.cpu().numpy()
+
     def capture(self):
         B.cfpp_stack_capture(self.ctx, self.packed, self.kv, self.x, self.pos, self.batch, self.out, self.s)
 

@@ -24,14 +24,14 @@ def _build(shape, seed, pos0, cap, max_batch):
     return ds, ws, kvs
 
 
-def _check_prompt(orc, shape, seed, pos0, T, max_batch, b=0, then_decode=True):
+def _check_prompt(orc, shape, seed, pos0, T, max_batch, b=0, then_decode=True, gemm_rows=0):
     cap = pos0 + T + 2
-    print(f"[case] prefill shape={shape.name} seed={seed} pos0={pos0} T={T} max_batch={max_batch} b={b}", flush=True)
+    print(f"[case] prefill shape={shape.name} seed={seed} pos0={pos0} T={T} max_batch={max_batch} b={b} gemm_rows={gemm_rows}", flush=True)
     ds, ws, kvs = _build(shape, seed, pos0, cap, max_batch)
     try:
         ds.set_options(mode=0)
         X = synth.x_input(shape, seed + 1, batch=T)
-        got = ds.prefill(X, pos0, b)
+        got = ds.prefill_gemm(X, pos0, b, gemm_rows) if gemm_rows else ds.prefill(X, pos0, b)
         ds.check()
         Ks = [kv[0][b].copy() for kv in kvs]
         Vs = [kv[1][b].copy() for kv in kvs]
@@ -85,6 +85,51 @@ def test_prompt_through_the_tiny_stack(orc, pos0, T, max_batch, b):
 def test_prompt_at_the_2_8b_shape(orc):
     shape = synth.ModelShape(2560, 32, 80, 20, 10240, n_layers=2, name="pythia-2.8b-x2")
     _check_prompt(orc, shape, 23, 100, 11, 8)
+
+
+# The same prompts through the prompt-sized kernels (cfpp_stack_prefill_gemm): LayerNorm launch,
+# four GEMMs on the matrix cores and one causal-attention launch per layer and pass.
+@pytest.mark.parametrize("pos0,T,max_batch,b,rows", [
+    (5, 19, 8, 0, 128),       # one pass, most of its tile padding
+    (0, 7, 3, 0, 128),        # from an empty cache
+    (3, 9, 8, 2, 256),        # into the cache of the third sequence
+    (0, 1, 8, 0, 128),        # a single token
+    (2, 150, 2, 1, 128),      # two passes (128 + 22): the second attends over the first one's rows
+    (0, 200, 1, 0, 256),      # several key tiles and query blocks, ragged at both ends
+])
+def test_prompt_through_the_tiny_stack_with_the_gemm_kernels(orc, pos0, T, max_batch, b, rows):
+    _check_prompt(orc, TINY_STACK, 19, pos0, T, max_batch, b, gemm_rows=rows)
+
+
+def test_prompt_at_the_2_8b_shape_with_the_gemm_kernels(orc):
+    shape = synth.ModelShape(2560, 32, 80, 20, 10240, n_layers=2, name="pythia-2.8b-x2")
+    _check_prompt(orc, shape, 29, 60, 70, 1, gemm_rows=128)
+
+
+def test_gemm_prompt_requests_that_are_refused():
+    import torch
+    from paper_2604_23553_amd import CfppError, binding as B
+    ds, ws, kvs = _build(TINY_STACK, 1, 0, 12, 8)
+    try:
+        X = synth.x_input(TINY_STACK, 2, batch=4)
+        assert B.cfpp_prefill_scratch_bytes(ds.cfg, 100) == 0 and B.cfpp_prefill_scratch_bytes(ds.cfg, 8192) == 0
+        with pytest.raises(CfppError) as e:
+            ds.prefill_gemm(X, 9, rows=128)               # positions 9..12 of a cache of 12
+        assert e.value.status == -1
+        need = B.cfpp_prefill_scratch_bytes(ds.cfg, 128)
+        xd = torch.from_numpy(X).to(ds.dev)
+        od = torch.zeros_like(xd)
+        small = torch.empty(need - 256, dtype=torch.uint8, device=ds.dev)
+        with pytest.raises(CfppError) as e:
+            B.cfpp_stack_prefill_gemm(ds.ctx, ds.packed, ds.kv, xd, 0, 4, 0, od, small, need - 256, 128, ds.s)
+        assert e.value.status == -3                       # scratch too small
+        with pytest.raises(CfppError) as e:
+            B.cfpp_stack_prefill_gemm(ds.ctx, ds.packed, ds.kv, xd, 0, 4, 0, od, small, need, 100, ds.s)
+        assert e.value.status == -1                       # rows not a multiple of 128
+        ds.prefill_gemm(X, 8, rows=128)                   # the last four rows fit
+        ds.check()
+    finally:
+        ds.close()
 
 
 def test_prompt_requests_that_are_refused():
