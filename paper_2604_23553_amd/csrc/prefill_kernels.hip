@@ -142,9 +142,10 @@ __device__ __forceinline__ void pf_store(const PfParams &P, int row, int col, fl
 // (v_mfma_f32_32x32x16_f16: a lane supplies 8 consecutive K values of its row),
 // each fed the head and the remainder plane of the activations; consecutive
 // instructions go to different accumulators.
-// Tiles are numbered with the token tiles fastest and dealt so that consecutive
-// numbers run on the same XCD (workgroup i runs on XCD i % 8): the token tiles
-// that share a tile of the weight matrix read it through one L2.
+// Tiles are numbered with the weight tiles fastest and dealt so that consecutive
+// numbers run on the same XCD (workgroup i runs on XCD i % 8): an XCD sweeps the
+// weight tiles against one token tile, whose two planes (1.3 MB at hidden 2560)
+// stay in its L2, instead of every workgroup pulling its token tile across the fabric.
 // splits > 1: workgroup z of a tile takes the z-th part of K and leaves its sums in
 // part[z][row][col] (rows of whole token tiles); k_pf_reduce adds the parts in order and finishes.
 constexpr int kPfBK = 32, kPfStride = 40;
@@ -161,8 +162,9 @@ __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__res
     const int per_xcd = (total + 7) >> 3;
     const int v = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
     if (v >= total) return;                               // (whole workgroup)
-    const int z = v % splits, tile = v / splits;
-    const int m0 = (tile % mt) * kPfTile, n0 = (tile / mt) * kPfTile;
+    const int tiles = total / splits, z = v / tiles, tile = v - z * tiles;
+    const int ntn = N / kPfTile;
+    const int m0 = (tile / ntn) * kPfTile, n0 = (tile % ntn) * kPfTile;
     const int kb = (K / splits) * z, nk = K / splits / kPfBK;
     // global -> LDS: a tile plane is 128 rows x 32 halves = 512 pieces of 16 bytes, two per thread
     const int lrow0 = tid >> 2, lrow1 = lrow0 + 64, lk = (tid & 3) * 8 + kb;

@@ -8,7 +8,7 @@ namespace cfpp {
 
 constexpr int kPfTile = 128;           // rows (tokens) and columns (output features) of a GEMM workgroup tile
 constexpr int kPfMaxRows = 4096;       // most tokens a pass takes
-constexpr int kPfSplitTiles = 384;     // most 128 x 128 parts a split product leaves: K is halved only while the parts number
+constexpr int kPfSplitTiles = 384;      // most 128 x 128 parts a split product leaves: K is halved only while the parts number
                                        // at most half of this, and the scratch holds this many
 
 // Scratch of one pass over `rows` tokens (rows a multiple of kPfTile), byte
