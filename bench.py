@@ -188,10 +188,39 @@ def secondary_configs(ds, layers, x, args):
     lens = synth.seq_lens(seed, 8, 1024, 8192)
     cs = block_copies(s69, lens, int(lens.max()) + 1, 8, 1)
     r = block_times(cs, lens, s69, (-1,), 100)
+    alg5 = cf.cfpp_algorithmic_bytes(cs[0].cfg, [int(v) for v in lens], 1)
     out["cfg5_block_pythia6.9b_batch8"] = {"workload": f"one Pythia-6.9B-shaped block, batch 8, cached positions {[int(v) for v in lens]} "
-                                                       "(1.1 GB per step: cold by construction; 70 % of the roofline = 180 us)",
+                                                       f"({alg5 / 1e9:.2f} GB per step: cold by construction; 70 % of the roofline = "
+                                                       f"{alg5 / (0.7 * HBM_PEAK_GBS * 1e3):.0f} us)",
                                            "by_launch_mode": {k: v["warm"] if "warm" in v else v for k, v in r.items()}}
     cs[0].close()
+    # prompt processing through the prompt-sized kernels: 512 tokens into the (now no longer needed) first
+    # rows of the headline stack's caches, one pass
+    T = 512
+    if T < ds.max_seq:
+        nbytes = cf.cfpp_prefill_scratch_bytes(ds.cfg, T)
+        scratch = torch.empty(nbytes, dtype=torch.uint8, device=ds.dev)
+        xd = torch.from_numpy(synth.x_input(shape, seed, T)).to(ds.dev)
+        od = torch.zeros_like(xd)
+        run = lambda: cf.cfpp_stack_prefill_gemm(ds.ctx, ds.packed, ds.kv, xd, 0, T, 0, od, scratch, nbytes, T, ds.s)
+        for _ in range(2):
+            run()
+        ds.stream.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(ds.stream)
+        for _ in range(5):
+            run()
+        b.record(ds.stream)
+        ds.stream.synchronize()
+        ds.check()
+        us = a.elapsed_time(b) * 1e3 / 5
+        h, f, L = shape.hidden, shape.ffn, shape.n_layers
+        flops = 2.0 * (4 * h * h + 2 * h * f) * T * L + 4.0 * h * L * (T * (T + 1) / 2)
+        out["prefill_pythia2.8b_32L_T512"] = {
+            "workload": "prompt of 512 tokens through the 32-layer stack from position 0, one pass (cfpp_stack_prefill_gemm)",
+            "us": round(us, 1), "tokens_per_s": round(T * 1e6 / us, 1), "useful_TFLOPs": round(flops / us / 1e6, 1),
+            "frac_of_f16_mfma_peak": round(flops / us / 1e6 / 2500.0, 4),
+            "note": "the path through the batched projections (8 tokens per pass): python bench.py --workload prefill --gemm-rows 0"}
     return out
 
 
