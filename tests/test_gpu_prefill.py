@@ -106,6 +106,25 @@ def test_prompt_at_the_2_8b_shape_with_the_gemm_kernels(orc):
     _check_prompt(orc, shape, 29, 60, 70, 1, gemm_rows=128)
 
 
+def test_gemm_prompt_with_head_dim_128_and_tanh_gelu(orc):
+    # the third head size of the attention launch (two dimensions per lane), with the other GELU reading
+    shape = synth.ModelShape(1024, 8, 128, 32, 4096, n_layers=2, flags=synth.FLAG_TANH_GELU, name="neox-h1024-d128-x2")
+    _check_prompt(orc, shape, 31, 7, 90, 1, gemm_rows=128)
+
+
+def test_gemm_prompt_refuses_the_sequential_form():
+    import dataclasses
+    from paper_2604_23553_amd import CfppError
+    shape = dataclasses.replace(TINY_STACK, flags=synth.FLAG_SEQUENTIAL_RESIDUAL)
+    ds, ws, kvs = _build(shape, 1, 0, 12, 1)
+    try:
+        with pytest.raises(CfppError) as e:
+            ds.prefill_gemm(synth.x_input(shape, 2, batch=4), 0, rows=128)
+        assert e.value.status == -2
+    finally:
+        ds.close()
+
+
 def test_gemm_prompt_requests_that_are_refused():
     import torch
     from paper_2604_23553_amd import CfppError, binding as B
