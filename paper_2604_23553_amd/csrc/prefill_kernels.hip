@@ -135,10 +135,12 @@ __device__ __forceinline__ void pf_store(const PfParams &P, int row, int col, fl
 }
 
 // ---------------------------------------------------------------------------
-// GEMM.  Workgroup: 256 threads = 2 x 2 wavefronts, tile 128 tokens x 128 output
-// features, K in steps of 32 through double-buffered LDS (rows 40 halves apart:
-// the 16-byte fragment reads of 16 consecutive rows hit 16 different groups of four
-// banks).  A wavefront owns 64 x 64 of the tile: 2 x 2 instruction tiles of 32 x 32
+// GEMM.  Workgroup: 256 threads = 2 x 2 wavefronts, tile BM tokens x 128 output
+// features (BM 128, or 64 when that is what brings several workgroups onto every
+// CU: while one waits for LDS another multiplies), K in steps of 32 through
+// double-buffered LDS (rows 40 halves apart: the 16-byte fragment reads of 16
+// consecutive rows hit 16 different groups of four banks).  A wavefront owns
+// BM/2 x 64 of the tile: BM/64 x 2 instruction tiles of 32 x 32
 // (v_mfma_f32_32x32x16_f16: a lane supplies 8 consecutive K values of its row),
 // each fed the head and the remainder plane of the activations; consecutive
 // instructions go to different accumulators.
@@ -150,73 +152,83 @@ __device__ __forceinline__ void pf_store(const PfParams &P, int row, int col, fl
 // part[z][row][col] (rows of whole token tiles); k_pf_reduce adds the parts in order and finishes.
 constexpr int kPfBK = 32, kPfStride = 40;
 
-template <int EPI>
+template <int EPI, int BM>
 __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__restrict__ Ah, const __half *__restrict__ Al,
                                                   const __half *__restrict__ W, int K, int N, int splits, float *part)
 {
-    __shared__ __align__(16) __half sA[2][2][kPfTile * kPfStride];
+    constexpr int MT = BM / 64;                            // instruction tiles of a wavefront along the tokens
+    constexpr int NA = BM / 64;                            // 16-byte pieces of an activation plane per thread and step
+    __shared__ __align__(16) __half sA[2][2][BM * kPfStride];
     __shared__ __align__(16) __half sW[2][kPfTile * kPfStride];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int mt = (P.n_rows + kPfTile - 1) / kPfTile, total = (N / kPfTile) * mt * splits;
+    const int mt = (P.n_rows + BM - 1) / BM, total = (N / kPfTile) * mt * splits;
     const int per_xcd = (total + 7) >> 3;
     const int v = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
     if (v >= total) return;                               // (whole workgroup)
     const int tiles = total / splits, z = v / tiles, tile = v - z * tiles;
     const int ntn = N / kPfTile;
-    const int m0 = (tile / ntn) * kPfTile, n0 = (tile % ntn) * kPfTile;
+    const int m0 = (tile / ntn) * BM, n0 = (tile % ntn) * kPfTile;
     const int kb = (K / splits) * z, nk = K / splits / kPfBK;
-    // global -> LDS: a tile plane is 128 rows x 32 halves = 512 pieces of 16 bytes, two per thread
-    const int lrow0 = tid >> 2, lrow1 = lrow0 + 64, lk = (tid & 3) * 8 + kb;
-    const __half *pa_h0 = Ah + (size_t)(m0 + lrow0) * K + lk, *pa_h1 = Ah + (size_t)(m0 + lrow1) * K + lk;
-    const __half *pa_l0 = Al + (size_t)(m0 + lrow0) * K + lk, *pa_l1 = Al + (size_t)(m0 + lrow1) * K + lk;
-    const __half *pw0 = W + (size_t)(n0 + lrow0) * K + lk, *pw1 = W + (size_t)(n0 + lrow1) * K + lk;
-    const int st0 = lrow0 * kPfStride + (tid & 3) * 8, st1 = lrow1 * kPfStride + (tid & 3) * 8;
+    // global -> LDS: a plane of 64 rows x 32 halves is 256 pieces of 16 bytes, one per thread
+    const int lrow = tid >> 2, lk = (tid & 3) * 8;
+    const __half *pa_h = Ah + (size_t)(m0 + lrow) * K + kb + lk, *pa_l = Al + (size_t)(m0 + lrow) * K + kb + lk;
+    const __half *pw = W + (size_t)(n0 + lrow) * K + kb + lk;
+    const size_t rstep = (size_t)64 * K;
+    const int st = lrow * kPfStride + lk;
     // Three register sets hold the tiles of the next three steps while the current one is
     // multiplied out of LDS: a global load has three steps to arrive.  Every step requests,
     // multiplies, writes LDS and meets the others once, without conditions around the loads
     // (steps past the end re-read the last tile and are not multiplied).
-    struct Regs { u32x4 ah0, ah1, al0, al1, w0, w1; } g0, g1, g2;
+    struct Regs { u32x4 ah[NA], al[NA], w[2]; } g0, g1, g2;
     const int nk1 = nk - 1;
     auto fetch = [&](Regs &g, int kt) {
         const int k0 = (kt < nk1 ? kt : nk1) * kPfBK;
-        g.ah0 = load16(pa_h0 + k0); g.ah1 = load16(pa_h1 + k0);
-        g.al0 = load16(pa_l0 + k0); g.al1 = load16(pa_l1 + k0);
-        g.w0 = load16(pw0 + k0); g.w1 = load16(pw1 + k0);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            g.ah[i] = load16(pa_h + i * rstep + k0);
+            g.al[i] = load16(pa_l + i * rstep + k0);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) g.w[i] = load16(pw + i * rstep + k0);
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto put = [&](__half *dst, u32x4 v4) { *reinterpret_cast<u32x4 *>(dst) = v4; };
     auto stash = [&](const Regs &g, int buf) {
-        put(&sA[buf][0][st0], g.ah0); put(&sA[buf][0][st1], g.ah1);
-        put(&sA[buf][1][st0], g.al0); put(&sA[buf][1][st1], g.al1);
-        put(&sW[buf][st0], g.w0); put(&sW[buf][st1], g.w1);
-    };
-    pf_f32x16 acc[2][2];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+        for (int i = 0; i < NA; ++i) {
+            *reinterpret_cast<u32x4 *>(&sA[buf][0][st + i * 64 * kPfStride]) = g.ah[i];
+            *reinterpret_cast<u32x4 *>(&sA[buf][1][st + i * 64 * kPfStride]) = g.al[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4 *>(&sW[buf][st + i * 64 * kPfStride]) = g.w[i];
+    };
+    pf_f32x16 acc[MT][2];
+#pragma unroll
+    for (int a = 0; a < MT; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
     // fragment of this lane: row lane % 32 of an instruction tile, halves 8 * (lane / 32) .. + 7 of a step of 16
     const int fr = lane & 31, fk = (lane >> 5) * 8;
-    const int a_off = (wm * 64 + fr) * kPfStride + fk, w_off = (wn * 64 + fr) * kPfStride + fk;
+    const int a_off = (wm * 32 * MT + fr) * kPfStride + fk, w_off = (wn * 64 + fr) * kPfStride + fk;
     auto multiply = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < kPfBK / 16; ++ks) {
-            pf_f16x8 ah[2], al[2], wf[2];
+            pf_f16x8 ah[MT], al[MT], wf[2];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < MT; ++t) {
                 ah[t] = *reinterpret_cast<const pf_f16x8 *>(&sA[buf][0][a_off + t * 32 * kPfStride + ks * 16]);
                 al[t] = *reinterpret_cast<const pf_f16x8 *>(&sA[buf][1][a_off + t * 32 * kPfStride + ks * 16]);
-                wf[t] = *reinterpret_cast<const pf_f16x8 *>(&sW[buf][w_off + t * 32 * kPfStride + ks * 16]);
             }
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int t = 0; t < 2; ++t) wf[t] = *reinterpret_cast<const pf_f16x8 *>(&sW[buf][w_off + t * 32 * kPfStride + ks * 16]);
+#pragma unroll
+            for (int a = 0; a < MT; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[a], wf[b], acc[a][b], 0, 0, 0);
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < MT; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[a], wf[b], acc[a][b], 0, 0, 0);
         }
@@ -237,12 +249,12 @@ __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__res
     for (int b = 0; b < 2; ++b) {
         const int col = n0 + wn * 64 + b * 32 + (lane & 31);
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < MT; ++a)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int row = m0 + wm * 64 + a * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                const int row = m0 + wm * 32 * MT + a * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
                 if (splits > 1) {
-                    part[((size_t)z * mt * kPfTile + row) * N + col] = acc[a][b][e];
+                    part[((size_t)z * mt * BM + row) * N + col] = acc[a][b][e];
                 } else {
                     const bool live = row < P.n_rows;
                     const float val = pf_complete<EPI>(P, live ? row : 0, col, acc[a][b][e]);
@@ -253,14 +265,14 @@ __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__res
     }
 }
 
-// the parts of a split-K product, added in order, then what follows the product; a thread
-// takes four consecutive columns of a row (two rotation pairs)
+// the parts of a split-K product (part rows: prows per part), added in order, then what
+// follows the product; a thread takes four consecutive columns of a row (two rotation pairs)
 template <int EPI>
-__global__ void __launch_bounds__(256) k_pf_reduce(PfParams P, const float *__restrict__ part, int N, int splits)
+__global__ void __launch_bounds__(256) k_pf_reduce(PfParams P, const float *__restrict__ part, int N, int splits, int prows)
 {
-    const int mt = (P.n_rows + kPfTile - 1) / kPfTile, n4 = N >> 2;
+    const int n4 = N >> 2;
     const unsigned n_el = (unsigned)P.n_rows * (unsigned)n4;
-    const size_t zstride = (size_t)mt * kPfTile * N;
+    const size_t zstride = (size_t)prows * N;
     for (unsigned e = blockIdx.x * 256u + threadIdx.x; e < n_el; e += gridDim.x * 256u) {
         const int row = (int)(e / (unsigned)n4), col = (int)(e - (unsigned)row * (unsigned)n4) * 4;
         const float *p = part + (size_t)row * N + col;
@@ -377,27 +389,38 @@ bool pf_supported(const Dims &dm)
            !(dm.flags & kFlagSequentialResidual) && dm.r % 2 == 0;
 }
 
-// splits of K for a product with few tiles: doubled while the parts stay within what the scratch
-// holds (kPfSplitTiles) and whole steps of 32
-static int pf_splits(int tiles, int K)
+// Tile height and splits of K for a product: 64-token tiles while 128-token ones would leave
+// fewer than two workgroups per CU; K halved while the tile parts stay within half of what the
+// scratch holds (kPfSplitTiles, in 128 x 128 parts) and whole steps of 32.
+struct PfPlan { int bm, splits; };
+static PfPlan pf_plan(int n_rows, int N, int K)
 {
-    int s = 1;
-    while (s < 8 && tiles * s <= kPfSplitTiles / 2 && K % (2 * s * kPfBK) == 0) s *= 2;   // (tiles * s <= kPfSplitTiles: what the scratch holds)
-    return s;
+    PfPlan p;
+    const int ntn = N / kPfTile;
+    p.bm = ntn * ((n_rows + 127) / 128) < 512 ? 64 : 128;
+    const int tiles = ntn * ((n_rows + p.bm - 1) / p.bm);
+    const int parts128 = p.bm == 64 ? (tiles + 1) / 2 : tiles;         // what a part costs in the scratch
+    p.splits = 1;
+    while (p.splits < 8 && tiles * p.splits <= 256 && parts128 * p.splits <= kPfSplitTiles / 2 && K % (2 * p.splits * kPfBK) == 0)
+        p.splits *= 2;
+    return p;
 }
 
 template <int EPI>
 static void pf_gemm(const PfParams &P, const __half *Ah, const __half *Al, const __half *W, int K, int N, float *part,
                     hipStream_t s)
 {
-    const int mt = (P.n_rows + kPfTile - 1) / kPfTile, tiles = (N / kPfTile) * mt;
-    const int splits = pf_splits(tiles, K);
-    const int grid = (tiles * splits + 7) / 8 * 8;
-    hipLaunchKernelGGL(k_pf_gemm<EPI>, dim3(grid), dim3(256), 0, s, P, Ah, Al, W, K, N, splits, part);
-    if (splits > 1) {
+    const PfPlan pl = pf_plan(P.n_rows, N, K);
+    const int mt = (P.n_rows + pl.bm - 1) / pl.bm, tiles = (N / kPfTile) * mt;
+    const int grid = (tiles * pl.splits + 7) / 8 * 8;
+    if (pl.bm == 64)
+        hipLaunchKernelGGL((k_pf_gemm<EPI, 64>), dim3(grid), dim3(256), 0, s, P, Ah, Al, W, K, N, pl.splits, part);
+    else
+        hipLaunchKernelGGL((k_pf_gemm<EPI, 128>), dim3(grid), dim3(256), 0, s, P, Ah, Al, W, K, N, pl.splits, part);
+    if (pl.splits > 1) {
         const size_t n_el = (size_t)P.n_rows * (N / 4);
         hipLaunchKernelGGL(k_pf_reduce<EPI>, dim3((unsigned)((n_el + 255) / 256)), dim3(256), 0, s, P, (const float *)part, N,
-                           splits);
+                           pl.splits, mt * pl.bm);
     }
 }
 
