@@ -14,8 +14,9 @@
 //                 the epilogue completes the LayerNorm from the packing's row
 //                 constants (QKV, MLP-up) and does what follows the product:
 //                 rotary + cache append + q | GELU -> planes | residual sums
-//   k_pf_attn<> : causal attention of a block of queries of one head over the
-//                 cache, keys in LDS tiles of 64 positions, online softmax
+//   k_pf_attn<> : causal attention of a block of 16 queries of one head over the cache,
+//                 keys in LDS tiles of 64 positions, both products on the matrix
+//                 cores (v_mfma_f32_16x16x16_f16), online softmax in fp32
 //
 // Every sum has a fixed order: one bit pattern per build and pass size.
 #include <hip/hip_runtime.h>
@@ -287,98 +288,162 @@ __global__ void __launch_bounds__(256) k_pf_reduce(PfParams P, const float *__re
 }
 
 // ---------------------------------------------------------------------------
-// Causal attention of kPfQB consecutive queries of one head: grid (H, blocks of
-// queries).  Keys and values of 64 positions at a time in LDS (rows D + 2 halves
-// apart: an odd number of words, so the lanes' row reads spread over the banks);
-// a wavefront takes its queries one after the other: lane = key for the scores,
-// lane = dimension (lane, lane + 64) for the weighted sum; online softmax in fp32.
+// Causal attention of kPfQB = 16 consecutive queries of one head: grid (H, blocks of
+// queries), 4 wavefronts, on the matrix cores (v_mfma_f32_16x16x16_f16).  Keys and
+// values of 64 positions at a time in LDS; wavefront w takes the tile's keys
+// 16 w .. 16 w + 15:
+//   S^T = K Q^T  (keys x queries): the instruction's result layout - a lane holds 4
+//         consecutive keys of query lane % 16 - is at once the layout of the first
+//         operand of the next product, so the weights never leave the registers;
+//   O_w += P V   (queries x dimensions), P = exp(S - m) with the running maximum m of
+//         the online softmax exchanged between the wavefronts through LDS once per
+//         tile; V sits in LDS transposed ([dimension][key]) for that.
+// q and P are fp32 values and enter as fp16 head + remainder (two instructions each),
+// K and V are the cache's fp16; sums in fp32.  The wavefronts' partial outputs and
+// partial softmax sums are added in wavefront order at the end.
 constexpr int kPfQB = 16;
+typedef _Float16 pf_f16x4 __attribute__((ext_vector_type(4)));
+
+// maximum / sum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (the 16-lane rows of the wavefront)
+__device__ __forceinline__ float pf_rows_max(float v)
+{
+    const unsigned u = __float_as_uint(v);
+    const auto p = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    v = fmaxf(__uint_as_float(p[0]), __uint_as_float(p[1]));
+    const unsigned u2 = __float_as_uint(v);
+    const auto q = __builtin_amdgcn_permlane32_swap(u2, u2, false, false);
+    return fmaxf(__uint_as_float(q[0]), __uint_as_float(q[1]));
+}
+__device__ __forceinline__ float pf_rows_sum(float v)
+{
+    const unsigned u = __float_as_uint(v);
+    const auto p = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    v = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+    const unsigned u2 = __float_as_uint(v);
+    const auto q = __builtin_amdgcn_permlane32_swap(u2, u2, false, false);
+    return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
 
 template <int D>
 __global__ void __launch_bounds__(256) k_pf_attn(PfParams P)
 {
-    constexpr int RS = D + 2;                              // halves per LDS row
-    __shared__ __align__(16) __half sK[64 * RS];
-    __shared__ __align__(16) __half sV[64 * RS];
-    __shared__ float sQ[kPfQB][D];
-    __shared__ float sP[4][64];
+    constexpr int QS = D + 4;                              // halves per row of q and K in LDS (8-byte fragment reads, spread over the banks)
+    constexpr int VS = 64 + 4;                             // halves per row of V transposed
+    constexpr int NB = D / 16;                             // 16-dimension blocks
+    __shared__ __align__(16) __half sQh[kPfQB * QS], sQl[kPfQB * QS];
+    constexpr int KVH = 64 * QS + D * VS;                  // halves of a tile of K and V
+    static_assert(KVH * 2 >= 4 * kPfQB * D * 4 && (64 * QS) % 8 == 0, "the wavefronts' outputs reuse the tile's memory");
+    __shared__ __align__(16) __half sKV[KVH];
+    __shared__ float sMax[4][kPfQB], sCorr[4][kPfQB], sL[4][kPfQB];
+    __half *sK = sKV, *sVt = sKV + 64 * QS;
+    float (*sO)[kPfQB][D] = reinterpret_cast<float (*)[kPfQB][D]>(sKV);      // after the last tile
     const Dims &dm = P.dm;
     const int head = blockIdx.x, q0 = blockIdx.y * kPfQB, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (q0 >= P.n_rows) return;
     const int nq = min(kPfQB, P.n_rows - q0);
     const float scale = 1.0f / sqrtf((float)D);
-    for (int e = tid; e < nq * D; e += 256) {
+    for (int e = tid; e < kPfQB * D; e += 256) {
         const int qi = e / D, dmi = e - qi * D;
-        sQ[qi][dmi] = P.q[(size_t)(q0 + qi) * dm.h + head * D + dmi] * scale;
+        const float v = qi < nq ? P.q[(size_t)(q0 + qi) * dm.h + head * D + dmi] * scale : 0.f;
+        __half hi, lo;
+        pf_split(v, hi, lo);
+        sQh[qi * QS + dmi] = hi; sQl[qi * QS + dmi] = lo;
     }
-    // this wavefront's queries: wave, wave + 4, ..
-    constexpr int QW = kPfQB / 4;
-    float m_run[QW], l_run[QW], o0[QW], o1[QW];
+    const int col = lane & 15, grp = lane >> 4;            // column of a result tile, group of 4 rows / 4 K values
+    const int qpos = P.pos0 + q0 + col;                    // position of the query this lane's S^T column belongs to
+    const bool qlive = col < nq;
+    float m_run = -INFINITY, l_part = 0.f;                 // running maximum (all wavefronts alike), this wavefront's sum
+    f32x4 O[NB];
 #pragma unroll
-    for (int k = 0; k < QW; ++k) { m_run[k] = -INFINITY; l_run[k] = 0.f; o0[k] = 0.f; o1[k] = 0.f; }
+    for (int nb = 0; nb < NB; ++nb) O[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int last_pos = P.pos0 + q0 + nq - 1;             // the block's last query attends up to here
     const __half *Kc = P.kv + kv_offset(dm, 0, P.b, head, 0, 0), *Vc = P.kv + kv_offset(dm, 1, P.b, head, 0, 0);
     for (int t0 = 0; t0 <= last_pos; t0 += 64) {
-        __syncthreads();                                   // the previous tile is no longer read (first: sQ is written)
+        __syncthreads();                                   // the previous tile is no longer read (first: q is written)
         // 64 positions x D dims of K and V: pieces of 8 halves (one 16-byte load), slab by slab
         for (int e = tid; e < 64 * (D / 8); e += 256) {
             const int pc = e / 64, t = e - pc * 64;        // piece pc = dims 8 pc .. 8 pc + 7 of position t0 + t
-            const int tp = min(t0 + t, last_pos);          // (positions past the block's last are never weighted)
+            const int tp = min(t0 + t, last_pos);          // (positions past the block's last are masked below)
             const size_t off = ((size_t)(pc >> 1) * dm.max_seq + tp) * 16 + (pc & 1) * 8;
             const u32x4 kk = load16(Kc + off), vv = load16(Vc + off);
-            unsigned *dk = reinterpret_cast<unsigned *>(&sK[t * RS + 8 * pc]);
-            unsigned *dv = reinterpret_cast<unsigned *>(&sV[t * RS + 8 * pc]);
+            unsigned *dk = reinterpret_cast<unsigned *>(&sK[t * QS + 8 * pc]);
             dk[0] = kk.x; dk[1] = kk.y; dk[2] = kk.z; dk[3] = kk.w;
-            dv[0] = vv.x; dv[1] = vv.y; dv[2] = vv.z; dv[3] = vv.w;
+            const __half *vh = reinterpret_cast<const __half *>(&vv);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sVt[(8 * pc + j) * VS + t] = vh[j];
         }
         __syncthreads();
+        // S^T of this wavefront's 16 keys: rows = keys 16 wave + 4 grp + v, column = query col
+        f32x4 st = {0.f, 0.f, 0.f, 0.f};
+        const __half *ka = &sK[(16 * wave + col) * QS + 4 * grp];
+        const __half *qh = &sQh[col * QS + 4 * grp], *ql = &sQl[col * QS + 4 * grp];
 #pragma unroll
-        for (int k = 0; k < QW; ++k) {
-            const int qi = wave + 4 * k;
-            const int qpos = P.pos0 + q0 + qi;
-            if (qi < nq && t0 <= qpos) {                   // (uniform)
-                // score of key t0 + lane
-                float sc = 0.f;
-                const unsigned *kr = reinterpret_cast<const unsigned *>(&sK[lane * RS]);
-#pragma unroll 8
-                for (int j = 0; j < D / 2; ++j) {
-                    const float2 kf = unpack_h2(kr[j]);
-                    sc = fmaf(sQ[qi][2 * j], kf.x, sc);
-                    sc = fmaf(sQ[qi][2 * j + 1], kf.y, sc);
-                }
-                const bool valid = t0 + lane <= qpos;
-                sc = valid ? sc : -INFINITY;
-                const float mt = wave_max(sc);             // finite: key t0 itself is valid
-                const float mn = fmaxf(m_run[k], mt);
-                const float corr = m_run[k] == -INFINITY ? 0.f : expf(m_run[k] - mn);
-                const float p = valid ? expf(sc - mn) : 0.f;
-                l_run[k] = l_run[k] * corr + wave_sum(p);
-                sP[wave][lane] = p;
-                float a0 = o0[k] * corr, a1 = o1[k] * corr;
-                const int nkeys = min(64, qpos - t0 + 1);
-                for (int j = 0; j < nkeys; ++j) {
-                    const float pj = sP[wave][j];
-                    a0 = fmaf(pj, __half2float(sV[j * RS + lane]), a0);
-                    if (D > 64) a1 = fmaf(pj, __half2float(sV[j * RS + (lane + 64 < D ? lane + 64 : 0)]), a1);
-                }
-                o0[k] = a0; o1[k] = a1;
-                m_run[k] = mn;
-            }
+        for (int ks = 0; ks < NB; ++ks) {
+            const pf_f16x4 kf = *reinterpret_cast<const pf_f16x4 *>(ka + 16 * ks);
+            st = __builtin_amdgcn_mfma_f32_16x16x16f16(kf, *reinterpret_cast<const pf_f16x4 *>(qh + 16 * ks), st, 0, 0, 0);
+            st = __builtin_amdgcn_mfma_f32_16x16x16f16(kf, *reinterpret_cast<const pf_f16x4 *>(ql + 16 * ks), st, 0, 0, 0);
+        }
+        const int key0 = t0 + 16 * wave + 4 * grp;
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            st[v] = qlive && key0 + v <= qpos ? st[v] : -INFINITY;
+            mloc = fmaxf(mloc, st[v]);
+        }
+        mloc = pf_rows_max(mloc);                          // over this wavefront's 16 keys, for query col
+        if (lane < 16) sMax[wave][lane] = mloc;
+        __syncthreads();
+        const float mt = fmaxf(fmaxf(sMax[0][col], sMax[1][col]), fmaxf(sMax[2][col], sMax[3][col]));
+        const float mn = fmaxf(m_run, mt);
+        const float corr = m_run == -INFINITY ? 0.f : expf(m_run - mn);     // (mn finite whenever m_run is)
+        float p[4], psum = 0.f;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            p[v] = st[v] == -INFINITY ? 0.f : expf(st[v] - mn);
+            psum += p[v];
+        }
+        l_part = l_part * corr + pf_rows_sum(psum);
+        m_run = mn;
+        if (lane < 16) sCorr[wave][lane] = corr;           // (read below by this wavefront only: no barrier)
+        pf_f16x4 ph, pl;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const _Float16 h = (_Float16)p[v];
+            ph[v] = h;
+            pl[v] = (_Float16)(p[v] - (float)h);
+        }
+        // O rows = queries 4 grp + v, column = dimension 16 nb + col: rescale, then add P V of this wavefront's keys
+        float cr[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) cr[v] = sCorr[wave][4 * grp + v];
+        const __half *vb = &sVt[col * VS + 16 * wave + 4 * grp];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            f32x4 o = O[nb];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[v] *= cr[v];
+            const pf_f16x4 vf = *reinterpret_cast<const pf_f16x4 *>(vb + 16 * nb * VS);
+            o = __builtin_amdgcn_mfma_f32_16x16x16f16(ph, vf, o, 0, 0, 0);
+            o = __builtin_amdgcn_mfma_f32_16x16x16f16(pl, vf, o, 0, 0, 0);
+            O[nb] = o;
         }
     }
+    // the wavefronts' parts, added in wavefront order
+    __syncthreads();                                       // (the last tile is no longer read)
 #pragma unroll
-    for (int k = 0; k < QW; ++k) {
-        const int qi = wave + 4 * k;
-        if (qi < nq) {
-            const size_t at = (size_t)(q0 + qi) * dm.h + head * D;
-            __half hi, lo;
-            pf_split(o0[k] / l_run[k], hi, lo);
-            P.oh[at + lane] = hi; P.ol[at + lane] = lo;
-            if (D > 64 && lane + 64 < D) {
-                pf_split(o1[k] / l_run[k], hi, lo);
-                P.oh[at + lane + 64] = hi; P.ol[at + lane + 64] = lo;
-            }
-        }
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sO[wave][4 * grp + v][16 * nb + col] = O[nb][v];
+    if (lane < 16) sL[wave][lane] = l_part;
+    __syncthreads();
+    for (int e = tid; e < nq * D; e += 256) {
+        const int qi = e / D, dmi = e - qi * D;
+        const float l = ((sL[0][qi] + sL[1][qi]) + sL[2][qi]) + sL[3][qi];
+        const float o = ((sO[0][qi][dmi] + sO[1][qi][dmi]) + sO[2][qi][dmi]) + sO[3][qi][dmi];
+        __half hi, lo;
+        pf_split(o / l, hi, lo);
+        const size_t at = (size_t)(q0 + qi) * dm.h + head * D + dmi;
+        P.oh[at] = hi; P.ol[at] = lo;
     }
 }
 
