@@ -35,6 +35,11 @@ __device__ __forceinline__ void pf_split(float v, __half &hi, __half &lo)
     lo = __float2half_rn(v - __half2float(hi));
 }
 
+__device__ __forceinline__ unsigned pf_pack2(float a, float b)
+{
+    return (unsigned)__half_as_ushort(__float2half_rn(a)) | (unsigned)__half_as_ushort(__float2half_rn(b)) << 16;
+}
+
 // ---------------------------------------------------------------------------
 // One workgroup of 256 threads per scratch row.  Rows past the pass's tokens get
 // zero planes (their products are never stored).
@@ -137,30 +142,44 @@ __device__ __forceinline__ void pf_store(const PfParams &P, int row, int col, fl
 
 // ---------------------------------------------------------------------------
 // GEMM.  Workgroup: 256 threads = 2 x 2 wavefronts, tile BM tokens x 128 output
-// features (BM 128, or 64 when that is what brings several workgroups onto every
-// CU: while one waits for LDS another multiplies), K in steps of 32 through
-// double-buffered LDS (rows 40 halves apart: the 16-byte fragment reads of 16
-// consecutive rows hit 16 different groups of four banks).  A wavefront owns
-// BM/2 x 64 of the tile: BM/64 x 2 instruction tiles of 32 x 32
-// (v_mfma_f32_32x32x16_f16: a lane supplies 8 consecutive K values of its row),
-// each fed the head and the remainder plane of the activations; consecutive
-// instructions go to different accumulators.
-// Tiles are numbered with the weight tiles fastest and dealt so that consecutive
-// numbers run on the same XCD (workgroup i runs on XCD i % 8): an XCD sweeps the
-// weight tiles against one token tile, whose two planes (1.3 MB at hidden 2560)
-// stay in its L2, instead of every workgroup pulling its token tile across the fabric.
+// features, K in steps of BK through double-buffered LDS.  BM 128 with BK 32, or - when
+// that is what brings several workgroups onto every CU: while one waits for LDS another
+// multiplies - BM 64 with BK 64 (whole 128-byte lines per row and step).  Rows sit
+// BK + 8 halves apart: the 16-byte fragment reads of 16 consecutive rows hit 16
+// different groups of four banks.  A wavefront owns BM/2 x 64 of the tile: BM/64 x 2
+// instruction tiles of 32 x 32 (v_mfma_f32_32x32x16_f16: a lane supplies 8
+// consecutive K values of its row), each fed the head and the remainder plane of the
+// activations; consecutive instructions go to different accumulators.
+// Tiles are dealt so that consecutive numbers run on the same XCD (workgroup i runs on
+// XCD i % 8).  An unsplit product numbers the token tiles fastest: the workgroups of an
+// XCD that run together share a few weight tiles, and each XCD reads its part of the
+// weights once; a split one numbers the weight tiles fastest (measured, a few percent each).
 // splits > 1: workgroup z of a tile takes the z-th part of K and leaves its sums in
 // part[z][row][col] (rows of whole token tiles); k_pf_reduce adds the parts in order and finishes.
-constexpr int kPfBK = 32, kPfStride = 40;
+// Otherwise the tile goes through LDS once more (fp32, completed LayerNorm, rotated
+// pairs), and what follows the product is stored from there in whole 16-byte pieces
+// along the destination's own order: the instruction's output layout would scatter
+// 2- and 4-byte pieces, which cost a quarter of the kernel.
+constexpr int kPfEpiStride = kPfTile + 8;                  // floats between rows of the staged tile: rows 4 apart sit 32 banks apart
 
-template <int EPI, int BM>
+template <int BM, int BK>
+constexpr int pf_gemm_lds_bytes()
+{
+    constexpr int steps = (4 * BM + 2 * kPfTile) * (BK + 8) * 2, staged = BM * kPfEpiStride * 4;
+    return steps > staged ? steps : staged;
+}
+
+template <int EPI, int BM, int BK>
 __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__restrict__ Ah, const __half *__restrict__ Al,
                                                   const __half *__restrict__ W, int K, int N, int splits, float *part)
 {
+    constexpr int kPfStride = BK + 8;                      // halves between rows in LDS
+    constexpr int PR = BK / 8, RP = 256 / PR;              // 16-byte pieces of a row; rows the 256 threads cover at once
     constexpr int MT = BM / 64;                            // instruction tiles of a wavefront along the tokens
-    constexpr int NA = BM / 64;                            // 16-byte pieces of an activation plane per thread and step
-    __shared__ __align__(16) __half sA[2][2][BM * kPfStride];
-    __shared__ __align__(16) __half sW[2][kPfTile * kPfStride];
+    constexpr int NA = BM / RP, NW = kPfTile / RP;         // 16-byte pieces per thread and step: of an activation plane, of the weights
+    extern __shared__ __align__(16) __half pf_lds[];       // [buffer][head, remainder][BM][stride], then [buffer][128][stride]
+    __half (*sA)[2][BM * kPfStride] = reinterpret_cast<__half (*)[2][BM * kPfStride]>(pf_lds);
+    __half (*sW)[kPfTile * kPfStride] = reinterpret_cast<__half (*)[kPfTile * kPfStride]>(pf_lds + 4 * BM * kPfStride);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int mt = (P.n_rows + BM - 1) / BM, total = (N / kPfTile) * mt * splits;
@@ -169,39 +188,39 @@ __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__res
     if (v >= total) return;                               // (whole workgroup)
     const int tiles = total / splits, z = v / tiles, tile = v - z * tiles;
     const int ntn = N / kPfTile;
-    const int m0 = (tile / ntn) * BM, n0 = (tile % ntn) * kPfTile;
-    const int kb = (K / splits) * z, nk = K / splits / kPfBK;
-    // global -> LDS: a plane of 64 rows x 32 halves is 256 pieces of 16 bytes, one per thread
-    const int lrow = tid >> 2, lk = (tid & 3) * 8;
+    const int m0 = (splits > 1 ? tile / ntn : tile % mt) * BM, n0 = (splits > 1 ? tile % ntn : tile / mt) * kPfTile;
+    const int kb = (K / splits) * z, nk = K / splits / BK;
+    // global -> LDS: RP rows x BK halves are 256 pieces of 16 bytes, one per thread
+    const int lrow = tid / PR, lk = (tid % PR) * 8;
     const __half *pa_h = Ah + (size_t)(m0 + lrow) * K + kb + lk, *pa_l = Al + (size_t)(m0 + lrow) * K + kb + lk;
     const __half *pw = W + (size_t)(n0 + lrow) * K + kb + lk;
-    const size_t rstep = (size_t)64 * K;
+    const size_t rstep = (size_t)RP * K;
     const int st = lrow * kPfStride + lk;
     // Three register sets hold the tiles of the next three steps while the current one is
     // multiplied out of LDS: a global load has three steps to arrive.  Every step requests,
     // multiplies, writes LDS and meets the others once, without conditions around the loads
     // (steps past the end re-read the last tile and are not multiplied).
-    struct Regs { u32x4 ah[NA], al[NA], w[2]; } g0, g1, g2;
+    struct Regs { u32x4 ah[NA], al[NA], w[NW]; } g0, g1, g2;
     const int nk1 = nk - 1;
     auto fetch = [&](Regs &g, int kt) {
-        const int k0 = (kt < nk1 ? kt : nk1) * kPfBK;
+        const int k0 = (kt < nk1 ? kt : nk1) * BK;
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             g.ah[i] = load16(pa_h + i * rstep + k0);
             g.al[i] = load16(pa_l + i * rstep + k0);
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) g.w[i] = load16(pw + i * rstep + k0);
+        for (int i = 0; i < NW; ++i) g.w[i] = load16(pw + i * rstep + k0);
         __builtin_amdgcn_sched_barrier(0);
     };
     auto stash = [&](const Regs &g, int buf) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            *reinterpret_cast<u32x4 *>(&sA[buf][0][st + i * 64 * kPfStride]) = g.ah[i];
-            *reinterpret_cast<u32x4 *>(&sA[buf][1][st + i * 64 * kPfStride]) = g.al[i];
+            *reinterpret_cast<u32x4 *>(&sA[buf][0][st + i * RP * kPfStride]) = g.ah[i];
+            *reinterpret_cast<u32x4 *>(&sA[buf][1][st + i * RP * kPfStride]) = g.al[i];
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4 *>(&sW[buf][st + i * 64 * kPfStride]) = g.w[i];
+        for (int i = 0; i < NW; ++i) *reinterpret_cast<u32x4 *>(&sW[buf][st + i * RP * kPfStride]) = g.w[i];
     };
     pf_f32x16 acc[MT][2];
 #pragma unroll
@@ -215,7 +234,7 @@ __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__res
     const int a_off = (wm * 32 * MT + fr) * kPfStride + fk, w_off = (wn * 64 + fr) * kPfStride + fk;
     auto multiply = [&](int buf) {
 #pragma unroll
-        for (int ks = 0; ks < kPfBK / 16; ++ks) {
+        for (int ks = 0; ks < BK / 16; ++ks) {
             pf_f16x8 ah[MT], al[MT], wf[2];
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
@@ -246,23 +265,136 @@ __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__res
         fetch(g2, kt + 5); if (kt + 2 < nk) multiply(b0); stash(g0, b1); __syncthreads();
     }
     // this lane holds, per instruction tile, column lane % 32 and rows 8 (e / 4) + 4 (lane / 32) + e % 4
+    const Dims &dm = P.dm;
+    if (splits > 1) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int col = n0 + wn * 64 + b * 32 + (lane & 31);
+#pragma unroll
+            for (int a = 0; a < MT; ++a)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wm * 32 * MT + a * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                    part[((size_t)z * mt * BM + row) * N + col] = acc[a][b][e];
+                }
+        }
+        return;
+    }
+    __syncthreads();                                       // the last step's fragments have been read: the memory is free
+    float *T = reinterpret_cast<float *>(pf_lds);          // [BM][kPfEpiStride]: the finished sums, columns in the packed order
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-        const int col = n0 + wn * 64 + b * 32 + (lane & 31);
+        const int cl = wn * 64 + b * 32 + (lane & 31), col = n0 + cl;
+        int ri = -1;                                       // QKV: index of this column inside the rotated part of its head's q or k, else -1
+        if (EPI == kPfQkv) {
+            const int pd = col / dm.d, i = col - pd * dm.d;
+            if (pd % 3 < 2 && i < dm.r) ri = i;
+        }
 #pragma unroll
         for (int a = 0; a < MT; ++a)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int row = m0 + wm * 32 * MT + a * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                if (splits > 1) {
-                    part[((size_t)z * mt * BM + row) * N + col] = acc[a][b][e];
+                const int rl = wm * 32 * MT + a * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                const int row = m0 + rl < P.n_rows ? m0 + rl : 0;           // (rows past the pass's tokens are never stored)
+                float val = pf_complete<EPI>(P, row, col, acc[a][b][e]);
+                if (EPI == kPfQkv) {
+                    const float other = dpp_mov<kDppXor1>(val);             // (all lanes: the neighbouring lane holds col ^ 1)
+                    if (ri >= 0) {
+                        const float2 cs = P.rope[(size_t)(P.pos0 + row) * (dm.r >> 1) + (ri >> 1)];
+                        val = ri & 1 ? val * cs.x + other * cs.y : val * cs.x - other * cs.y;
+                    }
+                }
+                T[rl * kPfEpiStride + cl] = val;
+            }
+    }
+    __syncthreads();
+    const int h = dm.h;
+    if (EPI == kPfQkv) {
+        // Work item: 8 consecutive dimensions of one token's q, k or v of one head.  Rotated dimension j
+        // of a head comes from packed column 2 j (first half) or 2 (j - r/2) + 1.  q: dimensions fastest
+        // (a row of q is contiguous); k, v: the two halves of a slab row, then tokens (the cache keeps
+        // 32 bytes per token and slab, tokens one after the other).  A head cut by the tile's edge is
+        // finished element by element, by this workgroup and its neighbour.
+        const int d = dm.d, r = dm.r, G = d >> 3;
+        const int pd_lo = n0 / d, pd_hi = (n0 + kPfTile - 1) / d, per_chunk = G * BM;
+        const int n_items = (pd_hi - pd_lo + 1) * per_chunk;
+        for (int it = tid; it < n_items; it += 256) {
+            const int ch = it / per_chunk, wi = it - ch * per_chunk, pd = pd_lo + ch, nh = pd / 3, c = pd - 3 * nh;
+            int rl, g;
+            if (c == 0) { rl = wi / G; g = wi - rl * G; }
+            else { const int slab = wi / (2 * BM), rem = wi - slab * 2 * BM; rl = rem >> 1; g = 2 * slab + (rem & 1); }
+            const int row = m0 + rl;
+            if (row >= P.n_rows || nh >= dm.H) continue;
+            float v[8];
+            unsigned in = 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int dd = 8 * g + j;
+                const int i = c < 2 && dd < r ? (dd < (r >> 1) ? 2 * dd : 2 * (dd - (r >> 1)) + 1) : dd;
+                const int cl = pd * d + i - n0;
+                const bool here = (unsigned)cl < (unsigned)kPfTile;
+                v[j] = here ? T[rl * kPfEpiStride + cl] : 0.f;
+                in |= (here ? 1u : 0u) << j;
+            }
+            if (c == 0) {
+                float *dst = P.q + (size_t)row * h + nh * d + 8 * g;
+                if (in == 0xffu) {
+                    *reinterpret_cast<f32x4 *>(dst) = f32x4{v[0], v[1], v[2], v[3]};
+                    *reinterpret_cast<f32x4 *>(dst + 4) = f32x4{v[4], v[5], v[6], v[7]};
                 } else {
-                    const bool live = row < P.n_rows;
-                    const float val = pf_complete<EPI>(P, live ? row : 0, col, acc[a][b][e]);
-                    const float other = EPI == kPfQkv ? dpp_mov<kDppXor1>(val) : 0.f;   // (all lanes: the neighbouring lane holds col ^ 1)
-                    if (live) pf_store<EPI>(P, row, col, val, other);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (in >> j & 1) dst[j] = v[j];
+                }
+            } else {
+                __half *dst = P.kv + kv_offset(dm, c - 1, P.b, nh, 8 * g, P.pos0 + row);
+                if (in == 0xffu) {
+                    u32x4 o;
+                    o.x = pf_pack2(v[0], v[1]); o.y = pf_pack2(v[2], v[3]); o.z = pf_pack2(v[4], v[5]); o.w = pf_pack2(v[6], v[7]);
+                    *reinterpret_cast<u32x4 *>(dst) = o;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (in >> j & 1) dst[j] = __float2half_rn(v[j]);
                 }
             }
+        }
+    } else if (EPI == kPfUp) {
+        for (int it = tid; it < BM * 16; it += 256) {      // 8 columns of a token: one 16-byte piece of each plane
+            const int rl = it >> 4, cg = (it & 15) * 8, row = m0 + rl;
+            if (row >= P.n_rows) continue;
+            const float *t = T + rl * kPfEpiStride + cg;
+            const f32x4 v0 = *reinterpret_cast<const f32x4 *>(t), v1 = *reinterpret_cast<const f32x4 *>(t + 4);
+            __half hi[8], lo[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                pf_split(gelu_act(v0[j], dm.flags), hi[j], lo[j]);
+                pf_split(gelu_act(v1[j], dm.flags), hi[4 + j], lo[4 + j]);
+            }
+            const size_t at = (size_t)row * dm.f + n0 + cg;
+            *reinterpret_cast<u32x4 *>(P.mh + at) = *reinterpret_cast<const u32x4 *>(hi);
+            *reinterpret_cast<u32x4 *>(P.ml + at) = *reinterpret_cast<const u32x4 *>(lo);
+        }
+    } else {
+        const __half *bias = P.w + (EPI == kPfDense ? P.lay.b_dense : P.lay.b_down);
+        const bool last = EPI == kPfDown && P.layer == P.n_layers - 1;
+        const float *res_in = EPI == kPfDense ? P.xres : P.xnext;
+        for (int it = tid; it < BM * 32; it += 256) {      // 4 columns of a token
+            const int rl = it >> 5, c4 = (it & 31) * 4, row = m0 + rl;
+            if (row >= P.n_rows) continue;
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(T + rl * kPfEpiStride + c4);
+            const size_t at = (size_t)row * h + n0 + c4;
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(res_in + at);
+            f32x4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j] = x[j] + (v[j] + __half2float(bias[n0 + c4 + j]));
+            if (last) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) P.out[at + j] = __float2half_rn(o[j]);
+            } else {
+                *reinterpret_cast<f32x4 *>(P.xnext + at) = o;
+            }
+        }
     }
 }
 
@@ -465,28 +597,37 @@ static PfPlan pf_plan(int n_rows, int N, int K)
     p.bm = ntn * ((n_rows + 127) / 128) < 512 ? 64 : 128;
     const int tiles = ntn * ((n_rows + p.bm - 1) / p.bm);
     const int parts128 = p.bm == 64 ? (tiles + 1) / 2 : tiles;         // what a part costs in the scratch
+    const int bk = p.bm == 64 ? 64 : 32;                              // (the kernel's K step for that height)
     p.splits = 1;
-    while (p.splits < 8 && tiles * p.splits <= 256 && parts128 * p.splits <= kPfSplitTiles / 2 && K % (2 * p.splits * kPfBK) == 0)
+    while (p.splits < 8 && tiles * p.splits <= 256 && parts128 * p.splits <= kPfSplitTiles / 2 && K % (2 * p.splits * bk) == 0)
         p.splits *= 2;
     return p;
 }
 
 template <int EPI>
-static void pf_gemm(const PfParams &P, const __half *Ah, const __half *Al, const __half *W, int K, int N, float *part,
+static hipError_t pf_gemm(const PfParams &P, const __half *Ah, const __half *Al, const __half *W, int K, int N, float *part,
                     hipStream_t s)
 {
     const PfPlan pl = pf_plan(P.n_rows, N, K);
     const int mt = (P.n_rows + pl.bm - 1) / pl.bm, tiles = (N / kPfTile) * mt;
     const int grid = (tiles * pl.splits + 7) / 8 * 8;
-    if (pl.bm == 64)
-        hipLaunchKernelGGL((k_pf_gemm<EPI, 64>), dim3(grid), dim3(256), 0, s, P, Ah, Al, W, K, N, pl.splits, part);
-    else
-        hipLaunchKernelGGL((k_pf_gemm<EPI, 128>), dim3(grid), dim3(256), 0, s, P, Ah, Al, W, K, N, pl.splits, part);
+    if (pl.bm == 64) {
+        constexpr int lds = pf_gemm_lds_bytes<64, 64>();
+        const hipError_t e = hipFuncSetAttribute((const void *)k_pf_gemm<EPI, 64, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((k_pf_gemm<EPI, 64, 64>), dim3(grid), dim3(256), lds, s, P, Ah, Al, W, K, N, pl.splits, part);
+    } else {
+        constexpr int lds = pf_gemm_lds_bytes<128, 32>();
+        const hipError_t e = hipFuncSetAttribute((const void *)k_pf_gemm<EPI, 128, 32>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((k_pf_gemm<EPI, 128, 32>), dim3(grid), dim3(256), lds, s, P, Ah, Al, W, K, N, pl.splits, part);
+    }
     if (pl.splits > 1) {
         const size_t n_el = (size_t)P.n_rows * (N / 4);
         hipLaunchKernelGGL(k_pf_reduce<EPI>, dim3((unsigned)((n_el + 255) / 256)), dim3(256), 0, s, P, (const float *)part, N,
                            pl.splits, mt * pl.bm);
     }
+    return hipSuccess;
 }
 
 hipError_t launch_pf_layer(const PfParams &P, hipStream_t s)
@@ -495,8 +636,10 @@ hipError_t launch_pf_layer(const PfParams &P, hipStream_t s)
     const int mt = (P.n_rows + kPfTile - 1) / kPfTile;
     const __half *w = P.w;
     hipLaunchKernelGGL(k_pf_ln, dim3(mt * kPfTile), dim3(256), 0, s, P);
-    pf_gemm<kPfQkv>(P, P.y1h, P.y1l, w + P.lay.w_qkv, dm.h, 3 * dm.h, P.part, s);
-    pf_gemm<kPfUp>(P, P.y2h, P.y2l, w + P.lay.w_up, dm.h, dm.f, P.part, s);
+    hipError_t e = pf_gemm<kPfQkv>(P, P.y1h, P.y1l, w + P.lay.w_qkv, dm.h, 3 * dm.h, P.part, s);
+    if (e != hipSuccess) return e;
+    e = pf_gemm<kPfUp>(P, P.y2h, P.y2l, w + P.lay.w_up, dm.h, dm.f, P.part, s);
+    if (e != hipSuccess) return e;
     const dim3 ag(dm.H, (P.n_rows + kPfQB - 1) / kPfQB);
     switch (dm.d) {
     case 64: hipLaunchKernelGGL(k_pf_attn<64>, ag, dim3(256), 0, s, P); break;
@@ -504,8 +647,10 @@ hipError_t launch_pf_layer(const PfParams &P, hipStream_t s)
     case 128: hipLaunchKernelGGL(k_pf_attn<128>, ag, dim3(256), 0, s, P); break;
     default: return hipErrorInvalidValue;
     }
-    pf_gemm<kPfDense>(P, P.oh, P.ol, w + P.lay.w_dense, dm.h, dm.h, P.part, s);
-    pf_gemm<kPfDown>(P, P.mh, P.ml, w + P.lay.w_down, dm.f, dm.h, P.part, s);
+    e = pf_gemm<kPfDense>(P, P.oh, P.ol, w + P.lay.w_dense, dm.h, dm.h, P.part, s);
+    if (e != hipSuccess) return e;
+    e = pf_gemm<kPfDown>(P, P.mh, P.ml, w + P.lay.w_down, dm.f, dm.h, P.part, s);
+    if (e != hipSuccess) return e;
     return hipGetLastError();
 }
 
