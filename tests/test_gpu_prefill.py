@@ -24,7 +24,7 @@ def _build(shape, seed, pos0, cap, max_batch):
     return ds, ws, kvs
 
 
-def _check_prompt(orc, shape, seed, pos0, T, max_batch, b=0, then_decode=True, gemm_rows=0):
+def _check_prompt(orc, shape, seed, pos0, T, max_batch, b=0, then_decode=True, gemm_rows=0, row_check_every=1):
     cap = pos0 + T + 2
     print(f"[case] prefill shape={shape.name} seed={seed} pos0={pos0} T={T} max_batch={max_batch} b={b} gemm_rows={gemm_rows}", flush=True)
     ds, ws, kvs = _build(shape, seed, pos0, cap, max_batch)
@@ -44,7 +44,7 @@ def _check_prompt(orc, shape, seed, pos0, T, max_batch, b=0, then_decode=True, g
             if l == 0:
                 # the first layer reads each token's own input row, the same bits on both sides: its
                 # rows must be correct roundings of the oracle's unrounded values
-                for t in range(T):
+                for t in range(0, T, row_check_every):
                     _, taps = orc.block_decode(shape, ws[0], kvs[0][0][b].copy(), kvs[0][1][b].copy(), pos0 + t,
                                                orc.half_to_real(X[t]), taps=True)
                     assert_appended_rows(kg[:, pos0 + t], vg[:, pos0 + t], shape, ws[0], orc.half_to_real(X[t]), taps,
@@ -110,6 +110,24 @@ def test_gemm_prompt_with_head_dim_128_and_tanh_gelu(orc):
     # the third head size of the attention launch (two dimensions per lane), with the other GELU reading
     shape = synth.ModelShape(1024, 8, 128, 32, 4096, n_layers=2, flags=synth.FLAG_TANH_GELU, name="neox-h1024-d128-x2")
     _check_prompt(orc, shape, 31, 7, 90, 1, gemm_rows=128)
+
+
+# The cases above are small enough that every product splits K (few tiles) and the parts meet in
+# k_pf_reduce.  These two are long enough for the other ways through the GEMM: products that are
+# not split and finish out of LDS, with 64-token tiles (600 tokens: QKV and up) and with 128-token
+# tiles (2200 tokens: QKV and up; dense and down unsplit with 64-token tiles), at a head size that
+# does not divide the 128-column tile (heads cut by tile edges) and a rotated part that is not a
+# multiple of 8 dimensions.  Layer-0 rows are held to the rounding bound for every 7th token.
+
+
+def test_gemm_prompt_long_enough_for_unsplit_products(orc):
+    shape = synth.ModelShape(1280, 16, 80, 20, 5120, n_layers=1, name="neox-h1280-x1")
+    _check_prompt(orc, shape, 37, 9, 600, 1, gemm_rows=640, row_check_every=7)
+
+
+def test_gemm_prompt_long_enough_for_128_token_tiles(orc):
+    shape = synth.ModelShape(1280, 16, 80, 20, 5120, n_layers=2, name="neox-h1280-x2")
+    _check_prompt(orc, shape, 41, 0, 2200, 1, gemm_rows=2304, row_check_every=7)
 
 
 def test_gemm_prompt_refuses_the_sequential_form():
