@@ -588,7 +588,7 @@ bool pf_supported(const Dims &dm)
 
 // Tile height and splits of K for a product: 64-token tiles while 128-token ones would leave
 // fewer than two workgroups per CU; K halved while the tile parts stay within half of what the
-// scratch holds (kPfSplitTiles, in 128 x 128 parts) and whole steps of 32.
+// scratch holds (kPfSplitTiles, in 128 x 128 parts) and every part is whole K steps of the kernel.
 struct PfPlan { int bm, splits; };
 static PfPlan pf_plan(int n_rows, int N, int K)
 {
