@@ -579,6 +579,144 @@ __global__ void __launch_bounds__(256) k_pf_attn(PfParams P)
     }
 }
 
+// The same attention for long passes: 64 consecutive queries per workgroup, 16 per wavefront,
+// every wavefront over all 64 keys of a tile.  A tile of K and V is then fetched once per 64
+// queries instead of once per 16 (at 4096 tokens the narrow kernel pulls 10 GB per layer out of
+// the L2), a wavefront's softmax is its own (no exchange between wavefronts), its q stays in
+// registers as instruction operands, and a wavefront skips the tiles behind its last query.
+// Blocks of later queries (more tiles) are started first.
+constexpr int kPfQW = 64;
+#ifndef PF_WIDE_FROM
+#define PF_WIDE_FROM 1024
+#endif
+constexpr int kPfWideFrom = PF_WIDE_FROM;             // tokens in a pass from which the wide kernel runs
+
+template <int D>
+__global__ void __launch_bounds__(256) k_pf_attn_wide(PfParams P)
+{
+    constexpr int QS = D + 4, VS = 64 + 4, NB = D / 16;
+    __shared__ __align__(16) __half sK[64 * QS];
+    __shared__ __align__(16) __half sVt[D * VS];
+    __shared__ float sX[4][16];                            // a per-query value from the lanes of the score layout to those of the output layout
+    const Dims &dm = P.dm;
+    const int head = blockIdx.x, q0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * kPfQW;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (q0 >= P.n_rows) return;
+    const int nq = min(kPfQW, P.n_rows - q0);
+    const float scale = 1.0f / sqrtf((float)D);
+    const int col = lane & 15, grp = lane >> 4;
+    const int qw0 = q0 + 16 * wave, qi = qw0 + col;        // this wavefront's first query, this lane's query in the score layout
+    const bool qlive = qi < P.n_rows;
+    const int qpos = P.pos0 + qi;
+    const int wave_last = qw0 < P.n_rows ? P.pos0 + min(qw0 + 15, P.n_rows - 1) : -1;
+    pf_f16x4 qh[NB], ql[NB];                               // Q^T fragments: dimensions 16 ks + 4 grp .. + 3 of query col
+#pragma unroll
+    for (int ks = 0; ks < NB; ++ks)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float v = qlive ? P.q[(size_t)qi * dm.h + head * D + 16 * ks + 4 * grp + j] * scale : 0.f;
+            const _Float16 hi = (_Float16)v;
+            qh[ks][j] = hi;
+            ql[ks][j] = (_Float16)(v - (float)hi);
+        }
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x4 O[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) O[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int last_pos = P.pos0 + q0 + nq - 1;
+    const __half *Kc = P.kv + kv_offset(dm, 0, P.b, head, 0, 0), *Vc = P.kv + kv_offset(dm, 1, P.b, head, 0, 0);
+    for (int t0 = 0; t0 <= last_pos; t0 += 64) {
+        __syncthreads();                                   // the previous tile is no longer read
+        for (int e = tid; e < 64 * (D / 8); e += 256) {
+            const int pc = e / 64, t = e - pc * 64;        // piece pc = dims 8 pc .. 8 pc + 7 of position t0 + t
+            const int tp = min(t0 + t, last_pos);          // (positions past the block's last are masked below)
+            const size_t off = ((size_t)(pc >> 1) * dm.max_seq + tp) * 16 + (pc & 1) * 8;
+            const u32x4 kk = load16(Kc + off), vv = load16(Vc + off);
+            unsigned *dk = reinterpret_cast<unsigned *>(&sK[t * QS + 8 * pc]);
+            dk[0] = kk.x; dk[1] = kk.y; dk[2] = kk.z; dk[3] = kk.w;
+            const __half *vh = reinterpret_cast<const __half *>(&vv);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sVt[(8 * pc + j) * VS + t] = vh[j];
+        }
+        __syncthreads();
+        if (t0 > wave_last) continue;                      // (whole wavefront; the barriers are above)
+        // S^T of the tile's four key blocks: rows = keys 16 kb + 4 grp + v, column = query col
+        f32x4 st[4];
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+            f32x4 a = {0.f, 0.f, 0.f, 0.f};
+            const __half *ka = &sK[(16 * kb + col) * QS + 4 * grp];
+#pragma unroll
+            for (int ks = 0; ks < NB; ++ks) {
+                const pf_f16x4 kf = *reinterpret_cast<const pf_f16x4 *>(ka + 16 * ks);
+                a = __builtin_amdgcn_mfma_f32_16x16x16f16(kf, qh[ks], a, 0, 0, 0);
+                a = __builtin_amdgcn_mfma_f32_16x16x16f16(kf, ql[ks], a, 0, 0, 0);
+            }
+            const int key0 = t0 + 16 * kb + 4 * grp;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                a[v] = qlive && key0 + v <= qpos ? a[v] : -INFINITY;
+                mloc = fmaxf(mloc, a[v]);
+            }
+            st[kb] = a;
+        }
+        mloc = pf_rows_max(mloc);                          // over the tile's 64 keys, for query col
+        const float mn = fmaxf(m_run, mloc);
+        const float corr = m_run == -INFINITY ? 0.f : expf(m_run - mn);
+        float psum = 0.f;
+        pf_f16x4 ph[4], pl[4];
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float pv = st[kb][v] == -INFINITY ? 0.f : expf(st[kb][v] - mn);
+                psum += pv;
+                const _Float16 hi = (_Float16)pv;
+                ph[kb][v] = hi;
+                pl[kb][v] = (_Float16)(pv - (float)hi);
+            }
+        l_run = l_run * corr + pf_rows_sum(psum);
+        m_run = mn;
+        if (lane < 16) sX[wave][lane] = corr;              // (written and read by this wavefront only: no barrier)
+        float cr[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) cr[v] = sX[wave][4 * grp + v];
+        // O rows = queries 4 grp + v, column = dimension 16 nb + col
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            f32x4 o = O[nb];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[v] *= cr[v];
+            const __half *vb = &sVt[(16 * nb + col) * VS + 4 * grp];
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+                const pf_f16x4 vf = *reinterpret_cast<const pf_f16x4 *>(vb + 16 * kb);
+                o = __builtin_amdgcn_mfma_f32_16x16x16f16(ph[kb], vf, o, 0, 0, 0);
+                o = __builtin_amdgcn_mfma_f32_16x16x16f16(pl[kb], vf, o, 0, 0, 0);
+            }
+            O[nb] = o;
+        }
+    }
+    if (lane < 16) sX[wave][lane] = l_run;
+    float lr[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) lr[v] = sX[wave][4 * grp + v];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int qo = qw0 + 4 * grp + v;
+        if (qo < P.n_rows) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                __half hi, lo;
+                pf_split(O[nb][v] / lr[v], hi, lo);
+                const size_t at = (size_t)qo * dm.h + head * D + 16 * nb + col;
+                P.oh[at] = hi; P.ol[at] = lo;
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 bool pf_supported(const Dims &dm)
 {
@@ -640,12 +778,22 @@ hipError_t launch_pf_layer(const PfParams &P, hipStream_t s)
     if (e != hipSuccess) return e;
     e = pf_gemm<kPfUp>(P, P.y2h, P.y2l, w + P.lay.w_up, dm.h, dm.f, P.part, s);
     if (e != hipSuccess) return e;
-    const dim3 ag(dm.H, (P.n_rows + kPfQB - 1) / kPfQB);
-    switch (dm.d) {
-    case 64: hipLaunchKernelGGL(k_pf_attn<64>, ag, dim3(256), 0, s, P); break;
-    case 80: hipLaunchKernelGGL(k_pf_attn<80>, ag, dim3(256), 0, s, P); break;
-    case 128: hipLaunchKernelGGL(k_pf_attn<128>, ag, dim3(256), 0, s, P); break;
-    default: return hipErrorInvalidValue;
+    if (P.n_rows >= kPfWideFrom) {
+        const dim3 ag(dm.H, (P.n_rows + kPfQW - 1) / kPfQW);
+        switch (dm.d) {
+        case 64: hipLaunchKernelGGL(k_pf_attn_wide<64>, ag, dim3(256), 0, s, P); break;
+        case 80: hipLaunchKernelGGL(k_pf_attn_wide<80>, ag, dim3(256), 0, s, P); break;
+        case 128: hipLaunchKernelGGL(k_pf_attn_wide<128>, ag, dim3(256), 0, s, P); break;
+        default: return hipErrorInvalidValue;
+        }
+    } else {
+        const dim3 ag(dm.H, (P.n_rows + kPfQB - 1) / kPfQB);
+        switch (dm.d) {
+        case 64: hipLaunchKernelGGL(k_pf_attn<64>, ag, dim3(256), 0, s, P); break;
+        case 80: hipLaunchKernelGGL(k_pf_attn<80>, ag, dim3(256), 0, s, P); break;
+        case 128: hipLaunchKernelGGL(k_pf_attn<128>, ag, dim3(256), 0, s, P); break;
+        default: return hipErrorInvalidValue;
+        }
     }
     e = pf_gemm<kPfDense>(P, P.oh, P.ol, w + P.lay.w_dense, dm.h, dm.h, P.part, s);
     if (e != hipSuccess) return e;

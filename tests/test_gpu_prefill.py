@@ -130,6 +130,19 @@ def test_gemm_prompt_long_enough_for_128_token_tiles(orc):
     _check_prompt(orc, shape, 41, 0, 2200, 1, gemm_rows=2304, row_check_every=7)
 
 
+# From 1024 tokens in a pass the attention launch is the 64-query kernel (16 queries per wavefront,
+# every wavefront over all keys of a tile); the 2200-token case above runs it at head size 80,
+# these two at 64 and 128, with a pass that ends inside a query block and inside a key tile.
+def test_gemm_prompt_wide_attention_head_dim_64(orc):
+    shape = synth.ModelShape(512, 8, 64, 16, 2048, n_layers=2, name="neox-h512-x2")
+    _check_prompt(orc, shape, 43, 3, 1100, 1, gemm_rows=1152, row_check_every=7)
+
+
+def test_gemm_prompt_wide_attention_head_dim_128(orc):
+    shape = synth.ModelShape(1024, 8, 128, 32, 4096, n_layers=1, flags=synth.FLAG_TANH_GELU, name="neox-h1024-d128-x1")
+    _check_prompt(orc, shape, 47, 0, 1030, 1, gemm_rows=1152, row_check_every=7)
+
+
 def test_gemm_prompt_refuses_the_sequential_form():
     import dataclasses
     from paper_2604_23553_amd import CfppError
