@@ -456,6 +456,43 @@ __device__ __forceinline__ float pf_rows_sum(float v)
     return __uint_as_float(q[0]) + __uint_as_float(q[1]);
 }
 
+// A tile of 64 cache positions x D dimensions of K and V on its way into LDS: pieces of 8 halves
+// (one 16-byte load, slab by slab) held in registers from the request, one tile ahead of the
+// arithmetic, to the store - K as rows [position][dimension], V transposed [dimension][position].
+// Positions past `last_pos` repeat that row (the callers mask them).
+template <int D>
+struct PfKvTile {
+    static constexpr int kPieces = 64 * (D / 8), kPer = (kPieces + 255) / 256;
+    u32x4 k[kPer], v[kPer];
+    __device__ __forceinline__ void request(const __half *Kc, const __half *Vc, int t0, int last_pos, int max_seq, int tid)
+    {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int e = min(tid + 256 * i, kPieces - 1);
+            const int pc = e / 64, t = e - pc * 64;        // piece pc = dims 8 pc .. 8 pc + 7 of position t0 + t
+            const int tp = min(t0 + t, last_pos);
+            const size_t off = ((size_t)(pc >> 1) * max_seq + tp) * 16 + (pc & 1) * 8;
+            k[i] = load16(Kc + off);
+            v[i] = load16(Vc + off);
+        }
+    }
+    __device__ __forceinline__ void store(__half *sK, __half *sVt, int QS, int VS, int tid) const
+    {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int e = tid + 256 * i;
+            if (e < kPieces) {
+                const int pc = e / 64, t = e - pc * 64;
+                unsigned *dk = reinterpret_cast<unsigned *>(&sK[t * QS + 8 * pc]);
+                dk[0] = k[i].x; dk[1] = k[i].y; dk[2] = k[i].z; dk[3] = k[i].w;
+                const __half *vh = reinterpret_cast<const __half *>(&v[i]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) sVt[(8 * pc + j) * VS + t] = vh[j];
+            }
+        }
+    }
+};
+
 template <int D>
 __global__ void __launch_bounds__(256) k_pf_attn(PfParams P)
 {
@@ -490,20 +527,12 @@ __global__ void __launch_bounds__(256) k_pf_attn(PfParams P)
     for (int nb = 0; nb < NB; ++nb) O[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int last_pos = P.pos0 + q0 + nq - 1;             // the block's last query attends up to here
     const __half *Kc = P.kv + kv_offset(dm, 0, P.b, head, 0, 0), *Vc = P.kv + kv_offset(dm, 1, P.b, head, 0, 0);
+    PfKvTile<D> tile;
+    tile.request(Kc, Vc, 0, last_pos, dm.max_seq, tid);
     for (int t0 = 0; t0 <= last_pos; t0 += 64) {
         __syncthreads();                                   // the previous tile is no longer read (first: q is written)
-        // 64 positions x D dims of K and V: pieces of 8 halves (one 16-byte load), slab by slab
-        for (int e = tid; e < 64 * (D / 8); e += 256) {
-            const int pc = e / 64, t = e - pc * 64;        // piece pc = dims 8 pc .. 8 pc + 7 of position t0 + t
-            const int tp = min(t0 + t, last_pos);          // (positions past the block's last are masked below)
-            const size_t off = ((size_t)(pc >> 1) * dm.max_seq + tp) * 16 + (pc & 1) * 8;
-            const u32x4 kk = load16(Kc + off), vv = load16(Vc + off);
-            unsigned *dk = reinterpret_cast<unsigned *>(&sK[t * QS + 8 * pc]);
-            dk[0] = kk.x; dk[1] = kk.y; dk[2] = kk.z; dk[3] = kk.w;
-            const __half *vh = reinterpret_cast<const __half *>(&vv);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) sVt[(8 * pc + j) * VS + t] = vh[j];
-        }
+        tile.store(sK, sVt, QS, VS, tid);
+        tile.request(Kc, Vc, t0 + 64, last_pos, dm.max_seq, tid);   // the next tile travels while this one is worked on
         __syncthreads();
         // S^T of this wavefront's 16 keys: rows = keys 16 wave + 4 grp + v, column = query col
         f32x4 st = {0.f, 0.f, 0.f, 0.f};
@@ -625,19 +654,12 @@ __global__ void __launch_bounds__(256) k_pf_attn_wide(PfParams P)
     for (int nb = 0; nb < NB; ++nb) O[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int last_pos = P.pos0 + q0 + nq - 1;
     const __half *Kc = P.kv + kv_offset(dm, 0, P.b, head, 0, 0), *Vc = P.kv + kv_offset(dm, 1, P.b, head, 0, 0);
+    PfKvTile<D> tile;
+    tile.request(Kc, Vc, 0, last_pos, dm.max_seq, tid);
     for (int t0 = 0; t0 <= last_pos; t0 += 64) {
         __syncthreads();                                   // the previous tile is no longer read
-        for (int e = tid; e < 64 * (D / 8); e += 256) {
-            const int pc = e / 64, t = e - pc * 64;        // piece pc = dims 8 pc .. 8 pc + 7 of position t0 + t
-            const int tp = min(t0 + t, last_pos);          // (positions past the block's last are masked below)
-            const size_t off = ((size_t)(pc >> 1) * dm.max_seq + tp) * 16 + (pc & 1) * 8;
-            const u32x4 kk = load16(Kc + off), vv = load16(Vc + off);
-            unsigned *dk = reinterpret_cast<unsigned *>(&sK[t * QS + 8 * pc]);
-            dk[0] = kk.x; dk[1] = kk.y; dk[2] = kk.z; dk[3] = kk.w;
-            const __half *vh = reinterpret_cast<const __half *>(&vv);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) sVt[(8 * pc + j) * VS + t] = vh[j];
-        }
+        tile.store(sK, sVt, QS, VS, tid);
+        tile.request(Kc, Vc, t0 + 64, last_pos, dm.max_seq, tid);   // the next tile travels while this one is worked on
         __syncthreads();
         if (t0 > wave_last) continue;                      // (whole wavefront; the barriers are above)
         // S^T of the tile's four key blocks: rows = keys 16 kb + 4 grp + v, column = query col
