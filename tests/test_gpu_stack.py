@@ -259,6 +259,35 @@ def test_full_pythia_2_8b_stack_graph_and_argmax(orc):
             ref16, _, _, _ = oracle_stack(orc, shape, ws, kvs, S2, x[0])
             ma, rl = assert_block_close(outs[0], ref16, f"32-layer output at {S2} cached positions")
             print(f"[result] S {S2}: max-abs {ma:.4e} rel-L2 {rl:.4e}", flush=True)
+        # The prompt-sized kernels on the same resident stack, in the configuration the benchmark
+        # times: 512 tokens from position 0 in one pass (64-token tiles, QKV and up unsplit, dense
+        # and down split over K).  The oracle takes one decode step per token, so the whole prompt is
+        # out of its reach at this depth; what it can compute one by one is checked against it -
+        # token 0 through all 32 layers (it attends to itself only) and the layer-0 cache rows of
+        # sampled tokens (they depend on the token's own input only) - and the last token's output
+        # is held against the decode path, which the cases above tie to the oracle: a decode step at
+        # position 511 over the rows the prompt left must agree with the prompt's own row 511.
+        print("[case] full 2.8B stack: prompt of 512 tokens through the prompt-sized kernels", flush=True)
+        T = 512
+        X = synth.x_input(shape, synth.MASTER_SEED + 5, batch=T)
+        ds.set_options(mode=0)
+        got = ds.prefill_gemm(X, 0, 0, T)
+        ds.check()
+        ref0, _, _, _ = oracle_stack(orc, shape, ws, kvs, 0, X[0])
+        ma, rl = assert_block_close(got[0], ref0, "prompt token 0 through 32 layers")
+        print(f"[result] prompt token 0: max-abs {ma:.4e} rel-L2 {rl:.4e}", flush=True)
+        kg, vg = ds.export_kv(0, 0, 0, T)
+        for t in (0, 1, 63, 64, 255, 300, 511):
+            _, taps = orc.block_decode(shape, ws[0], kvs[0][0][0].copy(), kvs[0][1][0].copy(), t, orc.half_to_real(X[t]),
+                                       taps=True)
+            assert_appended_rows(kg[:, t], vg[:, t], shape, ws[0], orc.half_to_real(X[t]), taps, f"prompt token {t} layer 0")
+        assert np.isfinite(got.astype(np.float32)).all()
+        ds.set_options(mode=2)
+        ds.set_inputs(X[T - 1:T], T - 1)
+        ds.stack_decode()
+        ds.check()
+        ma, rl = assert_block_close(got[T - 1], ds.result()[0], "prompt row 511 against a decode step over the prompt's rows")
+        print(f"[result] prompt row 511 vs decode step: max-abs {ma:.4e} rel-L2 {rl:.4e}", flush=True)
     finally:
         ds.close()
 
