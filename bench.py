@@ -171,18 +171,29 @@ def secondary_configs(ds, layers, x, args):
         c.close()
     # config 4: the 32-layer 6.9B-shaped stack, 2048 cached positions (weights from the device generator)
     s69 = synth.PYTHIA_6_9B
-    d4 = DeviceStack(s69, 2049, 1)
+    d4 = DeviceStack(s69, 4097, 1)
     for l in range(s69.n_layers):
         d4.load_layer_device(l, sdev.layer_tensors(s69, seed, l, d4.dev))
         sdev.fill_kv(d4.kv[l], seed, l)
     d4.set_options(mode=args.mode, grid=args.grid, threads=args.threads)
-    d4.set_inputs(synth.x_input(s69, seed), 2048)
+    x69 = synth.x_input(s69, seed)
+    d4.set_inputs(x69, 2048)
     d4.capture()
     us = time_replays([d4.ctx], d4.stream, 30, 6)
     d4.check()
     out["cfg4_stack_pythia6.9b_32L_s2048"] = entry(us, cf.cfpp_algorithmic_bytes(d4.cfg, [2048], s69.n_layers),
                                                    workload="32-layer Pythia-6.9B-shaped decode step, 2048 cached positions, batch 1, one graph replay",
                                                    launch_mode=MODE_NAMES[args.mode], tokens_per_s=round(1e6 / us, 1))
+    # the same resident stack over the paper's context sweep (Sec. 3 and appendix: 16 -> 2048 positions), and 4096
+    sweep69 = {}
+    for S in (16, 128, 512, 1024, 2048, 4096):
+        d4.set_inputs(x69, S)
+        d4.capture()
+        us = time_replays([d4.ctx], d4.stream, 20, 4)
+        d4.check()
+        sweep69[str(S)] = entry(us, cf.cfpp_algorithmic_bytes(d4.cfg, [S], s69.n_layers))
+    out["context_sweep_pythia6.9b_32L"] = {"unit": "us per token", "launch_mode": MODE_NAMES[args.mode], "by_cached_positions": sweep69,
+                                           "note": "weights and cache from the device generator (synth/device.py)"}
     d4.close()
     # config 5: one 6.9B-shaped block, 8 sequences with cached lengths drawn from [1024, 8192]
     lens = synth.seq_lens(seed, 8, 1024, 8192)

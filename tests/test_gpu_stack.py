@@ -333,6 +333,18 @@ def test_full_pythia_6_9b_stack(orc):
             kg, vg = ds.export_kv(last, 0, S, 1)
             assert_drifted_rows_close(kg[:, 0], Ks[last][:, S], "last layer appended K")
             assert_drifted_rows_close(vg[:, 0], Vs[last][:, S], "last layer appended V")
+        # the same resident stack at short contexts of the paper's sweep (Sec. 3 and appendix), whole-stack
+        # kernel; longest first, so that no run reads a row an earlier one appended
+        ds.set_options(mode=2)
+        for S2 in (512, 16):
+            print(f"[case] full 6.9B stack: {S2} cached positions", flush=True)
+            ds.set_inputs(x, S2)
+            ds.stack_decode()
+            ds.check()
+            out = ds.result()[0].copy()
+            ref16, _, _, _ = oracle_stack(orc, shape, ws, kvs, S2, x[0])
+            ma, rl = assert_block_close(out, ref16, f"32-layer 6.9B output at {S2} cached positions")
+            print(f"[result] S {S2}: max-abs {ma:.4e} rel-L2 {rl:.4e}", flush=True)
     finally:
         ds.close()
 
