@@ -99,6 +99,57 @@ def test_generation_graph_matches_oracle_over_64_steps(orc, mode):
         ds.close()
 
 
+def test_prompt_through_the_gemm_kernels_then_generation(orc):
+    """The whole flow from an empty cache: the prompt's embedding rows through the prompt-sized
+    kernels (cfpp_stack_prefill_gemm), then the generation graph from the prompt's last token on;
+    the oracle does the same with its token-by-token prompt loop and follows the GPU's tokens."""
+    S, steps, seed = 45, 24, 4711
+    cap = S + steps + 1
+    print(f"[case] prompt of {S} tokens, then {steps} generated", flush=True)
+    layers = synth.stack_weights(SHAPE, seed)
+    kv = [synth.kv_cache(SHAPE, seed, l, 0, cap) for l in range(SHAPE.n_layers)]
+    head = synth.lm_head(SHAPE, seed, vocab=VOCAB)
+    embed = synth.embedding(SHAPE, seed, vocab=VOCAB)
+    tokens = [int(t) for t in np.random.default_rng(seed).integers(0, VOCAB, S + 1)]
+    ds = _device(cap, layers, kv, head, embed, 0, 2)
+    try:
+        X = np.ascontiguousarray(embed[tokens[:S]])        # the tokens at positions 0 .. S-1
+        got_prompt = ds.prefill_gemm(X, 0, 0, 128)
+        ds.check()
+        ds.set_tokens(tokens, S)                           # the loop starts with token S at position S
+        ds.generate_capture()
+        hidden = []
+        for _ in range(steps):
+            ds.replay()
+            ds.stream.synchronize()
+            hidden.append(ds.out[0].cpu().numpy().copy())
+        ds.check()
+        got = ds.tokens.cpu().numpy()
+        assert int(ds.pos[0].item()) == S + steps and list(got[: S + 1]) == tokens
+        Ks = [k[0][0].copy() for k in kv]
+        Vs = [k[1][0].copy() for k in kv]
+        want_prompt, _ = orc.prefill(SHAPE, layers, Ks, Vs, 0, X)
+        for t in range(S):
+            assert_block_close(got_prompt[t], want_prompt[t], f"prompt token {t}")
+        ties = 0
+        for i in range(steps):
+            pos = S + i
+            h16, _ = orc.stack_decode(SHAPE, layers, Ks, Vs, pos, np.ascontiguousarray(embed[got[pos]]))
+            tok, lg = orc.next_token(SHAPE, head, h16)
+            assert_block_close(hidden[i], h16, f"hidden state of step {i}")
+            err = float(np.abs(orc.lm_head_logits(SHAPE, head, orc.half_to_real(hidden[i])) - lg).max())
+            top = np.argsort(lg)[-2:]
+            g = int(got[pos + 1])
+            if float(lg[top[1]] - lg[top[0]]) > 10 * err:
+                assert g == tok, f"step {i}: token {g}, oracle {tok}"
+            else:
+                ties += 1
+                assert g in top, f"step {i}: token {g} is neither leader of a near-tie"
+        assert ties <= 2
+    finally:
+        ds.close()
+
+
 def test_single_steps_logits_and_bit_identical_rerun(orc):
     S, steps = 20, 6
     print(f"[case] generation call by call S={S} steps={steps}", flush=True)
