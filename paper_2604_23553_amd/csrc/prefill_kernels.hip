@@ -41,53 +41,73 @@ __device__ __forceinline__ unsigned pf_pack2(float a, float b)
 }
 
 // ---------------------------------------------------------------------------
-// One workgroup of 256 threads per scratch row.  Rows past the pass's tokens get
-// zero planes (their products are never stored).
-constexpr int kPfLnPerThread = 16;     // hidden <= 4096
+// One wavefront per scratch row, four rows per workgroup, no barrier: a lane holds the
+// row's elements 4 (lane + 64 j) .. + 3, j < h / 256 (hidden: a multiple of 128, at most
+// 4096; with an odd number of 128s the upper half of the lanes sits out the last j).
+// Rows past the pass's tokens get zero planes (their products are never stored).
+constexpr int kPfLnVec = 16;           // float4 per lane: hidden <= 4096
 __global__ void __launch_bounds__(256) k_pf_ln(PfParams P)
 {
-    __shared__ float red[8];
     const Dims &dm = P.dm;
-    const int h = dm.h, row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = dm.h, lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
     __half *y1h = P.y1h + (size_t)row * h, *y1l = P.y1l + (size_t)row * h;
     __half *y2h = P.y2h + (size_t)row * h, *y2l = P.y2l + (size_t)row * h;
+    const int nv = h >> 2;                                 // groups of 4 elements in a row
     if (row >= P.n_rows) {
-        const __half z = __float2half_rn(0.f);
-        for (int i = tid; i < h; i += 256) { y1h[i] = z; y1l[i] = z; y2h[i] = z; y2l[i] = z; }
+        const uint2 z = {0u, 0u};
+        for (int g = lane; g < nv; g += 64) {
+            *reinterpret_cast<uint2 *>(y1h + 4 * g) = z; *reinterpret_cast<uint2 *>(y1l + 4 * g) = z;
+            *reinterpret_cast<uint2 *>(y2h + 4 * g) = z; *reinterpret_cast<uint2 *>(y2l + 4 * g) = z;
+        }
         return;
     }
-    float x[kPfLnPerThread];
+    f32x4 x[kPfLnVec];
     float s = 0.f;
 #pragma unroll
-    for (int k = 0; k < kPfLnPerThread; ++k) {
-        const int i = tid + 256 * k;
-        x[k] = 0.f;
-        if (i < h) x[k] = P.layer == 0 ? __half2float(P.x_in[(size_t)row * h + i]) : P.xres[(size_t)row * h + i];
-        s += x[k];
+    for (int j = 0; j < kPfLnVec; ++j) {
+        const int g = lane + 64 * j;
+        x[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (g < nv) {
+            if (P.layer == 0) {
+                const uint2 w = *reinterpret_cast<const uint2 *>(P.x_in + (size_t)row * h + 4 * g);
+                const float2 a = unpack_h2(w.x), b = unpack_h2(w.y);
+                x[j] = f32x4{a.x, a.y, b.x, b.y};
+                *reinterpret_cast<f32x4 *>(P.xres + (size_t)row * h + 4 * g) = x[j];
+            } else {
+                x[j] = *reinterpret_cast<const f32x4 *>(P.xres + (size_t)row * h + 4 * g);
+            }
+        }
+        s += (x[j][0] + x[j][1]) + (x[j][2] + x[j][3]);
     }
-    s = wave_sum(s);
-    if (lane == 0) red[wave] = s;
-    __syncthreads();
-    const float mean = ((red[0] + red[1]) + (red[2] + red[3])) / (float)h;
+    const float mean = wave_sum(s) / (float)h;
     float q = 0.f;
 #pragma unroll
-    for (int k = 0; k < kPfLnPerThread; ++k) {
-        const float dlt = tid + 256 * k < h ? x[k] - mean : 0.f;
-        q += dlt * dlt;
+    for (int j = 0; j < kPfLnVec; ++j) {
+        if (lane + 64 * j < nv) {
+            const f32x4 dl = x[j] - mean;
+            q += (dl[0] * dl[0] + dl[1] * dl[1]) + (dl[2] * dl[2] + dl[3] * dl[3]);
+        }
     }
-    q = wave_sum(q);
-    if (lane == 0) red[4 + wave] = q;
-    __syncthreads();
-    const float inv = 1.0f / sqrtf(((red[4] + red[5]) + (red[6] + red[7])) / (float)h + dm.ln_eps);
-    if (tid == 0) P.stats[row] = float2{mean, inv};
+    const float inv = 1.0f / sqrtf(wave_sum(q) / (float)h + dm.ln_eps);
+    if (lane == 0) P.stats[row] = float2{mean, inv};
     const __half *g1 = P.w + P.lay.ln1_g, *g2 = P.w + P.lay.ln2_g;
 #pragma unroll
-    for (int k = 0; k < kPfLnPerThread; ++k) {
-        const int i = tid + 256 * k;
-        if (i < h) {
-            if (P.layer == 0) P.xres[(size_t)row * h + i] = x[k];
-            pf_split(x[k] * __half2float(g1[i]), y1h[i], y1l[i]);
-            pf_split(x[k] * __half2float(g2[i]), y2h[i], y2l[i]);
+    for (int j = 0; j < kPfLnVec; ++j) {
+        const int g = lane + 64 * j;
+        if (g < nv) {
+            const uint2 w1 = *reinterpret_cast<const uint2 *>(g1 + 4 * g), w2 = *reinterpret_cast<const uint2 *>(g2 + 4 * g);
+            const float2 a1 = unpack_h2(w1.x), b1 = unpack_h2(w1.y), a2 = unpack_h2(w2.x), b2 = unpack_h2(w2.y);
+            const float ga[4] = {a1.x, a1.y, b1.x, b1.y}, gb[4] = {a2.x, a2.y, b2.x, b2.y};
+            __half h1[4], l1[4], h2[4], l2[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                pf_split(x[j][e] * ga[e], h1[e], l1[e]);
+                pf_split(x[j][e] * gb[e], h2[e], l2[e]);
+            }
+            *reinterpret_cast<uint2 *>(y1h + 4 * g) = *reinterpret_cast<const uint2 *>(h1);
+            *reinterpret_cast<uint2 *>(y1l + 4 * g) = *reinterpret_cast<const uint2 *>(l1);
+            *reinterpret_cast<uint2 *>(y2h + 4 * g) = *reinterpret_cast<const uint2 *>(h2);
+            *reinterpret_cast<uint2 *>(y2l + 4 * g) = *reinterpret_cast<const uint2 *>(l2);
         }
     }
 }
@@ -742,7 +762,7 @@ __global__ void __launch_bounds__(256) k_pf_attn_wide(PfParams P)
 // ---------------------------------------------------------------------------
 bool pf_supported(const Dims &dm)
 {
-    return dm.h % kPfTile == 0 && dm.f % kPfTile == 0 && dm.h <= 256 * kPfLnPerThread && (dm.d == 64 || dm.d == 80 || dm.d == 128) &&
+    return dm.h % kPfTile == 0 && dm.f % kPfTile == 0 && dm.h <= 256 * kPfLnVec && (dm.d == 64 || dm.d == 80 || dm.d == 128) &&
            !(dm.flags & kFlagSequentialResidual) && dm.r % 2 == 0;
 }
 
@@ -795,7 +815,7 @@ hipError_t launch_pf_layer(const PfParams &P, hipStream_t s)
     const Dims &dm = P.dm;
     const int mt = (P.n_rows + kPfTile - 1) / kPfTile;
     const __half *w = P.w;
-    hipLaunchKernelGGL(k_pf_ln, dim3(mt * kPfTile), dim3(256), 0, s, P);
+    hipLaunchKernelGGL(k_pf_ln, dim3(mt * kPfTile / 4), dim3(256), 0, s, P);
     hipError_t e = pf_gemm<kPfQkv>(P, P.y1h, P.y1l, w + P.lay.w_qkv, dm.h, 3 * dm.h, P.part, s);
     if (e != hipSuccess) return e;
     e = pf_gemm<kPfUp>(P, P.y2h, P.y2l, w + P.lay.w_up, dm.h, dm.f, P.part, s);
