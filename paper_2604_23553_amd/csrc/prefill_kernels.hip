@@ -791,6 +791,8 @@ static hipError_t pf_gemm(const PfParams &P, const __half *Ah, const __half *Al,
     const PfPlan pl = pf_plan(P.n_rows, N, K);
     const int mt = (P.n_rows + pl.bm - 1) / pl.bm, tiles = (N / kPfTile) * mt;
     const int grid = (tiles * pl.splits + 7) / 8 * 8;
+    // the parts of a split product, [splits][mt * bm][N] floats, must fit what the scratch holds for them
+    if (pl.splits > 1 && (size_t)pl.splits * mt * pl.bm * N > (size_t)kPfSplitTiles * kPfTile * kPfTile) return hipErrorInvalidValue;
     if (pl.bm == 64) {
         constexpr int lds = pf_gemm_lds_bytes<64, 64>();
         const hipError_t e = hipFuncSetAttribute((const void *)k_pf_gemm<EPI, 64, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
