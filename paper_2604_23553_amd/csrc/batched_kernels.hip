@@ -112,6 +112,7 @@ __device__ __forceinline__ bool bat_positions_ok(const BatParams &P)
 // read some row of the LDS region: their products land in columns of the result
 // that are never looked at.
 constexpr int kBatSet = 4;
+constexpr int kBatCtrWords = 4;      // LDS words kept for the counter of k_bat_qkv_up (16 bytes: what follows stays aligned)
 constexpr int kBatDepth = 3;         // sets in flight per wavefront (4 and more spill registers and are slower)
 
 struct BatSeg {
@@ -339,14 +340,25 @@ __device__ __forceinline__ void bat_put8(__half *yh, __half *yl, int at, const f
     *reinterpret_cast<u32x4 *>(yl + at) = lo.u;
 }
 
-// src[b * stride + 0..klen) (fp32, klen <= 4096 a multiple of 8) of every sequence -> hi/lo rows in
+// The 8-column chunk of the activation rows that a thread owns (index in chunks, -1: none): one
+// inside the 128-column units of its own wavefront (unit = wave + 8 k, the columns the wavefront's
+// sets read; 16 chunks per unit).  What a wavefront reads from the activations in LDS it has then
+// written itself, in program order: the stream needs no workgroup barrier around an exchange of
+// activations, and the wavefronts do not wait for one another there.
+__device__ __forceinline__ int bat_chunk(int tid, int klen)
+{
+    const int lane = tid & 63, unit = (tid >> 6) + 8 * (lane >> 4);
+    return unit < (klen >> 7) ? 16 * unit + (lane & 15) : -1;
+}
+
+// src[b * stride + 0..klen) (fp32, klen <= 4096 a multiple of 128) of every sequence -> hi/lo rows in
 // LDS: a thread owns one group of 8 values of every sequence; load() requests them all,
 // commit() converts and writes (other loads can be queued in between)
 struct BatStage {
     f32x4 v[kBatMax][2];
     __device__ __forceinline__ void load(const float *src, size_t stride, int klen, int nb, int tid)
     {
-        const int c = tid < (klen >> 3) ? tid : 0;
+        const int ch = bat_chunk(tid, klen), c = ch < 0 ? 0 : ch;
 #pragma unroll
         for (int b = 0; b < kBatMax; ++b) {
             const float *p = src + (size_t)(b < nb ? b : 0) * stride + 8 * c;
@@ -356,12 +368,13 @@ struct BatStage {
     }
     __device__ __forceinline__ void commit(int klen, __half *yh, __half *yl, int Ks, int nb, int tid) const
     {
-        if (tid < (klen >> 3)) {
+        const int ch = bat_chunk(tid, klen);
+        if (ch >= 0) {
 #pragma unroll
             for (int b = 0; b < kBatMax; ++b) {
                 if (b < nb) {
                     const float e[8] = {v[b][0][0], v[b][0][1], v[b][0][2], v[b][0][3], v[b][1][0], v[b][1][1], v[b][1][2], v[b][1][3]};
-                    bat_put8(yh, yl, b * Ks + 8 * tid, e);
+                    bat_put8(yh, yl, b * Ks + 8 * ch, e);
                 }
             }
         }
@@ -373,10 +386,10 @@ struct BatStage {
 //   W (gamma (x - mu) inv + beta) + b = inv (W (gamma x) - mu s) + c
 // with the two constants per row, s = W gamma and c = W beta + b, that the packing left
 // behind the tensors (PackedLayout::rc_qkv, rc_up; paper Sec. 2.2 for the operation).
-// A thread owns one group of 8 elements of every sequence (hidden <= 4096).  Mean and
-// variance (two passes, biased) are summed per wavefront into `stat` (2 * 8 * kBatMax
-// floats) and added in wavefront order by whoever needs them; the workgroup barriers
-// that the activations need anyway publish the sums.
+// A thread owns one group of 8 elements of every sequence (bat_chunk; hidden <= 4096).  Mean
+// and variance (two passes, biased) are summed per wavefront into `stat` (2 * 8 * kBatMax
+// floats) and added in wavefront order by whoever needs them; a counter in LDS says when
+// all wavefronts' sums of the first pass are there.
 struct BatLn {
     u32x4 raw16[kBatMax];          // layer 0: fp16 input
     f32x4 raw32[kBatMax][2];       // later layers: fp32 residual stream
@@ -385,8 +398,8 @@ struct BatLn {
 
     __device__ __forceinline__ void load(const BatParams &P, int tid)
     {
-        const int h = P.dm.h, nchunk = h >> 3;
-        const int c = tid < nchunk ? tid : 0;
+        const int h = P.dm.h;
+        const int ch = bat_chunk(tid, h), c = ch < 0 ? 0 : ch;
         if (P.layer == 0) {
 #pragma unroll
             for (int b = 0; b < kBatMax; ++b)
@@ -424,7 +437,8 @@ struct BatLn {
     // which: 0 = gamma of the LayerNorm in front of QKV, 1 = of the one in front of the MLP
     __device__ __forceinline__ void write_scaled(const BatParams &P, int which, __half *yh, __half *yl, int Ks, int tid) const
     {
-        if (tid >= (P.dm.h >> 3)) return;
+        const int ch = bat_chunk(tid, P.dm.h);
+        if (ch < 0) return;
         const u32x4 g = graw[which];
         const float2 g0 = unpack_h2(g.x), g1 = unpack_h2(g.y), g2 = unpack_h2(g.z), g3 = unpack_h2(g.w);
         const float gv[8] = {g0.x, g0.y, g1.x, g1.y, g2.x, g2.y, g3.x, g3.y};
@@ -434,7 +448,7 @@ struct BatLn {
                 float yv[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) yv[e] = xv[b][e] * gv[e];
-                bat_put8(yh, yl, b * Ks + 8 * tid, yv);
+                bat_put8(yh, yl, b * Ks + 8 * ch, yv);
             }
         }
     }
@@ -443,7 +457,7 @@ struct BatLn {
     __device__ __forceinline__ void sums(const BatParams &P, float *stat, int tid) const
     {
         const int lane = tid & 63, wave = tid >> 6;
-        const bool active = tid < (P.dm.h >> 3);
+        const bool active = bat_chunk(tid, P.dm.h) >= 0;
 #pragma unroll
         for (int b = 0; b < kBatMax; ++b) {
             float s = 0.f;
@@ -463,7 +477,7 @@ struct BatLn {
     __device__ __forceinline__ void squares(const BatParams &P, float *stat, int tid) const
     {
         const int lane = tid & 63, wave = tid >> 6;
-        const bool active = tid < (P.dm.h >> 3);
+        const bool active = bat_chunk(tid, P.dm.h) >= 0;
         float *stat2 = stat + 8 * kBatMax;
 #pragma unroll
         for (int b = 0; b < kBatMax; ++b) {
@@ -527,7 +541,7 @@ __host__ __device__ __forceinline__ int bat_rc(int rows) { return (rows + 3) & ~
 // its statistics are worked out once, and the two matrices are one stream: the MLP-up
 // weights are on their way while the second normalised input replaces the first in LDS.
 // A workgroup owns P.rows QKV rows and P.rows2 MLP-up rows; either share may be empty at
-// the end of the grid.  LDS: activations (heads, remainders) | LayerNorm sums | QKV sums |
+// the end of the grid.  LDS: activations (heads, remainders) | LayerNorm sums | counter | QKV sums |
 // MLP-up sums.
 __global__ void __launch_bounds__(512) k_bat_qkv_up(BatParams P)
 {
@@ -541,10 +555,13 @@ __global__ void __launch_bounds__(512) k_bat_qkv_up(BatParams P)
     if (q_n == 0 && u_n == 0) return;                      // (whole workgroup)
     const __half *w = P.w;
     float *stat = reinterpret_cast<float *>(yl + kBatMax * Ks);     // behind the activations
+    int *ctr = reinterpret_cast<int *>(stat + 2 * 8 * kBatMax);    // wavefronts whose first-pass sums are in `stat`
     const int rcq = bat_rc(P.rows), rcu = bat_rc(P.rows2);
-    float *redq = stat + 2 * 8 * kBatMax, *redu = redq + 8 * kBatMax * rcq;
-    // order of the requests: the layer input, then the first weights; gamma * x goes into LDS as
-    // soon as the input is here, the statistics follow where the wavefronts would wait anyway
+    float *redq = stat + 2 * 8 * kBatMax + kBatCtrWords, *redu = redq + 8 * kBatMax * rcq;
+    if (tid == 0) *ctr = 0;
+    __syncthreads();                                       // the only meeting before the sums are added: nothing is in flight yet
+    // order of the requests: the layer input, then the first weights; a wavefront puts gamma * x of
+    // its own columns into LDS as soon as its part of the input is here and starts on its sets
     BatLn ln;
     ln.load(P, tid);
     const BatSeg sq{(unsigned)P.lay.w_qkv * 2u, (unsigned)h * 2u, q_begin, q_n, redq, rcq};
@@ -554,16 +571,18 @@ __global__ void __launch_bounds__(512) k_bat_qkv_up(BatParams P)
     ln.unpack(P);
     ln.write_scaled(P, 0, yh, yl, Ks, tid);
     ln.sums(P, stat, tid);
-    __syncthreads();
+    lds_signal(ctr, tid & 63);
     bool squared = false;
     bs.run([](int) {}, [&](int) {
+        lds_await(ctr, 8, P.sync);                         // (long since reached) the means can be formed
         ln.squares(P, stat, tid);
         squared = true;
-        __syncthreads();                                   // gamma_1 * x is no longer read
-        ln.write_scaled(P, 1, yh, yl, Ks, tid);
-        __syncthreads();
+        ln.write_scaled(P, 1, yh, yl, Ks, tid);            // this wavefront's columns: it alone reads them
     });
-    if (!squared) ln.squares(P, stat, tid);                // (uniform: no MLP-up rows in this workgroup)
+    if (!squared) {                                        // (uniform: no MLP-up rows in this workgroup)
+        lds_await(ctr, 8, P.sync);
+        ln.squares(P, stat, tid);
+    }
     __syncthreads();
     const int b = tid & (kBatMax - 1);
     if (b >= P.nb) return;
@@ -599,14 +618,11 @@ __global__ void __launch_bounds__(512) k_bat_out(BatParams P)
     BatStream bs;
     st.load(P.o, (size_t)h, h, P.nb, tid);
     bs.begin(w, sd, sm, nslices, (unsigned)h * 2u, 1, h, yh, yl, Ks, tid);
-    st.commit(h, yh, yl, Ks, P.nb, tid);
-    __syncthreads();
+    st.commit(h, yh, yl, Ks, P.nb, tid);                   // this wavefront's columns: no meeting, here or between the segments
     bs.run([&](int seg) {                                  // seg = 1..nslices: slice seg - 1 of GELU(up), into registers
         st.load(P.m + (size_t)(seg - 1) * h, (size_t)f, h, P.nb, tid);
     }, [&](int) {
-        __syncthreads();                                   // the previous segment no longer reads the activations
         st.commit(h, yh, yl, Ks, P.nb, tid);
-        __syncthreads();
     });
     __syncthreads();
     const int b = tid & (kBatMax - 1);
@@ -635,7 +651,7 @@ size_t bat_lds_bytes(const Dims &dm, int grid)
     int rq, ru, rh;
     bat_rows(dm, grid, &rq, &ru, &rh);
     const size_t act = (size_t)2 * kBatMax * (dm.h + kBatPad) * sizeof(__half);
-    const size_t qkv_up = act + (2 * 8 * kBatMax + (size_t)8 * kBatMax * (bat_rc(rq) + bat_rc(ru))) * sizeof(float);
+    const size_t qkv_up = act + (2 * 8 * kBatMax + kBatCtrWords + (size_t)8 * kBatMax * (bat_rc(rq) + bat_rc(ru))) * sizeof(float);
     const size_t out = act + (size_t)8 * kBatMax * bat_rc(rh) * sizeof(float);
     return qkv_up > out ? qkv_up : out;
 }
