@@ -217,30 +217,33 @@ __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__res
     const size_t rstep = (size_t)RP * K;
     const int st = lrow * kPfStride + lk;
     // Three register sets hold the tiles of the next three steps while the current one is
-    // multiplied out of LDS: a global load has three steps to arrive.  Every step requests,
-    // multiplies, writes LDS and meets the others once, without conditions around the loads
-    // (steps past the end re-read the last tile and are not multiplied).
-    struct Regs { u32x4 ah[NA], al[NA], w[NW]; } g0, g1, g2;
+    // multiplied out of LDS: a global load has three steps to arrive.  A thread moves NP pieces of
+    // 16 bytes per step (its rows of the head plane, of the remainder plane, of the weights).
+    // A step is cut into its BK / 16 instruction groups, and each group requests its share of the
+    // tile three steps ahead, reads its fragments, issues its matrix instructions and writes its
+    // share of the next tile to the other LDS buffer: the vector-memory pipe, the LDS and the matrix
+    // pipe then work side by side instead of one after the other (timestamps of a step that did
+    // these four things in turn: 290 + 590 + 350 + 240 ns, each phase alone on its unit while both
+    // workgroups of a CU were in the same phase).  No conditions around the loads (steps past the
+    // end re-read the last tile and are not multiplied).
+    constexpr int NP = 2 * NA + NW, KS = BK / 16, PK = NP / KS;
+    static_assert(NP % KS == 0, "the pieces of a step divide evenly over its instruction groups");
+    struct Regs { u32x4 p[NP]; } g0, g1, g2;
     const int nk1 = nk - 1;
+    auto gsrc = [&](int i) { return i < NA ? pa_h + i * rstep : i < 2 * NA ? pa_l + (i - NA) * rstep : pw + (i - 2 * NA) * rstep; };
+    auto ldst = [&](int buf, int i) {
+        __half *base = i < NA ? &sA[buf][0][i * RP * kPfStride] : i < 2 * NA ? &sA[buf][1][(i - NA) * RP * kPfStride] : &sW[buf][(i - 2 * NA) * RP * kPfStride];
+        return reinterpret_cast<u32x4 *>(base + st);
+    };
     auto fetch = [&](Regs &g, int kt) {
         const int k0 = (kt < nk1 ? kt : nk1) * BK;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            g.ah[i] = load16(pa_h + i * rstep + k0);
-            g.al[i] = load16(pa_l + i * rstep + k0);
-        }
-#pragma unroll
-        for (int i = 0; i < NW; ++i) g.w[i] = load16(pw + i * rstep + k0);
+        for (int i = 0; i < NP; ++i) g.p[i] = load16(gsrc(i) + k0);
         __builtin_amdgcn_sched_barrier(0);
     };
     auto stash = [&](const Regs &g, int buf) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            *reinterpret_cast<u32x4 *>(&sA[buf][0][st + i * RP * kPfStride]) = g.ah[i];
-            *reinterpret_cast<u32x4 *>(&sA[buf][1][st + i * RP * kPfStride]) = g.al[i];
-        }
-#pragma unroll
-        for (int i = 0; i < NW; ++i) *reinterpret_cast<u32x4 *>(&sW[buf][st + i * RP * kPfStride]) = g.w[i];
+        for (int i = 0; i < NP; ++i) *ldst(buf, i) = g.p[i];
     };
     pf_f32x16 acc[MT][2];
 #pragma unroll
@@ -252,26 +255,36 @@ __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__res
     // fragment of this lane: row lane % 32 of an instruction tile, halves 8 * (lane / 32) .. + 7 of a step of 16
     const int fr = lane & 31, fk = (lane >> 5) * 8;
     const int a_off = (wm * 32 * MT + fr) * kPfStride + fk, w_off = (wn * 64 + fr) * kPfStride + fk;
-    auto multiply = [&](int buf) {
+    // one step: tile `kt_next` into gn, the tile in LDS buffer `buf` multiplied (if `live`), gs into the other buffer
+    auto step = [&](Regs &gn, int kt_next, int buf, bool live, const Regs &gs) {
+        const int k0 = (kt_next < nk1 ? kt_next : nk1) * BK;
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            pf_f16x8 ah[MT], al[MT], wf[2];
+        for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                ah[t] = *reinterpret_cast<const pf_f16x8 *>(&sA[buf][0][a_off + t * 32 * kPfStride + ks * 16]);
-                al[t] = *reinterpret_cast<const pf_f16x8 *>(&sA[buf][1][a_off + t * 32 * kPfStride + ks * 16]);
+            for (int i = ks * PK; i < (ks + 1) * PK; ++i) gn.p[i] = load16(gsrc(i) + k0);
+            if (live) {
+                pf_f16x8 ah[MT], al[MT], wf[2];
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    ah[t] = *reinterpret_cast<const pf_f16x8 *>(&sA[buf][0][a_off + t * 32 * kPfStride + ks * 16]);
+                    al[t] = *reinterpret_cast<const pf_f16x8 *>(&sA[buf][1][a_off + t * 32 * kPfStride + ks * 16]);
+                }
+#pragma unroll
+                for (int t = 0; t < 2; ++t) wf[t] = *reinterpret_cast<const pf_f16x8 *>(&sW[buf][w_off + t * 32 * kPfStride + ks * 16]);
+#pragma unroll
+                for (int a = 0; a < MT; ++a)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[a], wf[b], acc[a][b], 0, 0, 0);
+#pragma unroll
+                for (int a = 0; a < MT; ++a)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[a], wf[b], acc[a][b], 0, 0, 0);
             }
 #pragma unroll
-            for (int t = 0; t < 2; ++t) wf[t] = *reinterpret_cast<const pf_f16x8 *>(&sW[buf][w_off + t * 32 * kPfStride + ks * 16]);
-#pragma unroll
-            for (int a = 0; a < MT; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[a], wf[b], acc[a][b], 0, 0, 0);
-#pragma unroll
-            for (int a = 0; a < MT; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[a], wf[b], acc[a][b], 0, 0, 0);
+            for (int i = ks * PK; i < (ks + 1) * PK; ++i) *ldst(buf ^ 1, i) = gs.p[i];
+            __builtin_amdgcn_sched_barrier(0);
         }
+        __syncthreads();
     };
     fetch(g0, 0);
     fetch(g1, 1);
@@ -279,10 +292,10 @@ __global__ void __launch_bounds__(256) k_pf_gemm(PfParams P, const __half *__res
     stash(g0, 0);
     __syncthreads();
     for (int kt = 0; kt < nk; kt += 3) {                  // tile t sits in LDS buffer t % 2
-        const int b0 = kt & 1, b1 = b0 ^ 1;
-        fetch(g0, kt + 3); multiply(b0); stash(g1, b1); __syncthreads();
-        fetch(g1, kt + 4); if (kt + 1 < nk) multiply(b1); stash(g2, b0); __syncthreads();
-        fetch(g2, kt + 5); if (kt + 2 < nk) multiply(b0); stash(g0, b1); __syncthreads();
+        const int b0 = kt & 1;
+        step(g0, kt + 3, b0, true, g1);
+        step(g1, kt + 4, b0 ^ 1, kt + 1 < nk, g2);
+        step(g2, kt + 5, b0, kt + 2 < nk, g0);
     }
     // this lane holds, per instruction tile, column lane % 32 and rows 8 (e / 4) + 4 (lane / 32) + e % 4
     const Dims &dm = P.dm;
